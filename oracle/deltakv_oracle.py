@@ -1,0 +1,287 @@
+"""CPU oracle for the DeltaKV hot path (TEST INFRASTRUCTURE, not product code).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this module.  It shares no code with the HIP path and imports nothing from it.
+
+Everything is plain numpy in float64 over the exact values of the bf16 inputs.
+Library matmuls are used as single steps; there is no tiling, fusion or
+reordering beyond what the definitions state.
+
+What it follows (paper: "DeltaKV: Residual-Based KV Cache Compression via
+Long-Range Similarity"):
+
+* strided reference set T = {kv_t : t mod s = 0, t < i}        -- section 4.1
+* retrieval of the nearest reference (top-k with k = 1)          -- section 4.1
+* residual against the retrieved reference, then the
+  down-projection encoder                                        -- section 4.1 (compressor), appendix B.2 (lifecycle steps 1-3)
+* reconstruction KV_hat = f_d(z) + KV_ref with the bias-free
+  linear decoder f_d(z) = z W_d                                  -- section 4.1 (reconstruction), section 5.3 (light decompressor)
+* keep-ratio accounting KR                                       -- appendix D, equation (5)
+
+Readings where the paper is silent or differs from the build target are listed
+in the repository's design notes; the ones that shape this file:
+  - similarity is cosine over the per-(token, kv-head) vector K||V (256 values
+    for head_dim 128); a zero-norm vector scores 0 against everything;
+  - k = 1, ties go to the lowest reference ordinal;
+  - positions are 0-indexed, token 0 is a reference, candidates are strictly
+    earlier (ordinal j is token j*s < i);
+  - a reference token is stored raw and attends as itself: idx = own ordinal,
+    latent = 0;
+  - SPLIT mode keeps one latent per stream (z_K = r_K W_dK, z_V = r_V W_dV),
+    JOINT mode one latent per token-head (z = r_K W_dK + r_V W_dV, the paper's
+    single latent over Concat(K, V));
+  - latents are stored in bf16, rounded to nearest even from the float64 value.
+
+Pins (tests/test_oracle_*.py): the paper's two worked KR rows and its dense-KV
+size statement; brute-force retrieval with constructed ties; planted copies;
+full-rank orthonormal reconstruction; zero residual == dense attention over the
+gathered references; s = 1 == textbook attention (cross-checked with
+torch.nn.functional.scaled_dot_product_attention); L = 1 and q = 0 closed
+forms; direct == absorbed formulation; two-half log-sum-exp merge.  Absolute
+latent / attention values for arbitrary inputs are printed nowhere in the paper:
+for those, parity is pinned only through the invariants above.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SPLIT = 0
+JOINT = 1
+
+
+# ----------------------------------------------------------------------------
+# bf16 <-> float64 (exact widening; direct round-to-nearest-even narrowing)
+# ----------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def f64_round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bf16 value (ties to even) of each float64, returned as float64.
+
+    bf16 keeps 8 significant bits; its smallest subnormal is 2**-133.  The
+    rounding is done once, directly from float64 (no intermediate fp32 step).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                       # x = m * 2**e, 0.5 <= |m| < 1
+    q = np.maximum(e - 8, -133)              # exponent of one unit in the last place
+    y = np.rint(np.ldexp(x, -q))             # np.rint rounds half to even
+    out = np.ldexp(y, q)
+    big = np.abs(out) > 3.3895313892515355e38  # largest finite bf16
+    out = np.where(big, np.copysign(np.inf, x), out)
+    return np.where(np.isfinite(x), out, x)
+
+
+def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    r = f64_round_to_bf16(x).astype(np.float32)          # exact: value is a bf16
+    return (r.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+# ----------------------------------------------------------------------------
+# Keep-ratio accounting (appendix D, equation (5)) and cache sizes
+# ----------------------------------------------------------------------------
+def keep_ratio_eq5(n_full_layers: int, n_layers: int, s: int, dc_over_2dk: float,
+                   latent_bits: int = 16, raw_bits: int = 16) -> float:
+    """KR = L_full/L + L_sparse/L * (1/s + d_c/(2 d_k)); a latent stored in fewer
+    bits than the raw cache scales the second term (section 5.3, 4-bit residuals)."""
+    n_sparse = n_layers - n_full_layers
+    per_layer = 1.0 / s + dc_over_2dk * (latent_bits / raw_bits)
+    return n_full_layers / n_layers + n_sparse / n_layers * per_layer
+
+
+def dense_kv_bytes(batch: int, seq_len: int, n_layers: int, n_kv_heads: int, head_dim: int,
+                   bytes_per_value: int = 2) -> int:
+    return batch * seq_len * n_layers * 2 * n_kv_heads * head_dim * bytes_per_value
+
+
+def record_keep_ratio(mode: int, rank: int, head_dim: int, s: int, idx_bytes: int = 4,
+                      value_bytes: int = 2, norm_bytes: int = 0) -> float:
+    """Bytes kept per (token, kv-head) over the dense 2*head_dim values when every
+    token stores a latent record (and an index) and every s-th token is also
+    kept raw."""
+    lat = (rank if mode == JOINT else 2 * rank) * value_bytes
+    raw = 2 * head_dim * value_bytes
+    return (lat + idx_bytes + (raw + norm_bytes) / s) / raw
+
+
+# ----------------------------------------------------------------------------
+# Retrieval (section 4.1: reference set T and arg top-k with k = 1)
+# ----------------------------------------------------------------------------
+def cosine_scores(a: np.ndarray, refs: np.ndarray) -> np.ndarray:
+    """cos(a, refs[j]) for one vector a [n] against refs [m, n]; 0 where a norm is 0."""
+    a = np.asarray(a, dtype=np.float64)
+    refs = np.asarray(refs, dtype=np.float64)
+    na = np.sqrt(np.dot(a, a))
+    nb = np.sqrt(np.einsum("jn,jn->j", refs, refs))
+    den = na * nb
+    dots = refs @ a
+    return np.where(den > 0.0, dots / np.where(den > 0.0, den, 1.0), 0.0)
+
+
+def n_candidates(i: int, s: int) -> int:
+    """Number of reference ordinals j with j*s < i."""
+    return (i + s - 1) // s
+
+
+def retrieve_one(kv: np.ndarray, i: int, h: int, s: int):
+    """Best reference ordinal for token i, head h of kv [L, H, 2D]; returns (j, cos)."""
+    m = n_candidates(i, s)
+    c = cosine_scores(kv[i, h], kv[0:m * s:s, h])
+    j = int(np.argmax(c))            # first occurrence of the maximum == lowest ordinal
+    return j, float(c[j])
+
+
+def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.ndarray,
+             s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048):
+    """Compress tokens start..L-1 of one sequence.
+
+    K, V: float64 [L, H, D] -- the raw states of the WHOLE sequence so far (the
+    references are the raw tokens at multiples of s).  w_down_*: float64 [D, r].
+
+    Returns a dict of per-token results for tokens start..L-1 (index 0 of each
+    array is token `start`):
+      idx      int32   [n, H]      reference ordinal (own ordinal for reference tokens)
+      cos      float64 [n, H]      the winning cosine (1.0 stored for reference tokens)
+      z_k, z_v float64 [n, H, r]   unrounded latents (JOINT: z_v is z_k)
+      zb_k, zb_v uint16 [n, H, r]  bf16 bits of the stored latents
+    and the reference pool of the whole sequence:
+      ref_k, ref_v float64 [ceil(L/s), H, D]
+    """
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    L, H, D = K.shape
+    r = w_down_k.shape[1]
+    n = L - start
+    kv = np.concatenate([K, V], axis=2)                    # [L, H, 2D]
+    refs = kv[0::s]                                        # ordinal j <-> token j*s
+    ref_norm = np.sqrt(np.einsum("jhn,jhn->jh", refs, refs))
+    idx = np.zeros((n, H), dtype=np.int32)
+    cos = np.zeros((n, H), dtype=np.float64)
+    pos = np.arange(start, L)
+    is_ref = (pos % s) == 0
+    for b0 in range(0, n, token_block):
+        b1 = min(n, b0 + token_block)
+        p = pos[b0:b1]
+        ncand = (p + s - 1) // s                           # candidates j < ncand
+        mmax = int(ncand.max()) if len(p) else 0
+        for h in range(H):
+            a = kv[p, h]                                   # [nb, 2D]
+            na = np.sqrt(np.einsum("in,in->i", a, a))
+            if mmax == 0:
+                continue
+            dots = a @ refs[:mmax, h].T                    # [nb, mmax]
+            den = na[:, None] * ref_norm[None, :mmax, h]
+            c = np.where(den > 0.0, dots / np.where(den > 0.0, den, 1.0), 0.0)
+            c = np.where(np.arange(mmax)[None, :] < ncand[:, None], c, -np.inf)
+            j = np.argmax(c, axis=1)                       # lowest ordinal among equal maxima
+            idx[b0:b1, h] = j
+            cos[b0:b1, h] = c[np.arange(b1 - b0), j]
+    # reference tokens point at themselves and carry a zero latent
+    idx[is_ref] = (pos[is_ref] // s)[:, None]
+    cos[is_ref] = 1.0
+    tok_ref = idx.astype(np.int64) * s                     # token position of the chosen reference
+    hh = np.arange(H)[None, :]
+    r_k = K[pos[:, None], hh] - K[tok_ref, hh]             # [n, H, D]
+    r_v = V[pos[:, None], hh] - V[tok_ref, hh]
+    if mode == SPLIT:
+        z_k = r_k @ w_down_k
+        z_v = r_v @ w_down_v
+    else:
+        z_k = r_k @ w_down_k + r_v @ w_down_v
+        z_v = z_k
+    z_k[is_ref] = 0.0
+    if mode == SPLIT:
+        z_v[is_ref] = 0.0
+    out = {
+        "idx": idx, "cos": cos, "z_k": z_k, "z_v": z_v,
+        "zb_k": f64_to_bf16_bits(z_k), "ref_k": K[0::s].copy(), "ref_v": V[0::s].copy(),
+        "mode": mode, "s": s, "start": start,
+    }
+    out["zb_v"] = out["zb_k"] if mode == JOINT else f64_to_bf16_bits(z_v)
+    return out
+
+
+def cosine_of(K: np.ndarray, V: np.ndarray, i: int, h: int, j: int, s: int) -> float:
+    """cos between token i and reference ordinal j for head h (float64)."""
+    a = np.concatenate([K[i, h], V[i, h]]).astype(np.float64)
+    b = np.concatenate([K[j * s, h], V[j * s, h]]).astype(np.float64)
+    return float(cosine_scores(a, b[None, :])[0])
+
+
+# ----------------------------------------------------------------------------
+# Reconstruction and decode attention
+# ----------------------------------------------------------------------------
+def reconstruct(idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v):
+    """KV_hat = reference + z W_up for every (token, head).  Shapes: idx [L,H],
+    z_* [L,H,r], ref_* [n_ref,H,D], w_up_* [r,D]; all float64."""
+    L, H = idx.shape
+    hh = np.arange(H)[None, :]
+    k_hat = ref_k[idx, hh] + z_k @ w_up_k
+    v_hat = ref_v[idx, hh] + z_v @ w_up_v
+    return k_hat, v_hat
+
+
+def dense_attention(q, K, V, scale):
+    """Softmax attention of one query token over L cached tokens with grouped
+    query heads: q [Hq, D], K/V [L, Hkv, D]; q-head g reads kv-head g // (Hq/Hkv).
+    Returns out [Hq, D] and the natural-log log-sum-exp of the scaled logits [Hq]."""
+    q = np.asarray(q, dtype=np.float64)
+    Hq, D = q.shape
+    L, Hkv, _ = K.shape
+    G = Hq // Hkv
+    out = np.zeros((Hq, D))
+    lse = np.zeros(Hq)
+    for g in range(Hq):
+        h = g // G
+        logit = scale * (K[:, h, :] @ q[g])
+        m = np.max(logit)
+        e = np.exp(logit - m)
+        den = np.sum(e)
+        out[g] = (e / den) @ V[:, h, :]
+        lse[g] = m + np.log(den)
+    return out, lse
+
+
+def decode_attn_direct(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):
+    """Reconstruct every cached token, then attend (the definition)."""
+    k_hat, v_hat = reconstruct(idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v)
+    return dense_attention(q, k_hat, v_hat, scale)
+
+
+def decode_attn_absorbed(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):
+    """Same quantity through the linearity of the decoder: the query is pulled
+    through W_up once, scores split into a per-reference part and a latent part,
+    and the value sum splits into a per-reference weight sum and a latent sum.
+    Written independently of decode_attn_direct; used only as a cross-check."""
+    q = np.asarray(q, dtype=np.float64)
+    Hq, D = q.shape
+    L, Hkv = idx.shape
+    n_ref = ref_k.shape[0]
+    G = Hq // Hkv
+    out = np.zeros((Hq, D))
+    lse = np.zeros(Hq)
+    for g in range(Hq):
+        h = g // G
+        q_lat = w_up_k @ q[g]                              # [r]
+        s_ref = ref_k[:, h, :] @ q[g]                      # [n_ref]
+        logit = scale * (s_ref[idx[:, h]] + z_k[:, h, :] @ q_lat)
+        m = np.max(logit)
+        e = np.exp(logit - m)
+        den = np.sum(e)
+        w = np.bincount(idx[:, h], weights=e, minlength=n_ref)
+        out[g] = (w @ ref_v[:, h, :] + (e @ z_v[:, h, :]) @ w_up_v) / den
+        lse[g] = m + np.log(den)
+    return out, lse
+
+
+def merge_partials(outs, lses):
+    """Combine attention results over disjoint token sets from their outputs and
+    log-sum-exps (what a split-KV kernel's final step must equal)."""
+    lses = np.asarray(lses, dtype=np.float64)              # [n_parts, Hq]
+    outs = np.asarray(outs, dtype=np.float64)              # [n_parts, Hq, D]
+    m = np.max(lses, axis=0)
+    w = np.exp(lses - m[None, :])
+    den = np.sum(w, axis=0)
+    out = np.einsum("ph,phd->hd", w, outs) / den[:, None]
+    return out, m + np.log(den)

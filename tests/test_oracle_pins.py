@@ -1,0 +1,378 @@
+"""Pins for the CPU oracle: values the paper prints, closed forms, invariants,
+special cases that reduce to textbook / library routines, and brute force on
+tiny inputs.  None of these use the HIP path."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import deltakv_oracle as O
+from synthetic import generator as G
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append([float(x) for x in line.split()])
+    return out
+
+
+def _f64(bits):
+    return O.bf16_bits_to_f64(bits)
+
+
+def _small_case(seed=1, L=96, H=2, D=16, r=8, s=4, n_proto=6, joint=False):
+    K, V, cls = G.make_kv(seed, L, H, D, n_proto=n_proto, basis_dim=4)
+    P = G.make_projections(seed, D, r, joint=joint)
+    return _f64(K), _f64(V), cls, P
+
+
+# ---------------------------------------------------------------- P1: paper's printed values
+@pytest.mark.parametrize("row", _rows("kr_worked_rows.txt"))
+def test_keep_ratio_matches_paper_rows(row):
+    n_full, n_layers, s, dc, bits, want, tol = row
+    got = 100.0 * O.keep_ratio_eq5(int(n_full), int(n_layers), int(s), dc, latent_bits=int(bits))
+    assert abs(got - want) <= tol, (got, want)
+
+
+def test_dense_kv_size_statement():
+    b, L, nl, hkv, d, bpv, lo, hi = _rows("dense_kv_size.txt")[0]
+    gb = O.dense_kv_bytes(int(b), int(L), int(nl), int(hkv), int(d), int(bpv)) / 1e9
+    assert lo < gb < hi
+    assert abs(gb - 137.438953472) < 1e-6
+
+
+def test_record_keep_ratio_closed_forms():
+    # SPLIT r=64, D=128, s=16, int32 idx: (256 + 4 + 32)/512 ; JOINT: (128 + 4 + 32)/512
+    assert O.record_keep_ratio(O.SPLIT, 64, 128, 16) == pytest.approx(292 / 512)
+    assert O.record_keep_ratio(O.JOINT, 64, 128, 16) == pytest.approx(164 / 512)
+    # without the index and with s=10, JOINT d_c/2d_k = 0.25 reproduces equation (5)'s bracket
+    assert O.record_keep_ratio(O.JOINT, 64, 128, 10, idx_bytes=0) == pytest.approx(0.35)
+
+
+# ---------------------------------------------------------------- bf16 rounding
+def test_bf16_round_ties_to_even_and_matches_library_on_fp32_inputs():
+    import torch
+    # exact ties: 1 + 2^-8 is halfway between 1 and 1+2^-7 -> even (1.0); 1 + 3*2^-8 -> 1 + 2^-6
+    assert O.f64_round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert O.f64_round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert O.f64_round_to_bf16(np.array([-(1.0 + 2.0 ** -8 + 2.0 ** -40)]))[0] == -(1.0 + 2.0 ** -7)
+    # a value where rounding first to fp32 and then to bf16 gives the wrong answer
+    x = 1.0 + 2.0 ** -8 + 2.0 ** -30          # fp32 rounds it to the tie, bf16 then to 1.0
+    assert O.f64_round_to_bf16(np.array([x]))[0] == 1.0 + 2.0 ** -7
+    rng = np.random.default_rng(0)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.f64_round_to_bf16(v.astype(np.float64))
+    assert np.array_equal(got, want)
+    bits = O.f64_to_bf16_bits(v.astype(np.float64))
+    assert np.array_equal(O.bf16_bits_to_f64(bits), want)
+    # subnormal bf16 and zero
+    assert O.f64_round_to_bf16(np.array([2.0 ** -133, 2.0 ** -135, 0.0, -0.0])).tolist() == [2.0 ** -133, 0.0, 0.0, 0.0]
+
+
+# ---------------------------------------------------------------- P2: brute-force retrieval
+def _brute_retrieve(K, V, i, h, s):
+    """Plain loops, strict '>' over ascending ordinals."""
+    a = list(K[i, h]) + list(V[i, h])
+    na = math.sqrt(math.fsum(x * x for x in a))
+    best, bj = -math.inf, -1
+    j = 0
+    while j * s < i:
+        b = list(K[j * s, h]) + list(V[j * s, h])
+        nb = math.sqrt(math.fsum(x * x for x in b))
+        c = 0.0 if (na == 0.0 or nb == 0.0) else math.fsum(x * y for x, y in zip(a, b)) / (na * nb)
+        if c > best:
+            best, bj = c, j
+        j += 1
+    return bj, best
+
+
+def test_retrieval_equals_brute_force_with_ties():
+    K, V, cls, P = _small_case(seed=3, L=70, H=2, D=8, r=4, s=4)
+    # exact ties: make references 3 and 9 bit-identical copies of reference 1, and token 50 a scaled copy
+    for j in (3, 9):
+        K[j * 4], V[j * 4] = K[4].copy(), V[4].copy()
+    K[50], V[50] = 2.0 * K[4], 2.0 * V[4]
+    # a zero-norm token and a zero-norm reference
+    K[33], V[33] = 0.0, 0.0
+    K[8, 1], V[8, 1] = 0.0, 0.0
+    res = O.compress(K, V, _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"]), s=4)
+    for i in range(70):
+        for h in range(2):
+            if i % 4 == 0:
+                assert res["idx"][i, h] == i // 4
+                continue
+            bj, bc = _brute_retrieve(K, V, i, h, 4)
+            oj = int(res["idx"][i, h])
+            if oj != bj:   # only allowed when the two scores differ by rounding noise
+                assert abs(O.cosine_of(K, V, i, h, oj, 4) - bc) < 1e-14 and False, (i, h, oj, bj)
+            assert abs(res["cos"][i, h] - bc) < 1e-13
+    assert res["idx"][50, 0] == 1 and res["idx"][50, 1] == 1          # lowest of the tied 1, 3, 9
+    assert res["idx"][33, 0] == 0                                       # all scores 0 -> ordinal 0
+
+
+def test_candidates_are_strictly_earlier():
+    # token i may use ordinal j only if j*s < i: the token right after a reference can see it,
+    # a reference never sees itself as a candidate, and nothing looks forward.
+    assert [O.n_candidates(i, 4) for i in (1, 4, 5, 8, 9)] == [1, 1, 2, 2, 3]
+    K, V, cls, P = _small_case(seed=5, L=40, H=1, D=8, r=4, s=4)
+    K[21], V[21] = K[24].copy(), V[24].copy()      # identical to a LATER reference (ordinal 6)
+    res = O.compress(K, V, _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"]), s=4)
+    assert res["idx"][21, 0] < 6
+    assert np.all(res["idx"][:, 0] * 4 <= np.arange(40))
+
+
+def test_near_ties_resolved_in_float64():
+    rng = np.random.default_rng(7)
+    L, s, D = 14, 4, 8
+    K = rng.standard_normal((L, 1, D))
+    V = rng.standard_normal((L, 1, D))
+    base = np.concatenate([K[13, 0], V[13, 0]])
+    for eps, winner in ((1e-7, 2), (1e-5, 2)):
+        # ordinal 1 = base + small orthogonal perturbation (cos slightly < 1), ordinal 2 = exact direction
+        pert = rng.standard_normal(2 * D)
+        pert -= pert @ base / (base @ base) * base
+        pert *= math.sqrt(2 * eps) * np.linalg.norm(base) / np.linalg.norm(pert)
+        v1 = base + pert
+        K[4, 0], V[4, 0] = v1[:D], v1[D:]
+        K[8, 0], V[8, 0] = 3.0 * base[:D], 3.0 * base[D:]
+        res = O.compress(K, V, np.eye(D)[:, :4], np.eye(D)[:, :4], s=s)
+        assert res["idx"][13, 0] == winner
+        c1 = O.cosine_of(K, V, 13, 0, 1, s)
+        assert 0.2 * eps < 1.0 - c1 < 5 * eps
+
+
+# ---------------------------------------------------------------- P3 / P12
+def test_planted_copy_and_reference_round_trip():
+    K, V, cls, P = _small_case(seed=11, L=64, H=2, D=16, r=8, s=4)
+    K[37], V[37] = K[20].copy(), V[20].copy()            # token 37 := reference ordinal 5
+    wd = _f64(P["w_down_k_bf16"])
+    res = O.compress(K, V, wd, wd, s=4)
+    assert np.all(res["idx"][37] == 5)
+    assert np.allclose(res["cos"][37], 1.0, atol=1e-15)
+    assert np.all(res["z_k"][37] == 0) and np.all(res["z_v"][37] == 0)
+    ref_tok = np.arange(0, 64, 4)
+    assert np.array_equal(res["idx"][ref_tok], np.repeat((ref_tok // 4)[:, None], 2, 1))
+    assert np.all(res["z_k"][ref_tok] == 0) and np.all(res["zb_v"][ref_tok] == 0)
+    assert np.array_equal(res["ref_k"], K[0::4]) and np.array_equal(res["ref_v"], V[0::4])
+    wu = wd.T
+    kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"], wu, wu)
+    assert np.array_equal(kh[ref_tok], K[ref_tok]) and np.array_equal(vh[ref_tok], V[ref_tok])
+
+
+# ---------------------------------------------------------------- P4: full-rank orthonormal
+@pytest.mark.parametrize("joint", [False, True])
+def test_full_rank_orthonormal_reconstructs_exactly(joint):
+    D = 16
+    r = 2 * D if joint else D
+    K, V, cls, _ = _small_case(seed=13, L=80, H=2, D=D, r=8, s=4)
+    P = G.make_projections(99, D, r, joint=joint)
+    if not joint:      # distinct projections per stream, so that swapping them is caught
+        P2 = G.make_projections(100, D, r)
+        P["w_down_v_f64"], P["w_up_v_f64"] = P2["w_down_k_f64"], P2["w_up_k_f64"]
+    mode = O.JOINT if joint else O.SPLIT
+    res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4, mode=mode)
+    kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
+                           P["w_up_k_f64"], P["w_up_v_f64"])
+    assert np.max(np.abs(kh - K)) < 1e-12 and np.max(np.abs(vh - V)) < 1e-12
+
+
+def test_signed_permutation_projection_error_is_latent_rounding_only():
+    D = 16
+    K, V, cls, _ = _small_case(seed=17, L=80, H=2, D=D, r=8, s=4)
+    rng = np.random.default_rng(1)
+    W = np.zeros((D, D))
+    W[np.arange(D), rng.permutation(D)] = rng.choice([-1.0, 1.0], D)
+    res = O.compress(K, V, W, W, s=4)
+    zk = O.bf16_bits_to_f64(res["zb_k"])
+    zv = O.bf16_bits_to_f64(res["zb_v"])
+    kh, vh = O.reconstruct(res["idx"], zk, zv, res["ref_k"], res["ref_v"], W.T, W.T)
+    hh = np.arange(2)[None, :]
+    rk = K - res["ref_k"][res["idx"], hh]
+    # the reconstruction error is exactly the bf16 rounding error of each residual component
+    assert np.array_equal(kh - res["ref_k"][res["idx"], hh], O.f64_round_to_bf16(rk @ W) @ W.T)
+    assert np.max(np.abs(kh - K)) <= 2.0 ** -8 * np.max(np.abs(rk))   # half an ulp is below 2^-8 |x|
+    assert np.max(np.abs(kh - K)) > 0
+
+
+# ---------------------------------------------------------------- P11: subspace case
+def test_subspace_residual_is_captured_exactly():
+    # tokens = prototype + B c with no noise; if span(W_d) contains span(B) and the retrieved
+    # reference has the same prototype, the rank-r latent reconstructs the token exactly.
+    rng = np.random.default_rng(5)
+    D, rb, r, s, L = 16, 3, 6, 4, 64
+    Bm = G.orthonormal(rng, D, rb)
+    extra = G.orthonormal(rng, D, D)
+    Wd = np.linalg.qr(np.concatenate([Bm, extra[:, : r - rb]], axis=1))[0]      # spans B
+    proto = 10.0 * rng.standard_normal((3, 2, D))
+    cls = rng.integers(0, 3, L)
+    cls[:12:4] = [0, 1, 2]                                  # each class has an early reference
+    K = proto[cls, 0][:, None, :] + (rng.standard_normal((L, 1, rb)) @ Bm.T)
+    V = proto[cls, 1][:, None, :] + (rng.standard_normal((L, 1, rb)) @ Bm.T)
+    res = O.compress(K, V, Wd, Wd, s=s)
+    late = np.arange(12, L)
+    assert np.array_equal(cls[res["idx"][late, 0] * s], cls[late])     # same-prototype reference
+    kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"], Wd.T, Wd.T)
+    assert np.max(np.abs(kh[late] - K[late])) < 1e-12
+    assert np.max(np.abs(vh[late] - V[late])) < 1e-12
+    # and a projection that misses B does NOT reconstruct (the check can fail)
+    Wbad = np.linalg.qr(extra[:, :r] - Bm @ (Bm.T @ extra[:, :r]))[0]
+    res2 = O.compress(K, V, Wbad, Wbad, s=s)
+    kh2, _ = O.reconstruct(res2["idx"], res2["z_k"], res2["z_v"], res2["ref_k"], res2["ref_v"], Wbad.T, Wbad.T)
+    assert np.max(np.abs(kh2[late] - K[late])) > 1e-2
+
+
+# ---------------------------------------------------------------- P10: idempotence
+def test_projection_idempotence():
+    K, V, cls, P = _small_case(seed=19, L=96, H=2, D=16, r=8, s=4)
+    wd, wu = P["w_down_k_f64"], P["w_up_k_f64"]
+    res = O.compress(K, V, wd, wd, s=4)
+    kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"], wu, wu)
+    hh = np.arange(2)[None, :]
+    z2 = (kh - res["ref_k"][res["idx"], hh]) @ wd
+    assert np.max(np.abs(z2 - res["z_k"])) < 1e-12
+
+
+# ---------------------------------------------------------------- decode pins
+def _decode_case(seed=23, L=90, Hkv=2, Gq=3, D=16, r=8, s=4, joint=False):
+    K, V, cls, P = _small_case(seed=seed, L=L, H=Hkv, D=D, r=r, s=s, joint=joint)
+    mode = O.JOINT if joint else O.SPLIT
+    res = O.compress(K, V, _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"]), s=s, mode=mode)
+    q = _f64(G.make_queries(seed, 1, Hkv * Gq, D))[0]
+    zk, zv = _f64(res["zb_k"]), _f64(res["zb_v"])
+    wuk, wuv = _f64(P["w_up_k_bf16"]), _f64(P["w_up_v_bf16"])
+    return K, V, res, q, zk, zv, wuk, wuv
+
+
+def _torch_sdpa(q, K, V, scale):
+    import torch
+    import torch.nn.functional as F
+    Hq = q.shape[0]
+    Hkv = K.shape[1]
+    qt = torch.from_numpy(q)[None, :, None, :]                                  # [1,Hq,1,D]
+    kt = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(Hq // Hkv, 0)[None]
+    vt = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(Hq // Hkv, 0)[None]
+    return F.scaled_dot_product_attention(qt, kt, vt, scale=scale)[0, :, 0, :].numpy()
+
+
+def test_stride_one_is_textbook_attention_vs_library():            # P6
+    K, V, cls, P = _small_case(seed=29, L=50, H=2, D=16, r=8, s=1)
+    wd = _f64(P["w_down_k_bf16"])
+    res = O.compress(K, V, wd, wd, s=1)
+    assert np.array_equal(res["idx"][:, 0], np.arange(50)) and np.all(res["z_k"] == 0)
+    q = _f64(G.make_queries(29, 1, 6, 16))[0]
+    scale = 0.37
+    out, lse = O.decode_attn_direct(q, res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
+                                    wd.T, wd.T, scale)
+    want = _torch_sdpa(q, K, V, scale)
+    assert np.max(np.abs(out - want)) < 1e-12
+    # lse against scipy's logsumexp of the plain logits, GQA head map g -> g // 3
+    from scipy.special import logsumexp
+    for g in range(6):
+        assert abs(lse[g] - logsumexp(scale * (K[:, g // 3] @ q[g]))) < 1e-12
+
+
+def test_zero_residual_equals_dense_attention_over_gathered_references():   # P5
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case()
+    z0 = np.zeros_like(zk)
+    out, lse = O.decode_attn_direct(q, res["idx"], z0, z0, res["ref_k"], res["ref_v"], wuk, wuv, 0.25)
+    hh = np.arange(2)[None, :]
+    want = _torch_sdpa(q, res["ref_k"][res["idx"], hh], res["ref_v"][res["idx"], hh], 0.25)
+    assert np.max(np.abs(out - want)) < 1e-12
+
+
+def test_full_rank_decode_equals_dense_attention_over_raw_kv():
+    D = 16
+    K, V, cls, _ = _small_case(seed=31, L=70, H=2, D=D, r=8, s=4)
+    P = G.make_projections(5, D, D)
+    res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4)
+    q = _f64(G.make_queries(31, 1, 4, D))[0]
+    out, _ = O.decode_attn_direct(q, res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
+                                  P["w_up_k_f64"], P["w_up_v_f64"], 1 / 4.0)
+    assert np.max(np.abs(out - _torch_sdpa(q, K, V, 1 / 4.0))) < 1e-11
+
+
+def test_single_token_and_zero_query_closed_forms():              # P7
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(L=1)
+    out, lse = O.decode_attn_direct(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3)
+    for g in range(6):
+        assert np.array_equal(out[g], V[0, g // 3])
+        assert abs(lse[g] - 0.3 * (K[0, g // 3] @ q[g])) < 1e-13
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(L=77)
+    out, lse = O.decode_attn_direct(0 * q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3)
+    kh, vh = O.reconstruct(res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv)
+    for g in range(6):
+        assert np.max(np.abs(out[g] - vh[:, g // 3].mean(0))) < 1e-13
+        assert abs(lse[g] - math.log(77)) < 1e-13
+
+
+@pytest.mark.parametrize("joint", [False, True])
+def test_direct_equals_absorbed(joint):                              # P8
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=37, L=130, joint=joint)
+    a, la = O.decode_attn_direct(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25)
+    b, lb = O.decode_attn_absorbed(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25)
+    assert np.max(np.abs(a - b)) < 1e-10 and np.max(np.abs(la - lb)) < 1e-10
+
+
+def test_reconstruction_uses_the_indexed_reference_and_the_right_stream():
+    # one token, hand-built cache: K_hat = ref_k[idx] + z_k W_uk, V_hat = ref_v[idx] + z_v W_uv
+    rng = np.random.default_rng(3)
+    ref_k, ref_v = rng.standard_normal((3, 1, 4)), rng.standard_normal((3, 1, 4))
+    wuk, wuv = rng.standard_normal((2, 4)), rng.standard_normal((2, 4))
+    idx = np.array([[2]], dtype=np.int32)
+    zk, zv = np.array([[[1.0, -2.0]]]), np.array([[[0.5, 3.0]]])
+    kh, vh = O.reconstruct(idx, zk, zv, ref_k, ref_v, wuk, wuv)
+    assert np.allclose(kh[0, 0], ref_k[2, 0] + 1.0 * wuk[0] - 2.0 * wuk[1], atol=1e-15)
+    assert np.allclose(vh[0, 0], ref_v[2, 0] + 0.5 * wuv[0] + 3.0 * wuv[1], atol=1e-15)
+
+
+def test_lse_merge_of_two_halves_equals_whole():                   # P9
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=41, L=120)
+    whole, lw = O.decode_attn_direct(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25)
+    parts = []
+    for sl in (slice(0, 45), slice(45, 120)):
+        parts.append(O.decode_attn_direct(q, res["idx"][sl], zk[sl], zv[sl], res["ref_k"], res["ref_v"],
+                                          wuk, wuv, 0.25))
+    out, lse = O.merge_partials([p[0] for p in parts], [p[1] for p in parts])
+    assert np.max(np.abs(out - whole)) < 1e-12 and np.max(np.abs(lse - lw)) < 1e-12
+
+
+def test_joint_latent_is_sum_of_stream_projections():
+    K, V, cls, P = _small_case(seed=43, L=40, H=1, D=16, r=8, s=4, joint=True)
+    wk, wv = P["w_down_k_f64"], P["w_down_v_f64"]
+    res = O.compress(K, V, wk, wv, s=4, mode=O.JOINT)
+    i = 13
+    j = int(res["idx"][i, 0])
+    want = np.concatenate([K[i, 0] - K[4 * j, 0], V[i, 0] - V[4 * j, 0]]) @ np.concatenate([wk, wv], 0)
+    assert np.max(np.abs(res["z_k"][i, 0] - want)) < 1e-13
+    assert res["z_v"] is res["z_k"] and res["zb_v"] is res["zb_k"]
+
+
+def test_incremental_compress_matches_one_shot():
+    K, V, cls, P = _small_case(seed=47, L=75, H=2, D=16, r=8, s=4)
+    wd = _f64(P["w_down_k_bf16"])
+    full = O.compress(K, V, wd, wd, s=4)
+    part = O.compress(K, V, wd, wd, s=4, start=51)
+    assert np.array_equal(part["idx"], full["idx"][51:])
+    assert np.array_equal(part["zb_k"], full["zb_k"][51:]) and np.array_equal(part["zb_v"], full["zb_v"][51:])
+
+
+def test_generator_recipe_statistics():
+    # the inputs have the structure the recipe states: same-class tokens are close, others are not
+    K, V, cls = G.make_kv(G.seed_for(1), 2048, 2, 128, n_proto=256)
+    Kf = _f64(K)
+    same = [(i, j) for i in range(300, 340) for j in range(0, 300) if cls[i, 0] == cls[j, 0]]
+    assert len(same) > 5
+    def cs(i, j):
+        return Kf[i, 0] @ Kf[j, 0] / np.linalg.norm(Kf[i, 0]) / np.linalg.norm(Kf[j, 0])
+    assert np.mean([cs(i, j) for i, j in same]) > 0.6
+    assert abs(np.mean([cs(i, i - 1) for i in range(1, 400) if cls[i, 0] != cls[i - 1, 0]])) < 0.1
+    # per-token energy: 128 (prototype) + 32 (basis part, variance 2 x 16) + 0.32 (noise)
+    assert abs(np.mean(np.sum(Kf * Kf, -1)) - 160.3) < 4.0
