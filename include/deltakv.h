@@ -1,0 +1,204 @@
+/*
+ * deltakv.h -- C ABI of the MI355X (gfx950) DeltaKV hot path.
+ *
+ * Paper: "DeltaKV: Residual-Based KV Cache Compression via Long-Range
+ * Similarity".  The library implements two operations and the layout
+ * arithmetic they share:
+ *
+ *   deltakv_compress     section 4.1 (strided reference set, nearest-reference
+ *                        retrieval, residual, compressor) and appendix B.2
+ *                        "lifecycle management" steps 1-3 (residual against the
+ *                        assigned reference -> down-projection -> write to the
+ *                        latent pool), with the retrieval of appendix B.3
+ *                        ("batch distance" search as a dense matrix product).
+ *   deltakv_decode_attn  section 4.1 "Reconstruction" (KV_hat = f_d(z) + KV_ref)
+ *                        with the bias-free linear decoder of section 5.3,
+ *                        fused into grouped-query softmax attention for one new
+ *                        query token per sequence (the fused
+ *                        reconstruction-attention kernel that section 5.3 and
+ *                        appendix B.5 name as future work).
+ *   deltakv_paged_layout appendix B.1 (separate pools for raw reference tokens
+ *                        and for latents, addressed through per-sequence maps).
+ *
+ * Readings fixed by this build (the paper is silent or differs):
+ *   - one reference per (token, kv-head), chosen by cosine similarity over the
+ *     256-value vector K||V of that head, lowest ordinal wins ties (the paper's
+ *     retrieval is top-k by squared L2 over all heads, k = 4);
+ *   - positions are 0-indexed; token t is a reference iff t % ref_stride == 0,
+ *     its ordinal is t / ref_stride; candidates of token i are ordinals j with
+ *     j * ref_stride < i;
+ *   - a reference token is kept raw in the reference pool AND owns a latent
+ *     record (index = its own ordinal, latent = 0), so every cached token is
+ *     read the same way;
+ *   - SPLIT mode: z_K = (K - K_ref) W_dK, z_V = (V - V_ref) W_dV, two streams;
+ *     JOINT mode: z = (K - K_ref) W_dK + (V - V_ref) W_dV, one stream (the
+ *     paper's single latent over Concat(K, V));
+ *   - latents are bf16 (round to nearest even), accumulation is fp32.
+ *
+ * General conventions
+ *   - every function returns 0 on success or a negative DELTAKV_E_* code; no
+ *     function throws, allocates device memory, synchronises the device or uses
+ *     the default stream (kernels go to the stream passed in);
+ *   - "device" pointers are HIP device memory owned by the caller and must stay
+ *     valid until the stream has run the enqueued work; "host" pointers are
+ *     ordinary host memory read before the call returns;
+ *   - only host-visible arguments are validated.  Device contents (page ids,
+ *     slots, stored reference ordinals) are clamped into range before use, so a
+ *     corrupt cache gives wrong numbers, not a fault;
+ *   - bf16 buffers are raw 16-bit patterns (uint16_t).
+ */
+#ifndef DELTAKV_H
+#define DELTAKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DELTAKV_OK             0
+#define DELTAKV_E_INVALID_ARG (-1)  /* null pointer, negative size, inconsistent argument      */
+#define DELTAKV_E_UNSUPPORTED (-2)  /* shape outside what the kernels implement                */
+#define DELTAKV_E_WORKSPACE   (-3)  /* workspace missing, misaligned or too small              */
+#define DELTAKV_E_HIP         (-4)  /* a HIP runtime call failed (launch, attribute)           */
+
+#define DELTAKV_SPLIT 0
+#define DELTAKV_JOINT 1
+
+#define DELTAKV_METRIC_COSINE 0
+
+/* Problem dimensions.  v1 kernels need head_dim == 128, page_tokens == 16,
+ * rank a multiple of 16 in [16, 128], 1 <= n_q_heads / n_kv_heads <= 16 and
+ * n_q_heads % n_kv_heads == 0; anything else returns DELTAKV_E_UNSUPPORTED. */
+typedef struct {
+  int32_t n_kv_heads;
+  int32_t n_q_heads;
+  int32_t head_dim;
+  int32_t rank;         /* r: latent width per stream                              */
+  int32_t latent_mode;  /* DELTAKV_SPLIT or DELTAKV_JOINT                          */
+  int32_t ref_stride;   /* s >= 1: every s-th token is a reference                 */
+  int32_t page_tokens;  /* P: tokens per page                                      */
+  int32_t metric;       /* DELTAKV_METRIC_COSINE                                   */
+  int64_t n_pages;      /* capacity of the latent / index pools, in pages          */
+  int64_t n_ref_slots;  /* capacity of the reference pool, in reference tokens     */
+} deltakv_dims;
+
+/* Filled by deltakv_paged_layout; the only source of sizes and strides.
+ *
+ * Pools (all device memory, base addresses aligned to `alignment` bytes):
+ *   latent pool  bf16   [n_pages][n_kv_heads][n_streams] blocks of P*r values.
+ *                Inside a block the P x r latents of one (page, head, stream)
+ *                are stored in the order the matrix units consume them:
+ *                  stream 0 (scores operand; the only stream in JOINT mode):
+ *                    value (tok, c) at ((c/8)*P + tok)*8 + c%8
+ *                  stream 1 (value operand, SPLIT mode only):
+ *                    value (tok, c) at ((c/16)*64 + (tok/4)*16 + c%16)*4 + tok%4
+ *                deltakv_latent_block_offsets returns these as a table.
+ *   index pool   int32  [n_pages][n_kv_heads][P]   reference ordinal per token
+ *   reference pool bf16 [n_kv_heads][2][n_ref_slots][head_dim]   (0 = K, 1 = V)
+ *   reference inverse norms fp32 [n_kv_heads][n_ref_slots]: 1/||K||V|| of the
+ *                slot's raw vector (0 for a zero vector), written at admission.
+ * Strides are in elements of the pool's type. */
+typedef struct {
+  int64_t latent_pool_bytes, idx_pool_bytes, ref_pool_bytes, ref_norm_pool_bytes;
+  int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
+  int64_t idx_page_stride, idx_head_stride;
+  int64_t ref_head_stride, ref_kv_stride, ref_slot_stride;
+  int64_t ref_norm_head_stride;
+  int64_t compress_ws_bytes; /* workspace for deltakv_compress at the sizes asked  */
+  int64_t decode_ws_bytes;   /* workspace for deltakv_decode_attn at the sizes asked */
+  int32_t n_streams;         /* 2 in SPLIT mode, 1 in JOINT mode                   */
+  int32_t alignment;         /* required alignment of pools and workspaces, bytes  */
+} deltakv_layout;
+
+/* Host-only, pure.  Computes pool sizes / strides for `dims`, and workspace
+ * sizes good for any call with batch <= max_batch, at most max_new_tokens new
+ * tokens in total per compress call, and sequences of at most max_seq_len
+ * tokens (after appending).  Errors: INVALID_ARG (null, non-positive sizes),
+ * UNSUPPORTED (see deltakv_dims). */
+int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t max_new_tokens,
+                         int64_t max_seq_len, deltakv_layout* out);
+
+/* Host-only, pure.  out[tok * rank + c] = element offset of latent value
+ * (tok, c) inside one (page, head, stream) block; `out` holds P*rank int32. */
+int deltakv_latent_block_offsets(const deltakv_dims* dims, int32_t stream, int32_t* out);
+
+/* Host-only, pure.  Bytes this layout keeps per cached token (latent record +
+ * index + the amortised raw reference and its norm) over the bytes of the dense
+ * bf16 K and V it replaces: the per-layer bracket of the paper's keep-ratio
+ * accounting (appendix D, equation (5)) evaluated for the real record sizes. */
+double deltakv_keep_ratio(const deltakv_dims* dims);
+
+/* Residual compression of new tokens (prefill chunk or decode append).
+ *
+ * For sequence b, tokens cu_new[b] .. cu_new[b+1]-1 of k_new / v_new are its
+ * next tokens, at positions len_before[b], len_before[b]+1, ...  For each new
+ * token t and kv-head h:
+ *   t % s == 0: raw K,V copied to reference slot ref_tables[b][t/s], inverse
+ *               norm stored, index := t/s, latent := 0;
+ *   otherwise : index := argmax_j cos(K||V of t, K||V of reference ordinal j)
+ *               over j*s < t (lowest j on ties; references older than this call
+ *               are read from the reference pool), latent := the projected
+ *               residual against that reference, rounded to bf16.
+ * Results go to page block_tables[b][t / P], token slot t % P.
+ *
+ *   latent_pool, idx_pool, ref_pool, ref_inv_norm  device, read+written
+ *   block_tables  device int32 [batch][bt_stride]: logical page -> pool page
+ *   ref_tables    device int32 [batch][rt_stride]: reference ordinal -> slot
+ *   w_down_k/v    device bf16 [head_dim][rank]
+ *   k_new, v_new  device bf16 [n_new_total][n_kv_heads][head_dim]
+ *   cu_new        device int32 [batch+1]; cu_new_host: the same values on the host
+ *   len_before    device int32 [batch];   len_before_host: the same on the host
+ *   workspace     device, >= layout->compress_ws_bytes, aligned
+ *   stream        hipStream_t (as void*); must not be the null stream object of
+ *                 another device
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE (too small for this call), HIP. */
+int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* layout,
+                     void* latent_pool, int32_t* idx_pool, void* ref_pool, float* ref_inv_norm,
+                     const int32_t* block_tables, int32_t bt_stride,
+                     const int32_t* ref_tables, int32_t rt_stride,
+                     const void* w_down_k, const void* w_down_v,
+                     const void* k_new, const void* v_new,
+                     const int32_t* cu_new, const int32_t* cu_new_host,
+                     const int32_t* len_before, const int32_t* len_before_host,
+                     int32_t batch, void* workspace, int64_t ws_bytes, void* stream);
+
+/* Grouped-query softmax attention of one query token per sequence over the
+ * compressed cache: for q-head g (kv-head h = g / (n_q_heads/n_kv_heads)) and
+ * every cached token t < seq_lens[b],
+ *   K_hat = K_ref[idx] + z_K W_uK,  V_hat = V_ref[idx] + z_V W_uV  (JOINT: z_V = z_K)
+ *   out[g] = sum_t softmax_t(scale * q_g . K_hat_t) V_hat_t .
+ * The result equals reconstruct-then-attend; the kernels use the linearity of
+ * the decoder to score latents against W_uK q and to up-project the weighted
+ * latent sum once.
+ *
+ *   w_up_k/v      device bf16 [rank][head_dim]
+ *   q             device bf16 [batch][n_q_heads][head_dim]
+ *   seq_lens      device int32 [batch]; seq_lens_host: same values on the host
+ *                 (used to size the launch).  A sequence of length 0 gets out = 0
+ *                 and lse = -inf.
+ *   out           device bf16 [batch][n_q_heads][head_dim]
+ *   lse           device fp32 [batch][n_q_heads] natural-log sum of exp of the
+ *                 scaled logits, or NULL
+ * Errors: INVALID_ARG, UNSUPPORTED (a sequence needs more on-chip table space
+ * than one compute unit has: roughly seq_len/ref_stride * group size > 36000),
+ * WORKSPACE, HIP. */
+int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* layout,
+                        const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
+                        const int32_t* block_tables, int32_t bt_stride,
+                        const int32_t* ref_tables, int32_t rt_stride,
+                        const void* w_up_k, const void* w_up_v, const void* q,
+                        const int32_t* seq_lens, const int32_t* seq_lens_host,
+                        int32_t batch, float scale, void* out, float* lse,
+                        void* workspace, int64_t ws_bytes, void* stream);
+
+const char* deltakv_strerror(int code);
+/* For DELTAKV_E_HIP: which runtime call failed and the runtime's message (calling thread's last failure;
+ * empty string if none).  The pointer stays valid until the thread's next failing call. */
+const char* deltakv_last_error_detail(void);
+int deltakv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DELTAKV_H */

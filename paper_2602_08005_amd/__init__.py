@@ -1,0 +1,9 @@
+"""MI355X-native DeltaKV hot path: residual compression and fused decode attention (gfx950 HIP).
+
+The compute lives in libdeltakv.so (see include/deltakv.h); this package is the thin binding.
+Importing it loads the library and raises ImportError if it has not been built.
+"""
+from . import binding  # noqa: F401  (loads libdeltakv.so or fails)
+from .binding import (Dims, Layout, DeltaKVError, SPLIT, JOINT, make_dims, paged_layout,  # noqa: F401
+                      latent_block_offsets, keep_ratio, compress, decode_attn, version, strerror)
+from .cache import PagedCache  # noqa: F401

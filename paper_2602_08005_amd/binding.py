@@ -1,0 +1,161 @@
+"""ctypes binding of libdeltakv.so: the same names as include/deltakv.h.
+
+Argument marshalling only -- every step of the hot path runs inside the HIP
+library.  There is no fallback: if the library is missing, import fails.
+PyTorch tensors are used for device memory and streams (`data_ptr()`,
+`torch.cuda.current_stream().cuda_stream`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # noqa: F401  imported BEFORE the library is loaded: libdeltakv must bind to the HIP runtime
+              # that PyTorch ships (the streams and device pointers it is handed belong to that runtime)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdeltakv.so")
+
+OK, E_INVALID_ARG, E_UNSUPPORTED, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4
+SPLIT, JOINT = 0, 1
+METRIC_COSINE = 0
+
+
+class Dims(C.Structure):
+    _fields_ = [("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("rank", C.c_int32), ("latent_mode", C.c_int32), ("ref_stride", C.c_int32),
+                ("page_tokens", C.c_int32), ("metric", C.c_int32),
+                ("n_pages", C.c_int64), ("n_ref_slots", C.c_int64)]
+
+
+class Layout(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "latent_pool_bytes", "idx_pool_bytes", "ref_pool_bytes", "ref_norm_pool_bytes",
+        "latent_page_stride", "latent_head_stride", "latent_stream_stride",
+        "idx_page_stride", "idx_head_stride",
+        "ref_head_stride", "ref_kv_stride", "ref_slot_stride", "ref_norm_head_stride",
+        "compress_ws_bytes", "decode_ws_bytes")] + [("n_streams", C.c_int32), ("alignment", C.c_int32)]
+
+
+class DeltaKVError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = _lib.deltakv_last_error_detail().decode() if code == E_HIP else ""
+        super().__init__(f"{where}: {strerror(code)} ({code}) {detail}")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    with open("/proc/self/maps") as f:
+        runtimes = {ln.split()[-1] for ln in f if "libamdhip64" in ln}
+    if len(runtimes) > 1:
+        raise ImportError(f"two HIP runtimes are loaded ({sorted(runtimes)}); libdeltakv and PyTorch must share one")
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.deltakv_version.restype = C.c_int
+    lib.deltakv_strerror.restype = C.c_char_p
+    lib.deltakv_strerror.argtypes = [C.c_int]
+    lib.deltakv_last_error_detail.restype = C.c_char_p
+    lib.deltakv_paged_layout.restype = C.c_int
+    lib.deltakv_paged_layout.argtypes = [C.POINTER(Dims), i32, i64, i64, C.POINTER(Layout)]
+    lib.deltakv_latent_block_offsets.restype = C.c_int
+    lib.deltakv_latent_block_offsets.argtypes = [C.POINTER(Dims), i32, vp]
+    lib.deltakv_keep_ratio.restype = C.c_double
+    lib.deltakv_keep_ratio.argtypes = [C.POINTER(Dims)]
+    lib.deltakv_compress.restype = C.c_int
+    lib.deltakv_compress.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, vp, i32, vp, i32,
+                                     vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i64, vp]
+    lib.deltakv_decode_attn.restype = C.c_int
+    lib.deltakv_decode_attn.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
+                                        vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, i64, vp]
+    return lib
+
+
+_lib = _load()
+EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_paged_layout", "deltakv_latent_block_offsets",
+           "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn")
+
+
+def version() -> int:
+    return int(_lib.deltakv_version())
+
+
+def strerror(code: int) -> str:
+    return _lib.deltakv_strerror(int(code)).decode()
+
+
+def make_dims(n_kv_heads, n_q_heads, rank, n_pages, n_ref_slots, latent_mode=SPLIT, ref_stride=16,
+              head_dim=128, page_tokens=16, metric=METRIC_COSINE) -> Dims:
+    return Dims(n_kv_heads, n_q_heads, head_dim, rank, latent_mode, ref_stride, page_tokens, metric,
+                n_pages, n_ref_slots)
+
+
+def paged_layout(dims: Dims, max_batch: int, max_new_tokens: int, max_seq_len: int) -> Layout:
+    out = Layout()
+    rc = _lib.deltakv_paged_layout(C.byref(dims), max_batch, max_new_tokens, max_seq_len, C.byref(out))
+    if rc != OK:
+        raise DeltaKVError(rc, "deltakv_paged_layout")
+    return out
+
+
+def latent_block_offsets(dims: Dims, stream: int) -> np.ndarray:
+    out = np.empty((dims.page_tokens, dims.rank), dtype=np.int32)
+    rc = _lib.deltakv_latent_block_offsets(C.byref(dims), stream, out.ctypes.data)
+    if rc != OK:
+        raise DeltaKVError(rc, "deltakv_latent_block_offsets")
+    return out
+
+
+def keep_ratio(dims: Dims) -> float:
+    return float(_lib.deltakv_keep_ratio(C.byref(dims)))
+
+
+def _dp(t):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _host_i32(x) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x, dtype=np.int32))
+
+
+def compress(dims, layout, latent_pool, idx_pool, ref_pool, ref_inv_norm, block_tables, ref_tables,
+             w_down_k, w_down_v, k_new, v_new, cu_new, cu_new_host, len_before, len_before_host,
+             workspace, stream=None, check=True) -> int:
+    cu_h, lb_h = _host_i32(cu_new_host), _host_i32(len_before_host)
+    batch = len(lb_h)
+    rc = _lib.deltakv_compress(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool), _dp(ref_inv_norm),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_down_k), _dp(w_down_v), _dp(k_new), _dp(v_new), _dp(cu_new), cu_h.ctypes.data,
+        _dp(len_before), lb_h.ctypes.data, batch, _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_compress")
+    return rc
+
+
+def decode_attn(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref_tables, w_up_k, w_up_v, q,
+                seq_lens, seq_lens_host, scale, out, lse, workspace, stream=None, check=True) -> int:
+    sl_h = _host_i32(seq_lens_host)
+    rc = _lib.deltakv_decode_attn(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_up_k), _dp(w_up_v), _dp(q), _dp(seq_lens), sl_h.ctypes.data, len(sl_h), float(scale),
+        _dp(out), _dp(lse), _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_decode_attn")
+    return rc

@@ -1,0 +1,150 @@
+"""Device pools of the compressed cache and host-side placement helpers.
+
+Pure data placement: allocating the pools the C library describes, building
+block / reference tables, and copying logical (token-major) arrays into or out
+of the paged layout using the offset tables the library exports.  No arithmetic
+of the method lives here.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+class PagedCache:
+    """Pools + per-sequence maps for `batch` sequences.
+
+    page_ids[b] / ref_slots[b] give, per sequence, the pool page of each logical
+    page and the pool slot of each reference ordinal (contiguous if omitted).
+    """
+
+    def __init__(self, dims: B.Dims, max_batch: int, max_new_tokens: int, max_seq_len: int,
+                 device="cuda", page_ids=None, ref_slots=None):
+        import torch
+        self.torch = torch
+        self.dims = dims
+        self.layout = B.paged_layout(dims, max_batch, max_new_tokens, max_seq_len)
+        self.device = device
+        L = self.layout
+        self.latent_pool = torch.zeros(L.latent_pool_bytes // 2, dtype=torch.int16, device=device)
+        self.idx_pool = torch.zeros(L.idx_pool_bytes // 4, dtype=torch.int32, device=device)
+        self.ref_pool = torch.zeros(L.ref_pool_bytes // 2, dtype=torch.int16, device=device)
+        self.ref_inv_norm = torch.zeros(L.ref_norm_pool_bytes // 4, dtype=torch.float32, device=device)
+        P, S = dims.page_tokens, dims.ref_stride
+        self.max_pages = -(-max_seq_len // P)
+        self.max_refs = -(-max_seq_len // S)
+        bt = np.zeros((max_batch, self.max_pages), dtype=np.int32)
+        rt = np.zeros((max_batch, self.max_refs), dtype=np.int32)
+        for b in range(max_batch):
+            if page_ids is None:
+                bt[b] = np.arange(b * self.max_pages, (b + 1) * self.max_pages) % dims.n_pages
+            else:
+                bt[b, :len(page_ids[b])] = page_ids[b]
+            if ref_slots is None:
+                rt[b] = np.arange(b * self.max_refs, (b + 1) * self.max_refs) % dims.n_ref_slots
+            else:
+                rt[b, :len(ref_slots[b])] = ref_slots[b]
+        self.block_tables_host, self.ref_tables_host = bt, rt
+        self.block_tables = torch.from_numpy(bt).to(device)
+        self.ref_tables = torch.from_numpy(rt).to(device)
+        self.off = [B.latent_block_offsets(dims, s).astype(np.int64) for s in range(L.n_streams)]
+        self.compress_ws = torch.empty(max(L.compress_ws_bytes, 256), dtype=torch.uint8, device=device)
+        self.decode_ws = torch.empty(max(L.decode_ws_bytes, 256), dtype=torch.uint8, device=device)
+
+    # -- logical <-> paged copies (host numpy in, device pools updated) ---------------------------
+    def _latent_index(self, b: int, t0: int, t1: int, stream: int) -> np.ndarray:
+        d, L = self.dims, self.layout
+        t = np.arange(t0, t1)
+        page = self.block_tables_host[b, t // d.page_tokens].astype(np.int64)
+        base = page[:, None] * L.latent_page_stride + np.arange(d.n_kv_heads)[None, :] * L.latent_head_stride \
+            + stream * L.latent_stream_stride                                  # [n, H]
+        return base[:, :, None] + self.off[stream][t % d.page_tokens][:, None, :]   # [n, H, r]
+
+    def _idx_index(self, b: int, t0: int, t1: int) -> np.ndarray:
+        d, L = self.dims, self.layout
+        t = np.arange(t0, t1)
+        page = self.block_tables_host[b, t // d.page_tokens].astype(np.int64)
+        return page[:, None] * L.idx_page_stride + np.arange(d.n_kv_heads)[None, :] * L.idx_head_stride \
+            + (t % d.page_tokens)[:, None]
+
+    def _ref_index(self, b: int, j0: int, j1: int, kv: int) -> np.ndarray:
+        d, L = self.dims, self.layout
+        slot = self.ref_tables_host[b, j0:j1].astype(np.int64)
+        return (np.arange(d.n_kv_heads)[None, :, None] * L.ref_head_stride + kv * L.ref_kv_stride
+                + slot[:, None, None] * L.ref_slot_stride + np.arange(d.head_dim)[None, None, :])
+
+    def put_sequence(self, b: int, idx, zb_k, zb_v, ref_k_bits, ref_v_bits, ref_inv_norm=None, t0: int = 0,
+                     chunk: int = 16384):
+        """Copy token-major arrays of sequence b (tokens t0..t0+n-1; references 0..n_ref-1) into the pools."""
+        torch = self.torch
+        n = idx.shape[0]
+        for c0 in range(0, n, chunk):
+            c1 = min(n, c0 + chunk)
+            for stream, zb in enumerate((zb_k, zb_v)[: self.layout.n_streams]):
+                ii = torch.from_numpy(self._latent_index(b, t0 + c0, t0 + c1, stream).ravel()).to(self.device)
+                vv = torch.from_numpy(np.ascontiguousarray(zb[c0:c1]).view(np.int16).ravel()).to(self.device)
+                self.latent_pool[ii] = vv
+            ii = torch.from_numpy(self._idx_index(b, t0 + c0, t0 + c1).ravel()).to(self.device)
+            self.idx_pool[ii] = torch.from_numpy(np.ascontiguousarray(idx[c0:c1], dtype=np.int32).ravel()).to(self.device)
+        if ref_k_bits is not None:
+            nr = ref_k_bits.shape[0]
+            for c0 in range(0, nr, chunk):
+                c1 = min(nr, c0 + chunk)
+                for kv, bits in enumerate((ref_k_bits, ref_v_bits)):
+                    ii = torch.from_numpy(self._ref_index(b, c0, c1, kv).ravel()).to(self.device)
+                    self.ref_pool[ii] = torch.from_numpy(
+                        np.ascontiguousarray(bits[c0:c1]).view(np.int16).ravel()).to(self.device)
+            if ref_inv_norm is not None:
+                slot = self.ref_tables_host[b, :nr].astype(np.int64)
+                ii = (np.arange(self.dims.n_kv_heads)[None, :] * self.layout.ref_norm_head_stride + slot[:, None])
+                self.ref_inv_norm[torch.from_numpy(ii.ravel()).to(self.device)] = \
+                    torch.from_numpy(np.ascontiguousarray(ref_inv_norm, dtype=np.float32).ravel()).to(self.device)
+
+    def get_sequence(self, b: int, t0: int, t1: int):
+        """Token-major copies (numpy) of tokens t0..t1-1 of sequence b: idx, zb_k, zb_v."""
+        torch = self.torch
+        out = []
+        ii = torch.from_numpy(self._idx_index(b, t0, t1).ravel()).to(self.device)
+        idx = self.idx_pool[ii].cpu().numpy().reshape(t1 - t0, self.dims.n_kv_heads)
+        for stream in range(self.layout.n_streams):
+            ii = torch.from_numpy(self._latent_index(b, t0, t1, stream).ravel()).to(self.device)
+            out.append(self.latent_pool[ii].cpu().numpy().view(np.uint16)
+                       .reshape(t1 - t0, self.dims.n_kv_heads, self.dims.rank))
+        if len(out) == 1:
+            out.append(out[0])
+        return idx, out[0], out[1]
+
+    def get_refs(self, b: int, n_ref: int):
+        torch = self.torch
+        res = []
+        for kv in range(2):
+            ii = torch.from_numpy(self._ref_index(b, 0, n_ref, kv).ravel()).to(self.device)
+            res.append(self.ref_pool[ii].cpu().numpy().view(np.uint16)
+                       .reshape(n_ref, self.dims.n_kv_heads, self.dims.head_dim))
+        slot = self.ref_tables_host[b, :n_ref].astype(np.int64)
+        ii = (np.arange(self.dims.n_kv_heads)[None, :] * self.layout.ref_norm_head_stride + slot[:, None])
+        nrm = self.ref_inv_norm[torch.from_numpy(ii.ravel()).to(self.device)].cpu().numpy() \
+            .reshape(n_ref, self.dims.n_kv_heads)
+        return res[0], res[1], nrm
+
+    # -- calls ------------------------------------------------------------------------------------
+    def compress(self, w_down_k, w_down_v, k_new, v_new, cu_new_host, len_before_host, stream=None):
+        torch = self.torch
+        cu = torch.tensor(np.asarray(cu_new_host, dtype=np.int32), device=self.device)
+        lb = torch.tensor(np.asarray(len_before_host, dtype=np.int32), device=self.device)
+        return B.compress(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
+                          self.ref_inv_norm, self.block_tables, self.ref_tables, w_down_k, w_down_v, k_new,
+                          v_new, cu, cu_new_host, lb, len_before_host, self.compress_ws, stream)
+
+    def decode_attn(self, w_up_k, w_up_v, q, seq_lens_host, scale, out=None, lse=None, seq_lens=None,
+                    stream=None):
+        torch = self.torch
+        if seq_lens is None:
+            seq_lens = torch.tensor(np.asarray(seq_lens_host, dtype=np.int32), device=self.device)
+        if out is None:
+            out = torch.empty_like(q)
+        B.decode_attn(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
+                      self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host, scale,
+                      out, lse, self.decode_ws, stream)
+        return out

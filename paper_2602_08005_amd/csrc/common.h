@@ -1,0 +1,99 @@
+// Shared device/host declarations of the DeltaKV gfx950 kernels (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "deltakv.h"
+
+namespace dkv {
+
+constexpr int kWave = 64;
+constexpr int kHeadDim = 128;
+constexpr int kPage = 16;          // tokens per page
+constexpr int kRefChunk = 256;     // reference ordinals handled by one block of the per-reference kernels
+constexpr int kMaxSplits = 16;     // upper bound on token-range splits of one (sequence, kv-head)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// Softmax weights are 2^(x - m_ref - kExpBias) with m_ref the largest per-reference score; every
+// reference token is itself attended with a zero latent, so the true maximum is >= m_ref and the
+// weights cannot all underflow.  The bias leaves 2^(127-kExpBias) of headroom above m_ref.
+constexpr float kExpBias = 64.0f;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+__host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+__host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+__host__ __device__ inline int padded_group(int g) { return (g + 3) & ~3; }
+
+// Token-range split s of a sequence with n_pages pages: pages [p0, p1).  The same arithmetic is used
+// by the streaming kernel (which owns the range) and by the kernels that consume its partial results.
+struct SplitPlan {
+  int n_splits;   // splits actually used by this sequence (<= grid's split count)
+  int per;        // pages per split
+};
+__host__ __device__ inline SplitPlan plan_splits(int n_pages, int max_splits, int pages_per_split) {
+  SplitPlan sp;
+  int want = ceil_div(n_pages, pages_per_split);
+  sp.n_splits = want < 1 ? 1 : (want > max_splits ? max_splits : want);
+  sp.per = ceil_div(n_pages, sp.n_splits);
+  return sp;
+}
+// Number of reference ordinals that tokens [0, end_tok) can point at.
+__host__ __device__ inline int refs_below(int end_tok, int stride) { return ceil_div(end_tok, stride); }
+
+// ---- decode workspace carving (host computes, kernels receive pointers) -------------------------
+struct DecodeWs {
+  int64_t status;   // int32[4]   bit 0: a logit left the range the biased exponent can hold
+  int64_t qlat;     // bf16 [2][B][Hq][R]         (W_uK q) * scale * log2(e), split into bf16 hi + lo parts
+  int64_t sref;     // fp32 [B][Hkv][n_ref_max][Gp]  per-reference scores, log2 units
+  int64_t cmax;     // fp32 [B][Hkv][n_chunk_max][Gp] per-chunk maxima of sref
+  int64_t lpart;    // fp32 [B][Hkv][S][Gp]
+  int64_t xpart;    // fp32 [B][Hkv][S][Gp]          largest exponent argument seen
+  int64_t accpart;  // fp32 [B][Hkv][S][Gp][R]
+  int64_t opart;    // fp32 [B][Hkv][n_chunk_max][Gp][128]
+  int64_t wpart;    // fp32 [B][Hkv][S][n_ref_max][Gp]
+  int64_t total;
+};
+inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_ref_max, int splits) {
+  const int64_t G = d.n_q_heads / d.n_kv_heads, Gp = padded_group((int)G), R = d.rank;
+  const int64_t BH = batch * d.n_kv_heads, nch = ceil_div64(n_ref_max, kRefChunk);
+  DecodeWs w;
+  int64_t o = 0;
+  auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
+  w.status = take(16);
+  w.qlat = take(2 * batch * d.n_q_heads * R * 2);
+  w.sref = take(BH * n_ref_max * Gp * 4);
+  w.cmax = take(BH * nch * Gp * 4);
+  w.lpart = take(BH * splits * Gp * 4);
+  w.xpart = take(BH * splits * Gp * 4);
+  w.accpart = take(BH * splits * Gp * R * 4);
+  w.opart = take(BH * nch * Gp * kHeadDim * 4);
+  w.wpart = take(BH * splits * n_ref_max * Gp * 4);
+  w.total = o;
+  return w;
+}
+
+// Records which HIP call failed (shown by deltakv_last_error_detail) and passes the code through.
+hipError_t note_hip_error(hipError_t e, const char* what);
+// Largest dynamic LDS a block may ask for on the current device, bytes.
+size_t device_lds_limit();
+
+#ifdef __HIPCC__
+__device__ inline float bf16lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
+__device__ inline uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline uint32_t pack_bf16(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+__device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+#endif
+
+}  // namespace dkv

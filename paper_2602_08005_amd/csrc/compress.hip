@@ -1,0 +1,478 @@
+// Residual compression of new tokens into the DeltaKV cache, gfx950.
+//
+// Section 4.1: reference set T = {t : t mod s = 0, t < i}; retrieval of the nearest reference
+// (here top-1 by cosine over the per-head vector K||V, lowest ordinal on ties); appendix B.2
+// "lifecycle management": residual against the assigned reference -> down-projection -> write to the
+// latent pool; appendix B.3: the reference search is a dense matrix product.
+//
+// Three kernels per call:
+//   admit_refs     : new tokens at multiples of s are copied raw into the reference pool, with 1/||K||V||
+//   sim_top2       : MFMA GEMM [new tokens x 256] . [references x 256]^T per kv-head with a fused
+//                    epilogue that scales by the reference's inverse norm, applies the causal candidate
+//                    mask and keeps (best, second best, arg best) per token -- scores never leave the chip
+//   select_project : merges reference-range splits, re-scores in fp64 every token whose two best fp32
+//                    scores are closer than the fp32 error bound (so the stored ordinal is the exact
+//                    arg-max), forms the residual in fp32, splits it into bf16 hi+lo parts, projects with
+//                    W_down on MFMA and writes bf16 latents + ordinals into the token's page
+#include "common.h"
+#include "launch.h"
+
+namespace dkv {
+
+__device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // largest b with cu[b] <= n
+  int lo = 0, hi = batch - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (cu[mid] <= n) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// ------------------------------------------------------------------------------------------------
+// admit_refs: one wave per (new token, kv-head); grid (ceil(n_new*Hkv/4)), 256 threads.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int l = threadIdx.x & 63;
+  if (item >= P.n_new_total * P.Hkv) return;
+  const int n = item / P.Hkv, h = item % P.Hkv;
+  const int b = find_seq(P.cu_new, P.batch, n);
+  const int pos = P.len_before[b] + (n - P.cu_new[b]);
+  if (pos % P.stride != 0) return;
+  const int ord = pos / P.stride;
+  if (ord >= P.rt_stride) return;
+  const int slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
+  const uint32_t kx = reinterpret_cast<const uint32_t*>(P.k_new + ((int64_t)n * P.Hkv + h) * kHeadDim)[l];
+  const uint32_t vx = reinterpret_cast<const uint32_t*>(P.v_new + ((int64_t)n * P.Hkv + h) * kHeadDim)[l];
+  uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+  reinterpret_cast<uint32_t*>(rk)[l] = kx;
+  reinterpret_cast<uint32_t*>(rk + P.ref_kv_stride)[l] = vx;
+  float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
+  if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// sim_top2: grid (tiles_max, NS, B*Hkv), 256 threads = 4 waves, wave tile (16*RB) tokens x 64 references.
+// ------------------------------------------------------------------------------------------------
+constexpr int kNT = 64;                 // references per LDS tile
+constexpr int kRowPad = 264;            // bf16 elements per staged reference row (256 + 8: shifts banks)
+
+struct Top2 {
+  float best, second;
+  int idx;
+};
+__device__ inline void top2_push(Top2& t, float v, int j) {   // strict '>' keeps the earliest ordinal
+  const bool gt = v > t.best;
+  t.second = __builtin_amdgcn_fmed3f(t.best, t.second, v);
+  t.idx = gt ? j : t.idx;
+  t.best = fmaxf(t.best, v);
+}
+__device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
+  const bool take = (ob > a.best) || (ob == a.best && oi >= 0 && (a.idx < 0 || oi < a.idx));
+  const float lo = fminf(a.best, ob);
+  a.second = fmaxf(fmaxf(a.second, os), lo);
+  a.best = fmaxf(a.best, ob);
+  a.idx = take ? oi : a.idx;
+}
+
+template <int RB>
+__global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
+  constexpr int WM = 16 * RB, MT = 4 * WM;
+  extern __shared__ uint16_t lds_raw[];
+  float* nrm = reinterpret_cast<float*>(lds_raw + 2 * kNT * kRowPad);   // [2][kNT]
+
+  const int tt = blockIdx.x, split = blockIdx.y;
+  const int b = blockIdx.z / P.Hkv, h = blockIdx.z % P.Hkv;
+  const int n_new = P.cu_new[b + 1] - P.cu_new[b];
+  if (tt * MT >= n_new) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int lb = P.len_before[b];
+  const int rows_valid = min(MT, n_new - tt * MT);
+  const int pos_last = lb + tt * MT + rows_valid - 1;
+  const int ncand_tile = min(refs_below(pos_last, P.stride), P.rt_stride);   // ordinals any row may use
+  // this split's reference range, in whole tiles
+  const int tiles_all = ceil_div(ncand_tile, kNT);
+  const int tiles_per = ceil_div(tiles_all, P.NS);
+  const int t_begin = split * tiles_per, t_end = min(tiles_all, t_begin + tiles_per);
+
+  // A operands: this wave's token rows, K (kk 0..3) then V (kk 4..7)
+  bf16x8 a[RB][8];
+  const int row0 = tt * MT + w * WM;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = row0 + rb * 16 + ln;
+    const bool ok = r < n_new;
+    const int64_t n = P.cu_new[b] + (ok ? r : 0);
+    const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
+    const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 x = *reinterpret_cast<const uint4*>(kr + (4 * kk + lg) * 8);
+      uint4 y = *reinterpret_cast<const uint4*>(vr + (4 * kk + lg) * 8);
+      if (!ok) { x = make_uint4(0, 0, 0, 0); y = x; }
+      a[rb][kk] = __builtin_bit_cast(bf16x8, x);
+      a[rb][4 + kk] = __builtin_bit_cast(bf16x8, y);
+    }
+  }
+  Top2 best[RB][4];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) best[rb][i] = Top2{-INFINITY, -INFINITY, -1};
+
+  const uint16_t* refk = P.ref + (int64_t)h * P.ref_head_stride;
+  const uint16_t* refv = refk + P.ref_kv_stride;
+  const float* rnorm = P.ref_inv_norm + (int64_t)h * P.ref_norm_head_stride;
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+
+  // stage reference tile `t` into buffer `buf`: 64 rows x 32 pieces of 16 bytes, 8 pieces per thread
+  auto stage_load = [&](int t, uint4 (&regs)[8], float& nr) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int q = tid + 256 * i, row = q >> 5, c16 = q & 31;
+      const int j = t * kNT + row;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (j < ncand_tile) {
+        const int slot = clampi(rtab[j], 0, (int)P.n_ref_slots - 1);
+        const uint16_t* src = (c16 < 16 ? refk : refv) + (int64_t)slot * kHeadDim + (c16 & 15) * 8;
+        v = *reinterpret_cast<const uint4*>(src);
+      }
+      regs[i] = v;
+    }
+    nr = 0.f;
+    if (tid < kNT) {
+      const int j = t * kNT + tid;
+      if (j < ncand_tile) nr = rnorm[clampi(rtab[j], 0, (int)P.n_ref_slots - 1)];
+    }
+  };
+  auto stage_store = [&](int buf, const uint4 (&regs)[8], float nr) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int q = tid + 256 * i, row = q >> 5, c16 = q & 31;
+      *reinterpret_cast<uint4*>(lds_raw + (buf * kNT + row) * kRowPad + c16 * 8) = regs[i];
+    }
+    if (tid < kNT) nrm[buf * kNT + tid] = nr;
+  };
+
+  if (t_begin < t_end) {
+    uint4 regs[8];
+    float nr;
+    stage_load(t_begin, regs, nr);
+    stage_store(0, regs, nr);
+    __syncthreads();
+    for (int t = t_begin; t < t_end; ++t) {
+      const int buf = (t - t_begin) & 1;
+      const bool more = t + 1 < t_end;
+      if (more) stage_load(t + 1, regs, nr);
+      float4v acc[RB][4];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = float4v{0.f, 0.f, 0.f, 0.f};
+      const uint16_t* tb = lds_raw + buf * kNT * kRowPad;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) {
+          const bf16x8 bop = *reinterpret_cast<const bf16x8*>(tb + (cb * 16 + ln) * kRowPad + (4 * kk + lg) * 8);
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb)
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk], bop, acc[rb][cb], 0, 0, 0);
+        }
+      }
+      // epilogue: lane holds token rows 4*lg+i (per rb) of reference column cb*16+ln
+      const int jt0 = t * kNT;
+      const int pos_first = lb + row0;                       // smallest position in this wave's rows
+      const bool full = (jt0 + kNT - 1) * P.stride < pos_first && (jt0 + kNT) <= ncand_tile;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const int j = jt0 + cb * 16 + ln;
+        const float inv = nrm[buf * kNT + cb * 16 + ln];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float v = acc[rb][cb][i] * inv;
+            if (!full) {
+              const int pos = lb + row0 + rb * 16 + 4 * lg + i;
+              const bool ok = (int64_t)j * P.stride < pos && j < ncand_tile;
+              v = ok ? v : -INFINITY;
+            }
+            top2_push(best[rb][i], v, j);
+          }
+      }
+      if (more) stage_store(buf ^ 1, regs, nr);
+      __syncthreads();
+    }
+  }
+  // merge the 16 column lanes of every row; ties go to the lower ordinal
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Top2 t = best[rb][i];
+      if (t.best == -INFINITY) t.idx = -1;
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) {
+        const float ob = __shfl_xor(t.best, o), os = __shfl_xor(t.second, o);
+        const int oi = __shfl_xor(t.idx, o);
+        top2_merge(t, ob, os, oi);
+      }
+      const int r = row0 + rb * 16 + 4 * lg + i;
+      if (ln == 0 && r < n_new) {
+        float4 o;
+        o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = 0.f;
+        const int64_t n = P.cu_new[b] + r;
+        *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// select_project: grid (page_tiles_max, B), 256 threads; wave w handles kv-heads w, w+4, ...
+// A wave owns one page of one sequence: lane (ln, lg) <-> token slot ln of the page, 8-wide chunk.
+// ------------------------------------------------------------------------------------------------
+constexpr int kWPad = 136;   // bf16 elements per staged W_down^T row (128 + 8)
+
+template <int R>
+__global__ __launch_bounds__(256) void k_select_project(CompressParams P) {
+  constexpr int NB = R / 16;
+  extern __shared__ uint16_t wlds[];   // [2][R][kWPad]: W_dK^T, W_dV^T
+  const int b = blockIdx.y;
+  const int lb = P.len_before[b];
+  const int n_new = P.cu_new[b + 1] - P.cu_new[b];
+  const int la = lb + n_new;
+  const int page_first = lb / kPage;
+  const int lp = page_first + blockIdx.x;         // logical page of the sequence
+  if (n_new <= 0 || lp * kPage >= la) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  // stage W_down^T (both streams): element (c, d) <- w_down[d][c]
+  for (int i = tid; i < 2 * R * kHeadDim; i += 256) {
+    const int st = i / (R * kHeadDim), rem = i % (R * kHeadDim), d = rem / R, c = rem % R;
+    wlds[(st * R + c) * kWPad + d] = (st ? P.w_down_v : P.w_down_k)[d * R + c];
+  }
+  __syncthreads();
+  const int pos = lp * kPage + ln;
+  const bool tok_ok = pos >= lb && pos < la;
+  const int64_t n = P.cu_new[b] + (tok_ok ? pos - lb : 0);
+  const bool is_ref = (pos % P.stride) == 0;
+  int page = P.block_tables[(int64_t)b * P.bt_stride + min(lp, P.bt_stride - 1)];
+  page = clampi(page, 0, (int)P.n_pages_pool - 1);
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+
+  for (int h = w; h < P.Hkv; h += 4) {
+    const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
+    const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+    uint4 xk[4], xv[4];
+    float ss = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      xk[kk] = *reinterpret_cast<const uint4*>(kr + (4 * kk + lg) * 8);
+      xv[kk] = *reinterpret_cast<const uint4*>(vr + (4 * kk + lg) * 8);
+      const uint32_t u[8] = {xk[kk].x, xk[kk].y, xk[kk].z, xk[kk].w, xv[kk].x, xv[kk].y, xv[kk].z, xv[kk].w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += bf16lo(u[e]) * bf16lo(u[e]) + bf16hi(u[e]) * bf16hi(u[e]);
+    }
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    const float na = sqrtf(ss);
+    // merge the reference-range splits (ascending ranges: strict '>' keeps the lowest ordinal)
+    float bb = -INFINITY, b2 = -INFINITY;
+    int bi = -1;
+    if (tok_ok && !is_ref) {
+      const float4* pp = reinterpret_cast<const float4*>(P.part) + (n * P.Hkv + h) * P.NS;
+      for (int s = 0; s < P.NS; ++s) {
+        const float4 o = pp[s];
+        const int oi = __float_as_int(o.z);
+        if (oi < 0) continue;
+        if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
+        else b2 = fmaxf(b2, o.x);
+      }
+    }
+    int ord = is_ref ? pos / P.stride : bi;
+    // fp32 scores carry an error of at most ~256 * 2^-24 of |a||b|; closer pairs are re-scored in fp64
+    bool amb = tok_ok && !is_ref && (bi < 0 || !(bb - b2 > 1e-4f * na));
+    uint64_t todo = __ballot(amb && lg == 0);
+    while (todo) {
+      const int src = __ffsll((unsigned long long)todo) - 1;   // lane (ln = src, lg = 0)
+      todo &= todo - 1;
+      const int spos = lp * kPage + src;
+      const int64_t sn = P.cu_new[b] + (spos - lb);
+      const int ncand = min(refs_below(spos, P.stride), P.rt_stride);
+      const uint16_t* ak = P.k_new + (sn * P.Hkv + h) * kHeadDim;
+      const uint16_t* av = P.v_new + (sn * P.Hkv + h) * kHeadDim;
+      double aa = 0.0;
+      for (int d = 0; d < kHeadDim; ++d) {
+        const double x = (double)bf16lo(ak[d]), y = (double)bf16lo(av[d]);
+        aa += x * x + y * y;
+      }
+      const double dna = sqrt(aa);
+      double cbest = -1e300;
+      int jbest = 0x7fffffff;
+      for (int j = l; j < ncand; j += 64) {
+        const int slot = clampi(rtab[j], 0, (int)P.n_ref_slots - 1);
+        const uint16_t* bk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+        const uint16_t* bv = bk + P.ref_kv_stride;
+        double dot = 0.0, nb2 = 0.0;
+        for (int d = 0; d < kHeadDim; ++d) {
+          const double x = (double)bf16lo(bk[d]), y = (double)bf16lo(bv[d]);
+          dot += (double)bf16lo(ak[d]) * x + (double)bf16lo(av[d]) * y;
+          nb2 += x * x + y * y;
+        }
+        const double den = dna * sqrt(nb2);
+        const double c = den > 0.0 ? dot / den : 0.0;
+        if (c > cbest) { cbest = c; jbest = j; }
+      }
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const double oc = __shfl_xor(cbest, o);
+        const int oj = __shfl_xor(jbest, o);
+        if (oc > cbest || (oc == cbest && oj < jbest)) { cbest = oc; jbest = oj; }
+      }
+      if (ln == src) ord = jbest;
+    }
+    ord = clampi(ord, 0, P.rt_stride - 1);
+    // residual against the chosen raw reference, fp32 (exact for bf16 inputs), split into bf16 hi + lo
+    const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
+    const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+    const uint16_t* rv = rk + P.ref_kv_stride;
+    const bool zero = !tok_ok || is_ref;
+    bf16x8 res[2][4][2];   // [stream][kk][hi/lo]
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const uint4 x = st ? xv[kk] : xk[kk];
+        const uint4 y = *reinterpret_cast<const uint4*>((st ? rv : rk) + (4 * kk + lg) * 8);
+        const uint32_t xu[4] = {x.x, x.y, x.z, x.w}, yu[4] = {y.x, y.y, y.z, y.w};
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float r0 = bf16lo(xu[e]) - bf16lo(yu[e]), r1 = bf16hi(xu[e]) - bf16hi(yu[e]);
+          if (zero) { r0 = 0.f; r1 = 0.f; }
+          const uint32_t h0 = f32_to_bf16_bits(r0), h1 = f32_to_bf16_bits(r1);
+          hi[e] = h0 | (h1 << 16);
+          lo[e] = pack_bf16(r0 - __uint_as_float(h0 << 16), r1 - __uint_as_float(h1 << 16));
+        }
+        res[st][kk][0] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+        res[st][kk][1] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+      }
+    uint16_t* lat = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+    // stream 0 (scores-operand order): D^T[c][token], lane holds 4 consecutive c of token ln
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 wk = *reinterpret_cast<const bf16x8*>(wlds + (nb * 16 + ln) * kWPad + (4 * kk + lg) * 8);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk, res[0][kk][0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wk, res[0][kk][1], acc, 0, 0, 0);
+        if (P.joint) {
+          const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wlds + (R + nb * 16 + ln) * kWPad + (4 * kk + lg) * 8);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, res[1][kk][0], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, res[1][kk][1], acc, 0, 0, 0);
+        }
+      }
+      if (tok_ok) {
+        const int c = nb * 16 + 4 * lg;
+        uint2 o;
+        o.x = pack_bf16(acc[0], acc[1]);
+        o.y = pack_bf16(acc[2], acc[3]);
+        *reinterpret_cast<uint2*>(lat + ((c >> 3) * kPage + ln) * 8 + (c & 7)) = o;
+      }
+    }
+    if (!P.joint) {
+      // stream 1 (value-operand order): D[token][c], lane holds tokens 4*lg..4*lg+3 of column ln
+      uint16_t* latv = lat + P.latent_stream_stride;
+      const int t0 = lp * kPage + 4 * lg;                    // position of this lane's first token
+      const bool all4 = t0 >= lb && t0 + 3 < la;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 wv = *reinterpret_cast<const bf16x8*>(wlds + (R + nb * 16 + ln) * kWPad + (4 * kk + lg) * 8);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(res[1][kk][0], wv, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(res[1][kk][1], wv, acc, 0, 0, 0);
+        }
+        uint16_t* dst = latv + (nb * 64 + l) * 4;
+        if (all4) {
+          uint2 o;
+          o.x = pack_bf16(acc[0], acc[1]);
+          o.y = pack_bf16(acc[2], acc[3]);
+          *reinterpret_cast<uint2*>(dst) = o;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (t0 + i >= lb && t0 + i < la) dst[i] = (uint16_t)f32_to_bf16_bits(acc[i]);
+        }
+      }
+    }
+    if (tok_ok && lg == 0)
+      P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + ln] = ord;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host launcher
+// ------------------------------------------------------------------------------------------------
+template <int RB>
+static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
+  const size_t lds = 2 * kNT * kRowPad * 2 + 2 * kNT * 4;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<RB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(similarity kernel LDS)");
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_sim_top2<RB>), grid, dim3(256), lds, st, P);
+  return note_hip_error(hipGetLastError(), "launch of sim_top2");
+}
+
+template <int R>
+static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t st) {
+  const size_t lds = 2 * R * kWPad * 2;
+  static bool attr_set = false;
+  if (!attr_set && lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_select_project<R>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(projection kernel LDS)");
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_select_project<R>), grid, dim3(256), lds, st, P);
+  return note_hip_error(hipGetLastError(), "launch of select_project");
+}
+
+int sim_tile_rows(int rb) { return 64 * rb; }
+
+hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st) {
+  hipError_t e;
+  const int items = P.n_new_total * P.Hkv;
+  hipLaunchKernelGGL(k_admit_refs, dim3(ceil_div(items, 4)), dim3(256), 0, st, P);
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of admit_refs");
+  dim3 gs(tiles_max, P.NS, P.batch * P.Hkv);
+  switch (rb) {
+    case 1: e = launch_sim<1>(P, gs, st); break;
+    case 2: e = launch_sim<2>(P, gs, st); break;
+    case 4: e = launch_sim<4>(P, gs, st); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess) return e;
+  dim3 gp(page_tiles_max, P.batch);
+  switch (P.R) {
+    case 16: return launch_project<16>(P, gp, st);
+    case 32: return launch_project<32>(P, gp, st);
+    case 48: return launch_project<48>(P, gp, st);
+    case 64: return launch_project<64>(P, gp, st);
+    case 80: return launch_project<80>(P, gp, st);
+    case 96: return launch_project<96>(P, gp, st);
+    case 112: return launch_project<112>(P, gp, st);
+    case 128: return launch_project<128>(P, gp, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace dkv

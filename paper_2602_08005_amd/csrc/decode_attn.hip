@@ -1,0 +1,511 @@
+// Fused decode attention over the DeltaKV compressed cache, gfx950.
+//
+// Section 4.1 ("Reconstruction") defines KV_hat = f_d(z) + KV_ref; section 5.3 gives the bias-free
+// linear decoder f_d(z) = z W_u.  With a linear decoder the attention over reconstructed tokens
+//     logit_t = scale * q . (K_ref[idx_t] + z_K,t W_uK)
+//     out     = sum_t p_t (V_ref[idx_t] + z_V,t W_uV) / sum_t p_t
+// regroups exactly into
+//     logit_t = S_ref[idx_t] + (W_uK q) . z_K,t          S_ref[j] = scale * q . K_ref[j]
+//     out     = ( sum_j w_j V_ref[j] + (sum_t p_t z_V,t) W_uV ) / sum_t p_t ,  w_j = sum_{t: idx_t = j} p_t
+// so each raw reference is read once per step (not once per token that points at it) and the per-token
+// work is two small contractions against the latent streams.  Four kernels per call:
+//   ref_scores  : S_ref for every reference ordinal (MFMA, q x K_ref tiles), chunk maxima, W_uK q
+//   stream      : the HBM-bound pass over latents + indices; scores and the weighted latent sum on MFMA,
+//                 w_j accumulated in an LDS table with hardware float atomics, one partial set per split
+//   ref_values  : sum_j w_j V_ref[j] per reference chunk
+//   finalize    : merges splits/chunks, up-projects the latent sum through W_uV, normalises, writes bf16
+// All softmax weights use one fixed exponent offset per (sequence, q-head): m_ref = max_j S_ref[j].  A
+// reference token is cached with idx = own ordinal and z = 0, so its logit IS S_ref[j]; the true maximum
+// is therefore >= m_ref, partial sums from different waves/splits add without rescaling, and the sum of
+// weights is >= 2^-kExpBias > 0.
+#include "common.h"
+#include "launch.h"
+
+namespace dkv {
+
+
+__device__ inline int seq_len_of(const DecodeParams& P, int b) {
+  return clampi(P.seq_lens[b], 0, P.max_seq_len);
+}
+
+__device__ inline float wave16_max(float v) {   // max over the 16 lanes that share lane/16
+  v = fmaxf(v, __shfl_xor(v, 1));
+  v = fmaxf(v, __shfl_xor(v, 2));
+  v = fmaxf(v, __shfl_xor(v, 4));
+  v = fmaxf(v, __shfl_xor(v, 8));
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// ref_scores: grid (n_chunk_max, Hkv, B), 256 threads.  Each wave scores 16 references per MFMA step:
+// D[g][j] = sum_d q[g][d] K_ref[j][d].
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // the status word is cleared here rather than by a memset node, so that a caller may capture the call
+  if (chunk == 0 && h == 0 && b == 0 && threadIdx.x == 0) *P.status = 0;
+  const int L = seq_len_of(P, b);
+  const int n_ref = refs_below(L, P.stride);
+  const int j0 = chunk * kRefChunk;
+  if (j0 >= n_ref) return;
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63, ln = l & 15, lg = l >> 4;
+  __shared__ float red[4][16];
+
+  // A operand: q rows of this kv-head's group (rows >= G are zero)
+  bf16x8 qa[4];
+  {
+    const uint16_t* qrow = P.q + ((int64_t)b * P.Hq + (int64_t)h * P.G + (ln < P.G ? ln : 0)) * kHeadDim;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 v = *reinterpret_cast<const uint4*>(qrow + (4 * kk + lg) * 8);
+      if (ln >= P.G) v = make_uint4(0, 0, 0, 0);
+      qa[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;   // K half
+  float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+  for (int step = 0; step < kRefChunk / 64; ++step) {
+    const int jb = j0 + w * 64 + step * 16;
+    if (jb >= n_ref) break;
+    const int j = jb + ln;
+    const bool valid = j < n_ref;
+    int slot = P.ref_tables[(int64_t)b * P.rt_stride + (valid ? j : n_ref - 1)];
+    slot = clampi(slot, 0, (int)P.n_ref_slots - 1);
+    const uint16_t* krow = kbase + (int64_t)slot * kHeadDim;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 v = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, v), acc, 0, 0, 0);
+    }
+    // lane holds rows g = 4*lg + i of column j
+    float4 o;
+    o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
+    o.z = acc[2] * P.qk_scale_log2; o.w = acc[3] * P.qk_scale_log2;
+    if (valid && 4 * lg < P.Gp)
+      *reinterpret_cast<float4*>(P.sref + (bh * P.n_ref_max + j) * P.Gp + 4 * lg) = o;
+    if (valid) {
+      mx[0] = fmaxf(mx[0], o.x); mx[1] = fmaxf(mx[1], o.y);
+      mx[2] = fmaxf(mx[2], o.z); mx[3] = fmaxf(mx[3], o.w);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) mx[i] = wave16_max(mx[i]);
+  if (ln == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) red[w][4 * lg + i] = mx[i];
+  }
+  __syncthreads();
+  if (threadIdx.x < P.Gp) {
+    float m = fmaxf(fmaxf(red[0][threadIdx.x], red[1][threadIdx.x]), fmaxf(red[2][threadIdx.x], red[3][threadIdx.x]));
+    P.cmax[(bh * P.n_chunk_max + chunk) * P.Gp + threadIdx.x] = m;
+  }
+
+  // chunk 0, last wave: q_lat[g][c] = scale*log2e * sum_d q[g][d] W_uK[c][d], stored bf16
+  if (chunk == 0 && w == 3) {
+    for (int nb = 0; nb < P.R / 16; ++nb) {
+      const uint16_t* wrow = P.w_up_k + (int64_t)(nb * 16 + ln) * kHeadDim;
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        uint4 v = *reinterpret_cast<const uint4*>(wrow + (4 * kk + lg) * 8);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, v), acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int g = 4 * lg + i;
+        if (g < P.G) {
+          const float v = acc[i] * P.qk_scale_log2;
+          const uint32_t hi = f32_to_bf16_bits(v);
+          const int64_t at = ((int64_t)b * P.Hq + (int64_t)h * P.G + g) * P.R + nb * 16 + ln;
+          P.qlat[at] = (uint16_t)hi;
+          P.qlat[P.qlat_lo_offset + at] = (uint16_t)f32_to_bf16_bits(v - __uint_as_float(hi << 16));
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// stream: grid (S, Hkv, B), NW waves.  Dynamic LDS: [n_tab] w table, then small reduction buffers.
+// ------------------------------------------------------------------------------------------------
+template <int R>
+struct Tile {
+  static constexpr int NKK = (R + 31) / 32;
+  static constexpr int NB = R / 16;
+  uint4 zk[NKK];
+  uint2 zv[NB];
+  int4 id;
+  int nvalid;
+};
+
+template <int R, bool JOINT>
+__device__ inline void load_tile(const DecodeParams& P, int b, int h, int p, int L, int l, Tile<R>& t) {
+  const int lg = l >> 4;
+  int page = P.block_tables[(int64_t)b * P.bt_stride + p];
+  page = clampi(page, 0, (int)P.n_pages_pool - 1);
+  const uint16_t* base = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+#pragma unroll
+  for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
+    if (4 * kk + lg < R / 8)
+      t.zk[kk] = *reinterpret_cast<const uint4*>(base + (64 * kk + l) * 8);
+    else
+      t.zk[kk] = make_uint4(0, 0, 0, 0);
+  }
+  if (!JOINT) {
+    const uint16_t* vb = base + P.latent_stream_stride;
+#pragma unroll
+    for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (nb * 64 + l) * 4);
+  }
+  t.id = *reinterpret_cast<const int4*>(P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + lg * 4);
+  t.nvalid = L - p * kPage;
+}
+
+template <int R, int NW, bool JOINT>
+__global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
+  extern __shared__ float smem[];
+  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int L = seq_len_of(P, b);
+  if (L <= 0) return;
+  const int n_pages = ceil_div(L, kPage);
+  const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
+  if (s >= sp.n_splits) return;
+  const int p0 = s * sp.per, p1 = min(n_pages, p0 + sp.per);
+  if (p0 >= p1) return;
+  const int end_tok = min(L, p1 * kPage);
+  const int n_cov = refs_below(end_tok, P.stride);      // ordinals this split can touch
+  const int n_ref = refs_below(L, P.stride);
+  const int Gp = P.Gp, G = P.G;
+  const int n_tab = n_cov * Gp;
+  float* tab = smem;
+  float* accbuf = smem + ((n_tab + 3) & ~3);              // [Gp][R]
+  float* lbuf = accbuf + Gp * R;                          // [16]
+  float* xbuf = lbuf + 16;                                // [NW][16]
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  for (int i = tid; i < n_tab; i += NW * 64) tab[i] = 0.f;
+  for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
+
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const int gq = ln < Gp ? ln : Gp - 1;                   // column of the score table this lane reads
+  const bool ghead = ln < G;
+  // exponent offset for q-head g = ln: chunk maxima of the per-reference scores
+  float mref = -INFINITY;
+  {
+    const int nch = ceil_div(n_ref, kRefChunk);
+    for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
+  }
+  const float cinit = -(mref + kExpBias);
+  // B operand of the score product: (W_uK q) for head g = ln, latent chunk 4*kk + lg
+  // (stored as bf16 hi + lo parts, so that the latent part of the logit keeps fp32-like accuracy)
+  bf16x8 qb[Tile<R>::NKK], qbl[Tile<R>::NKK];
+  {
+    const uint16_t* qrow = P.qlat + ((int64_t)b * P.Hq + (int64_t)h * G + (ghead ? ln : 0)) * R;
+#pragma unroll
+    for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
+      uint4 v = make_uint4(0, 0, 0, 0), vl = v;
+      if (ghead && 4 * kk + lg < R / 8) {
+        v = *reinterpret_cast<const uint4*>(qrow + (4 * kk + lg) * 8);
+        vl = *reinterpret_cast<const uint4*>(qrow + P.qlat_lo_offset + (4 * kk + lg) * 8);
+      }
+      qb[kk] = __builtin_bit_cast(bf16x8, v);
+      qbl[kk] = __builtin_bit_cast(bf16x8, vl);
+    }
+  }
+  const float* srow = P.sref + bh * P.n_ref_max * Gp + gq;
+  __syncthreads();
+
+  float4v acc[Tile<R>::NB];
+#pragma unroll
+  for (int nb = 0; nb < Tile<R>::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+  float lsum = 0.f, xmax = -INFINITY;
+
+  auto gather = [&](Tile<R>& t, float (&sr)[4]) {
+    t.id.x = clampi(t.id.x, 0, n_cov - 1); t.id.y = clampi(t.id.y, 0, n_cov - 1);
+    t.id.z = clampi(t.id.z, 0, n_cov - 1); t.id.w = clampi(t.id.w, 0, n_cov - 1);
+    sr[0] = srow[t.id.x * Gp]; sr[1] = srow[t.id.y * Gp];
+    sr[2] = srow[t.id.z * Gp]; sr[3] = srow[t.id.w * Gp];
+  };
+  auto compute = [&](Tile<R>& t, const float (&sr)[4]) {
+    float4v d = {cinit, cinit, cinit, cinit};
+#pragma unroll
+    for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qbl[kk], d, 0, 0, 0);
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qb[kk], d, 0, 0, 0);
+    }
+    const int ids[4] = {t.id.x, t.id.y, t.id.z, t.id.w};
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool ok = ghead && (4 * lg + e < t.nvalid);
+      const float x = ok ? d[e] + sr[e] : -INFINITY;
+      xmax = fmaxf(xmax, x);
+      p[e] = __builtin_amdgcn_exp2f(x);
+      lsum += p[e];
+      if (ok) atomicAdd(&tab[ids[e] * Gp + ln], p[e]);
+    }
+    uint2 pk;
+    pk.x = pack_bf16(p[0], p[1]);
+    pk.y = pack_bf16(p[2], p[3]);
+    const short4v pa = __builtin_bit_cast(short4v, pk);
+    if (!JOINT) {
+      if (t.nvalid < kPage) {    // tail page: slots past the sequence end hold garbage
+#pragma unroll
+        for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+          const int left = t.nvalid - 4 * lg;   // valid tokens among this lane's four
+          if (left < 4) t.zv[nb].y &= left < 3 ? 0u : 0x0000ffffu;
+          if (left < 2) t.zv[nb].x &= left < 1 ? 0u : 0x0000ffffu;
+        }
+      }
+#pragma unroll
+      for (int nb = 0; nb < Tile<R>::NB; ++nb)
+        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(short4v, t.zv[nb]), acc[nb], 0, 0, 0);
+    }
+  };
+
+  // three-stage software pipeline over this wave's pages: loads two pages ahead, score gather one ahead
+  {
+    Tile<R> t0, t1, t2;
+    float s0[4], s1[4], s2[4];
+    int p = p0 + w;
+    if (p < p1) {
+      load_tile<R, JOINT>(P, b, h, p, L, l, t0);
+      if (p + NW < p1) load_tile<R, JOINT>(P, b, h, p + NW, L, l, t1);
+      gather(t0, s0);
+      // step(a, b, c): page p in a (scores gathered), p+NW in b (loaded), c free
+#define DKV_STEP(A, SA, B, SB, C)                                                  \
+      {                                                                             \
+        if (p + 2 * NW < p1) load_tile<R, JOINT>(P, b, h, p + 2 * NW, L, l, C);     \
+        if (p + NW < p1) gather(B, SB);                                             \
+        compute(A, SA);                                                             \
+        p += NW;                                                                    \
+        if (p >= p1) break;                                                         \
+      }
+      for (;;) {
+        DKV_STEP(t0, s0, t1, s1, t2)
+        DKV_STEP(t1, s1, t2, s2, t0)
+        DKV_STEP(t2, s2, t0, s0, t1)
+      }
+#undef DKV_STEP
+    }
+  }
+
+  // ---- block reduction of the per-wave partials -------------------------------------------------
+  lsum += __shfl_xor(lsum, 16);
+  lsum += __shfl_xor(lsum, 32);
+  xmax = fmaxf(xmax, __shfl_xor(xmax, 16));
+  xmax = fmaxf(xmax, __shfl_xor(xmax, 32));
+  if (l < 16) {
+    atomicAdd(&lbuf[l], lsum);
+    xbuf[w * 16 + l] = xmax;
+  }
+#pragma unroll
+  for (int nb = 0; nb < Tile<R>::NB; ++nb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int g = 4 * lg + i;
+      if (g < G) atomicAdd(&accbuf[g * R + nb * 16 + ln], acc[nb][i]);
+    }
+  __syncthreads();
+  const int64_t part = bh * P.S + s;
+  if (tid < Gp) {
+    P.lpart[part * Gp + tid] = lbuf[tid];
+    float xm = -INFINITY;
+    for (int ww = 0; ww < NW; ++ww) xm = fmaxf(xm, xbuf[ww * 16 + tid]);
+    P.xpart[part * Gp + tid] = xm;
+  }
+  for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i];
+  float* wp = P.wpart + part * P.n_ref_max * Gp;
+  for (int i = tid * 4; i < n_tab; i += NW * 64 * 4)
+    *reinterpret_cast<float4*>(wp + i) = *reinterpret_cast<const float4*>(tab + i);
+}
+
+// ------------------------------------------------------------------------------------------------
+// ref_values: grid (n_chunk_max, Hkv, B), 256 threads.  opart[chunk][g][d] = sum_{j in chunk} w_j[g] V_ref[j][d]
+// lane = (row-in-group l/16, 8-wide d chunk l%16); a wave reads four 256-byte V rows per load.
+// ------------------------------------------------------------------------------------------------
+template <int GP>
+__global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int L = seq_len_of(P, b);
+  const int n_ref = refs_below(L, P.stride);
+  const int j0 = chunk * kRefChunk;
+  if (j0 >= n_ref) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int n_pages = ceil_div(L, kPage);
+  const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;   // V half
+  __shared__ float red[4][GP][kHeadDim];
+
+  float acc[GP][8];
+#pragma unroll
+  for (int g = 0; g < GP; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+
+  for (int it = 0; it < kRefChunk / 16; ++it) {
+    const int j = j0 + w * (kRefChunk / 4) + it * 4 + lg;
+    if (j >= n_ref) continue;
+    int slot = P.ref_tables[(int64_t)b * P.rt_stride + j];
+    slot = clampi(slot, 0, (int)P.n_ref_slots - 1);
+    const uint4 v = *reinterpret_cast<const uint4*>(vbase + (int64_t)slot * kHeadDim + ln * 8);
+    float wj[GP];
+#pragma unroll
+    for (int g = 0; g < GP; ++g) wj[g] = 0.f;
+    for (int s = 0; s < sp.n_splits; ++s) {
+      const int p1 = min(n_pages, (s + 1) * sp.per);
+      if (s * sp.per >= p1) break;
+      const int cov = refs_below(min(L, p1 * kPage), P.stride);
+      if (j >= cov) continue;
+      const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
+#pragma unroll
+      for (int g4 = 0; g4 < GP; g4 += 4) {
+        const float4 t = *reinterpret_cast<const float4*>(wp + g4);
+        wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
+      }
+    }
+    const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const float lo = bf16lo(vv[e2]), hi = bf16hi(vv[e2]);
+#pragma unroll
+      for (int g = 0; g < GP; ++g) {
+        acc[g][2 * e2] += wj[g] * lo;
+        acc[g][2 * e2 + 1] += wj[g] * hi;
+      }
+    }
+  }
+  // sum the four row groups of the wave, then the four waves
+#pragma unroll
+  for (int g = 0; g < GP; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[g][e];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[g][e] = v;
+    }
+  if (lg == 0) {
+#pragma unroll
+    for (int g = 0; g < GP; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[w][g][ln * 8 + e] = acc[g][e];
+  }
+  __syncthreads();
+  float* op = P.opart + (bh * P.n_chunk_max + chunk) * GP * kHeadDim;
+  for (int i = tid; i < GP * kHeadDim; i += 256) {
+    const int g = i / kHeadDim, d = i % kHeadDim;
+    op[i] = red[0][g][d] + red[1][g][d] + red[2][g][d] + red[3][g][d];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// finalize: grid (Hkv, B), 128 threads (thread = output dim d).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
+  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int L = seq_len_of(P, b);
+  const int G = P.G, Gp = P.Gp, R = P.R;
+  if (L <= 0) {
+    for (int g = 0; g < G; ++g) {
+      P.out[((int64_t)b * P.Hq + (int64_t)h * G + g) * kHeadDim + d] = 0;
+      if (P.lse && d == 0) P.lse[(int64_t)b * P.Hq + h * G + g] = -INFINITY;
+    }
+    return;
+  }
+  __shared__ float zsum[128];
+  const int n_ref = refs_below(L, P.stride);
+  const int nch = ceil_div(n_ref, kRefChunk);
+  const int n_pages = ceil_div(L, kPage);
+  const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
+  int n_used = 0;
+  for (int s = 0; s < sp.n_splits; ++s)
+    if (s * sp.per < n_pages) n_used = s + 1;
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const uint16_t* wv = P.w_up_v;
+  for (int g = 0; g < G; ++g) {
+    float lsum = 0.f, xm = -INFINITY, mref = -INFINITY;
+    for (int s = 0; s < n_used; ++s) {
+      lsum += P.lpart[(bh * P.S + s) * Gp + g];
+      xm = fmaxf(xm, P.xpart[(bh * P.S + s) * Gp + g]);
+    }
+    for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
+    __syncthreads();
+    if (d < R) {
+      float a = 0.f;
+      for (int s = 0; s < n_used; ++s) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
+      zsum[d] = a;
+    }
+    __syncthreads();
+    float o = 0.f;
+    for (int c = 0; c < nch; ++c) o += P.opart[((bh * P.n_chunk_max + c) * Gp + g) * kHeadDim + d];
+    for (int c = 0; c < R; ++c) o += zsum[c] * bf16lo(wv[(int64_t)c * kHeadDim + d]);
+    const float res = o / lsum;
+    P.out[((int64_t)b * P.Hq + (int64_t)h * G + g) * kHeadDim + d] = (uint16_t)f32_to_bf16_bits(res);
+    if (d == 0) {
+      if (P.lse) P.lse[(int64_t)b * P.Hq + h * G + g] = (mref + kExpBias + __log2f(lsum)) * kLn2;
+      // exponent arguments above ~60 (relative to the bias) risk overflow of the fp32 sums
+      if (!(xm < 60.0f) || !(lsum > 0.f) || !(lsum < INFINITY)) atomicOr(P.status, 1);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host launcher
+// ------------------------------------------------------------------------------------------------
+template <int R, int NW, bool JOINT>
+static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  static size_t attr_bytes = 48 * 1024;
+  if (lds > attr_bytes) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, JOINT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
+    if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
+    attr_bytes = device_lds_limit();
+  }
+  hipLaunchKernelGGL((k_stream<R, NW, JOINT>), grid, dim3(NW * 64), lds, st, P);
+  return note_hip_error(hipGetLastError(), "launch of the stream kernel");
+}
+
+template <int NW, bool JOINT>
+static hipError_t dispatch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  switch (P.R) {
+    case 16: return launch_stream<16, NW, JOINT>(P, grid, lds, st);
+    case 32: return launch_stream<32, NW, JOINT>(P, grid, lds, st);
+    case 48: return launch_stream<48, NW, JOINT>(P, grid, lds, st);
+    case 64: return launch_stream<64, NW, JOINT>(P, grid, lds, st);
+    case 80: return launch_stream<80, NW, JOINT>(P, grid, lds, st);
+    case 96: return launch_stream<96, NW, JOINT>(P, grid, lds, st);
+    case 112: return launch_stream<112, NW, JOINT>(P, grid, lds, st);
+    case 128: return launch_stream<128, NW, JOINT>(P, grid, lds, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw) {
+  return (size_t)(((n_ref_max * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
+}
+
+hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st) {
+  hipError_t e;
+  dim3 gchunk(P.n_chunk_max, P.Hkv, batch);
+  hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
+  dim3 gs(P.S, P.Hkv, batch);
+  if (P.joint) return hipErrorInvalidValue;   // JOINT streaming kernel: not built yet
+  e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
+  if (e != hipSuccess) return e;
+  switch (P.Gp) {
+    case 4: hipLaunchKernelGGL(k_ref_values<4>, gchunk, dim3(256), 0, st, P); break;
+    case 8: hipLaunchKernelGGL(k_ref_values<8>, gchunk, dim3(256), 0, st, P); break;
+    case 12: hipLaunchKernelGGL(k_ref_values<12>, gchunk, dim3(256), 0, st, P); break;
+    case 16: hipLaunchKernelGGL(k_ref_values<16>, gchunk, dim3(256), 0, st, P); break;
+    default: return hipErrorInvalidValue;
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_values");
+  hipLaunchKernelGGL(k_finalize, dim3(P.Hkv, batch), dim3(128), 0, st, P);
+  return note_hip_error(hipGetLastError(), "launch of finalize");
+}
+
+}  // namespace dkv

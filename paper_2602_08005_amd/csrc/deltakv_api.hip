@@ -1,0 +1,337 @@
+// C ABI of libdeltakv: argument validation, layout arithmetic, workspace carving, launches.
+// See include/deltakv.h for the contract of every entry point.
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+#include "launch.h"
+
+using namespace dkv;
+
+namespace {
+
+int check_dims(const deltakv_dims* d) {
+  if (!d) return DELTAKV_E_INVALID_ARG;
+  if (d->n_kv_heads <= 0 || d->n_q_heads <= 0 || d->head_dim <= 0 || d->rank <= 0 || d->ref_stride <= 0 ||
+      d->page_tokens <= 0 || d->n_pages <= 0 || d->n_ref_slots <= 0)
+    return DELTAKV_E_INVALID_ARG;
+  if (d->latent_mode != DELTAKV_SPLIT && d->latent_mode != DELTAKV_JOINT) return DELTAKV_E_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads != 0) return DELTAKV_E_UNSUPPORTED;
+  if (d->n_q_heads / d->n_kv_heads > 16) return DELTAKV_E_UNSUPPORTED;
+  if (d->head_dim != kHeadDim || d->page_tokens != kPage) return DELTAKV_E_UNSUPPORTED;
+  if (d->rank % 16 != 0 || d->rank < 16 || d->rank > 128) return DELTAKV_E_UNSUPPORTED;
+  if (d->metric != DELTAKV_METRIC_COSINE) return DELTAKV_E_UNSUPPORTED;
+  if (d->n_pages > (1ll << 31) - 1 || d->n_ref_slots > (1ll << 31) - 1) return DELTAKV_E_UNSUPPORTED;
+  return DELTAKV_OK;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int device_cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+thread_local char g_detail[256] = "";
+
+}  // namespace
+
+namespace dkv {
+hipError_t note_hip_error(hipError_t e, const char* what) {
+  if (e != hipSuccess) snprintf(g_detail, sizeof(g_detail), "%s: %s", what, hipGetErrorString(e));
+  return e;
+}
+size_t device_lds_limit() {
+  static size_t lim = 0;
+  if (lim == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && n > 0)
+      lim = (size_t)n;
+    else
+      lim = 64 * 1024;
+  }
+  return lim;
+}
+}  // namespace dkv
+
+extern "C" {
+
+int deltakv_version(void) { return 1; }
+
+const char* deltakv_last_error_detail(void) { return g_detail; }
+
+const char* deltakv_strerror(int code) {
+  switch (code) {
+    case DELTAKV_OK: return "ok";
+    case DELTAKV_E_INVALID_ARG: return "invalid argument";
+    case DELTAKV_E_UNSUPPORTED: return "unsupported shape";
+    case DELTAKV_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case DELTAKV_E_HIP: return "HIP runtime error";
+  }
+  return "unknown error code";
+}
+
+int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t max_new_tokens,
+                         int64_t max_seq_len, deltakv_layout* out) {
+  int rc = check_dims(dims);
+  if (rc != DELTAKV_OK) return rc;
+  if (!out || max_batch <= 0 || max_new_tokens < 0 || max_seq_len <= 0) return DELTAKV_E_INVALID_ARG;
+  if (max_seq_len > (1ll << 30)) return DELTAKV_E_UNSUPPORTED;
+  memset(out, 0, sizeof(*out));
+  const int64_t H = dims->n_kv_heads, P = dims->page_tokens, R = dims->rank, D = dims->head_dim;
+  out->n_streams = dims->latent_mode == DELTAKV_JOINT ? 1 : 2;
+  out->alignment = 256;
+  out->latent_stream_stride = P * R;
+  out->latent_head_stride = out->n_streams * out->latent_stream_stride;
+  out->latent_page_stride = H * out->latent_head_stride;
+  out->latent_pool_bytes = dims->n_pages * out->latent_page_stride * 2;
+  out->idx_head_stride = P;
+  out->idx_page_stride = H * P;
+  out->idx_pool_bytes = dims->n_pages * out->idx_page_stride * 4;
+  out->ref_slot_stride = D;
+  out->ref_kv_stride = dims->n_ref_slots * D;
+  out->ref_head_stride = 2 * out->ref_kv_stride;
+  out->ref_pool_bytes = H * out->ref_head_stride * 2;
+  out->ref_norm_head_stride = dims->n_ref_slots;
+  out->ref_norm_pool_bytes = H * dims->n_ref_slots * 4;
+  const int64_t n_ref_max = ceil_div64(max_seq_len, dims->ref_stride);
+  out->decode_ws_bytes = plan_decode_ws(*dims, max_batch, n_ref_max, kMaxSplits).total;
+  out->compress_ws_bytes = plan_compress_ws(*dims, max_batch, max_new_tokens, n_ref_max).total;
+  return DELTAKV_OK;
+}
+
+int deltakv_latent_block_offsets(const deltakv_dims* dims, int32_t stream, int32_t* out) {
+  int rc = check_dims(dims);
+  if (rc != DELTAKV_OK) return rc;
+  if (!out || stream < 0 || stream > 1) return DELTAKV_E_INVALID_ARG;
+  if (stream == 1 && dims->latent_mode == DELTAKV_JOINT) return DELTAKV_E_INVALID_ARG;
+  const int P = dims->page_tokens, R = dims->rank;
+  for (int tok = 0; tok < P; ++tok)
+    for (int c = 0; c < R; ++c)
+      out[tok * R + c] = stream == 0 ? ((c / 8) * P + tok) * 8 + c % 8
+                                     : ((c / 16) * 64 + (tok / 4) * 16 + c % 16) * 4 + tok % 4;
+  return DELTAKV_OK;
+}
+
+double deltakv_keep_ratio(const deltakv_dims* dims) {
+  if (check_dims(dims) != DELTAKV_OK) return -1.0;
+  const double streams = dims->latent_mode == DELTAKV_JOINT ? 1.0 : 2.0;
+  const double raw = 2.0 * dims->head_dim * 2.0;
+  const double rec = streams * dims->rank * 2.0 + 4.0;
+  return (rec + (raw + 4.0) / dims->ref_stride) / raw;
+}
+
+int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                        const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                        int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                        const void* w_up_v, const void* q, const int32_t* seq_lens,
+                        const int32_t* seq_lens_host, int32_t batch, float scale, void* out, float* lse,
+                        void* workspace, int64_t ws_bytes, void* stream) {
+  int rc = check_dims(dims);
+  if (rc != DELTAKV_OK) return rc;
+  if (!lay || !latent_pool || !idx_pool || !ref_pool || !block_tables || !ref_tables || !w_up_k || !w_up_v ||
+      !q || !seq_lens || !seq_lens_host || !out || batch < 0 || bt_stride <= 0 || rt_stride <= 0 ||
+      !(scale == scale))
+    return DELTAKV_E_INVALID_ARG;
+  if (batch == 0) return DELTAKV_OK;
+  if (batch > 65535) return DELTAKV_E_UNSUPPORTED;
+  if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
+  if (!aligned(latent_pool, 16) || !aligned(idx_pool, 16) || !aligned(ref_pool, 16) || !aligned(q, 16) ||
+      !aligned(w_up_k, 16) || !aligned(w_up_v, 16))
+    return DELTAKV_E_INVALID_ARG;
+  int max_len = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_lens_host[b] < 0) return DELTAKV_E_INVALID_ARG;
+    if (seq_lens_host[b] > max_len) max_len = seq_lens_host[b];
+  }
+  const int P = dims->page_tokens, S = dims->ref_stride;
+  const int max_pages = ceil_div(max_len > 0 ? max_len : 1, P);
+  const int n_ref_max = ceil_div(max_len > 0 ? max_len : 1, S);
+  if (max_pages > bt_stride || n_ref_max > rt_stride) return DELTAKV_E_INVALID_ARG;
+  if ((int64_t)max_pages > dims->n_pages * 1ll || (int64_t)n_ref_max > dims->n_ref_slots * 1ll)
+    return DELTAKV_E_INVALID_ARG;
+  if (dims->latent_mode == DELTAKV_JOINT) return DELTAKV_E_UNSUPPORTED;   // JOINT streaming kernel: not built yet
+
+  const int G = dims->n_q_heads / dims->n_kv_heads, Gp = padded_group(G), R = dims->rank;
+  int nw = 8;
+  size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
+  const size_t kLdsLimit = device_lds_limit();
+  if (lds > kLdsLimit / 2) {   // one block per compute unit: give it more waves
+    nw = 16;
+    lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
+  }
+  if (lds > kLdsLimit) return DELTAKV_E_UNSUPPORTED;
+  int per_cu = (int)(kLdsLimit / lds);
+  const int wave_cap = 32 / nw;
+  if (per_cu > wave_cap) per_cu = wave_cap;
+  const int64_t slots = (int64_t)device_cu_count() * per_cu;
+  const int64_t pairs = (int64_t)batch * dims->n_kv_heads;
+  int splits = (int)ceil_div64(2 * slots, pairs);
+  const int split_cap = max_pages / 8 > 1 ? max_pages / 8 : 1;    // at least 8 pages per split
+  if (splits > split_cap) splits = split_cap;
+  if (splits > kMaxSplits) splits = kMaxSplits;
+  if (splits < 1) splits = 1;
+  DecodeWs ws = plan_decode_ws(*dims, batch, n_ref_max, splits);
+  while (ws.total > ws_bytes && splits > 1) {
+    --splits;
+    ws = plan_decode_ws(*dims, batch, n_ref_max, splits);
+  }
+  if (ws.total > ws_bytes) return DELTAKV_E_WORKSPACE;
+
+  DecodeParams Pm;
+  memset(&Pm, 0, sizeof(Pm));
+  Pm.latent = static_cast<const uint16_t*>(latent_pool);
+  Pm.idx = idx_pool;
+  Pm.ref = static_cast<const uint16_t*>(ref_pool);
+  Pm.block_tables = block_tables;
+  Pm.ref_tables = ref_tables;
+  Pm.seq_lens = seq_lens;
+  Pm.bt_stride = bt_stride;
+  Pm.rt_stride = rt_stride;
+  Pm.latent_page_stride = lay->latent_page_stride;
+  Pm.latent_head_stride = lay->latent_head_stride;
+  Pm.latent_stream_stride = lay->latent_stream_stride;
+  Pm.idx_page_stride = lay->idx_page_stride;
+  Pm.idx_head_stride = lay->idx_head_stride;
+  Pm.ref_head_stride = lay->ref_head_stride;
+  Pm.ref_kv_stride = lay->ref_kv_stride;
+  Pm.n_pages_pool = dims->n_pages;
+  Pm.n_ref_slots = dims->n_ref_slots;
+  Pm.w_up_k = static_cast<const uint16_t*>(w_up_k);
+  Pm.w_up_v = static_cast<const uint16_t*>(w_up_v);
+  Pm.q = static_cast<const uint16_t*>(q);
+  Pm.out = static_cast<uint16_t*>(out);
+  Pm.lse = lse;
+  Pm.Hkv = dims->n_kv_heads;
+  Pm.Hq = dims->n_q_heads;
+  Pm.G = G;
+  Pm.Gp = Gp;
+  Pm.R = R;
+  Pm.stride = S;
+  Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.max_seq_len = max_len;
+  Pm.n_ref_max = n_ref_max;
+  Pm.n_chunk_max = ceil_div(n_ref_max, kRefChunk);
+  Pm.S = splits;
+  Pm.pages_per_split = ceil_div(max_pages, splits);
+  Pm.qk_scale_log2 = scale * kLog2e;
+  char* wsb = static_cast<char*>(workspace);
+  Pm.status = reinterpret_cast<int32_t*>(wsb + ws.status);
+  Pm.qlat = reinterpret_cast<uint16_t*>(wsb + ws.qlat);
+  Pm.qlat_lo_offset = (int64_t)batch * dims->n_q_heads * R;
+  Pm.sref = reinterpret_cast<float*>(wsb + ws.sref);
+  Pm.cmax = reinterpret_cast<float*>(wsb + ws.cmax);
+  Pm.lpart = reinterpret_cast<float*>(wsb + ws.lpart);
+  Pm.xpart = reinterpret_cast<float*>(wsb + ws.xpart);
+  Pm.accpart = reinterpret_cast<float*>(wsb + ws.accpart);
+  Pm.opart = reinterpret_cast<float*>(wsb + ws.opart);
+  Pm.wpart = reinterpret_cast<float*>(wsb + ws.wpart);
+  hipError_t e = launch_decode(Pm, batch, nw, lds, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
+}
+
+int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
+                     void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
+                     const int32_t* ref_tables, int32_t rt_stride, const void* w_down_k, const void* w_down_v,
+                     const void* k_new, const void* v_new, const int32_t* cu_new, const int32_t* cu_new_host,
+                     const int32_t* len_before, const int32_t* len_before_host, int32_t batch, void* workspace,
+                     int64_t ws_bytes, void* stream) {
+  int rc = check_dims(dims);
+  if (rc != DELTAKV_OK) return rc;
+  if (!lay || !latent_pool || !idx_pool || !ref_pool || !ref_inv_norm || !block_tables || !ref_tables ||
+      !w_down_k || !w_down_v || !k_new || !v_new || !cu_new || !cu_new_host || !len_before ||
+      !len_before_host || batch < 0 || bt_stride <= 0 || rt_stride <= 0)
+    return DELTAKV_E_INVALID_ARG;
+  if (batch == 0) return DELTAKV_OK;
+  if (batch > 65535 / dims->n_kv_heads) return DELTAKV_E_UNSUPPORTED;
+  if (!aligned(latent_pool, 16) || !aligned(idx_pool, 16) || !aligned(ref_pool, 16) || !aligned(k_new, 16) ||
+      !aligned(v_new, 16) || !aligned(w_down_k, 2) || !aligned(w_down_v, 2))
+    return DELTAKV_E_INVALID_ARG;
+  if (cu_new_host[0] != 0) return DELTAKV_E_INVALID_ARG;
+  const int P = dims->page_tokens, S = dims->ref_stride;
+  int max_new = 0, page_tiles_max = 0;
+  int64_t tiles_total_rows = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t nb = (int64_t)cu_new_host[b + 1] - cu_new_host[b];
+    const int64_t lb = len_before_host[b];
+    if (nb < 0 || lb < 0 || lb + nb > (1ll << 30)) return DELTAKV_E_INVALID_ARG;
+    if (nb == 0) continue;
+    const int64_t la = lb + nb;
+    if (ceil_div64(la, P) > bt_stride || ceil_div64(la, S) > rt_stride) return DELTAKV_E_INVALID_ARG;
+    if (ceil_div64(la, P) > dims->n_pages || ceil_div64(la, S) > dims->n_ref_slots) return DELTAKV_E_INVALID_ARG;
+    if (nb > max_new) max_new = (int)nb;
+    const int pt = (int)(ceil_div64(la, P) - lb / P);
+    if (pt > page_tiles_max) page_tiles_max = pt;
+    tiles_total_rows += nb;
+  }
+  const int n_new_total = cu_new_host[batch];
+  if (n_new_total == 0) return DELTAKV_OK;
+  if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
+  const int rb = max_new >= 1024 ? 4 : (max_new >= 128 ? 2 : 1);
+  const int mt = sim_tile_rows(rb);
+  const int tiles_max = ceil_div(max_new, mt);
+  int64_t tiles_total = 0;
+  int64_t max_len_after = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t nb = (int64_t)cu_new_host[b + 1] - cu_new_host[b];
+    tiles_total += ceil_div64(nb, mt);
+    if (nb > 0 && len_before_host[b] + nb > max_len_after) max_len_after = len_before_host[b] + nb;
+  }
+  // spread the reference scan of small calls (decode append) over enough blocks to fill the chip
+  int64_t ns = ceil_div64(4ll * device_cu_count(), tiles_total * dims->n_kv_heads);
+  const int64_t ref_tiles = ceil_div64(ceil_div64(max_len_after, S), 64);
+  if (ns > ref_tiles) ns = ref_tiles;
+  if (ns > 64) ns = 64;
+  const int64_t per_split = (int64_t)n_new_total * dims->n_kv_heads * 16;
+  if (ns > ws_bytes / per_split) ns = ws_bytes / per_split;
+  if (ns < 1) return DELTAKV_E_WORKSPACE;
+  if (tiles_max > 65535 * 32768ll || page_tiles_max <= 0) return DELTAKV_E_UNSUPPORTED;
+
+  CompressParams Pm;
+  memset(&Pm, 0, sizeof(Pm));
+  Pm.latent = static_cast<uint16_t*>(latent_pool);
+  Pm.idx = idx_pool;
+  Pm.ref = static_cast<uint16_t*>(ref_pool);
+  Pm.ref_inv_norm = ref_inv_norm;
+  Pm.block_tables = block_tables;
+  Pm.ref_tables = ref_tables;
+  Pm.bt_stride = bt_stride;
+  Pm.rt_stride = rt_stride;
+  Pm.latent_page_stride = lay->latent_page_stride;
+  Pm.latent_head_stride = lay->latent_head_stride;
+  Pm.latent_stream_stride = lay->latent_stream_stride;
+  Pm.idx_page_stride = lay->idx_page_stride;
+  Pm.idx_head_stride = lay->idx_head_stride;
+  Pm.ref_head_stride = lay->ref_head_stride;
+  Pm.ref_kv_stride = lay->ref_kv_stride;
+  Pm.ref_norm_head_stride = lay->ref_norm_head_stride;
+  Pm.n_pages_pool = dims->n_pages;
+  Pm.n_ref_slots = dims->n_ref_slots;
+  Pm.w_down_k = static_cast<const uint16_t*>(w_down_k);
+  Pm.w_down_v = static_cast<const uint16_t*>(w_down_v);
+  Pm.k_new = static_cast<const uint16_t*>(k_new);
+  Pm.v_new = static_cast<const uint16_t*>(v_new);
+  Pm.cu_new = cu_new;
+  Pm.len_before = len_before;
+  Pm.batch = batch;
+  Pm.n_new_total = n_new_total;
+  Pm.Hkv = dims->n_kv_heads;
+  Pm.R = dims->rank;
+  Pm.stride = S;
+  Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.NS = (int)ns;
+  Pm.part = static_cast<float*>(workspace);
+  hipError_t e = launch_compress(Pm, rb, tiles_max, page_tiles_max, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
+}
+
+}  // extern "C"

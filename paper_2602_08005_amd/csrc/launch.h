@@ -1,0 +1,90 @@
+// Kernel parameter blocks and host launchers shared by the C ABI file and the kernel files.
+#pragma once
+#include "common.h"
+
+namespace dkv {
+
+struct DecodeParams {
+  // cache
+  const uint16_t* latent;
+  const int32_t* idx;
+  const uint16_t* ref;
+  const int32_t* block_tables;
+  const int32_t* ref_tables;
+  const int32_t* seq_lens;
+  int bt_stride, rt_stride;
+  int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
+  int64_t idx_page_stride, idx_head_stride;
+  int64_t ref_head_stride, ref_kv_stride;
+  int64_t n_pages_pool, n_ref_slots;
+  // weights / query / outputs
+  const uint16_t* w_up_k;
+  const uint16_t* w_up_v;
+  const uint16_t* q;
+  uint16_t* out;
+  float* lse;
+  // shape
+  int Hkv, Hq, G, Gp, R, stride, joint;
+  int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)
+  int n_ref_max, n_chunk_max;
+  int S, pages_per_split;   // split grid
+  float qk_scale_log2;      // scale * log2(e)
+  // workspace
+  int32_t* status;
+  uint16_t* qlat;
+  int64_t qlat_lo_offset;   // elements from the hi part to the lo part of qlat
+  float* sref;
+  float* cmax;
+  float* lpart;
+  float* xpart;
+  float* accpart;
+  float* opart;
+  float* wpart;
+};
+
+struct CompressParams {
+  uint16_t* latent;
+  int32_t* idx;
+  uint16_t* ref;
+  float* ref_inv_norm;
+  const int32_t* block_tables;
+  const int32_t* ref_tables;
+  int bt_stride, rt_stride;
+  int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
+  int64_t idx_page_stride, idx_head_stride;
+  int64_t ref_head_stride, ref_kv_stride, ref_norm_head_stride;
+  int64_t n_pages_pool, n_ref_slots;
+  const uint16_t* w_down_k;
+  const uint16_t* w_down_v;
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  const int32_t* cu_new;
+  const int32_t* len_before;
+  int batch, n_new_total;
+  int Hkv, R, stride, joint;
+  int NS;            // reference-range splits of the similarity search
+  float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), unused
+};
+
+struct CompressWs {
+  int64_t part;
+  int64_t total;
+};
+inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t max_batch, int64_t max_new_tokens, int64_t) {
+  CompressWs w;
+  w.part = 0;
+  w.total = align_up((max_new_tokens + 64 * max_batch) * d.n_kv_heads * 16, 256);
+  return w;
+}
+
+// Token rows per block of the similarity kernel for row-block factor rb (1, 2 or 4).
+int sim_tile_rows(int rb);
+// Enqueues the three compress kernels on `st`.
+hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st);
+
+// LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
+size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw);
+// Enqueues the four decode kernels on `st`.
+hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st);
+
+}  // namespace dkv

@@ -1,0 +1,53 @@
+"""Shared helpers of the GPU parity tests: build a case with the generator, compress it with the
+oracle, and place it in a PagedCache."""
+import numpy as np
+
+from oracle import deltakv_oracle as O
+from synthetic import generator as G
+
+f64 = O.bf16_bits_to_f64
+
+
+def dev_bits(bits):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+
+
+def out_f64(t):
+    return f64(t.detach().cpu().numpy().view(np.uint16))
+
+
+class Case:
+    """One sequence per entry of `lens`; raw K/V, oracle-compressed cache, projections."""
+
+    def __init__(self, seed, lens, Hkv=8, Hq=32, r=64, s=16, n_proto=64, joint=False, D=128):
+        self.lens, self.Hkv, self.Hq, self.r, self.s, self.D, self.joint = list(lens), Hkv, Hq, r, s, D, joint
+        self.W = G.make_projections(seed, D, r, joint=joint)
+        self.K, self.V, self.res = [], [], []
+        mode = O.JOINT if joint else O.SPLIT
+        for b, L in enumerate(self.lens):
+            K, V, _ = G.make_kv(seed + 17 * b, max(L, 1), Hkv, D, n_proto=n_proto)
+            K, V = K[:L], V[:L]
+            self.K.append(K)
+            self.V.append(V)
+            if L > 0:
+                self.res.append(O.compress(f64(K), f64(V), f64(self.W["w_down_k_bf16"]), f64(self.W["w_down_v_bf16"]),
+                                           s=s, mode=mode))
+            else:
+                self.res.append(None)
+        self.q = G.make_queries(seed, len(self.lens), Hq, D)
+
+    def oracle_decode(self, b, scale, q=None):
+        r = self.res[b]
+        qq = f64(self.q[b]) if q is None else q
+        return O.decode_attn_direct(qq, r["idx"], f64(r["zb_k"]), f64(r["zb_v"]), r["ref_k"], r["ref_v"],
+                                    f64(self.W["w_up_k_bf16"]), f64(self.W["w_up_v_bf16"]), scale)
+
+
+def check_attention(got, want, what=""):
+    """Spec bar: max-abs <= 2e-2; plus a relative L2 bar so that near-zero outputs cannot pass vacuously."""
+    err = float(np.max(np.abs(got - want)))
+    rel = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
+    assert err <= 2e-2, f"{what}: max-abs {err}"
+    assert rel <= 1e-2, f"{what}: relative L2 {rel}"
+    return err, rel

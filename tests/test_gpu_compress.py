@@ -1,0 +1,184 @@
+"""GPU parity of deltakv_compress against the CPU oracle: reference ordinals bit-exact (a different ordinal is
+accepted only where the oracle's own scores tie within 1e-6), latents equal to the oracle's bf16 latents to
+one bf16 ulp, raw references copied exactly."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16_ulp(x):
+    ax = np.maximum(np.abs(x), 2.0 ** -126)
+    return 2.0 ** (np.floor(np.log2(ax)) - 7)
+
+
+def _check_against_oracle(K, V, W, s, joint, idx, zk, zv, t0=0):
+    """idx/zk/zv: GPU results for tokens t0.. ; K, V: raw bits of the whole sequence."""
+    from oracle import deltakv_oracle as O
+    f = O.bf16_bits_to_f64
+    Kf, Vf = f(K), f(V)
+    mode = O.JOINT if joint else O.SPLIT
+    wdk, wdv = f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"])
+    ref = O.compress(Kf, Vf, wdk, wdv, s=s, mode=mode, start=t0)
+    diff = np.argwhere(idx != ref["idx"])
+    for (i, h) in diff:                      # allowed only on near-ties of the oracle's own scores
+        c_gpu = O.cosine_of(Kf, Vf, t0 + i, h, int(idx[i, h]), s)
+        assert c_gpu >= ref["cos"][i, h] - 1e-6, (i, h, idx[i, h], ref["idx"][i, h], c_gpu, ref["cos"][i, h])
+        assert idx[i, h] * s < t0 + i
+    # latents: recompute the oracle residual with the GPU's ordinal where it (legitimately) differs
+    z_k, z_v = ref["z_k"].copy(), ref["z_v"] if joint else ref["z_v"].copy()
+    for (i, h) in diff:
+        t = t0 + i
+        rk, rv = Kf[t, h] - Kf[idx[i, h] * s, h], Vf[t, h] - Vf[idx[i, h] * s, h]
+        if joint:
+            z_k[i, h] = rk @ wdk + rv @ wdv
+        else:
+            z_k[i, h], z_v[i, h] = rk @ wdk, rv @ wdv
+    for got, want in ((zk, z_k), (zv, z_v)):
+        g = f(got)
+        tol = _bf16_ulp(want) + 1e-6
+        bad = np.abs(g - O.f64_round_to_bf16(want)) > tol
+        assert not bad.any(), (np.argwhere(bad)[:5], g[bad][:5], want[bad][:5])
+    exact = np.mean(f(zk) == O.f64_round_to_bf16(z_k))
+    assert exact > 0.98, exact              # nearly all latents are the correctly rounded value
+    return len(diff)
+
+
+def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, n_proto=16, perm=None, Hq=None,
+                   capacity=0):
+    """Build sequences of lens_before+lens_new tokens; prefill `before` and then append `new` on the GPU."""
+    import torch
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    from tests.helpers import dev_bits
+    B = len(lens_new)
+    total = [a + b for a, b in zip(lens_before, lens_new)]
+    max_len = max(max(total), 1, capacity)
+    pps, rps = -(-max_len // 16), -(-max_len // s)
+    n_pages, n_slots = B * pps + 3, B * rps + 3
+    page_ids = ref_slots = None
+    if perm is not None:
+        pp, rp = G.page_permutation(perm, B * pps, n_pages), G.page_permutation(perm + 1, B * rps, n_slots)
+        page_ids = [pp[b * pps:(b + 1) * pps] for b in range(B)]
+        ref_slots = [rp[b * rps:(b + 1) * rps] for b in range(B)]
+    dims = dk.make_dims(Hkv, Hq or 4 * Hkv, r, n_pages, n_slots, ref_stride=s, latent_mode=dk.JOINT if joint else dk.SPLIT)
+    cache = dk.PagedCache(dims, B, max(sum(lens_new), sum(lens_before), 1), max_len, page_ids=page_ids, ref_slots=ref_slots)
+    cache.latent_pool.fill_(0x7FC0)
+    cache.idx_pool.fill_(-7)
+    W = G.make_projections(seed, 128, r, joint=joint)
+    KV = [G.make_kv(seed + 31 * b, max(total[b], 1, capacity), Hkv, 128, n_proto=n_proto)[:2] for b in range(B)]
+    wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
+    for phase, (starts, counts) in enumerate((([0] * B, lens_before), (lens_before, lens_new))):
+        if sum(counts) == 0:
+            continue
+        kn = np.concatenate([KV[b][0][starts[b]:starts[b] + counts[b]] for b in range(B)])
+        vn = np.concatenate([KV[b][1][starts[b]:starts[b] + counts[b]] for b in range(B)])
+        cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+        cache.compress(wk, wv, dev_bits(kn), dev_bits(vn), cu, np.asarray(starts, dtype=np.int32))
+    torch.cuda.synchronize()
+    return cache, KV, W, total
+
+
+def _verify(cache, KV, W, total, s, joint):
+    n_diff = 0
+    for b, L in enumerate(total):
+        if L == 0:
+            continue
+        idx, zk, zv = cache.get_sequence(b, 0, L)
+        K, V = KV[b][0][:L], KV[b][1][:L]
+        n_diff += _check_against_oracle(K, V, W, s, joint, idx, zk, zv)
+        n_ref = -(-L // s)
+        rk, rv, nrm = cache.get_refs(b, n_ref)
+        assert np.array_equal(rk, K[::s]) and np.array_equal(rv, V[::s])
+        from oracle import deltakv_oracle as O
+        kv = np.concatenate([O.bf16_bits_to_f64(K[::s]), O.bf16_bits_to_f64(V[::s])], axis=2)
+        assert np.allclose(nrm, 1.0 / np.sqrt(np.sum(kv * kv, axis=2)), rtol=1e-5)
+    return n_diff
+
+
+def test_tiny_config_prefill_matches_oracle():
+    """2048 tokens, 8 kv-heads x 128, rank 64, 256 prototypes, references every 16th earlier token."""
+    from synthetic import generator as G
+    cache, KV, W, total = _compress_case(G.seed_for(1), [0], [2048], Hkv=8, r=64, n_proto=256)
+    _verify(cache, KV, W, total, 16, False)
+
+
+@pytest.mark.parametrize("L", [1, 2, 16, 17, 31, 100, 1000])
+def test_prefill_ragged_lengths(L):
+    cache, KV, W, total = _compress_case(100 + L, [0], [L])
+    _verify(cache, KV, W, total, 16, False)
+
+
+@pytest.mark.parametrize("r,joint,s", [(16, False, 16), (48, False, 16), (128, False, 16), (64, True, 16),
+                                       (48, True, 16), (64, False, 10), (32, False, 1), (64, False, 5)])
+def test_ranks_modes_strides(r, joint, s):
+    cache, KV, W, total = _compress_case(200 + r + s, [0], [700], Hkv=3, r=r, s=s, joint=joint, Hq=3)
+    _verify(cache, KV, W, total, s, joint)
+
+
+def test_append_after_prefill_batched_and_paged():
+    """Prefill four sequences, then append 1..40 tokens to each (one is empty, one appends nothing)."""
+    cache, KV, W, total = _compress_case(300, [500, 0, 37, 1024, 64], [1, 3, 40, 16, 0], Hkv=4, r=48, perm=5, Hq=28)
+    _verify(cache, KV, W, total, 16, False)
+
+
+def test_decode_appends_one_token_at_a_time():
+    import torch
+    from tests.helpers import dev_bits
+    cache, KV, W, total = _compress_case(400, [0], [200], capacity=200)
+    # rebuild by appending the last 40 tokens one by one on top of a 160-token prefill
+    cache2, KV2, W2, _ = _compress_case(400, [0], [160], capacity=200)
+    wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
+    K, V = KV[0]
+    for t in range(160, 200):
+        cache2.compress(wk, wv, dev_bits(K[t:t + 1]), dev_bits(V[t:t + 1]), [0, 1], [t])
+    torch.cuda.synchronize()
+    a, b = cache.get_sequence(0, 0, 200), cache2.get_sequence(0, 0, 200)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    _verify(cache2, KV, W, [200], 16, False)
+
+
+def test_exact_and_near_ties_pick_the_oracle_ordinal():
+    """Duplicate references (exact ties -> lowest ordinal) and a token that is an exact copy of a reference."""
+    import torch
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    from tests.helpers import dev_bits
+    L, Hkv, r = 400, 2, 64
+    K, V, _ = G.make_kv(500, L, Hkv, 128, n_proto=8)
+    for j in (3, 9, 14):                       # references 3, 9, 14 are bit-identical to reference 1
+        K[16 * j], V[16 * j] = K[16], V[16]
+    K[250], V[250] = K[16], V[16]              # exact copy -> cos = 1 for ordinals 1, 3, 9, 14 -> ordinal 1
+    K[300, 0], V[300, 0] = 0, 0                # zero vector -> all scores 0 -> ordinal 0
+    W = G.make_projections(500, 128, r)
+    dims = dk.make_dims(Hkv, 8, r, 32, 32)
+    cache = dk.PagedCache(dims, 1, L, L)
+    cache.compress(dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"]), dev_bits(K), dev_bits(V), [0, L], [0])
+    torch.cuda.synchronize()
+    idx, zk, zv = cache.get_sequence(0, 0, L)
+    assert np.all(idx[250] == 1) and np.all(zk[250] == 0) and np.all(zv[250] == 0)
+    assert idx[300, 0] == 0
+    from oracle import deltakv_oracle as O
+    ref = O.compress(O.bf16_bits_to_f64(K), O.bf16_bits_to_f64(V), O.bf16_bits_to_f64(W["w_down_k_bf16"]),
+                     O.bf16_bits_to_f64(W["w_down_v_bf16"]), s=16)
+    assert np.array_equal(idx, ref["idx"])
+
+
+def test_compress_then_decode_end_to_end():
+    """The cache the GPU builds, read by the GPU decode kernel, matches the oracle's own pipeline."""
+    import torch
+    from oracle import deltakv_oracle as O
+    from synthetic import generator as G
+    from tests.helpers import dev_bits, out_f64, check_attention
+    cache, KV, W, total = _compress_case(600, [0, 0], [1500, 333], Hkv=2, r=64, Hq=8)
+    q = G.make_queries(600, 2, 8, 128)
+    out = cache.decode_attn(dev_bits(W["w_up_k_bf16"]), dev_bits(W["w_up_v_bf16"]), dev_bits(q), total, 1 / np.sqrt(128))
+    torch.cuda.synchronize()
+    got = out_f64(out)
+    f = O.bf16_bits_to_f64
+    for b, L in enumerate(total):
+        ref = O.compress(f(KV[b][0][:L]), f(KV[b][1][:L]), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=16)
+        want, _ = O.decode_attn_direct(f(q[b]), ref["idx"], f(ref["zb_k"]), f(ref["zb_v"]), ref["ref_k"], ref["ref_v"],
+                                       f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), 1 / np.sqrt(128))
+        check_attention(got[b], want, f"seq {b}")

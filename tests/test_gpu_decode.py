@@ -1,0 +1,168 @@
+"""GPU parity of deltakv_decode_attn against the CPU oracle (caches built by the oracle's compress and
+placed into the paged layout).  Bar: max-abs <= 2e-2 on bf16 outputs, plus relative L2 <= 1e-2."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(case, page_perm_seed=None, pool_slack=1.25):
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    B = len(case.lens)
+    max_len = max(max(case.lens), 1)
+    per_seq_pages = -(-max_len // 16)
+    per_seq_refs = -(-max_len // case.s)
+    n_pages = int(B * per_seq_pages * pool_slack) + 1
+    n_slots = int(B * per_seq_refs * pool_slack) + 1
+    page_ids = ref_slots = None
+    if page_perm_seed is not None:
+        pp = G.page_permutation(page_perm_seed, B * per_seq_pages, n_pages)
+        rp = G.page_permutation(page_perm_seed + 1, B * per_seq_refs, n_slots)
+        page_ids = [pp[b * per_seq_pages:(b + 1) * per_seq_pages] for b in range(B)]
+        ref_slots = [rp[b * per_seq_refs:(b + 1) * per_seq_refs] for b in range(B)]
+    dims = dk.make_dims(case.Hkv, case.Hq, case.r, n_pages, n_slots, ref_stride=case.s,
+                        latent_mode=dk.JOINT if case.joint else dk.SPLIT)
+    cache = dk.PagedCache(dims, B, 16, max_len, page_ids=page_ids, ref_slots=ref_slots)
+    # poison the pools so that a read of an unwritten slot shows up (0x7fc0 = bf16 NaN)
+    cache.latent_pool.fill_(0x7FC0)
+    cache.idx_pool.fill_(0x7FFFFFF0)
+    for b, L in enumerate(case.lens):
+        if L > 0:
+            r = case.res[b]
+            cache.put_sequence(b, r["idx"], r["zb_k"], r["zb_v"], case.K[b][::case.s], case.V[b][::case.s])
+    return cache
+
+
+def _run(case, cache, scale, q_bits=None, want_lse=True):
+    import torch
+    from tests.helpers import dev_bits, out_f64
+    q = dev_bits(case.q if q_bits is None else q_bits)
+    lse = torch.full((len(case.lens), case.Hq), 123.0, dtype=torch.float32, device="cuda") if want_lse else None
+    out = cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), q, case.lens, scale, lse=lse)
+    torch.cuda.synchronize()
+    status = int(cache.decode_ws[:4].view(torch.int32)[0].item())
+    return out_f64(out), (lse.cpu().numpy().astype(np.float64) if want_lse else None), status
+
+
+def _compare(case, got, lse, scale, q_f64=None):
+    from tests.helpers import check_attention
+    worst = 0.0
+    for b, L in enumerate(case.lens):
+        if L == 0:
+            assert np.all(got[b] == 0) and np.all(np.isneginf(lse[b]))
+            continue
+        want, wl = case.oracle_decode(b, scale, None if q_f64 is None else q_f64[b])
+        err, rel = check_attention(got[b], want, f"seq {b} len {L}")
+        worst = max(worst, err)
+        if lse is not None:
+            assert np.max(np.abs(lse[b] - wl)) <= 2e-2, (b, np.max(np.abs(lse[b] - wl)))
+    return worst
+
+
+def test_tiny_config_matches_oracle():
+    """1 layer, batch 1, 2048 cached tokens, 8 kv-heads x 128, 32 query heads, rank 64, 256 prototypes."""
+    from tests.helpers import Case
+    from synthetic import generator as G
+    case = Case(G.seed_for(1), [2048], Hkv=8, Hq=32, r=64, n_proto=256)
+    cache = _setup(case)
+    scale = 1.0 / np.sqrt(128)
+    got, lse, status = _run(case, cache, scale)
+    assert status == 0
+    _compare(case, got, lse, scale)
+
+
+@pytest.mark.parametrize("L", [1, 15, 16, 17, 100, 2041, 4100])
+def test_ragged_lengths(L):
+    from tests.helpers import Case
+    case = Case(1000 + L, [L], Hkv=2, Hq=8, r=64, n_proto=16)
+    cache = _setup(case)
+    got, lse, status = _run(case, cache, 0.1)
+    assert status == 0
+    _compare(case, got, lse, 0.1)
+
+
+@pytest.mark.parametrize("r,Hkv,Hq", [(16, 2, 2), (32, 2, 8), (48, 4, 28), (128, 1, 4), (64, 1, 16), (80, 2, 6)])
+def test_ranks_and_group_sizes(r, Hkv, Hq):
+    from tests.helpers import Case
+    case = Case(2000 + r + Hq, [777], Hkv=Hkv, Hq=Hq, r=r, n_proto=16)
+    cache = _setup(case)
+    got, lse, status = _run(case, cache, 0.09)
+    assert status == 0
+    _compare(case, got, lse, 0.09)
+
+
+def test_batch_of_mixed_lengths_paged_and_contiguous_agree():
+    """Random page / slot permutation over a shared pool gives the same bits as the contiguous layout."""
+    from tests.helpers import Case
+    case = Case(3000, [300, 0, 4097, 33, 1500], Hkv=4, Hq=28, r=48, n_proto=32)
+    scale = 1.0 / np.sqrt(128)
+    got_c, lse_c, st = _run(case, _setup(case), scale)
+    assert st == 0
+    _compare(case, got_c, lse_c, scale)
+    got_p, lse_p, st = _run(case, _setup(case, page_perm_seed=77), scale)
+    assert st == 0
+    _compare(case, got_p, lse_p, scale)
+    # the two layouts run the same arithmetic; only the order of float atomics may differ
+    assert np.max(np.abs(got_p - got_c)) <= 2.0 ** -7 * max(1.0, np.max(np.abs(got_c)))
+
+
+def test_needle_query_gives_order_one_outputs():
+    """q = 8 * K_hat of one token: one weight dominates, so outputs are O(|V|) and errors cannot hide."""
+    from tests.helpers import Case, f64
+    from oracle import deltakv_oracle as O
+    from synthetic import generator as G
+    case = Case(4000, [3000], Hkv=2, Hq=8, r=64, n_proto=32)
+    r = case.res[0]
+    kh, vh = O.reconstruct(r["idx"], f64(r["zb_k"]), f64(r["zb_v"]), r["ref_k"], r["ref_v"],
+                           f64(case.W["w_up_k_bf16"]), f64(case.W["w_up_v_bf16"]))
+    t_star = [1234, 17, 2999, 640, 5, 2048, 777, 1601]
+    qn = np.stack([8.0 * kh[t_star[g], g // 4] for g in range(8)])
+    q_bits = G.f32_to_bf16_bits(qn.astype(np.float32))[None]
+    cache = _setup(case)
+    scale = 1.0 / np.sqrt(128)
+    got, lse, status = _run(case, cache, scale, q_bits=q_bits)
+    assert status == 0
+    want, _ = case.oracle_decode(0, scale, f64(q_bits[0]))
+    assert np.max(np.abs(want)) > 1.0
+    _compare(case, got, lse, scale, q_f64=f64(q_bits))
+
+
+def test_long_sequence_uses_several_splits():
+    from tests.helpers import Case
+    case = Case(5000, [40000], Hkv=1, Hq=4, r=64, n_proto=64)
+    cache = _setup(case)
+    scale = 1.0 / np.sqrt(128)
+    got, lse, status = _run(case, cache, scale)
+    assert status == 0
+    _compare(case, got, lse, scale)
+
+
+def test_zero_query_gives_mean_of_reconstructed_values():
+    from tests.helpers import Case, f64
+    from oracle import deltakv_oracle as O
+    case = Case(6000, [500], Hkv=2, Hq=4, r=32, n_proto=8)
+    cache = _setup(case)
+    q0 = np.zeros_like(case.q)
+    got, lse, status = _run(case, cache, 0.2, q_bits=q0)
+    r = case.res[0]
+    _, vh = O.reconstruct(r["idx"], f64(r["zb_k"]), f64(r["zb_v"]), r["ref_k"], r["ref_v"],
+                          f64(case.W["w_up_k_bf16"]), f64(case.W["w_up_v_bf16"]))
+    for g in range(4):
+        assert np.max(np.abs(got[0, g] - vh[:, g // 2].mean(0))) <= 1e-2
+        assert abs(lse[0, g] - np.log(500)) < 1e-3
+
+
+def test_unsupported_and_workspace_errors_on_device():
+    import torch
+    import paper_2602_08005_amd as dk
+    from paper_2602_08005_amd import binding as B
+    from tests.helpers import Case, dev_bits
+    case = Case(7000, [64], Hkv=2, Hq=8, r=64, n_proto=8)
+    cache = _setup(case)
+    small = torch.empty(512, dtype=torch.uint8, device="cuda")
+    rc = B.decode_attn(cache.dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool, cache.block_tables,
+                       cache.ref_tables, dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(case.q),
+                       torch.tensor([64], dtype=torch.int32, device="cuda"), [64], 0.1, torch.empty(8 * 128, dtype=torch.int16, device="cuda"),
+                       None, small, check=False)
+    assert rc == B.E_WORKSPACE
