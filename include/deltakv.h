@@ -198,6 +198,18 @@ const char* deltakv_strerror(int code);
 const char* deltakv_last_error_detail(void);
 int deltakv_version(void);
 
+/* Per-kernel timing for benchmarks.  Between deltakv_timing_begin() and deltakv_timing_end() every
+ * compress / decode call records a HIP event on its stream before its first kernel and after each
+ * kernel (use one stream, call from one thread).  deltakv_timing_end waits for the last event and
+ * returns, per kernel, the summed time between the surrounding events in milliseconds (this includes
+ * the launch gap in front of the kernel) and the number of launches.  Kernel order:
+ *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
+ *   4 admit_refs, 5 sim_top2, 6 select_project          (deltakv_compress)
+ * Arrays are host memory with n >= DELTAKV_N_KERNELS entries.  Errors: INVALID_ARG, HIP. */
+#define DELTAKV_N_KERNELS 7
+int deltakv_timing_begin(void);
+int deltakv_timing_end(float* ms_by_kernel, int32_t* launches_by_kernel, int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

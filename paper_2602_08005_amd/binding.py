@@ -59,6 +59,9 @@ def _load() -> C.CDLL:
     lib.deltakv_strerror.restype = C.c_char_p
     lib.deltakv_strerror.argtypes = [C.c_int]
     lib.deltakv_last_error_detail.restype = C.c_char_p
+    lib.deltakv_timing_begin.restype = C.c_int
+    lib.deltakv_timing_end.restype = C.c_int
+    lib.deltakv_timing_end.argtypes = [vp, vp, i32]
     lib.deltakv_paged_layout.restype = C.c_int
     lib.deltakv_paged_layout.argtypes = [C.POINTER(Dims), i32, i64, i64, C.POINTER(Layout)]
     lib.deltakv_latent_block_offsets.restype = C.c_int
@@ -75,7 +78,9 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_paged_layout", "deltakv_latent_block_offsets",
+KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", "sim_top2", "select_project")
+EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
+           "deltakv_timing_end", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn")
 
 
@@ -85,6 +90,22 @@ def version() -> int:
 
 def strerror(code: int) -> str:
     return _lib.deltakv_strerror(int(code)).decode()
+
+
+def timing_begin() -> None:
+    rc = _lib.deltakv_timing_begin()
+    if rc != OK:
+        raise DeltaKVError(rc, "deltakv_timing_begin")
+
+
+def timing_end() -> dict:
+    """{kernel name: (total ms, launches)} for the calls since timing_begin()."""
+    ms = np.zeros(len(KERNEL_NAMES), dtype=np.float32)
+    cnt = np.zeros(len(KERNEL_NAMES), dtype=np.int32)
+    rc = _lib.deltakv_timing_end(ms.ctypes.data, cnt.ctypes.data, len(KERNEL_NAMES))
+    if rc != OK:
+        raise DeltaKVError(rc, "deltakv_timing_end")
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(KERNEL_NAMES)}
 
 
 def make_dims(n_kv_heads, n_q_heads, rank, n_pages, n_ref_slots, latent_mode=SPLIT, ref_stride=16,

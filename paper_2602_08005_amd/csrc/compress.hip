@@ -451,8 +451,10 @@ int sim_tile_rows(int rb) { return 64 * rb; }
 hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st) {
   hipError_t e;
   const int items = P.n_new_total * P.Hkv;
+  timing_mark(-1, st);
   hipLaunchKernelGGL(k_admit_refs, dim3(ceil_div(items, 4)), dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of admit_refs");
+  timing_mark(K_ADMIT, st);
   dim3 gs(tiles_max, P.NS, P.batch * P.Hkv);
   switch (rb) {
     case 1: e = launch_sim<1>(P, gs, st); break;
@@ -461,18 +463,21 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
+  timing_mark(K_SIM, st);
   dim3 gp(page_tiles_max, P.batch);
+  e = hipErrorInvalidValue;
   switch (P.R) {
-    case 16: return launch_project<16>(P, gp, st);
-    case 32: return launch_project<32>(P, gp, st);
-    case 48: return launch_project<48>(P, gp, st);
-    case 64: return launch_project<64>(P, gp, st);
-    case 80: return launch_project<80>(P, gp, st);
-    case 96: return launch_project<96>(P, gp, st);
-    case 112: return launch_project<112>(P, gp, st);
-    case 128: return launch_project<128>(P, gp, st);
+    case 16: e = launch_project<16>(P, gp, st); break;
+    case 32: e = launch_project<32>(P, gp, st); break;
+    case 48: e = launch_project<48>(P, gp, st); break;
+    case 64: e = launch_project<64>(P, gp, st); break;
+    case 80: e = launch_project<80>(P, gp, st); break;
+    case 96: e = launch_project<96>(P, gp, st); break;
+    case 112: e = launch_project<112>(P, gp, st); break;
+    case 128: e = launch_project<128>(P, gp, st); break;
   }
-  return hipErrorInvalidValue;
+  timing_mark(K_PROJECT, st);
+  return e;
 }
 
 }  // namespace dkv

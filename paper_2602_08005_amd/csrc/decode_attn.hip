@@ -490,12 +490,15 @@ size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw) {
 hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st) {
   hipError_t e;
   dim3 gchunk(P.n_chunk_max, P.Hkv, batch);
+  timing_mark(-1, st);
   hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
+  timing_mark(K_REF_SCORES, st);
   dim3 gs(P.S, P.Hkv, batch);
   if (P.joint) return hipErrorInvalidValue;   // JOINT streaming kernel: not built yet
   e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
   if (e != hipSuccess) return e;
+  timing_mark(K_STREAM, st);
   switch (P.Gp) {
     case 4: hipLaunchKernelGGL(k_ref_values<4>, gchunk, dim3(256), 0, st, P); break;
     case 8: hipLaunchKernelGGL(k_ref_values<8>, gchunk, dim3(256), 0, st, P); break;
@@ -504,8 +507,11 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, h
     default: return hipErrorInvalidValue;
   }
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_values");
+  timing_mark(K_REF_VALUES, st);
   hipLaunchKernelGGL(k_finalize, dim3(P.Hkv, batch), dim3(128), 0, st, P);
-  return note_hip_error(hipGetLastError(), "launch of finalize");
+  e = note_hip_error(hipGetLastError(), "launch of finalize");
+  timing_mark(K_FINALIZE, st);
+  return e;
 }
 
 }  // namespace dkv

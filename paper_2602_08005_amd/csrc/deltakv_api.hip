@@ -1,6 +1,8 @@
 // C ABI of libdeltakv: argument validation, layout arithmetic, workspace carving, launches.
 // See include/deltakv.h for the contract of every entry point.
 #include <stdio.h>
+
+#include <vector>
 #include <string.h>
 
 #include "common.h"
@@ -42,12 +44,33 @@ int device_cu_count() {
 
 thread_local char g_detail[256] = "";
 
+// per-kernel timing state (one timed region at a time, one stream)
+struct Mark { hipEvent_t ev; int id; };
+bool g_timing = false;
+std::vector<Mark> g_marks;
+std::vector<hipEvent_t> g_event_pool;
+
 }  // namespace
 
 namespace dkv {
 hipError_t note_hip_error(hipError_t e, const char* what) {
   if (e != hipSuccess) snprintf(g_detail, sizeof(g_detail), "%s: %s", what, hipGetErrorString(e));
   return e;
+}
+void timing_mark(int kernel_id, hipStream_t st) {
+  if (!g_timing) return;
+  hipEvent_t ev;
+  if (!g_event_pool.empty()) {
+    ev = g_event_pool.back();
+    g_event_pool.pop_back();
+  } else if (hipEventCreate(&ev) != hipSuccess) {
+    return;
+  }
+  if (hipEventRecord(ev, st) != hipSuccess) {
+    g_event_pool.push_back(ev);
+    return;
+  }
+  g_marks.push_back(Mark{ev, kernel_id});
 }
 size_t device_lds_limit() {
   static size_t lim = 0;
@@ -68,6 +91,32 @@ extern "C" {
 int deltakv_version(void) { return 1; }
 
 const char* deltakv_last_error_detail(void) { return g_detail; }
+
+int deltakv_timing_begin(void) {
+  for (auto& m : g_marks) g_event_pool.push_back(m.ev);
+  g_marks.clear();
+  g_timing = true;
+  return DELTAKV_OK;
+}
+
+int deltakv_timing_end(float* ms_by_kernel, int32_t* launches_by_kernel, int32_t n) {
+  g_timing = false;
+  if (!ms_by_kernel || !launches_by_kernel || n < DELTAKV_N_KERNELS) return DELTAKV_E_INVALID_ARG;
+  for (int i = 0; i < n; ++i) { ms_by_kernel[i] = 0.f; launches_by_kernel[i] = 0; }
+  int rc = DELTAKV_OK;
+  if (!g_marks.empty() && hipEventSynchronize(g_marks.back().ev) != hipSuccess) rc = DELTAKV_E_HIP;
+  for (size_t i = 1; i < g_marks.size() && rc == DELTAKV_OK; ++i) {
+    const int id = g_marks[i].id;
+    if (id < 0 || id >= DELTAKV_N_KERNELS) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_marks[i - 1].ev, g_marks[i].ev) != hipSuccess) { rc = DELTAKV_E_HIP; break; }
+    ms_by_kernel[id] += ms;
+    launches_by_kernel[id] += 1;
+  }
+  for (auto& m : g_marks) g_event_pool.push_back(m.ev);
+  g_marks.clear();
+  return rc;
+}
 
 const char* deltakv_strerror(int code) {
   switch (code) {

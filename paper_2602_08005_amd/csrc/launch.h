@@ -82,6 +82,11 @@ int sim_tile_rows(int rb);
 // Enqueues the three compress kernels on `st`.
 hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st);
 
+// Optional per-kernel timing (deltakv_timing_begin / deltakv_timing_end): when enabled, launchers call
+// timing_mark(kernel_id, stream) before the first kernel (id -1) and after every kernel.
+enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_PROJECT, K_COUNT };
+void timing_mark(int kernel_id, hipStream_t st);
+
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
 size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw);
 // Enqueues the four decode kernels on `st`.
