@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--rank", type=int, default=64)
     ap.add_argument("--protos", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")
     args = ap.parse_args()
@@ -59,6 +60,9 @@ def main():
     from synthetic import generator as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    for kv in args.tune:
+        name, val = kv.split("=")
+        B.tune(name, int(val))
     torch.cuda.set_device(0)
     Bt, L, NL, Hkv, Hq, r, D, s = args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, 128, 16
     scale = 1.0 / np.sqrt(D)

@@ -198,6 +198,12 @@ const char* deltakv_strerror(int code);
 const char* deltakv_last_error_detail(void);
 int deltakv_version(void);
 
+/* Launch-shape overrides for benchmark sweeps (process-wide; value 0 restores the automatic choice):
+ *   "stream_waves"  waves per block of the decode streaming kernel (8 or 16)
+ *   "splits"        token-range splits per (sequence, kv-head) in decode (1..16)
+ * Results do not depend on these beyond floating-point summation order.  Errors: INVALID_ARG. */
+int deltakv_tune(const char* name, int32_t value);
+
 /* Per-kernel timing for benchmarks.  Between deltakv_timing_begin() and deltakv_timing_end() every
  * compress / decode call records a HIP event on its stream before its first kernel and after each
  * kernel (use one stream, call from one thread).  deltakv_timing_end waits for the last event and

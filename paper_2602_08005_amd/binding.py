@@ -59,6 +59,8 @@ def _load() -> C.CDLL:
     lib.deltakv_strerror.restype = C.c_char_p
     lib.deltakv_strerror.argtypes = [C.c_int]
     lib.deltakv_last_error_detail.restype = C.c_char_p
+    lib.deltakv_tune.restype = C.c_int
+    lib.deltakv_tune.argtypes = [C.c_char_p, i32]
     lib.deltakv_timing_begin.restype = C.c_int
     lib.deltakv_timing_end.restype = C.c_int
     lib.deltakv_timing_end.argtypes = [vp, vp, i32]
@@ -80,7 +82,7 @@ def _load() -> C.CDLL:
 _lib = _load()
 KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", "sim_top2", "select_project")
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
-           "deltakv_timing_end", "deltakv_paged_layout", "deltakv_latent_block_offsets",
+           "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn")
 
 
@@ -90,6 +92,12 @@ def version() -> int:
 
 def strerror(code: int) -> str:
     return _lib.deltakv_strerror(int(code)).decode()
+
+
+def tune(name: str, value: int) -> None:
+    rc = _lib.deltakv_tune(name.encode(), int(value))
+    if rc != OK:
+        raise DeltaKVError(rc, f"deltakv_tune({name})")
 
 
 def timing_begin() -> None:

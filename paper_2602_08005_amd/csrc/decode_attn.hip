@@ -142,10 +142,8 @@ struct Tile {
 };
 
 template <int R, bool JOINT>
-__device__ inline void load_tile(const DecodeParams& P, int b, int h, int p, int L, int l, Tile<R>& t) {
+__device__ inline void load_tile(const DecodeParams& P, int page, int h, int nvalid, int l, Tile<R>& t) {
   const int lg = l >> 4;
-  int page = P.block_tables[(int64_t)b * P.bt_stride + p];
-  page = clampi(page, 0, (int)P.n_pages_pool - 1);
   const uint16_t* base = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
 #pragma unroll
   for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
@@ -160,13 +158,19 @@ __device__ inline void load_tile(const DecodeParams& P, int b, int h, int p, int
     for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (nb * 64 + l) * 4);
   }
   t.id = *reinterpret_cast<const int4*>(P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + lg * 4);
-  t.nvalid = L - p * kPage;
+  t.nvalid = nvalid;
 }
 
-template <int R, int NW, bool JOINT>
+// Grid: 1-D.  Workgroups are handed to the eight XCDs round-robin by id, and each XCD has its own L2, so
+// id -> (xcd = id % 8, k = id / 8), (sequence, kv-head) pair = (k / S) * 8 + xcd, split = k % S: every split
+// of a pair runs on the same XCD and shares that L2's copy of the pair's per-reference score table.
+template <int R, int NW, int ST, bool JOINT>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   extern __shared__ float smem[];
-  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int xcd = blockIdx.x & 7, kq = blockIdx.x >> 3;
+  const int pair = (kq / P.S) * 8 + xcd, s = kq % P.S;
+  if (pair >= P.batch * P.Hkv) return;
+  const int b = pair / P.Hkv, h = pair % P.Hkv;
   const int L = seq_len_of(P, b);
   if (L <= 0) return;
   const int n_pages = ceil_div(L, kPage);
@@ -183,7 +187,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   float* accbuf = smem + ((n_tab + 3) & ~3);              // [Gp][R]
   float* lbuf = accbuf + Gp * R;                          // [16]
   float* xbuf = lbuf + 16;                                // [NW][16]
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   for (int i = tid; i < n_tab; i += NW * 64) tab[i] = 0.f;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
 
@@ -250,7 +255,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     pk.y = pack_bf16(p[2], p[3]);
     const short4v pa = __builtin_bit_cast(short4v, pk);
     if (!JOINT) {
-      if (t.nvalid < kPage) {    // tail page: slots past the sequence end hold garbage
+      if (t.nvalid < kPage) {    // tail page (or a pipeline slot past the range): mask slots that hold garbage
 #pragma unroll
         for (int nb = 0; nb < Tile<R>::NB; ++nb) {
           const int left = t.nvalid - 4 * lg;   // valid tokens among this lane's four
@@ -264,30 +269,32 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   };
 
-  // three-stage software pipeline over this wave's pages: loads two pages ahead, score gather one ahead
-  {
-    Tile<R> t0, t1, t2;
-    float s0[4], s1[4], s2[4];
-    int p = p0 + w;
-    if (p < p1) {
-      load_tile<R, JOINT>(P, b, h, p, L, l, t0);
-      if (p + NW < p1) load_tile<R, JOINT>(P, b, h, p + NW, L, l, t1);
-      gather(t0, s0);
-      // step(a, b, c): page p in a (scores gathered), p+NW in b (loaded), c free
-#define DKV_STEP(A, SA, B, SB, C)                                                  \
-      {                                                                             \
-        if (p + 2 * NW < p1) load_tile<R, JOINT>(P, b, h, p + 2 * NW, L, l, C);     \
-        if (p + NW < p1) gather(B, SB);                                             \
-        compute(A, SA);                                                             \
-        p += NW;                                                                    \
-        if (p >= p1) break;                                                         \
+  // Software pipeline over this wave's pages p0+w, p0+w+NW, ...: in steady state ST-1 pages of loads are in
+  // flight and the score gather of the next page has been issued while the current page is computed.  Every
+  // load in the loop is unconditional (slots past the wave's range re-read its last page and are computed
+  // with zero valid tokens), so the hardware wait counters can be set exactly.
+  const int n_my = (p1 - p0 - w + NW - 1) / NW;            // pages of this wave
+  if (n_my > 0) {
+    const int32_t* bt = P.block_tables + (int64_t)b * P.bt_stride;
+    auto page_id = [&](int i) {                               // pool page of this wave's i-th page (clamped)
+      const int ii = i < n_my ? i : n_my - 1;
+      return clampi(bt[p0 + w + ii * NW], 0, (int)P.n_pages_pool - 1);
+    };
+    auto valid_of = [&](int i) { return i < n_my ? L - (p0 + w + i * NW) * kPage : 0; };
+    Tile<R> t[ST];
+    float sr[ST][4];
+#pragma unroll
+    for (int u = 0; u < ST - 1; ++u) load_tile<R, JOINT>(P, page_id(u), h, valid_of(u), l, t[u]);
+    int pg_next = page_id(ST - 1);
+    gather(t[0], sr[0]);
+    for (int i = 0; i < n_my; i += ST) {
+#pragma unroll
+      for (int u = 0; u < ST; ++u) {
+        load_tile<R, JOINT>(P, pg_next, h, valid_of(i + u + ST - 1), l, t[(u + ST - 1) % ST]);
+        pg_next = page_id(i + u + ST);
+        gather(t[(u + 1) % ST], sr[(u + 1) % ST]);
+        compute(t[u], sr[u]);
       }
-      for (;;) {
-        DKV_STEP(t0, s0, t1, s1, t2)
-        DKV_STEP(t1, s1, t2, s2, t0)
-        DKV_STEP(t2, s2, t0, s0, t1)
-      }
-#undef DKV_STEP
     }
   }
 
@@ -457,14 +464,15 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 template <int R, int NW, bool JOINT>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  constexpr int ST = NW >= 16 ? 3 : 4;   // pipeline slots per wave
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, JOINT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, JOINT>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 
@@ -494,7 +502,7 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, h
   hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);
-  dim3 gs(P.S, P.Hkv, batch);
+  dim3 gs(ceil_div(batch * P.Hkv, 8) * 8 * P.S);
   if (P.joint) return hipErrorInvalidValue;   // JOINT streaming kernel: not built yet
   e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
   if (e != hipSuccess) return e;

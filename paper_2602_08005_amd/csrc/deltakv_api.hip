@@ -44,6 +44,10 @@ int device_cu_count() {
 
 thread_local char g_detail[256] = "";
 
+// launch-shape overrides for sweeps (0 = automatic)
+int g_tune_stream_waves = 0;
+int g_tune_splits = 0;
+
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
 bool g_timing = false;
@@ -91,6 +95,20 @@ extern "C" {
 int deltakv_version(void) { return 1; }
 
 const char* deltakv_last_error_detail(void) { return g_detail; }
+
+int deltakv_tune(const char* name, int32_t value) {
+  if (!name || value < 0) return DELTAKV_E_INVALID_ARG;
+  if (!strcmp(name, "stream_waves")) {
+    if (value != 0 && value != 8 && value != 16) return DELTAKV_E_INVALID_ARG;
+    g_tune_stream_waves = value;
+  } else if (!strcmp(name, "splits")) {
+    if (value > kMaxSplits) return DELTAKV_E_INVALID_ARG;
+    g_tune_splits = value;
+  } else {
+    return DELTAKV_E_INVALID_ARG;
+  }
+  return DELTAKV_OK;
+}
 
 int deltakv_timing_begin(void) {
   for (auto& m : g_marks) g_event_pool.push_back(m.ev);
@@ -211,13 +229,9 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   if (dims->latent_mode == DELTAKV_JOINT) return DELTAKV_E_UNSUPPORTED;   // JOINT streaming kernel: not built yet
 
   const int G = dims->n_q_heads / dims->n_kv_heads, Gp = padded_group(G), R = dims->rank;
-  int nw = 8;
-  size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
+  const int nw = g_tune_stream_waves ? g_tune_stream_waves : 8;
+  const size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
   const size_t kLdsLimit = device_lds_limit();
-  if (lds > kLdsLimit / 2) {   // one block per compute unit: give it more waves
-    nw = 16;
-    lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
-  }
   if (lds > kLdsLimit) return DELTAKV_E_UNSUPPORTED;
   int per_cu = (int)(kLdsLimit / lds);
   const int wave_cap = 32 / nw;
@@ -229,6 +243,7 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   if (splits > split_cap) splits = split_cap;
   if (splits > kMaxSplits) splits = kMaxSplits;
   if (splits < 1) splits = 1;
+  if (g_tune_splits) splits = g_tune_splits < split_cap ? g_tune_splits : split_cap;
   DecodeWs ws = plan_decode_ws(*dims, batch, n_ref_max, splits);
   while (ws.total > ws_bytes && splits > 1) {
     --splits;
@@ -260,6 +275,7 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   Pm.q = static_cast<const uint16_t*>(q);
   Pm.out = static_cast<uint16_t*>(out);
   Pm.lse = lse;
+  Pm.batch = batch;
   Pm.Hkv = dims->n_kv_heads;
   Pm.Hq = dims->n_q_heads;
   Pm.G = G;

@@ -24,7 +24,7 @@ struct DecodeParams {
   uint16_t* out;
   float* lse;
   // shape
-  int Hkv, Hq, G, Gp, R, stride, joint;
+  int batch, Hkv, Hq, G, Gp, R, stride, joint;
   int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)
   int n_ref_max, n_chunk_max;
   int S, pages_per_split;   // split grid
