@@ -65,21 +65,30 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;   // K half
   float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  // all loads of the wave's four 16-reference steps are issued before the first MFMA (rows past the end
+  // re-read the last reference and are dropped afterwards)
+  constexpr int NSTEP = kRefChunk / 64;
+  int slot[NSTEP];
+  uint4 kv[NSTEP][4];
 #pragma unroll
-  for (int step = 0; step < kRefChunk / 64; ++step) {
-    const int jb = j0 + w * 64 + step * 16;
-    if (jb >= n_ref) break;
-    const int j = jb + ln;
+  for (int step = 0; step < NSTEP; ++step) {
+    const int j = min(j0 + w * 64 + step * 16 + ln, n_ref - 1);
+    slot[step] = P.ref_tables[(int64_t)b * P.rt_stride + j];
+  }
+#pragma unroll
+  for (int step = 0; step < NSTEP; ++step) {
+    const uint16_t* krow = kbase + (int64_t)clampi(slot[step], 0, (int)P.n_ref_slots - 1) * kHeadDim;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) kv[step][kk] = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
+  }
+#pragma unroll
+  for (int step = 0; step < NSTEP; ++step) {
+    const int j = j0 + w * 64 + step * 16 + ln;
     const bool valid = j < n_ref;
-    int slot = P.ref_tables[(int64_t)b * P.rt_stride + (valid ? j : n_ref - 1)];
-    slot = clampi(slot, 0, (int)P.n_ref_slots - 1);
-    const uint16_t* krow = kbase + (int64_t)slot * kHeadDim;
     float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      uint4 v = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, v), acc, 0, 0, 0);
-    }
+    for (int kk = 0; kk < 4; ++kk)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv[step][kk]), acc, 0, 0, 0);
     // lane holds rows g = 4*lg + i of column j
     float4 o;
     o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
@@ -345,42 +354,68 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;   // V half
   __shared__ float red[4][GP][kHeadDim];
+  __shared__ float wsum[kRefChunk][GP];
+  __shared__ int slots[kRefChunk];
 
+  // phase 1: thread t sums the split partials of reference j0+t (coalesced across threads) and fetches its slot
+  {
+    const int j = j0 + tid;
+    float wj[GP];
+#pragma unroll
+    for (int g = 0; g < GP; ++g) wj[g] = 0.f;
+    int slot = 0;
+    if (j < n_ref) {
+      slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + j], 0, (int)P.n_ref_slots - 1);
+#pragma unroll
+      for (int s = 0; s < kMaxSplits; ++s) {
+        const int p1 = min(n_pages, (s + 1) * sp.per);
+        const int cov = refs_below(min(L, p1 * kPage), P.stride);   // ordinals split s wrote
+        if (s < sp.n_splits && s * sp.per < p1 && j < cov) {
+          const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
+#pragma unroll
+          for (int g4 = 0; g4 < GP; g4 += 4) {
+            const float4 t = *reinterpret_cast<const float4*>(wp + g4);
+            wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < GP; ++g) wsum[tid][g] = wj[g];
+    slots[tid] = slot;
+  }
+  __syncthreads();
+
+  // phase 2: lane = (row-in-group lg, 8-wide d chunk ln); a wave reads four 256-byte V rows per load and
+  // keeps eight such loads in flight
   float acc[GP][8];
 #pragma unroll
   for (int g = 0; g < GP; ++g)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-
-  for (int it = 0; it < kRefChunk / 16; ++it) {
-    const int j = j0 + w * (kRefChunk / 4) + it * 4 + lg;
-    if (j >= n_ref) continue;
-    int slot = P.ref_tables[(int64_t)b * P.rt_stride + j];
-    slot = clampi(slot, 0, (int)P.n_ref_slots - 1);
-    const uint4 v = *reinterpret_cast<const uint4*>(vbase + (int64_t)slot * kHeadDim + ln * 8);
-    float wj[GP];
+  constexpr int UN = 8;
+  for (int it0 = 0; it0 < kRefChunk / 16; it0 += UN) {
+    uint4 v[UN];
 #pragma unroll
-    for (int g = 0; g < GP; ++g) wj[g] = 0.f;
-    for (int s = 0; s < sp.n_splits; ++s) {
-      const int p1 = min(n_pages, (s + 1) * sp.per);
-      if (s * sp.per >= p1) break;
-      const int cov = refs_below(min(L, p1 * kPage), P.stride);
-      if (j >= cov) continue;
-      const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
-#pragma unroll
-      for (int g4 = 0; g4 < GP; g4 += 4) {
-        const float4 t = *reinterpret_cast<const float4*>(wp + g4);
-        wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
-      }
+    for (int u = 0; u < UN; ++u) {
+      const int row = w * (kRefChunk / 4) + (it0 + u) * 4 + lg;
+      v[u] = *reinterpret_cast<const uint4*>(vbase + (int64_t)slots[row] * kHeadDim + ln * 8);
     }
-    const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      const float lo = bf16lo(vv[e2]), hi = bf16hi(vv[e2]);
+    for (int u = 0; u < UN; ++u) {
+      const int row = w * (kRefChunk / 4) + (it0 + u) * 4 + lg;
+      float wj[GP];
 #pragma unroll
-      for (int g = 0; g < GP; ++g) {
-        acc[g][2 * e2] += wj[g] * lo;
-        acc[g][2 * e2 + 1] += wj[g] * hi;
+      for (int g = 0; g < GP; ++g) wj[g] = wsum[row][g];     // zero for rows past the end
+      const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float lo = bf16lo(vv[e2]), hi = bf16hi(vv[e2]);
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+          acc[g][2 * e2] += wj[g] * lo;
+          acc[g][2 * e2 + 1] += wj[g] * hi;
+        }
       }
     }
   }
@@ -409,20 +444,21 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// finalize: grid (Hkv, B), 128 threads (thread = output dim d).
+// finalize: grid (Hq, B), 128 threads (thread = output dim d); one block per query head.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
-  const int h = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int L = seq_len_of(P, b);
+  const int gh = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
   const int G = P.G, Gp = P.Gp, R = P.R;
+  const int h = gh / G, g = gh % G;
+  const int L = seq_len_of(P, b);
+  const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
   if (L <= 0) {
-    for (int g = 0; g < G; ++g) {
-      P.out[((int64_t)b * P.Hq + (int64_t)h * G + g) * kHeadDim + d] = 0;
-      if (P.lse && d == 0) P.lse[(int64_t)b * P.Hq + h * G + g] = -INFINITY;
-    }
+    P.out[orow + d] = 0;
+    if (P.lse && d == 0) P.lse[(int64_t)b * P.Hq + gh] = -INFINITY;
     return;
   }
   __shared__ float zsum[128];
+  __shared__ float redm[2];
   const int n_ref = refs_below(L, P.stride);
   const int nch = ceil_div(n_ref, kRefChunk);
   const int n_pages = ceil_div(L, kPage);
@@ -431,31 +467,47 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   for (int s = 0; s < sp.n_splits; ++s)
     if (s * sp.per < n_pages) n_used = s + 1;
   const int64_t bh = (int64_t)b * P.Hkv + h;
-  const uint16_t* wv = P.w_up_v;
-  for (int g = 0; g < G; ++g) {
-    float lsum = 0.f, xm = -INFINITY, mref = -INFINITY;
-    for (int s = 0; s < n_used; ++s) {
+  float lsum = 0.f, xm = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s)
+    if (s < n_used) {
       lsum += P.lpart[(bh * P.S + s) * Gp + g];
       xm = fmaxf(xm, P.xpart[(bh * P.S + s) * Gp + g]);
     }
-    for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
-    __syncthreads();
-    if (d < R) {
-      float a = 0.f;
-      for (int s = 0; s < n_used; ++s) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
-      zsum[d] = a;
-    }
-    __syncthreads();
-    float o = 0.f;
-    for (int c = 0; c < nch; ++c) o += P.opart[((bh * P.n_chunk_max + c) * Gp + g) * kHeadDim + d];
-    for (int c = 0; c < R; ++c) o += zsum[c] * bf16lo(wv[(int64_t)c * kHeadDim + d]);
-    const float res = o / lsum;
-    P.out[((int64_t)b * P.Hq + (int64_t)h * G + g) * kHeadDim + d] = (uint16_t)f32_to_bf16_bits(res);
-    if (d == 0) {
-      if (P.lse) P.lse[(int64_t)b * P.Hq + h * G + g] = (mref + kExpBias + __log2f(lsum)) * kLn2;
-      // exponent arguments above ~60 (relative to the bias) risk overflow of the fp32 sums
-      if (!(xm < 60.0f) || !(lsum > 0.f) || !(lsum < INFINITY)) atomicOr(P.status, 1);
-    }
+  float mref = -INFINITY;
+  for (int c = d; c < nch; c += 128) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) mref = fmaxf(mref, __shfl_xor(mref, o));
+  if ((d & 63) == 0) redm[d >> 6] = mref;
+  if (d < R) {
+    float a = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s)
+      if (s < n_used) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
+    zsum[d] = a;
+  }
+  __syncthreads();
+  mref = fmaxf(redm[0], redm[1]);
+  float o = 0.f;
+  const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
+  const int64_t cstride = (int64_t)Gp * kHeadDim;
+  int c = 0;
+  for (; c + 8 <= nch; c += 8) {
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = op[(c + u) * cstride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) o += t[u];
+  }
+  for (; c < nch; ++c) o += op[c * cstride];
+  const uint16_t* wv = P.w_up_v + d;
+#pragma unroll 16
+  for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wv[(int64_t)cc * kHeadDim]);
+  P.out[orow + d] = (uint16_t)f32_to_bf16_bits(o / lsum);
+  if (d == 0) {
+    if (P.lse) P.lse[(int64_t)b * P.Hq + gh] = (mref + kExpBias + __log2f(lsum)) * kLn2;
+    // exponent arguments above ~60 (relative to the bias) risk overflow of the fp32 sums
+    if (!(xm < 60.0f) || !(lsum > 0.f) || !(lsum < INFINITY)) atomicOr(P.status, 1);
   }
 }
 
@@ -516,7 +568,7 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, h
   }
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_values");
   timing_mark(K_REF_VALUES, st);
-  hipLaunchKernelGGL(k_finalize, dim3(P.Hkv, batch), dim3(128), 0, st, P);
+  hipLaunchKernelGGL(k_finalize, dim3(P.Hq, batch), dim3(128), 0, st, P);
   e = note_hip_error(hipGetLastError(), "launch of finalize");
   timing_mark(K_FINALIZE, st);
   return e;
