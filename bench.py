@@ -26,6 +26,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per k_stream launch at the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
+# plain copy of known size (profiles/decode_cfg3_k_stream.md): read 2.299 GB + written 0.038 GB.
+MEASURED_STREAM_TRAFFIC_CFG3 = 2_337_000_000
 
 
 def log(*a):
@@ -45,6 +48,8 @@ def main():
     ap.add_argument("--rank", type=int, default=64)
     ap.add_argument("--protos", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run 5 plain device copies of this many MiB (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")
@@ -60,6 +65,15 @@ def main():
     from synthetic import generator as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 5}))
+        return
     for kv in args.tune:
         name, val = kv.split("=")
         B.tune(name, int(val))
@@ -137,6 +151,8 @@ def main():
     path_bytes = units * (2 * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
+    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64):
+        roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3
     kernel_ms = {}
     if timing:
         for k, (ms, n) in kern.items():
