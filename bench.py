@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--q-heads", type=int, default=32)
     ap.add_argument("--rank", type=int, default=64)
     ap.add_argument("--protos", type=int, default=1024)
+    ap.add_argument("--mode", choices=["split", "joint"], default="split",
+                    help="split: one rank-r latent per stream (default, the literal config shapes); "
+                         "joint: one rank-r latent per (token, kv-head) over K||V")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run 5 plain device copies of this many MiB (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -81,10 +84,13 @@ def main():
     Bt, L, NL, Hkv, Hq, r, D, s = args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, 128, 16
     scale = 1.0 / np.sqrt(D)
     pages_per_seq, refs_per_seq = -(-L // 16), -(-L // s)
-    dims = dk.make_dims(Hkv, Hq, r, n_pages=Bt * pages_per_seq, n_ref_slots=Bt * refs_per_seq)
+    joint = args.mode == "joint"
+    n_streams = 1 if joint else 2
+    dims = dk.make_dims(Hkv, Hq, r, n_pages=Bt * pages_per_seq, n_ref_slots=Bt * refs_per_seq,
+                        latent_mode=dk.JOINT if joint else dk.SPLIT)
     t_setup = time.time()
     cache = dk.PagedCache(dims, Bt, L, L)
-    W = G.make_projections(G.seed_for(3), D, r)
+    W = G.make_projections(G.seed_for(3), D, r, joint=joint)
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv = dev(W["w_down_k_bf16"]), dev(W["w_down_v_bf16"])
     wuk, wuv = dev(W["w_up_k_bf16"]), dev(W["w_up_v_bf16"])
@@ -147,11 +153,11 @@ def main():
 
     # ---- roofline of the dominant kernel (the streaming pass over latents + indices)
     units = Bt * L * Hkv                                  # (token, kv-head) records per launch
-    stream_bytes = units * (2 * r * 2 + 4)                # two bf16 latent streams + int32 ordinal
-    path_bytes = units * (2 * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
+    stream_bytes = units * (n_streams * r * 2 + 4)                # bf16 latent stream(s) + int32 ordinal
+    path_bytes = units * (n_streams * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64):
+    if (Bt, L, Hkv, Hq, r, joint) == (8, 131072, 8, 32, 64, False):
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3
     kernel_ms = {}
     if timing:
@@ -192,8 +198,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"long-context decode: batch {Bt} x {L} tokens, {NL} layers sequential, "
-                               f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, SPLIT latents, stride {s}, 16-token pages",
-                   "latent_mode": "SPLIT", "keep_ratio": round(dk.keep_ratio(dims), 4),
+                               f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents, stride {s}, 16-token pages",
+                   "latent_mode": args.mode.upper(), "keep_ratio": round(dk.keep_ratio(dims), 4),
                    "layers_are_copies_of_layer0": True},
         "roofline": roof,
         "cpu_baseline": cpu,

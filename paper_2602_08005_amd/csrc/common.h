@@ -26,7 +26,9 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 __host__ __device__ inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
-__host__ __device__ inline int padded_group(int g) { return (g + 3) & ~3; }
+// Query heads per kv-head padded to a power of two (4, 8 or 16): row width of the per-reference tables.
+__host__ __device__ inline int padded_group(int g) { return g <= 4 ? 4 : (g <= 8 ? 8 : 16); }
+__host__ __device__ inline int group_shift(int gp) { return gp == 4 ? 2 : (gp == 8 ? 3 : 4); }
 
 // Token-range split s of a sequence with n_pages pages: pages [p0, p1).  The same arithmetic is used
 // by the streaming kernel (which owns the range) and by the kernels that consume its partial results.

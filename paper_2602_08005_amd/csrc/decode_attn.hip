@@ -144,14 +144,12 @@ template <int R>
 struct Tile {
   static constexpr int NKK = (R + 31) / 32;
   static constexpr int NB = R / 16;
-  uint4 zk[NKK];
-  uint2 zv[NB];
-  int4 id;
-  int nvalid;
+  uint4 zk[NKK];   // scores operand: token l%16, latent chunk l/16 + 4*kk
+  uint2 zv[NB];    // value operand: column l%16 + 16*nb, tokens 4*(l/16)..+3
 };
 
 template <int R, bool JOINT>
-__device__ inline void load_tile(const DecodeParams& P, int page, int h, int nvalid, int l, Tile<R>& t) {
+__device__ inline void load_latents(const DecodeParams& P, int page, int h, int l, Tile<R>& t) {
   const int lg = l >> 4;
   const uint16_t* base = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
 #pragma unroll
@@ -166,8 +164,10 @@ __device__ inline void load_tile(const DecodeParams& P, int page, int h, int nva
 #pragma unroll
     for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (nb * 64 + l) * 4);
   }
-  t.id = *reinterpret_cast<const int4*>(P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + lg * 4);
-  t.nvalid = nvalid;
+}
+__device__ inline int4 load_ordinals(const DecodeParams& P, int page, int h, int l) {
+  return *reinterpret_cast<const int4*>(P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride +
+                                        (l >> 4) * 4);
 }
 
 // Grid: 1-D.  Workgroups are handed to the eight XCDs round-robin by id, and each XCD has its own L2, so
@@ -198,6 +198,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   float* xbuf = lbuf + 16;                                // [NW][16]
   const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // JOINT: per-wave [16 tokens][R + 8] bf16 scratch used to turn the single latent stream (stored in
+  // scores-operand order) into the value-operand order of the P.z product
+  constexpr int TRP = R + 8;
+  uint16_t* tr = reinterpret_cast<uint16_t*>(xbuf + NW * 16) + w * 16 * TRP;
   for (int i = tid; i < n_tab; i += NW * 64) tab[i] = 0.f;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
 
@@ -228,81 +232,129 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   }
   const float* srow = P.sref + bh * P.n_ref_max * Gp + gq;
+  const int gsh = group_shift(Gp);
+  const uint32_t id_hi = (uint32_t)(n_cov - 1);
   __syncthreads();
 
   float4v acc[Tile<R>::NB];
 #pragma unroll
   for (int nb = 0; nb < Tile<R>::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
   float lsum = 0.f, xmax = -INFINITY;
+  // lanes that hold no query head start their accumulator at -inf, so their weights are exactly 0
+  const float cstart = ghead ? cinit : -INFINITY;
 
-  auto gather = [&](Tile<R>& t, float (&sr)[4]) {
-    t.id.x = clampi(t.id.x, 0, n_cov - 1); t.id.y = clampi(t.id.y, 0, n_cov - 1);
-    t.id.z = clampi(t.id.z, 0, n_cov - 1); t.id.w = clampi(t.id.w, 0, n_cov - 1);
-    sr[0] = srow[t.id.x * Gp]; sr[1] = srow[t.id.y * Gp];
-    sr[2] = srow[t.id.z * Gp]; sr[3] = srow[t.id.w * Gp];
+  auto gather = [&](int4& id, float (&sr)[4]) {
+    // stored ordinals are clamped (unsigned min: negatives become the last ordinal), never trusted
+    id.x = (int)min((uint32_t)id.x, id_hi); id.y = (int)min((uint32_t)id.y, id_hi);
+    id.z = (int)min((uint32_t)id.z, id_hi); id.w = (int)min((uint32_t)id.w, id_hi);
+    sr[0] = srow[(uint32_t)id.x << gsh]; sr[1] = srow[(uint32_t)id.y << gsh];
+    sr[2] = srow[(uint32_t)id.z << gsh]; sr[3] = srow[(uint32_t)id.w << gsh];
   };
-  auto compute = [&](Tile<R>& t, const float (&sr)[4]) {
-    float4v d = {cinit, cinit, cinit, cinit};
+  auto compute = [&](Tile<R>& t, const int4& id, const float (&sr)[4], const int nvalid) {
+    float4v d = {cstart, cstart, cstart, cstart};
 #pragma unroll
     for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
       d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qbl[kk], d, 0, 0, 0);
       d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qb[kk], d, 0, 0, 0);
     }
-    const int ids[4] = {t.id.x, t.id.y, t.id.z, t.id.w};
+    const int ids[4] = {id.x, id.y, id.z, id.w};
     float p[4];
+    if (nvalid >= kPage) {       // full page: no per-token masking
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const bool ok = ghead && (4 * lg + e < t.nvalid);
-      const float x = ok ? d[e] + sr[e] : -INFINITY;
-      xmax = fmaxf(xmax, x);
-      p[e] = __builtin_amdgcn_exp2f(x);
-      lsum += p[e];
-      if (ok) atomicAdd(&tab[ids[e] * Gp + ln], p[e]);
+      for (int e = 0; e < 4; ++e) {
+        const float x = d[e] + sr[e];
+        xmax = fmaxf(xmax, x);
+        p[e] = __builtin_amdgcn_exp2f(x);
+        lsum += p[e];
+      }
+    } else {                       // tail page, or a pipeline slot past the range (nvalid <= 0)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x = (4 * lg + e < nvalid) ? d[e] + sr[e] : -INFINITY;   // select, not arithmetic:
+        xmax = fmaxf(xmax, x);                                               // garbage slots may hold NaN
+        p[e] = __builtin_amdgcn_exp2f(x);
+        lsum += p[e];
+      }
+    }
+    if (ghead) {                   // weights of masked tokens are 0; their (clamped) ordinal is a valid entry
+#pragma unroll
+      for (int e = 0; e < 4; ++e) atomicAdd(&tab[((uint32_t)ids[e] << gsh) + ln], p[e]);
     }
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
     pk.y = pack_bf16(p[2], p[3]);
     const short4v pa = __builtin_bit_cast(short4v, pk);
-    if (!JOINT) {
-      if (t.nvalid < kPage) {    // tail page (or a pipeline slot past the range): mask slots that hold garbage
+    if (JOINT) {
 #pragma unroll
-        for (int nb = 0; nb < Tile<R>::NB; ++nb) {
-          const int left = t.nvalid - 4 * lg;   // valid tokens among this lane's four
-          if (left < 4) t.zv[nb].y &= left < 3 ? 0u : 0x0000ffffu;
-          if (left < 2) t.zv[nb].x &= left < 1 ? 0u : 0x0000ffffu;
-        }
+      for (int kk = 0; kk < Tile<R>::NKK; ++kk)
+        if (4 * kk + lg < R / 8) *reinterpret_cast<uint4*>(tr + ln * TRP + (4 * kk + lg) * 8) = t.zk[kk];
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+        const uint16_t* src = tr + (4 * lg) * TRP + nb * 16 + ln;
+        t.zv[nb].x = (uint32_t)src[0] | ((uint32_t)src[TRP] << 16);
+        t.zv[nb].y = (uint32_t)src[2 * TRP] | ((uint32_t)src[3 * TRP] << 16);
       }
+      __builtin_amdgcn_wave_barrier();
+    }
+    if (nvalid < kPage) {    // mask value-operand slots that hold garbage
 #pragma unroll
-      for (int nb = 0; nb < Tile<R>::NB; ++nb)
-        acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(short4v, t.zv[nb]), acc[nb], 0, 0, 0);
+      for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+        const int left = nvalid - 4 * lg;   // valid tokens among this lane's four
+        if (left < 4) t.zv[nb].y &= left < 3 ? 0u : 0x0000ffffu;
+        if (left < 2) t.zv[nb].x &= left < 1 ? 0u : 0x0000ffffu;
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+      acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(short4v, t.zv[nb]), acc[nb], 0, 0, 0);
     }
   };
 
-  // Software pipeline over this wave's pages p0+w, p0+w+NW, ...: in steady state ST-1 pages of loads are in
-  // flight and the score gather of the next page has been issued while the current page is computed.  Every
-  // load in the loop is unconditional (slots past the wave's range re-read its last page and are computed
-  // with zero valid tokens), so the hardware wait counters can be set exactly.
+  // Software pipeline over this wave's pages p0+w, p0+w+NW, ...  While page i is computed, the ordinals of
+  // page i+LZ+1, the latents of page i+LZ and the per-reference score gather of page i+LG are in flight.  The
+  // vector-memory counter retires in order, so what may still be outstanding when page i is computed is what
+  // was issued after gather(i): LG pages of loads.  LG is therefore chosen as large as the 6-bit counter and
+  // the register file allow (about 16 KB in flight per wave), which is what covers HBM latency with only two
+  // waves per SIMD.  Every load in the loop is unconditional (slots past the wave's range re-read its last
+  // page and are computed with zero valid tokens), so the wait counts can be set exactly.
   const int n_my = (p1 - p0 - w + NW - 1) / NW;            // pages of this wave
   if (n_my > 0) {
+    constexpr int LZ = ST - 2, LG = ST - 3;
+    static_assert(ST >= 4, "ring size");
     const int32_t* bt = P.block_tables + (int64_t)b * P.bt_stride;
-    auto page_id = [&](int i) {                               // pool page of this wave's i-th page (clamped)
-      const int ii = i < n_my ? i : n_my - 1;
-      return clampi(bt[p0 + w + ii * NW], 0, (int)P.n_pages_pool - 1);
+    // Blocks start at different points of their (cyclic) page range: ranges of different sequences and splits
+    // begin at large power-of-two distances, and blocks that advance in lockstep from such addresses would
+    // keep hitting the same HBM channels.  The order is free because every partial sum simply adds.
+    const int rot = (int)(((uint32_t)pair * 2654435761u + (uint32_t)s * 40503u) >> 8) % n_my;
+    auto slot_of = [&](int i) {                               // i-th page of this wave in rotated order
+      int ii = (i < n_my ? i : n_my - 1) + rot;
+      return ii >= n_my ? ii - n_my : ii;
     };
-    auto valid_of = [&](int i) { return i < n_my ? L - (p0 + w + i * NW) * kPage : 0; };
+    auto page_id = [&](int i) {                               // its pool page (clamped into the pool)
+      return clampi(bt[p0 + w + slot_of(i) * NW], 0, (int)P.n_pages_pool - 1);
+    };
+    auto valid_of = [&](int i) { return i < n_my ? L - (p0 + w + slot_of(i) * NW) * kPage : 0; };
     Tile<R> t[ST];
+    int4 id[ST];
     float sr[ST][4];
+    int pg[ST];
 #pragma unroll
-    for (int u = 0; u < ST - 1; ++u) load_tile<R, JOINT>(P, page_id(u), h, valid_of(u), l, t[u]);
-    int pg_next = page_id(ST - 1);
-    gather(t[0], sr[0]);
+    for (int u = 0; u < ST; ++u) pg[u] = page_id(u);
+#pragma unroll
+    for (int u = 0; u < LZ + 1; ++u) id[u] = load_ordinals(P, pg[u], h, l);
+#pragma unroll
+    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT>(P, pg[u], h, l, t[u]);
+#pragma unroll
+    for (int u = 0; u < LG; ++u) gather(id[u], sr[u]);
     for (int i = 0; i < n_my; i += ST) {
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
-        load_tile<R, JOINT>(P, pg_next, h, valid_of(i + u + ST - 1), l, t[(u + ST - 1) % ST]);
-        pg_next = page_id(i + u + ST);
-        gather(t[(u + 1) % ST], sr[(u + 1) % ST]);
-        compute(t[u], sr[u]);
+        id[(u + LZ + 1) % ST] = load_ordinals(P, pg[(u + LZ + 1) % ST], h, l);
+        load_latents<R, JOINT>(P, pg[(u + LZ) % ST], h, l, t[(u + LZ) % ST]);
+        pg[u] = page_id(i + u + ST);
+        gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
+        compute(t[u], id[u], sr[u], valid_of(i + u));
       }
     }
   }
@@ -516,7 +568,12 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 template <int R, int NW, bool JOINT>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
-  constexpr int ST = NW >= 16 ? 3 : 4;   // pipeline slots per wave
+  // Ring slots of the software pipeline.  Measured on MI355X: beyond three pages of latents in flight per wave
+  // (ST = 5) the kernel does not get faster -- with all arithmetic removed the same load stream runs only 7 %
+  // faster -- and longer rings only cost registers and instruction-cache footprint.
+  constexpr int NKK = (R + 31) / 32, NB = R / 16;
+  constexpr int regs_per_page = 4 * NKK + (JOINT ? 0 : 2 * NB) + 8;
+  constexpr int ST = (5 * regs_per_page <= 150) ? 5 : 4;
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT>),
@@ -543,8 +600,10 @@ static hipError_t dispatch_stream(const DecodeParams& P, dim3 grid, size_t lds, 
   return hipErrorInvalidValue;
 }
 
-size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw) {
-  return (size_t)(((n_ref_max * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
+size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint) {
+  size_t b = (size_t)(((n_ref_max * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
+  if (joint) b += (size_t)nw * 16 * (R + 8) * 2;
+  return b;
 }
 
 hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st) {
@@ -555,14 +614,15 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, h
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);
   dim3 gs(ceil_div(batch * P.Hkv, 8) * 8 * P.S);
-  if (P.joint) return hipErrorInvalidValue;   // JOINT streaming kernel: not built yet
-  e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
+  if (P.joint)
+    e = (nw == 16) ? dispatch_stream<16, true>(P, gs, lds, st) : dispatch_stream<8, true>(P, gs, lds, st);
+  else
+    e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
   if (e != hipSuccess) return e;
   timing_mark(K_STREAM, st);
   switch (P.Gp) {
     case 4: hipLaunchKernelGGL(k_ref_values<4>, gchunk, dim3(256), 0, st, P); break;
     case 8: hipLaunchKernelGGL(k_ref_values<8>, gchunk, dim3(256), 0, st, P); break;
-    case 12: hipLaunchKernelGGL(k_ref_values<12>, gchunk, dim3(256), 0, st, P); break;
     case 16: hipLaunchKernelGGL(k_ref_values<16>, gchunk, dim3(256), 0, st, P); break;
     default: return hipErrorInvalidValue;
   }

@@ -226,11 +226,10 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   if (max_pages > bt_stride || n_ref_max > rt_stride) return DELTAKV_E_INVALID_ARG;
   if ((int64_t)max_pages > dims->n_pages * 1ll || (int64_t)n_ref_max > dims->n_ref_slots * 1ll)
     return DELTAKV_E_INVALID_ARG;
-  if (dims->latent_mode == DELTAKV_JOINT) return DELTAKV_E_UNSUPPORTED;   // JOINT streaming kernel: not built yet
 
   const int G = dims->n_q_heads / dims->n_kv_heads, Gp = padded_group(G), R = dims->rank;
   const int nw = g_tune_stream_waves ? g_tune_stream_waves : 8;
-  const size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw);
+  const size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw, dims->latent_mode == DELTAKV_JOINT);
   const size_t kLdsLimit = device_lds_limit();
   if (lds > kLdsLimit) return DELTAKV_E_UNSUPPORTED;
   int per_cu = (int)(kLdsLimit / lds);

@@ -88,7 +88,7 @@ enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K
 void timing_mark(int kernel_id, hipStream_t st);
 
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
-size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw);
+size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint);
 // Enqueues the four decode kernels on `st`.
 hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st);
 

@@ -92,6 +92,18 @@ def test_ranks_and_group_sizes(r, Hkv, Hq):
     _compare(case, got, lse, 0.09)
 
 
+@pytest.mark.parametrize("r,Hkv,Hq,L", [(64, 8, 32, 2048), (48, 4, 28, 1111), (16, 1, 1, 300), (128, 2, 4, 530), (96, 1, 12, 77)])
+def test_joint_mode(r, Hkv, Hq, L):
+    """One latent per (token, kv-head) over K||V, used both for scores and for values."""
+    from tests.helpers import Case
+    case = Case(2500 + r + Hq, [L, L // 3], Hkv=Hkv, Hq=Hq, r=r, n_proto=16, joint=True)
+    cache = _setup(case, page_perm_seed=r)
+    scale = 1.0 / np.sqrt(128)
+    got, lse, status = _run(case, cache, scale)
+    assert status == 0
+    _compare(case, got, lse, scale)
+
+
 def test_batch_of_mixed_lengths_paged_and_contiguous_agree():
     """Random page / slot permutation over a shared pool gives the same bits as the contiguous layout."""
     from tests.helpers import Case
