@@ -210,9 +210,9 @@ int deltakv_tune(const char* name, int32_t value);
  * returns, per kernel, the summed time between the surrounding events in milliseconds (this includes
  * the launch gap in front of the kernel) and the number of launches.  Kernel order:
  *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
- *   4 admit_refs, 5 sim_top2, 6 select_project          (deltakv_compress)
+ *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress)
  * Arrays are host memory with n >= DELTAKV_N_KERNELS entries.  Errors: INVALID_ARG, HIP. */
-#define DELTAKV_N_KERNELS 7
+#define DELTAKV_N_KERNELS 9
 int deltakv_timing_begin(void);
 int deltakv_timing_end(float* ms_by_kernel, int32_t* launches_by_kernel, int32_t n);
 

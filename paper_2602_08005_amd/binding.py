@@ -80,7 +80,8 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", "sim_top2", "select_project")
+KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", "sim_top2", "resolve", "exact",
+                "project")
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn")

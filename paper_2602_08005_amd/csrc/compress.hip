@@ -5,15 +5,18 @@
 // "lifecycle management": residual against the assigned reference -> down-projection -> write to the
 // latent pool; appendix B.3: the reference search is a dense matrix product.
 //
-// Three kernels per call:
-//   admit_refs     : new tokens at multiples of s are copied raw into the reference pool, with 1/||K||V||
-//   sim_top2       : MFMA GEMM [new tokens x 256] . [references x 256]^T per kv-head with a fused
-//                    epilogue that scales by the reference's inverse norm, applies the causal candidate
-//                    mask and keeps (best, second best, arg best) per token -- scores never leave the chip
-//   select_project : merges reference-range splits, re-scores in fp64 every token whose two best fp32
-//                    scores are closer than the fp32 error bound (so the stored ordinal is the exact
-//                    arg-max), forms the residual in fp32, splits it into bf16 hi+lo parts, projects with
-//                    W_down on MFMA and writes bf16 latents + ordinals into the token's page
+// Five kernels per call:
+//   admit_refs : new tokens at multiples of s are copied raw into the reference pool, with 1/||K||V||
+//   sim_top2   : MFMA GEMM [new tokens x 256] . [references x 256]^T per kv-head with a fused epilogue that
+//                scales by the reference's inverse norm, applies the causal candidate mask and keeps
+//                (best, second best, arg best) per token -- scores never leave the chip
+//   resolve    : merges reference-range splits; a token whose two best fp32 scores are closer than the fp32
+//                error bound is queued for exact re-scoring, every other token gets its ordinal
+//   exact      : queued tokens, 16 at a time, against all their candidates on the fp64 matrix unit
+//                (v_mfma_f64_16x16x4) with the definition's formula, so the stored ordinal is the exact
+//                arg-max with lowest-ordinal tie-break
+//   project    : residual in fp32 (exact for bf16 inputs), split into bf16 hi+lo parts, W_down on MFMA,
+//                bf16 latents + ordinals written into the token's page
 #include "common.h"
 #include "launch.h"
 
@@ -32,6 +35,8 @@ __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // large
 // admit_refs: one wave per (new token, kv-head); grid (ceil(n_new*Hkv/4)), 256 threads.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
+  if (blockIdx.x == 0)   // queue counters of the exact re-scoring pass (cleared here, not by a memset node)
+    for (int i = threadIdx.x; i < P.batch * P.Hkv; i += 256) P.flag_count[i] = 0;
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int l = threadIdx.x & 63;
   if (item >= P.n_new_total * P.Hkv) return;
@@ -115,6 +120,22 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
       a[rb][kk] = __builtin_bit_cast(bf16x8, x);
       a[rb][4 + kk] = __builtin_bit_cast(bf16x8, y);
     }
+  }
+  // squared norm of each token row (lane ln ends up with the value of row ln of every row block)
+  float na2[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float ss = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const uint4 u = __builtin_bit_cast(uint4, a[rb][kk]);
+      const uint32_t uu[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ss += bf16lo(uu[e]) * bf16lo(uu[e]) + bf16hi(uu[e]) * bf16hi(uu[e]);
+    }
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    na2[rb] = ss;
   }
   Top2 best[RB][4];
 #pragma unroll
@@ -221,9 +242,10 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
         top2_merge(t, ob, os, oi);
       }
       const int r = row0 + rb * 16 + 4 * lg + i;
+      const float n2 = __shfl(na2[rb], 4 * lg + i);
       if (ln == 0 && r < n_new) {
         float4 o;
-        o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = 0.f;
+        o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = n2;
         const int64_t n = P.cu_new[b] + r;
         *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
       }
@@ -231,13 +253,167 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// select_project: grid (page_tiles_max, B), 256 threads; wave w handles kv-heads w, w+4, ...
+// resolve: one thread per (new token, kv-head); grid ceil(n_new*Hkv/256).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
+  const int item = blockIdx.x * 256 + threadIdx.x;
+  if (item >= P.n_new_total * P.Hkv) return;
+  const int n = item / P.Hkv, h = item % P.Hkv;
+  const int b = find_seq(P.cu_new, P.batch, n);
+  const int pos = P.len_before[b] + (n - P.cu_new[b]);
+  int ord;
+  if (pos % P.stride == 0) {
+    ord = pos / P.stride;
+  } else {
+    // merge the reference-range splits (ascending ranges: strict '>' keeps the lowest ordinal)
+    float bb = -INFINITY, b2 = -INFINITY, na2 = 0.f;
+    int bi = -1;
+    const float4* pp = reinterpret_cast<const float4*>(P.part) + (int64_t)item * P.NS;
+    for (int s = 0; s < P.NS; ++s) {
+      const float4 o = pp[s];
+      na2 = o.w;
+      const int oi = __float_as_int(o.z);
+      if (oi < 0) continue;
+      if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
+      else b2 = fmaxf(b2, o.x);
+    }
+    // fp32 scores carry an error of at most ~256 * 2^-24 |a||b|; closer pairs are re-scored exactly
+    if (bi < 0 || !(bb - b2 > 1e-4f * sqrtf(na2))) {
+      const int at = atomicAdd(&P.flag_count[b * P.Hkv + h], 1);
+      P.flag_list[(int64_t)h * P.n_new_total + P.cu_new[b] + at] = n;
+      ord = 0;
+    } else {
+      ord = bi;
+    }
+  }
+  P.ord[item] = ord;
+}
+
+// ------------------------------------------------------------------------------------------------
+// exact: grid (kExactX, B*Hkv), 256 threads.  A block takes 16 queued tokens of its (sequence, kv-head) at a
+// time; its four waves share the candidate references (wave w takes reference tiles w, w+4, ...).
+// D[token][ref] = sum_d a[token][d] b[ref][d] in fp64 on v_mfma_f64_16x16x4 (operand layout checked on the
+// hardware with one-hot inputs): lane (ln, lg) supplies element e
+// of its 8-wide chunk as the k = lg slot of step (kk, e), identically for both operands.
+// ------------------------------------------------------------------------------------------------
+constexpr int kExactX = 32;
+typedef double double4v __attribute__((ext_vector_type(4)));
+
+__device__ inline double bf16_elem_f64(const uint4& c, int e) {
+  const uint32_t u = (e < 2) ? c.x : (e < 4) ? c.y : (e < 6) ? c.z : c.w;
+  return (double)((e & 1) ? bf16hi(u) : bf16lo(u));
+}
+
+__global__ __launch_bounds__(256) void k_exact(CompressParams P) {
+  const int b = blockIdx.y / P.Hkv, h = blockIdx.y % P.Hkv;
+  const int cnt = P.flag_count[blockIdx.y];
+  const int n_tiles = ceil_div(cnt, 16);
+  if ((int)blockIdx.x >= n_tiles) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int lb = P.len_before[b];
+  const int32_t* list = P.flag_list + (int64_t)h * P.n_new_total + P.cu_new[b];
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+  const uint16_t* refk = P.ref + (int64_t)h * P.ref_head_stride;
+  const uint16_t* refv = refk + P.ref_kv_stride;
+  __shared__ double red_c[4][16];
+  __shared__ int red_j[4][16];
+
+  for (int tile = blockIdx.x; tile < n_tiles; tile += kExactX) {
+    // lane ln <-> queued token tile*16 + ln (rows past the end repeat the last one and are not written)
+    const int qi = min(tile * 16 + ln, cnt - 1);
+    const int n = list[qi];
+    const int pos = lb + (n - P.cu_new[b]);
+    const uint16_t* ak = P.k_new + ((int64_t)n * P.Hkv + h) * kHeadDim;
+    const uint16_t* av = P.v_new + ((int64_t)n * P.Hkv + h) * kHeadDim;
+    uint4 a[8];
+    double na2 = 0.0;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      a[kk] = *reinterpret_cast<const uint4*>(ak + (4 * kk + lg) * 8);
+      a[4 + kk] = *reinterpret_cast<const uint4*>(av + (4 * kk + lg) * 8);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const double x = bf16_elem_f64(a[kk], e); na2 += x * x; }
+    na2 += __shfl_xor(na2, 16);
+    na2 += __shfl_xor(na2, 32);
+    const double na = sqrt(na2);
+    int pmax = pos;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) pmax = max(pmax, __shfl_xor(pmax, o));
+    const int ncand = min(refs_below(pmax, P.stride), P.rt_stride);
+    // accumulator register i of the fp64 MFMA holds token row 4*i + lg (rows are interleaved over the lane
+    // groups, unlike the 32-bit variants where a lane group holds four consecutive rows)
+    double na_row[4];
+    int pos_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { na_row[i] = __shfl(na, 4 * i + lg); pos_row[i] = __shfl(pos, 4 * i + lg); }
+    double cbest[4] = {-1e300, -1e300, -1e300, -1e300};
+    int jbest[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+    for (int rt = w; rt * 16 < ncand; rt += 4) {
+      const int j = rt * 16 + ln;
+      const int slot = clampi(rtab[min(j, ncand - 1)], 0, (int)P.n_ref_slots - 1);
+      uint4 bq[8];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bq[kk] = *reinterpret_cast<const uint4*>(refk + (int64_t)slot * kHeadDim + (4 * kk + lg) * 8);
+        bq[4 + kk] = *reinterpret_cast<const uint4*>(refv + (int64_t)slot * kHeadDim + (4 * kk + lg) * 8);
+      }
+      double nb2 = 0.0;
+      double4v acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const double x = bf16_elem_f64(a[kk], e), y = bf16_elem_f64(bq[kk], e);
+          nb2 += y * y;
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x, y, acc, 0, 0, 0);
+        }
+      nb2 += __shfl_xor(nb2, 16);
+      nb2 += __shfl_xor(nb2, 32);
+      const double nb = sqrt(nb2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const double den = na_row[i] * nb;
+        const double c = den > 0.0 ? acc[i] / den : 0.0;
+        const bool ok = j < ncand && (int64_t)j * P.stride < pos_row[i];
+        if (ok && c > cbest[i]) { cbest[i] = c; jbest[i] = j; }   // ascending j per lane: strict '>'
+      }
+    }
+    // best over the 16 reference lanes, then over the four waves; ties go to the lower ordinal
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) {
+        const double oc = __shfl_xor(cbest[i], o);
+        const int oj = __shfl_xor(jbest[i], o);
+        if (oc > cbest[i] || (oc == cbest[i] && oj < jbest[i])) { cbest[i] = oc; jbest[i] = oj; }
+      }
+      if (ln == 0) { red_c[w][4 * i + lg] = cbest[i]; red_j[w][4 * i + lg] = jbest[i]; }
+    }
+    __syncthreads();
+    if (tid < 16 && tile * 16 + tid < cnt) {
+      double c = red_c[0][tid];
+      int j = red_j[0][tid];
+#pragma unroll
+      for (int ww = 1; ww < 4; ++ww)
+        if (red_c[ww][tid] > c || (red_c[ww][tid] == c && red_j[ww][tid] < j)) { c = red_c[ww][tid]; j = red_j[ww][tid]; }
+      const int nn = list[tile * 16 + tid];
+      P.ord[(int64_t)nn * P.Hkv + h] = (j == 0x7fffffff) ? 0 : j;
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// project: grid (page_tiles_max, B), 256 threads; wave w handles kv-heads w, w+4, ...
 // A wave owns one page of one sequence: lane (ln, lg) <-> token slot ln of the page, 8-wide chunk.
 // ------------------------------------------------------------------------------------------------
 constexpr int kWPad = 136;   // bf16 elements per staged W_down^T row (128 + 8)
 
 template <int R>
-__global__ __launch_bounds__(256) void k_select_project(CompressParams P) {
+__global__ __launch_bounds__(256) void k_project(CompressParams P) {
   constexpr int NB = R / 16;
   extern __shared__ uint16_t wlds[];   // [2][R][kWPad]: W_dK^T, W_dV^T
   const int b = blockIdx.y;
@@ -265,75 +441,7 @@ __global__ __launch_bounds__(256) void k_select_project(CompressParams P) {
   for (int h = w; h < P.Hkv; h += 4) {
     const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
     const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
-    uint4 xk[4], xv[4];
-    float ss = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      xk[kk] = *reinterpret_cast<const uint4*>(kr + (4 * kk + lg) * 8);
-      xv[kk] = *reinterpret_cast<const uint4*>(vr + (4 * kk + lg) * 8);
-      const uint32_t u[8] = {xk[kk].x, xk[kk].y, xk[kk].z, xk[kk].w, xv[kk].x, xv[kk].y, xv[kk].z, xv[kk].w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ss += bf16lo(u[e]) * bf16lo(u[e]) + bf16hi(u[e]) * bf16hi(u[e]);
-    }
-    ss += __shfl_xor(ss, 16);
-    ss += __shfl_xor(ss, 32);
-    const float na = sqrtf(ss);
-    // merge the reference-range splits (ascending ranges: strict '>' keeps the lowest ordinal)
-    float bb = -INFINITY, b2 = -INFINITY;
-    int bi = -1;
-    if (tok_ok && !is_ref) {
-      const float4* pp = reinterpret_cast<const float4*>(P.part) + (n * P.Hkv + h) * P.NS;
-      for (int s = 0; s < P.NS; ++s) {
-        const float4 o = pp[s];
-        const int oi = __float_as_int(o.z);
-        if (oi < 0) continue;
-        if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
-        else b2 = fmaxf(b2, o.x);
-      }
-    }
-    int ord = is_ref ? pos / P.stride : bi;
-    // fp32 scores carry an error of at most ~256 * 2^-24 of |a||b|; closer pairs are re-scored in fp64
-    bool amb = tok_ok && !is_ref && (bi < 0 || !(bb - b2 > 1e-4f * na));
-    uint64_t todo = __ballot(amb && lg == 0);
-    while (todo) {
-      const int src = __ffsll((unsigned long long)todo) - 1;   // lane (ln = src, lg = 0)
-      todo &= todo - 1;
-      const int spos = lp * kPage + src;
-      const int64_t sn = P.cu_new[b] + (spos - lb);
-      const int ncand = min(refs_below(spos, P.stride), P.rt_stride);
-      const uint16_t* ak = P.k_new + (sn * P.Hkv + h) * kHeadDim;
-      const uint16_t* av = P.v_new + (sn * P.Hkv + h) * kHeadDim;
-      double aa = 0.0;
-      for (int d = 0; d < kHeadDim; ++d) {
-        const double x = (double)bf16lo(ak[d]), y = (double)bf16lo(av[d]);
-        aa += x * x + y * y;
-      }
-      const double dna = sqrt(aa);
-      double cbest = -1e300;
-      int jbest = 0x7fffffff;
-      for (int j = l; j < ncand; j += 64) {
-        const int slot = clampi(rtab[j], 0, (int)P.n_ref_slots - 1);
-        const uint16_t* bk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
-        const uint16_t* bv = bk + P.ref_kv_stride;
-        double dot = 0.0, nb2 = 0.0;
-        for (int d = 0; d < kHeadDim; ++d) {
-          const double x = (double)bf16lo(bk[d]), y = (double)bf16lo(bv[d]);
-          dot += (double)bf16lo(ak[d]) * x + (double)bf16lo(av[d]) * y;
-          nb2 += x * x + y * y;
-        }
-        const double den = dna * sqrt(nb2);
-        const double c = den > 0.0 ? dot / den : 0.0;
-        if (c > cbest) { cbest = c; jbest = j; }
-      }
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const double oc = __shfl_xor(cbest, o);
-        const int oj = __shfl_xor(jbest, o);
-        if (oc > cbest || (oc == cbest && oj < jbest)) { cbest = oc; jbest = oj; }
-      }
-      if (ln == src) ord = jbest;
-    }
-    ord = clampi(ord, 0, P.rt_stride - 1);
+    const int ord = clampi(P.ord[n * P.Hkv + h], 0, P.rt_stride - 1);
     // residual against the chosen raw reference, fp32 (exact for bf16 inputs), split into bf16 hi + lo
     const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
     const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
@@ -344,7 +452,7 @@ __global__ __launch_bounds__(256) void k_select_project(CompressParams P) {
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        const uint4 x = st ? xv[kk] : xk[kk];
+        const uint4 x = *reinterpret_cast<const uint4*>((st ? vr : kr) + (4 * kk + lg) * 8);
         const uint4 y = *reinterpret_cast<const uint4*>((st ? rv : rk) + (4 * kk + lg) * 8);
         const uint32_t xu[4] = {x.x, x.y, x.z, x.w}, yu[4] = {y.x, y.y, y.z, y.w};
         uint32_t hi[4], lo[4];
@@ -352,9 +460,8 @@ __global__ __launch_bounds__(256) void k_select_project(CompressParams P) {
         for (int e = 0; e < 4; ++e) {
           float r0 = bf16lo(xu[e]) - bf16lo(yu[e]), r1 = bf16hi(xu[e]) - bf16hi(yu[e]);
           if (zero) { r0 = 0.f; r1 = 0.f; }
-          const uint32_t h0 = f32_to_bf16_bits(r0), h1 = f32_to_bf16_bits(r1);
-          hi[e] = h0 | (h1 << 16);
-          lo[e] = pack_bf16(r0 - __uint_as_float(h0 << 16), r1 - __uint_as_float(h1 << 16));
+          hi[e] = pack_bf16(r0, r1);
+          lo[e] = pack_bf16(r0 - bf16lo(hi[e]), r1 - bf16hi(hi[e]));
         }
         res[st][kk][0] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
         res[st][kk][1] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
@@ -437,13 +544,13 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
   const size_t lds = 2 * R * kWPad * 2;
   static bool attr_set = false;
   if (!attr_set && lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_select_project<R>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project<R>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(projection kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_select_project<R>), grid, dim3(256), lds, st, P);
-  return note_hip_error(hipGetLastError(), "launch of select_project");
+  hipLaunchKernelGGL((k_project<R>), grid, dim3(256), lds, st, P);
+  return note_hip_error(hipGetLastError(), "launch of project");
 }
 
 int sim_tile_rows(int rb) { return 64 * rb; }
@@ -464,6 +571,12 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
   }
   if (e != hipSuccess) return e;
   timing_mark(K_SIM, st);
+  hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
+  timing_mark(K_RESOLVE, st);
+  hipLaunchKernelGGL(k_exact, dim3(kExactX, P.batch * P.Hkv), dim3(256), 0, st, P);
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
+  timing_mark(K_EXACT, st);
   dim3 gp(page_tiles_max, P.batch);
   e = hipErrorInvalidValue;
   switch (P.R) {

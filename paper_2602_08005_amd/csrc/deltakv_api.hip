@@ -355,8 +355,10 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   const int64_t ref_tiles = ceil_div64(ceil_div64(max_len_after, S), 64);
   if (ns > ref_tiles) ns = ref_tiles;
   if (ns > 64) ns = 64;
+  const CompressWs cw = plan_compress_ws(*dims, batch, n_new_total, 0);
   const int64_t per_split = (int64_t)n_new_total * dims->n_kv_heads * 16;
-  if (ns > ws_bytes / per_split) ns = ws_bytes / per_split;
+  if (ws_bytes < cw.part + per_split) return DELTAKV_E_WORKSPACE;
+  if (ns > (ws_bytes - cw.part) / per_split) ns = (ws_bytes - cw.part) / per_split;
   if (ns < 1) return DELTAKV_E_WORKSPACE;
   if (tiles_max > 65535 * 32768ll || page_tiles_max <= 0) return DELTAKV_E_UNSUPPORTED;
 
@@ -393,7 +395,11 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.stride = S;
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
   Pm.NS = (int)ns;
-  Pm.part = static_cast<float*>(workspace);
+  char* wsb = static_cast<char*>(workspace);
+  Pm.ord = reinterpret_cast<int32_t*>(wsb + cw.ord);
+  Pm.flag_count = reinterpret_cast<int32_t*>(wsb + cw.flag_count);
+  Pm.flag_list = reinterpret_cast<int32_t*>(wsb + cw.flag_list);
+  Pm.part = reinterpret_cast<float*>(wsb + cw.part);
   hipError_t e = launch_compress(Pm, rb, tiles_max, page_tiles_max, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }

@@ -63,17 +63,27 @@ struct CompressParams {
   int batch, n_new_total;
   int Hkv, R, stride, joint;
   int NS;            // reference-range splits of the similarity search
-  float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), unused
+  float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), |token|^2
+  int32_t* ord;        // [n_new_total][Hkv] chosen reference ordinal
+  int32_t* flag_count; // [batch][Hkv] tokens queued for exact re-scoring
+  int32_t* flag_list;  // [Hkv][n_new_total] queued token indices, sequence b's segment starts at cu_new[b]
 };
 
 struct CompressWs {
-  int64_t part;
+  int64_t ord, flag_count, flag_list, part;   // byte offsets; `part` takes everything from its offset on
   int64_t total;
 };
-inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t max_batch, int64_t max_new_tokens, int64_t) {
+// Offsets for a call with n_new tokens in total; `total` is sized for max_new_tokens with room for up to
+// 64 reference-range splits of small calls.
+inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t n_new, int64_t) {
   CompressWs w;
-  w.part = 0;
-  w.total = align_up((max_new_tokens + 64 * max_batch) * d.n_kv_heads * 16, 256);
+  int64_t o = 0;
+  auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
+  w.ord = take(n_new * d.n_kv_heads * 4);
+  w.flag_count = take(batch * d.n_kv_heads * 4);
+  w.flag_list = take(n_new * d.n_kv_heads * 4);
+  w.part = o;
+  w.total = o + align_up((n_new + 64 * batch) * d.n_kv_heads * 16, 256);
   return w;
 }
 
@@ -84,7 +94,7 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
 
 // Optional per-kernel timing (deltakv_timing_begin / deltakv_timing_end): when enabled, launchers call
 // timing_mark(kernel_id, stream) before the first kernel (id -1) and after every kernel.
-enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_PROJECT, K_COUNT };
+enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_RESOLVE, K_EXACT, K_PROJECT, K_COUNT };
 void timing_mark(int kernel_id, hipStream_t st);
 
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
