@@ -32,23 +32,22 @@ __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // large
 }
 
 // ------------------------------------------------------------------------------------------------
-// admit_refs: one wave per (new token, kv-head); grid (ceil(n_new*Hkv/4)), 256 threads.
+// admit_refs: one wave per (new reference token, kv-head); grid (ceil(max new refs * Hkv / 4), B), 256 threads.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
-  if (blockIdx.x == 0)   // queue counters of the exact re-scoring pass (cleared here, not by a memset node)
+  if (blockIdx.x == 0 && blockIdx.y == 0)   // queue counters of the exact pass (cleared here, not by a memset node)
     for (int i = threadIdx.x; i < P.batch * P.Hkv; i += 256) P.flag_count[i] = 0;
+  const int b = blockIdx.y;
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int l = threadIdx.x & 63;
-  if (item >= P.n_new_total * P.Hkv) return;
-  const int n = item / P.Hkv, h = item % P.Hkv;
-  const int b = find_seq(P.cu_new, P.batch, n);
-  const int pos = P.len_before[b] + (n - P.cu_new[b]);
-  if (pos % P.stride != 0) return;
-  const int ord = pos / P.stride;
-  if (ord >= P.rt_stride) return;
+  const int lb = P.len_before[b], la = lb + P.cu_new[b + 1] - P.cu_new[b];
+  const int ord = refs_below(lb, P.stride) + item / P.Hkv, h = item % P.Hkv;   // first new reference: ceil(lb / s)
+  const int64_t pos = (int64_t)ord * P.stride;
+  if (pos >= la || ord >= P.rt_stride) return;
+  const int64_t n = P.cu_new[b] + (pos - lb);
   const int slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
-  const uint32_t kx = reinterpret_cast<const uint32_t*>(P.k_new + ((int64_t)n * P.Hkv + h) * kHeadDim)[l];
-  const uint32_t vx = reinterpret_cast<const uint32_t*>(P.v_new + ((int64_t)n * P.Hkv + h) * kHeadDim)[l];
+  const uint32_t kx = reinterpret_cast<const uint32_t*>(P.k_new + (n * P.Hkv + h) * kHeadDim)[l];
+  const uint32_t vx = reinterpret_cast<const uint32_t*>(P.v_new + (n * P.Hkv + h) * kHeadDim)[l];
   uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
   reinterpret_cast<uint32_t*>(rk)[l] = kx;
   reinterpret_cast<uint32_t*>(rk + P.ref_kv_stride)[l] = vx;
@@ -59,9 +58,10 @@ __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// sim_top2: grid (tiles_max, NS, B*Hkv), 256 threads = 4 waves, wave tile (16*RB) tokens x 64 references.
+// sim_top2: grid (tiles_max, NS, B*Hkv), 256 threads = 4 waves, wave tile (16*TB) tokens x 64 references.
 // ------------------------------------------------------------------------------------------------
 constexpr int kNT = 64;                 // references per LDS tile
+constexpr int kKeyIdxMask = 0xFFFFFF;   // low 24 bits of an exact-pass key hold (2^24 - 1 - ordinal)
 constexpr int kRowPad = 264;            // bf16 elements per staged reference row (256 + 8: shifts banks)
 
 struct Top2 {
@@ -82,17 +82,23 @@ __device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
   a.idx = take ? oi : a.idx;
 }
 
-template <int RB>
-__global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
-  constexpr int WM = 16 * RB, MT = 4 * WM;
+// The product is issued as D[reference][token] (A = 16 staged reference rows from LDS, B = this wave's token
+// rows, resident in registers): a lane then owns ONE token per 16-token block and sees four references per
+// MFMA result, so the running (best, second, arg best) is one small state per token block instead of one per
+// accumulator row, and only the four lane groups have to be merged at the end.
+template <int TB>
+__global__ __launch_bounds__(256, 2) void k_sim_top2(CompressParams P) {
+  constexpr int WM = 16 * TB, MT = 4 * WM;
   extern __shared__ uint16_t lds_raw[];
   float* nrm = reinterpret_cast<float*>(lds_raw + 2 * kNT * kRowPad);   // [2][kNT]
 
-  const int tt = blockIdx.x, split = blockIdx.y;
+  // token tiles with the most candidate references are scheduled first (the causal search gets longer with position)
+  const int tt = (int)gridDim.x - 1 - (int)blockIdx.x, split = blockIdx.y;
   const int b = blockIdx.z / P.Hkv, h = blockIdx.z % P.Hkv;
   const int n_new = P.cu_new[b + 1] - P.cu_new[b];
   if (tt * MT >= n_new) return;
-  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lb = P.len_before[b];
   const int rows_valid = min(MT, n_new - tt * MT);
   const int pos_last = lb + tt * MT + rows_valid - 1;
@@ -102,53 +108,45 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
   const int tiles_per = ceil_div(tiles_all, P.NS);
   const int t_begin = split * tiles_per, t_end = min(tiles_all, t_begin + tiles_per);
 
-  // A operands: this wave's token rows, K (kk 0..3) then V (kk 4..7)
-  bf16x8 a[RB][8];
+  // B operands: this wave's token rows (lane ln <-> token ln of each block), K (kk 0..3) then V (kk 4..7)
+  bf16x8 tok[TB][8];
+  float na2[TB];
+  int pos[TB];
   const int row0 = tt * MT + w * WM;
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int r = row0 + rb * 16 + ln;
+  for (int tb = 0; tb < TB; ++tb) {
+    const int r = row0 + tb * 16 + ln;
     const bool ok = r < n_new;
+    pos[tb] = lb + r;
     const int64_t n = P.cu_new[b] + (ok ? r : 0);
     const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
     const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+    float ss = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       uint4 x = *reinterpret_cast<const uint4*>(kr + (4 * kk + lg) * 8);
       uint4 y = *reinterpret_cast<const uint4*>(vr + (4 * kk + lg) * 8);
       if (!ok) { x = make_uint4(0, 0, 0, 0); y = x; }
-      a[rb][kk] = __builtin_bit_cast(bf16x8, x);
-      a[rb][4 + kk] = __builtin_bit_cast(bf16x8, y);
-    }
-  }
-  // squared norm of each token row (lane ln ends up with the value of row ln of every row block)
-  float na2[RB];
+      tok[tb][kk] = __builtin_bit_cast(bf16x8, x);
+      tok[tb][4 + kk] = __builtin_bit_cast(bf16x8, y);
+      const uint32_t uu[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    float ss = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const uint4 u = __builtin_bit_cast(uint4, a[rb][kk]);
-      const uint32_t uu[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) ss += bf16lo(uu[e]) * bf16lo(uu[e]) + bf16hi(uu[e]) * bf16hi(uu[e]);
+      for (int e = 0; e < 8; ++e) ss += bf16lo(uu[e]) * bf16lo(uu[e]) + bf16hi(uu[e]) * bf16hi(uu[e]);
     }
     ss += __shfl_xor(ss, 16);
     ss += __shfl_xor(ss, 32);
-    na2[rb] = ss;
+    na2[tb] = ss;
   }
-  Top2 best[RB][4];
+  Top2 st[TB];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) best[rb][i] = Top2{-INFINITY, -INFINITY, -1};
+  for (int tb = 0; tb < TB; ++tb) st[tb] = Top2{-INFINITY, -INFINITY, -1};
 
   const uint16_t* refk = P.ref + (int64_t)h * P.ref_head_stride;
   const uint16_t* refv = refk + P.ref_kv_stride;
   const float* rnorm = P.ref_inv_norm + (int64_t)h * P.ref_norm_head_stride;
   const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
 
-  // stage reference tile `t` into buffer `buf`: 64 rows x 32 pieces of 16 bytes, 8 pieces per thread
+  // stage reference tile `t`: 64 rows x 32 pieces of 16 bytes, 8 pieces per thread
   auto stage_load = [&](int t, uint4 (&regs)[8], float& nr) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -183,73 +181,69 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
     stage_load(t_begin, regs, nr);
     stage_store(0, regs, nr);
     __syncthreads();
+    const int pos_first = lb + row0;                         // smallest position in this wave's rows
     for (int t = t_begin; t < t_end; ++t) {
       const int buf = (t - t_begin) & 1;
       const bool more = t + 1 < t_end;
       if (more) stage_load(t + 1, regs, nr);
-      float4v acc[RB][4];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb) acc[rb][cb] = float4v{0.f, 0.f, 0.f, 0.f};
-      const uint16_t* tb = lds_raw + buf * kNT * kRowPad;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          const bf16x8 bop = *reinterpret_cast<const bf16x8*>(tb + (cb * 16 + ln) * kRowPad + (4 * kk + lg) * 8);
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rb][kk], bop, acc[rb][cb], 0, 0, 0);
-        }
-      }
-      // epilogue: lane holds token rows 4*lg+i (per rb) of reference column cb*16+ln
-      const int jt0 = t * kNT;
-      const int pos_first = lb + row0;                       // smallest position in this wave's rows
-      const bool full = (jt0 + kNT - 1) * P.stride < pos_first && (jt0 + kNT) <= ncand_tile;
+      const uint16_t* tbuf = lds_raw + buf * kNT * kRowPad;
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb) {
-        const int j = jt0 + cb * 16 + ln;
-        const float inv = nrm[buf * kNT + cb * 16 + ln];
+        float4v acc[TB];
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int tb = 0; tb < TB; ++tb) acc[tb] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float v = acc[rb][cb][i] * inv;
-            if (!full) {
-              const int pos = lb + row0 + rb * 16 + 4 * lg + i;
-              const bool ok = (int64_t)j * P.stride < pos && j < ncand_tile;
-              v = ok ? v : -INFINITY;
+        for (int kk = 0; kk < 8; ++kk) {
+          const bf16x8 aop = *reinterpret_cast<const bf16x8*>(tbuf + (cb * 16 + ln) * kRowPad + (4 * kk + lg) * 8);
+#pragma unroll
+          for (int tb = 0; tb < TB; ++tb)
+            acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, tok[tb][kk], acc[tb], 0, 0, 0);
+        }
+        // lane holds references jb + i (i = 0..3) of token ln in every block
+        const float4 inv = *reinterpret_cast<const float4*>(nrm + buf * kNT + cb * 16 + 4 * lg);
+        const float invs[4] = {inv.x, inv.y, inv.z, inv.w};
+        const int jb0 = t * kNT + cb * 16;
+        const int jb = jb0 + 4 * lg;
+        const int code0 = (t * 4 + cb) * 4;                  // wave-uniform; the ordinal is rebuilt from it at the end
+        const bool full = (int64_t)(jb0 + 15) * P.stride < pos_first && jb0 + 16 <= ncand_tile;
+        if (full) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], acc[tb][i] * invs[i], code0 + i);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+              const bool ok = (int64_t)(jb + i) * P.stride < pos[tb] && jb + i < ncand_tile;
+              top2_push(st[tb], ok ? acc[tb][i] * invs[i] : -INFINITY, code0 + i);
             }
-            top2_push(best[rb][i], v, j);
-          }
+        }
       }
       if (more) stage_store(buf ^ 1, regs, nr);
       __syncthreads();
     }
   }
-  // merge the 16 column lanes of every row; ties go to the lower ordinal
+  // rebuild ordinals, merge the four lane groups of every token; ties go to the lower ordinal
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int tb = 0; tb < TB; ++tb) {
+    Top2 t = st[tb];
+    t.idx = (t.best == -INFINITY || t.idx < 0) ? -1 : (t.idx >> 2) * 16 + 4 * lg + (t.idx & 3);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      Top2 t = best[rb][i];
-      if (t.best == -INFINITY) t.idx = -1;
-#pragma unroll
-      for (int o = 1; o < 16; o <<= 1) {
-        const float ob = __shfl_xor(t.best, o), os = __shfl_xor(t.second, o);
-        const int oi = __shfl_xor(t.idx, o);
-        top2_merge(t, ob, os, oi);
-      }
-      const int r = row0 + rb * 16 + 4 * lg + i;
-      const float n2 = __shfl(na2[rb], 4 * lg + i);
-      if (ln == 0 && r < n_new) {
-        float4 o;
-        o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = n2;
-        const int64_t n = P.cu_new[b] + r;
-        *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
-      }
+    for (int o = 16; o < 64; o <<= 1) {
+      const float ob = __shfl_xor(t.best, o), os = __shfl_xor(t.second, o);
+      const int oi = __shfl_xor(t.idx, o);
+      top2_merge(t, ob, os, oi);
     }
+    const int r = row0 + tb * 16 + ln;
+    if (lg == 0 && r < n_new) {
+      float4 o;
+      o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = na2[tb];
+      const int64_t n = P.cu_new[b] + r;
+      *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -277,11 +271,13 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
       if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
       else b2 = fmaxf(b2, o.x);
     }
-    // fp32 scores carry an error of at most ~256 * 2^-24 |a||b|; closer pairs are re-scored exactly
-    if (bi < 0 || !(bb - b2 > 1e-4f * sqrtf(na2))) {
+    // each fp32 score (256 exact products summed in fp32, times the stored inverse norm) is within
+    // 256 * 2^-24 |a| = 1.53e-5 |a| of the exact value; pairs closer than twice that (plus slack) are re-scored
+    if (bi < 0 || !(bb - b2 > 4e-5f * sqrtf(na2))) {
       const int at = atomicAdd(&P.flag_count[b * P.Hkv + h], 1);
       P.flag_list[(int64_t)h * P.n_new_total + P.cu_new[b] + at] = n;
-      ord = 0;
+      P.exact_key[item] = kKeyIdxMask;          // (lowest score, ordinal 0); raised by the exact pass
+      ord = -1;
     } else {
       ord = bi;
     }
@@ -290,13 +286,15 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// exact: grid (kExactX, B*Hkv), 256 threads.  A block takes 16 queued tokens of its (sequence, kv-head) at a
-// time; its four waves share the candidate references (wave w takes reference tiles w, w+4, ...).
+// exact: grid (kExactX, kExactSplits, B*Hkv), 256 threads.  A block takes 16 queued tokens of its
+// (sequence, kv-head) at a time and every kExactSplits*4-th 16-reference tile per wave.
 // D[token][ref] = sum_d a[token][d] b[ref][d] in fp64 on v_mfma_f64_16x16x4 (operand layout checked on the
-// hardware with one-hot inputs): lane (ln, lg) supplies element e
-// of its 8-wide chunk as the k = lg slot of step (kk, e), identically for both operands.
+// hardware with one-hot inputs): lane (ln, lg) supplies element e of its 8-wide chunk as the k = lg slot of
+// step (kk, e), identically for both operands.  Waves publish their best with a 64-bit atomic max on the key
+// (cosine in 2^-38 steps above -1) << 24 | (2^24-1 - ordinal): the larger cosine wins, then the lower ordinal.
 // ------------------------------------------------------------------------------------------------
-constexpr int kExactX = 32;
+constexpr int kExactX = 8;    // few blocks: an idle block of this kernel still costs a dispatch with ~240 registers per lane
+constexpr int kExactSplits = 8;
 typedef double double4v __attribute__((ext_vector_type(4)));
 
 __device__ inline double bf16_elem_f64(const uint4& c, int e) {
@@ -305,8 +303,8 @@ __device__ inline double bf16_elem_f64(const uint4& c, int e) {
 }
 
 __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
-  const int b = blockIdx.y / P.Hkv, h = blockIdx.y % P.Hkv;
-  const int cnt = P.flag_count[blockIdx.y];
+  const int b = blockIdx.z / P.Hkv, h = blockIdx.z % P.Hkv;
+  const int cnt = P.flag_count[blockIdx.z];
   const int n_tiles = ceil_div(cnt, 16);
   if ((int)blockIdx.x >= n_tiles) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
@@ -315,11 +313,10 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
   const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
   const uint16_t* refk = P.ref + (int64_t)h * P.ref_head_stride;
   const uint16_t* refv = refk + P.ref_kv_stride;
-  __shared__ double red_c[4][16];
-  __shared__ int red_j[4][16];
+  const int lane_tile0 = blockIdx.y * 4 + w, tile_step = kExactSplits * 4;
 
   for (int tile = blockIdx.x; tile < n_tiles; tile += kExactX) {
-    // lane ln <-> queued token tile*16 + ln (rows past the end repeat the last one and are not written)
+    // lane ln <-> queued token tile*16 + ln (rows past the end repeat the last one and are not published)
     const int qi = min(tile * 16 + ln, cnt - 1);
     const int n = list[qi];
     const int pos = lb + (n - P.cu_new[b]);
@@ -346,12 +343,16 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
     // accumulator register i of the fp64 MFMA holds token row 4*i + lg (rows are interleaved over the lane
     // groups, unlike the 32-bit variants where a lane group holds four consecutive rows)
     double na_row[4];
-    int pos_row[4];
+    int pos_row[4], n_row[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { na_row[i] = __shfl(na, 4 * i + lg); pos_row[i] = __shfl(pos, 4 * i + lg); }
-    double cbest[4] = {-1e300, -1e300, -1e300, -1e300};
+    for (int i = 0; i < 4; ++i) {
+      na_row[i] = __shfl(na, 4 * i + lg);
+      pos_row[i] = __shfl(pos, 4 * i + lg);
+      n_row[i] = __shfl(n, 4 * i + lg);
+    }
+    double cbest[4] = {-2.0, -2.0, -2.0, -2.0};
     int jbest[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
-    for (int rt = w; rt * 16 < ncand; rt += 4) {
+    for (int rt = lane_tile0; rt * 16 < ncand; rt += tile_step) {
       const int j = rt * 16 + ln;
       const int slot = clampi(rtab[min(j, ncand - 1)], 0, (int)P.n_ref_slots - 1);
       uint4 bq[8];
@@ -381,7 +382,7 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
         if (ok && c > cbest[i]) { cbest[i] = c; jbest[i] = j; }   // ascending j per lane: strict '>'
       }
     }
-    // best over the 16 reference lanes, then over the four waves; ties go to the lower ordinal
+    // best over the 16 reference lanes (ties go to the lower ordinal), then one atomic per token row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -390,19 +391,13 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
         const int oj = __shfl_xor(jbest[i], o);
         if (oc > cbest[i] || (oc == cbest[i] && oj < jbest[i])) { cbest[i] = oc; jbest[i] = oj; }
       }
-      if (ln == 0) { red_c[w][4 * i + lg] = cbest[i]; red_j[w][4 * i + lg] = jbest[i]; }
+      if (ln == 0 && tile * 16 + 4 * i + lg < cnt && jbest[i] != 0x7fffffff) {
+        const double cc = fmin(fmax(cbest[i], -1.0), 1.0) + 1.0;                      // [0, 2]
+        const unsigned long long q = (unsigned long long)(cc * 274877906944.0 + 0.5);    // 2^-38 steps, q <= 2^39
+        const unsigned long long key = (q << 24) | (unsigned long long)(kKeyIdxMask - (jbest[i] & kKeyIdxMask));
+        atomicMax(reinterpret_cast<unsigned long long*>(P.exact_key) + ((int64_t)n_row[i] * P.Hkv + h), key);
+      }
     }
-    __syncthreads();
-    if (tid < 16 && tile * 16 + tid < cnt) {
-      double c = red_c[0][tid];
-      int j = red_j[0][tid];
-#pragma unroll
-      for (int ww = 1; ww < 4; ++ww)
-        if (red_c[ww][tid] > c || (red_c[ww][tid] == c && red_j[ww][tid] < j)) { c = red_c[ww][tid]; j = red_j[ww][tid]; }
-      const int nn = list[tile * 16 + tid];
-      P.ord[(int64_t)nn * P.Hkv + h] = (j == 0x7fffffff) ? 0 : j;
-    }
-    __syncthreads();
   }
 }
 
@@ -441,7 +436,9 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   for (int h = w; h < P.Hkv; h += 4) {
     const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
     const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
-    const int ord = clampi(P.ord[n * P.Hkv + h], 0, P.rt_stride - 1);
+    int ord = P.ord[n * P.Hkv + h];
+    if (ord < 0) ord = kKeyIdxMask - (int)(P.exact_key[n * P.Hkv + h] & kKeyIdxMask);   // decided by the exact pass
+    ord = clampi(ord, 0, P.rt_stride - 1);
     // residual against the chosen raw reference, fp32 (exact for bf16 inputs), split into bf16 hi + lo
     const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
     const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
@@ -525,17 +522,17 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int RB>
+template <int TB>
 static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
   const size_t lds = 2 * kNT * kRowPad * 2 + 2 * kNT * 4;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<RB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(similarity kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_sim_top2<RB>), grid, dim3(256), lds, st, P);
+  hipLaunchKernelGGL((k_sim_top2<TB>), grid, dim3(256), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of sim_top2");
 }
 
@@ -555,11 +552,13 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
 
 int sim_tile_rows(int rb) { return 64 * rb; }
 
-hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st) {
+hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, int max_new_refs,
+                           hipStream_t st) {
   hipError_t e;
   const int items = P.n_new_total * P.Hkv;
   timing_mark(-1, st);
-  hipLaunchKernelGGL(k_admit_refs, dim3(ceil_div(items, 4)), dim3(256), 0, st, P);
+  hipLaunchKernelGGL(k_admit_refs, dim3(ceil_div(max_new_refs * P.Hkv, 4) > 0 ? ceil_div(max_new_refs * P.Hkv, 4) : 1, P.batch),
+                     dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of admit_refs");
   timing_mark(K_ADMIT, st);
   dim3 gs(tiles_max, P.NS, P.batch * P.Hkv);
@@ -574,7 +573,7 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
   hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
   timing_mark(K_RESOLVE, st);
-  hipLaunchKernelGGL(k_exact, dim3(kExactX, P.batch * P.Hkv), dim3(256), 0, st, P);
+  hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
   timing_mark(K_EXACT, st);
   dim3 gp(page_tiles_max, P.batch);

@@ -47,6 +47,8 @@ thread_local char g_detail[256] = "";
 // launch-shape overrides for sweeps (0 = automatic)
 int g_tune_stream_waves = 0;
 int g_tune_splits = 0;
+int g_tune_sim_tb = 0;
+int g_tune_sim_ns = 0;
 
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
@@ -104,6 +106,12 @@ int deltakv_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "splits")) {
     if (value > kMaxSplits) return DELTAKV_E_INVALID_ARG;
     g_tune_splits = value;
+  } else if (!strcmp(name, "sim_ns")) {
+    if (value > 64) return DELTAKV_E_INVALID_ARG;
+    g_tune_sim_ns = value;
+  } else if (!strcmp(name, "sim_tb")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4) return DELTAKV_E_INVALID_ARG;
+    g_tune_sim_tb = value;
   } else {
     return DELTAKV_E_INVALID_ARG;
   }
@@ -317,12 +325,13 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
     return DELTAKV_E_INVALID_ARG;
   if (batch == 0) return DELTAKV_OK;
   if (batch > 65535 / dims->n_kv_heads) return DELTAKV_E_UNSUPPORTED;
+  if (rt_stride > (1 << 24)) return DELTAKV_E_UNSUPPORTED;   // exact-pass keys carry 24-bit ordinals
   if (!aligned(latent_pool, 16) || !aligned(idx_pool, 16) || !aligned(ref_pool, 16) || !aligned(k_new, 16) ||
       !aligned(v_new, 16) || !aligned(w_down_k, 2) || !aligned(w_down_v, 2))
     return DELTAKV_E_INVALID_ARG;
   if (cu_new_host[0] != 0) return DELTAKV_E_INVALID_ARG;
   const int P = dims->page_tokens, S = dims->ref_stride;
-  int max_new = 0, page_tiles_max = 0;
+  int max_new = 0, page_tiles_max = 0, max_new_refs = 0;
   int64_t tiles_total_rows = 0;
   for (int b = 0; b < batch; ++b) {
     const int64_t nb = (int64_t)cu_new_host[b + 1] - cu_new_host[b];
@@ -335,12 +344,14 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
     if (nb > max_new) max_new = (int)nb;
     const int pt = (int)(ceil_div64(la, P) - lb / P);
     if (pt > page_tiles_max) page_tiles_max = pt;
+    const int nr = (int)(ceil_div64(la, S) - ceil_div64(lb, S));
+    if (nr > max_new_refs) max_new_refs = nr;
     tiles_total_rows += nb;
   }
   const int n_new_total = cu_new_host[batch];
   if (n_new_total == 0) return DELTAKV_OK;
   if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
-  const int rb = max_new >= 1024 ? 4 : (max_new >= 128 ? 2 : 1);
+  const int rb = g_tune_sim_tb ? g_tune_sim_tb : (max_new >= 1024 ? 4 : (max_new >= 128 ? 2 : 1));
   const int mt = sim_tile_rows(rb);
   const int tiles_max = ceil_div(max_new, mt);
   int64_t tiles_total = 0;
@@ -353,6 +364,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   // spread the reference scan of small calls (decode append) over enough blocks to fill the chip
   int64_t ns = ceil_div64(4ll * device_cu_count(), tiles_total * dims->n_kv_heads);
   const int64_t ref_tiles = ceil_div64(ceil_div64(max_len_after, S), 64);
+  if (g_tune_sim_ns) ns = g_tune_sim_ns;
   if (ns > ref_tiles) ns = ref_tiles;
   if (ns > 64) ns = 64;
   const CompressWs cw = plan_compress_ws(*dims, batch, n_new_total, 0);
@@ -399,8 +411,9 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.ord = reinterpret_cast<int32_t*>(wsb + cw.ord);
   Pm.flag_count = reinterpret_cast<int32_t*>(wsb + cw.flag_count);
   Pm.flag_list = reinterpret_cast<int32_t*>(wsb + cw.flag_list);
+  Pm.exact_key = reinterpret_cast<uint64_t*>(wsb + cw.exact_key);
   Pm.part = reinterpret_cast<float*>(wsb + cw.part);
-  hipError_t e = launch_compress(Pm, rb, tiles_max, page_tiles_max, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_compress(Pm, rb, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 

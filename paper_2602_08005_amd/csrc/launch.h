@@ -67,14 +67,15 @@ struct CompressParams {
   int32_t* ord;        // [n_new_total][Hkv] chosen reference ordinal
   int32_t* flag_count; // [batch][Hkv] tokens queued for exact re-scoring
   int32_t* flag_list;  // [Hkv][n_new_total] queued token indices, sequence b's segment starts at cu_new[b]
+  uint64_t* exact_key; // [n_new_total][Hkv] result keys of the exact pass (valid for queued tokens)
 };
 
 struct CompressWs {
-  int64_t ord, flag_count, flag_list, part;   // byte offsets; `part` takes everything from its offset on
+  int64_t ord, flag_count, flag_list, exact_key, part;   // byte offsets; `part` takes everything from its offset on
   int64_t total;
 };
-// Offsets for a call with n_new tokens in total; `total` is sized for max_new_tokens with room for up to
-// 64 reference-range splits of small calls.
+// Offsets for a call with n_new tokens in total; `total` leaves room for 8 reference-range splits of a large
+// call and up to 64 of a small one.
 inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t n_new, int64_t) {
   CompressWs w;
   int64_t o = 0;
@@ -82,15 +83,18 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
   w.ord = take(n_new * d.n_kv_heads * 4);
   w.flag_count = take(batch * d.n_kv_heads * 4);
   w.flag_list = take(n_new * d.n_kv_heads * 4);
+  w.exact_key = take(n_new * d.n_kv_heads * 8);
   w.part = o;
-  w.total = o + align_up((n_new + 64 * batch) * d.n_kv_heads * 16, 256);
+  const int64_t slots = 8 * n_new > n_new + 64 * batch ? 8 * n_new : n_new + 64 * batch;
+  w.total = o + align_up(slots * d.n_kv_heads * 16, 256);
   return w;
 }
 
 // Token rows per block of the similarity kernel for row-block factor rb (1, 2 or 4).
 int sim_tile_rows(int rb);
 // Enqueues the three compress kernels on `st`.
-hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, hipStream_t st);
+hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, int max_new_refs,
+                           hipStream_t st);
 
 // Optional per-kernel timing (deltakv_timing_begin / deltakv_timing_end): when enabled, launchers call
 // timing_mark(kernel_id, stream) before the first kernel (id -1) and after every kernel.
