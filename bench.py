@@ -110,6 +110,190 @@ def prefill_workload(args, torch, dk, B, G):
     print(json.dumps(result))
 
 
+def _oracle_decode_seq(cache, b, L, K, V, W, q_bits_row, s, scale):
+    """CPU oracle decode of sequence b from the GPU-built cache (ordinals/latents read back) and raw references."""
+    from oracle import deltakv_oracle as O
+    f = O.bf16_bits_to_f64
+    i0, zk0, zv0 = cache.get_sequence(b, 0, L)
+    t0 = time.perf_counter()
+    want, _ = O.decode_attn_direct(f(q_bits_row), i0, f(zk0), f(zv0), f(K[:L:s]), f(V[:L:s]),
+                                   f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
+    return want, time.perf_counter() - t0
+
+
+def ragged_workload(args, torch, dk, B, G):
+    """64 sequences, lengths log-uniform in [4096, 65536], 4 kv-heads x 128, 28 query heads, rank 48; latents and
+    ordinals live in 16-token pages scattered randomly over a shared pool 1.25x the needed size."""
+    nseq, Hkv, Hq, r, D, s = 64, 4, 28, 48, 128, 16
+    scale = 1.0 / np.sqrt(D)
+    joint = args.mode == "joint"
+    n_streams = 1 if joint else 2
+    lens = G.loguniform_lengths(G.seed_for(5), nseq, 4096, 65536)
+    pages = [-(-int(L) // 16) for L in lens]
+    refs = [-(-int(L) // s) for L in lens]
+    n_pages, n_slots = int(sum(pages) * 1.25), int(sum(refs) * 1.25)
+    pp = G.page_permutation(G.seed_for(5), sum(pages), n_pages)
+    rp = G.page_permutation(G.seed_for(5, 1), sum(refs), n_slots)
+    cp, cr = np.concatenate([[0], np.cumsum(pages)]), np.concatenate([[0], np.cumsum(refs)])
+    dims = dk.make_dims(Hkv, Hq, r, n_pages=n_pages, n_ref_slots=n_slots, latent_mode=dk.JOINT if joint else dk.SPLIT)
+    Lmax = int(lens.max())
+    cache = dk.PagedCache(dims, nseq, Lmax, Lmax, page_ids=[pp[cp[b]:cp[b + 1]] for b in range(nseq)],
+                          ref_slots=[rp[cr[b]:cr[b + 1]] for b in range(nseq)])
+    W = G.make_projections(G.seed_for(5), D, r, joint=joint)
+    dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    wdk, wdv, wuk, wuv = (dev(W[k]) for k in ("w_down_k_bf16", "w_down_v_bf16", "w_up_k_bf16", "w_up_v_bf16"))
+    order = np.argsort(lens)
+    keep = {int(order[0]): None, int(order[nseq // 2]): None, int(order[-1]): None}
+    for b in range(nseq):
+        K, V, _ = G.make_kv(G.seed_for(5, 0, b + 1), int(lens[b]), Hkv, D, n_proto=args.protos, threads=16)
+        if b in keep:
+            keep[b] = (K, V)
+        cache.compress(wdk, wdv, dev(K), dev(V), [0, int(lens[b])], [0], first_seq=b)
+    q_bits = G.make_queries(G.seed_for(5), nseq, Hq, D)
+    q = dev(q_bits)
+    out = torch.empty_like(q)
+    sl = torch.from_numpy(lens.astype(np.int32)).cuda()
+    torch.cuda.synchronize()
+
+    def step():
+        B.decode_attn(dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool, cache.block_tables,
+                      cache.ref_tables, wuk, wuv, q, sl, lens, scale, out, None, cache.decode_ws)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    B.timing_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kern = B.timing_end()
+    ms = elapsed * 1e3 / args.steps
+    units = int(lens.sum()) * Hkv
+    stream_bytes = units * (n_streams * r * 2 + 4)
+    path_bytes = units * (n_streams * r * 2 + 4 + 2 * D * 2 / s)
+    ms_stream = kern["stream"][0] / max(kern["stream"][1], 1)
+    worst, t_or = 0.0, 0.0
+    f64 = None
+    from oracle import deltakv_oracle as O
+    for b, (K, V) in keep.items():
+        want, t = _oracle_decode_seq(cache, b, int(lens[b]), K, V, W, q_bits[b], s, scale)
+        got = O.bf16_bits_to_f64(out[b].cpu().numpy().view(np.uint16))
+        worst = max(worst, float(np.max(np.abs(got - want))))
+        t_or += t
+    samp_tokens = sum(int(lens[b]) for b in keep)
+    result = {
+        "metric": "decode-attn tokens/s over compressed cache (irregular paged batch)",
+        "value": round(nseq / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"irregular paged batch: {nseq} sequences, lengths log-uniform in [4096, 65536] "
+                               f"({int(lens.sum())} tokens), {Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, "
+                               f"{args.mode.upper()} latents, pages scattered over a pool 1.25x the needed size, 1 layer"},
+        "roofline": {"bound": "hbm", "kernel": "k_stream", "achieved": round(stream_bytes / (ms_stream * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(stream_bytes / (ms_stream * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": stream_bytes, "avg_launch_ms": round(ms_stream, 5)},
+        "cpu_baseline": {"value": round(nseq / (t_or * int(lens.sum()) / samp_tokens), 3), "unit": "tokens/s",
+                         "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+                         "sample": f"shortest, median and longest sequence ({samp_tokens} tokens, {t_or:.2f} s), "
+                                   "scaled by token count"},
+        "path_hbm_frac": round(path_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "kernel_ms": {k: round(v / n, 5) for k, (v, n) in kern.items() if n},
+        "parity": {"what": "shortest, median, longest sequence vs CPU oracle", "max_abs_err": worst},
+    }
+    print(json.dumps(result))
+
+
+def append_workload(args, torch, dk, B, G):
+    """Llama-3.1-8B-shaped single layer: batch 1, 32768-token context, 256 decode steps, each appending one
+    compressed token and then attending over the whole cache."""
+    L0, nsteps, Hkv, Hq, r, D, s = 32768, 256, args.kv_heads, args.q_heads, args.rank, 128, 16
+    scale = 1.0 / np.sqrt(D)
+    joint = args.mode == "joint"
+    Lmax = L0 + nsteps
+    dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-Lmax // 16), n_ref_slots=-(-Lmax // s),
+                        latent_mode=dk.JOINT if joint else dk.SPLIT)
+    cache = dk.PagedCache(dims, 1, L0, Lmax)
+    W = G.make_projections(G.seed_for(2), D, r, joint=joint)
+    dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    wdk, wdv, wuk, wuv = (dev(W[k]) for k in ("w_down_k_bf16", "w_down_v_bf16", "w_up_k_bf16", "w_up_v_bf16"))
+    K, V, _ = G.make_kv(G.seed_for(2), Lmax, Hkv, D, n_proto=args.protos, threads=16)
+    Kd, Vd = dev(K), dev(V)
+    q_bits = G.make_queries(G.seed_for(2), nsteps, Hq, D)
+    qd = dev(q_bits)
+    outs = torch.empty_like(qd)
+    cu = torch.tensor([0, 1], dtype=torch.int32, device="cuda")
+    lbs = [torch.tensor([L0 + i], dtype=torch.int32, device="cuda") for i in range(nsteps)]
+    sls = [torch.tensor([L0 + i + 1], dtype=torch.int32, device="cuda") for i in range(nsteps)]
+
+    def run(timed):
+        cache.compress(wdk, wdv, Kd[:L0], Vd[:L0], [0, L0], [0])          # prefill (not timed)
+        torch.cuda.synchronize()
+        if timed:
+            B.timing_begin()
+        t0 = time.perf_counter()
+        for i in range(nsteps):
+            t = L0 + i
+            B.compress(dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool, cache.ref_inv_norm,
+                       cache.block_tables, cache.ref_tables, wdk, wdv, Kd[t:t + 1], Vd[t:t + 1], cu, [0, 1], lbs[i], [t],
+                       cache.compress_ws)
+            B.decode_attn(dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool, cache.block_tables,
+                          cache.ref_tables, wuk, wuv, qd[i:i + 1], sls[i], [t + 1], scale, outs[i:i + 1], None,
+                          cache.decode_ws)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    for _ in range(max(args.warmup, 1)):
+        run(False)
+    elapsed = run(True)
+    kern = B.timing_end()
+    us = elapsed * 1e6 / nsteps
+    # parity at steps 0, 127, 255: ordinals of the appended tokens and the attention output
+    from oracle import deltakv_oracle as O
+    f = O.bf16_bits_to_f64
+    ref = O.compress(f(K), f(V), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s,
+                     mode=O.JOINT if joint else O.SPLIT, start=L0)
+    idx, zk, zv = cache.get_sequence(0, L0, Lmax)
+    mism = int(np.sum(idx != ref["idx"]))
+    worst, t_or = 0.0, 0.0
+    i_all, zk_all, zv_all = cache.get_sequence(0, 0, Lmax)
+    for i in (0, 127, 255):
+        Lc = L0 + i + 1
+        t0 = time.perf_counter()
+        want, _ = O.decode_attn_direct(f(q_bits[i]), i_all[:Lc], f(zk_all[:Lc]), f(zv_all[:Lc]), f(K[:Lc:s]), f(V[:Lc:s]),
+                                       f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
+        t_or += time.perf_counter() - t0
+        got = f(outs[i].cpu().numpy().view(np.uint16))
+        worst = max(worst, float(np.max(np.abs(got - want))))
+    units = (L0 + nsteps // 2) * Hkv
+    n_streams = 1 if joint else 2
+    result = {
+        "metric": "decode tokens/s, single sequence (append one compressed token, then attend)",
+        "value": round(1e6 / us, 1), "unit": "tokens/s", "n_gpus": 1, "steps": nsteps, "warmup": args.warmup,
+        "ms_per_step": round(us / 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"single layer, batch 1, context {L0} -> {Lmax} over {nsteps} steps, {Hkv} kv-heads x {D}, "
+                               f"{Hq} q-heads, rank {r}, {args.mode.upper()} latents"},
+        "roofline": {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": None, "traffic": None,
+                     "note": "latency-bound: 76 MB per step would take 9.6 us at 8 TB/s",
+                     "algorithmic_bytes_per_launch": units * (n_streams * r * 2 + 4)},
+        "cpu_baseline": {"value": round(3 / t_or, 3), "unit": "tokens/s",
+                         "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+                         "sample": f"decode attention at steps 0, 127, 255 ({t_or:.2f} s); the append's retrieval is not included"},
+        "kernel_us": {k: round(v / n * 1e3, 2) for k, (v, n) in kern.items() if n},
+        "parity": {"what": "ordinals of all 256 appended tokens; attention output at steps 0, 127, 255",
+                   "ordinal_mismatches": mism, "max_abs_err": worst},
+    }
+    if kern["stream"][1]:
+        ms_stream = kern["stream"][0] / kern["stream"][1]
+        ach = result["roofline"]["algorithmic_bytes_per_launch"] / (ms_stream * 1e-3) / 1e9
+        result["roofline"]["achieved"], result["roofline"]["frac"] = round(ach, 1), round(ach / HBM_PEAK_GBS, 4)
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,7 +312,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run 5 plain device copies of this many MiB (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE)")
-    ap.add_argument("--workload", choices=["decode128k", "prefill32k"], default="decode128k",
+    ap.add_argument("--workload", choices=["decode128k", "prefill32k", "ragged", "append32k"], default="decode128k",
                     help="decode128k: the headline long-context decode (default); prefill32k: compression of one "
                          "32768-token prompt over the layers (reports compress tokens/s and the similarity GEMM's "
                          "fraction of the MFMA roofline)")
@@ -162,6 +346,10 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "prefill32k":
         return prefill_workload(args, torch, dk, B, G)
+    if args.workload == "ragged":
+        return ragged_workload(args, torch, dk, B, G)
+    if args.workload == "append32k":
+        return append_workload(args, torch, dk, B, G)
     Bt, L, NL, Hkv, Hq, r, D, s = args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, 128, 16
     scale = 1.0 / np.sqrt(D)
     pages_per_seq, refs_per_seq = -(-L // 16), -(-L // s)

@@ -173,7 +173,7 @@ __device__ inline int4 load_ordinals(const DecodeParams& P, int page, int h, int
 // Grid: 1-D.  Workgroups are handed to the eight XCDs round-robin by id, and each XCD has its own L2, so
 // id -> (xcd = id % 8, k = id / 8), (sequence, kv-head) pair = (k / S) * 8 + xcd, split = k % S: every split
 // of a pair runs on the same XCD and shares that L2's copy of the pair's per-reference score table.
-template <int R, int NW, int ST, bool JOINT>
+template <int R, int NW, int PIPE_LG, bool JOINT>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   extern __shared__ float smem[];
   const int xcd = blockIdx.x & 7, kq = blockIdx.x >> 3;
@@ -289,11 +289,16 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       for (int kk = 0; kk < Tile<R>::NKK; ++kk)
         if (4 * kk + lg < R / 8) *reinterpret_cast<uint4*>(tr + ln * TRP + (4 * kk + lg) * 8) = t.zk[kk];
       __builtin_amdgcn_wave_barrier();
+      // LDS transpose load (ds_read_b64_tr_b16; behaviour checked on the hardware): within each 16-lane group
+      // lane j supplies the address of a 4-element chunk and lane i receives element i%4 of the chunks
+      // supplied by lanes i/4, i/4+4, i/4+8, i/4+12.  Lane j of group lg points at token 4*lg + j/4, columns
+      // 16*nb + 4*(j%4)..+3, so lane i ends up with tokens 4*lg..4*lg+3 of column 16*nb + i: the value operand.
 #pragma unroll
       for (int nb = 0; nb < Tile<R>::NB; ++nb) {
-        const uint16_t* src = tr + (4 * lg) * TRP + nb * 16 + ln;
-        t.zv[nb].x = (uint32_t)src[0] | ((uint32_t)src[TRP] << 16);
-        t.zv[nb].y = (uint32_t)src[2 * TRP] | ((uint32_t)src[3 * TRP] << 16);
+        typedef short s4 __attribute__((ext_vector_type(4)));
+        const uint16_t* src = tr + (4 * lg + (ln >> 2)) * TRP + nb * 16 + (ln & 3) * 4;
+        const s4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)src);
+        t.zv[nb] = __builtin_bit_cast(uint2, v);
       }
       __builtin_amdgcn_wave_barrier();
     }
@@ -312,16 +317,16 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   };
 
   // Software pipeline over this wave's pages p0+w, p0+w+NW, ...  While page i is computed, the ordinals of
-  // page i+LZ+1, the latents of page i+LZ and the per-reference score gather of page i+LG are in flight.  The
-  // vector-memory counter retires in order, so what may still be outstanding when page i is computed is what
-  // was issued after gather(i): LG pages of loads.  LG is therefore chosen as large as the 6-bit counter and
-  // the register file allow (about 16 KB in flight per wave), which is what covers HBM latency with only two
-  // waves per SIMD.  Every load in the loop is unconditional (slots past the wave's range re-read its last
-  // page and are computed with zero valid tokens), so the wait counts can be set exactly.
+  // page i+LI, the latents of page i+LZ and the per-reference score gather of page i+LG are in flight.  The
+  // vector-memory counter retires in order, so a wait for some load is a wait for everything issued before it:
+  //   * compute(i) waits for gather(i), issued LG iterations earlier -> LG pages of loads may stay outstanding;
+  //   * gather(i+LG) needs the ordinals of page i+LG as addresses; they were issued LI-LG iterations earlier,
+  //     so LI-LG >= LG keeps that wait from draining the pipe.
+  // Every load in the loop is unconditional (slots past the wave's range re-read its last page and are
+  // computed with zero valid tokens), so the compiler can set the wait counts exactly.
   const int n_my = (p1 - p0 - w + NW - 1) / NW;            // pages of this wave
   if (n_my > 0) {
-    constexpr int LZ = ST - 2, LG = ST - 3;
-    static_assert(ST >= 4, "ring size");
+    constexpr int LG = PIPE_LG, LZ = PIPE_LG + 1, LI = 2 * PIPE_LG + 1, ST = LI + 1;
     const int32_t* bt = P.block_tables + (int64_t)b * P.bt_stride;
     // Blocks start at different points of their (cyclic) page range: ranges of different sequences and splits
     // begin at large power-of-two distances, and blocks that advance in lockstep from such addresses would
@@ -331,26 +336,40 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       int ii = (i < n_my ? i : n_my - 1) + rot;
       return ii >= n_my ? ii - n_my : ii;
     };
-    auto page_id = [&](int i) {                               // its pool page (clamped into the pool)
-      return clampi(bt[p0 + w + slot_of(i) * NW], 0, (int)P.n_pages_pool - 1);
-    };
     auto valid_of = [&](int i) { return i < n_my ? L - (p0 + w + slot_of(i) * NW) * kPage : 0; };
+    // Pool pages of the wave's pages come from the block table 64 at a time with ONE vector load (lane k holds
+    // the page of the wave's (base + k)-th page) and are handed to the loop with v_readlane.  A scalar load per
+    // iteration would sit in the same out-of-order counter as the LDS atomics and force a full
+    // wait-for-everything each iteration.
+    auto page_vec = [&](int base) {
+      return clampi(bt[p0 + w + slot_of(base + l) * NW], 0, (int)P.n_pages_pool - 1);
+    };
+    int pgv0 = page_vec(0), pgv1 = page_vec(64), base0 = 0;
+    auto page_id = [&](int k) {                               // k in [base0, base0 + 128)
+      const int d = k - base0;
+      return d < 64 ? __builtin_amdgcn_readlane(pgv0, d) : __builtin_amdgcn_readlane(pgv1, d - 64);
+    };
     Tile<R> t[ST];
     int4 id[ST];
     float sr[ST][4];
-    int pg[ST];
+    int pg[ST];          // pg[k % ST] = pool page of the wave's k-th page, kept LI+1 pages ahead
 #pragma unroll
     for (int u = 0; u < ST; ++u) pg[u] = page_id(u);
 #pragma unroll
-    for (int u = 0; u < LZ + 1; ++u) id[u] = load_ordinals(P, pg[u], h, l);
+    for (int u = 0; u < LI; ++u) id[u] = load_ordinals(P, pg[u], h, l);
 #pragma unroll
     for (int u = 0; u < LZ; ++u) load_latents<R, JOINT>(P, pg[u], h, l, t[u]);
 #pragma unroll
     for (int u = 0; u < LG; ++u) gather(id[u], sr[u]);
     for (int i = 0; i < n_my; i += ST) {
+      if (i + ST >= base0 + 64) {         // this iteration's lookups k in [i+ST, i+2ST) lie past the first vector
+        pgv0 = pgv1;
+        base0 += 64;
+        pgv1 = page_vec(base0 + 64);
+      }
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
-        id[(u + LZ + 1) % ST] = load_ordinals(P, pg[(u + LZ + 1) % ST], h, l);
+        id[(u + LI) % ST] = load_ordinals(P, pg[(u + LI) % ST], h, l);
         load_latents<R, JOINT>(P, pg[(u + LZ) % ST], h, l, t[(u + LZ) % ST]);
         pg[u] = page_id(i + u + ST);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
@@ -568,12 +587,16 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 template <int R, int NW, bool JOINT>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
-  // Ring slots of the software pipeline.  Measured on MI355X: beyond three pages of latents in flight per wave
-  // (ST = 5) the kernel does not get faster -- with all arithmetic removed the same load stream runs only 7 %
-  // faster -- and longer rings only cost registers and instruction-cache footprint.
+  // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
+  // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
-  constexpr int regs_per_page = 4 * NKK + (JOINT ? 0 : 2 * NB) + 8;
-  constexpr int ST = (5 * regs_per_page <= 150) ? 5 : 4;
+  constexpr int loads_per_page = 1 + NKK + (JOINT ? 0 : NB) + 4;
+  constexpr int tile_regs = 4 * NKK + (JOINT ? 0 : 2 * NB);
+  // live registers ~ (LG+2) latent tiles + (2LG+2) ordinal quads + (LG+1) score quads + ~80 for the rest
+  constexpr int by_regs = ((NW >= 16 ? 110 : 215) - 92 - 2 * tile_regs) / (tile_regs + 12);
+  constexpr int by_counter = 56 / loads_per_page;
+  constexpr int lg0 = by_counter < by_regs ? by_counter : by_regs;
+  constexpr int ST = lg0 < 1 ? 1 : (lg0 > 6 ? 6 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT>),
