@@ -134,6 +134,8 @@ def ragged_workload(args, torch, dk, B, G):
     n_pages, n_slots = int(sum(pages) * 1.25), int(sum(refs) * 1.25)
     pp = G.page_permutation(G.seed_for(5), sum(pages), n_pages)
     rp = G.page_permutation(G.seed_for(5, 1), sum(refs), n_slots)
+    if args.contiguous:
+        pp, rp = np.arange(sum(pages), dtype=np.int32), np.arange(sum(refs), dtype=np.int32)
     cp, cr = np.concatenate([[0], np.cumsum(pages)]), np.concatenate([[0], np.cumsum(refs)])
     dims = dk.make_dims(Hkv, Hq, r, n_pages=n_pages, n_ref_slots=n_slots, latent_mode=dk.JOINT if joint else dk.SPLIT)
     Lmax = int(lens.max())
@@ -316,6 +318,7 @@ def main():
                     help="decode128k: the headline long-context decode (default); prefill32k: compression of one "
                          "32768-token prompt over the layers (reports compress tokens/s and the similarity GEMM's "
                          "fraction of the MFMA roofline)")
+    ap.add_argument("--contiguous", action="store_true", help="ragged workload: identity page placement (experiment)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")

@@ -17,6 +17,8 @@
 //                arg-max with lowest-ordinal tie-break
 //   project    : residual in fp32 (exact for bf16 inputs), split into bf16 hi+lo parts, W_down on MFMA,
 //                bf16 latents + ordinals written into the token's page
+#include <type_traits>
+
 #include "common.h"
 #include "launch.h"
 
@@ -86,11 +88,17 @@ __device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
 // rows, resident in registers): a lane then owns ONE token per 16-token block and sees four references per
 // MFMA result, so the running (best, second, arg best) is one small state per token block instead of one per
 // accumulator row, and only the four lane groups have to be merged at the end.
+//
+// One wave per SIMD with the whole register file (token operands 128 registers, two operand sets, two
+// accumulator sets), software-pipelined by hand: while the 8*TB MFMAs of step q run, the LDS reads of step
+// q+1's operands are in flight and the VALU epilogue of step q-1 (scale, mask, top-2) is issued in the MFMA
+// shadow; reference tiles are staged through three LDS buffers so that one barrier per tile suffices.
 template <int TB>
-__global__ __launch_bounds__(256, 2) void k_sim_top2(CompressParams P) {
+__global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
   constexpr int WM = 16 * TB, MT = 4 * WM;
+  constexpr int kTile = kNT * 256;                           // bf16 elements of one staged tile (64 rows x 512 B)
   extern __shared__ uint16_t lds_raw[];
-  float* nrm = reinterpret_cast<float*>(lds_raw + 2 * kNT * kRowPad);   // [2][kNT]
+  float* nrm = reinterpret_cast<float*>(lds_raw + 3 * kTile);   // [3][kNT]
 
   // token tiles with the most candidate references are scheduled first (the causal search gets longer with position)
   const int tt = (int)gridDim.x - 1 - (int)blockIdx.x, split = blockIdx.y;
@@ -107,17 +115,18 @@ __global__ __launch_bounds__(256, 2) void k_sim_top2(CompressParams P) {
   const int tiles_all = ceil_div(ncand_tile, kNT);
   const int tiles_per = ceil_div(tiles_all, P.NS);
   const int t_begin = split * tiles_per, t_end = min(tiles_all, t_begin + tiles_per);
+  const int n_t = t_end - t_begin;
 
   // B operands: this wave's token rows (lane ln <-> token ln of each block), K (kk 0..3) then V (kk 4..7)
   bf16x8 tok[TB][8];
   float na2[TB];
-  int pos[TB];
+  int ncand_tok[TB];          // candidates of the lane's token: ordinals j with j*s < pos, capped by the tile's
   const int row0 = tt * MT + w * WM;
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
     const int r = row0 + tb * 16 + ln;
     const bool ok = r < n_new;
-    pos[tb] = lb + r;
+    ncand_tok[tb] = ok ? min(refs_below(lb + r, P.stride), ncand_tile) : 0;
     const int64_t n = P.cu_new[b] + (ok ? r : 0);
     const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
     const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
@@ -146,84 +155,147 @@ __global__ __launch_bounds__(256, 2) void k_sim_top2(CompressParams P) {
   const float* rnorm = P.ref_inv_norm + (int64_t)h * P.ref_norm_head_stride;
   const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
 
-  // stage reference tile `t`: 64 rows x 32 pieces of 16 bytes, 8 pieces per thread
-  auto stage_load = [&](int t, uint4 (&regs)[8], float& nr) {
+  // Reference tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+  // a wave-uniform base + 16*l; placement checked on the hardware), no staging registers.  A tile is 64 rows of
+  // 32 sixteen-byte chunks (K half then V half), unpadded; chunk c of row r is stored at position c ^ (r & 7),
+  // which the loads realise by permuting their SOURCE chunk, so that the 16 rows read by one operand fetch hit
+  // distinct banks.  Wave w issues loads i = 0..7 of a tile; load (w, i) fills rows 2*(8w+i) and 2*(8w+i)+1.
+  // Every wave also copies the 64 inverse norms (same values to the same place: keeps all waves' load counts equal).
+  const int my_row = l >> 5;                                  // which of the two rows of a load this lane fills
+  const int my_pos = l & 31;                                  // position inside the row
+  auto load_slots = [&](int t, int (&slot)[9]) {              // pool slots of the rows this lane will fill
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int q = tid + 256 * i, row = q >> 5, c16 = q & 31;
-      const int j = t * kNT + row;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (j < ncand_tile) {
-        const int slot = clampi(rtab[j], 0, (int)P.n_ref_slots - 1);
-        const uint16_t* src = (c16 < 16 ? refk : refv) + (int64_t)slot * kHeadDim + (c16 & 15) * 8;
-        v = *reinterpret_cast<const uint4*>(src);
-      }
-      regs[i] = v;
-    }
-    nr = 0.f;
-    if (tid < kNT) {
-      const int j = t * kNT + tid;
-      if (j < ncand_tile) nr = rnorm[clampi(rtab[j], 0, (int)P.n_ref_slots - 1)];
-    }
+      const int r = 2 * (8 * w + i) + my_row;
+      slot[i] = rtab[min(t * kNT + r, ncand_tile - 1)];       // rows past the end repeat the last reference
+    }                                                          // (they are masked by the candidate count)
+    slot[8] = rtab[min(t * kNT + l, ncand_tile - 1)];
   };
-  auto stage_store = [&](int buf, const uint4 (&regs)[8], float nr) {
+  auto issue_tile = [&](int buf, const int (&slot)[9]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int q = tid + 256 * i, row = q >> 5, c16 = q & 31;
-      *reinterpret_cast<uint4*>(lds_raw + (buf * kNT + row) * kRowPad + c16 * 8) = regs[i];
+      const int r = 2 * (8 * w + i) + my_row;
+      const int c = my_pos ^ (r & 7);
+      const uint16_t* src = (c < 16 ? refk : refv) + (int64_t)clampi(slot[i], 0, (int)P.n_ref_slots - 1) * kHeadDim + (c & 15) * 8;
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)(lds_raw + buf * kTile + (8 * w + i) * 512),
+                                       16, 0, 0);
     }
-    if (tid < kNT) nrm[buf * kNT + tid] = nr;
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rnorm + clampi(slot[8], 0, (int)P.n_ref_slots - 1)),
+                                     (void __attribute__((address_space(3)))*)(nrm + buf * kNT), 4, 0, 0);
+  };
+  // s_waitcnt for the vector-memory counter only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+  auto wait_vm = [](auto N) {
+    constexpr int n = decltype(N)::value;
+    __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
   };
 
-  if (t_begin < t_end) {
-    uint4 regs[8];
-    float nr;
-    stage_load(t_begin, regs, nr);
-    stage_store(0, regs, nr);
+  if (n_t > 0) {
+    // Per tile and wave: 9 slot loads (S) then 9 direct loads (D).  Order of issue: S(0) S(1) D(0) S(2) D(1) |
+    // tile ti: S(ti+3) D(ti+2) ... so D(ti+1), needed at the end of tile ti, has two tiles of work to land in,
+    // and everything issued after it is S(ti+3), D(ti+2): 18 loads.
+    int slot_a[9], slot_b[9];                                 // slots of tiles ti+2 (a) and ti+3 (b)
+    load_slots(t_begin, slot_a);
+    load_slots(t_begin + (n_t > 1 ? 1 : 0), slot_b);
+    issue_tile(0, slot_a);
+    load_slots(t_begin + min(2, n_t - 1), slot_a);
+    issue_tile(1, slot_b);
+    wait_vm(std::integral_constant<int, 18>{});              // D(0) has landed (S(2), D(1) may be outstanding)
     __syncthreads();
     const int pos_first = lb + row0;                         // smallest position in this wave's rows
-    for (int t = t_begin; t < t_end; ++t) {
-      const int buf = (t - t_begin) & 1;
-      const bool more = t + 1 < t_end;
-      if (more) stage_load(t + 1, regs, nr);
-      const uint16_t* tbuf = lds_raw + buf * kNT * kRowPad;
+
+    struct Step { float inv[4]; int jb; int code0; };
+    bf16x8 aop[2][8];
+    float4v acc[2][TB];
+    Step inext, icur, iprev;                                  // of the step being prefetched / computed / finished
+    const int swz = ln & 7;
+    // operands and inverse norms of step (ti, cb): every LDS read of a tile happens before the barrier that
+    // lets other waves overwrite its buffer
+    auto prefetch = [&](int ti, int cb, bf16x8 (&dst)[8], Step& s) {
+      const int buf = ti % 3;
+      const uint16_t* base = lds_raw + buf * kTile + (cb * 16 + ln) * 256;
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        float4v acc[TB];
+      for (int kk = 0; kk < 8; ++kk) dst[kk] = *reinterpret_cast<const bf16x8*>(base + (((4 * kk + lg) ^ swz) * 8));
+      const float4 inv = *reinterpret_cast<const float4*>(nrm + buf * kNT + cb * 16 + 4 * lg);
+      s.inv[0] = inv.x; s.inv[1] = inv.y; s.inv[2] = inv.z; s.inv[3] = inv.w;
+      s.jb = (t_begin + ti) * kNT + cb * 16 + 4 * lg;
+      s.code0 = ((t_begin + ti) * 4 + cb) * 4;               // wave-uniform; the ordinal is rebuilt from it at the end
+    };
+    auto mfmas = [&](const bf16x8 (&a)[8], float4v (&c)[TB]) {
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) acc[tb] = float4v{0.f, 0.f, 0.f, 0.f};
+      for (int tb = 0; tb < TB; ++tb) c[tb] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-          const bf16x8 aop = *reinterpret_cast<const bf16x8*>(tbuf + (cb * 16 + ln) * kRowPad + (4 * kk + lg) * 8);
+      for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
-          for (int tb = 0; tb < TB; ++tb)
-            acc[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, tok[tb][kk], acc[tb], 0, 0, 0);
-        }
-        // lane holds references jb + i (i = 0..3) of token ln in every block
-        const float4 inv = *reinterpret_cast<const float4*>(nrm + buf * kNT + cb * 16 + 4 * lg);
-        const float invs[4] = {inv.x, inv.y, inv.z, inv.w};
-        const int jb0 = t * kNT + cb * 16;
-        const int jb = jb0 + 4 * lg;
-        const int code0 = (t * 4 + cb) * 4;                  // wave-uniform; the ordinal is rebuilt from it at the end
-        const bool full = (int64_t)(jb0 + 15) * P.stride < pos_first && jb0 + 16 <= ncand_tile;
-        if (full) {
+        for (int tb = 0; tb < TB; ++tb) c[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kk], tok[tb][kk], c[tb], 0, 0, 0);
+    };
+    // lane holds references s.jb + i (i = 0..3) of token ln in every block
+    auto epilogue_full = [&](const float4v (&c)[TB], const Step& s) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], acc[tb][i] * invs[i], code0 + i);
-        } else {
+        for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], c[tb][i] * s.inv[i], s.code0 + i);
+    };
+    auto epilogue_masked = [&](const float4v (&c)[TB], const Step& s) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+      for (int tb = 0; tb < TB; ++tb) {
+        const int left = ncand_tok[tb] - s.jb;               // this lane's references i < left are candidates
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-              const bool ok = (int64_t)(jb + i) * P.stride < pos[tb] && jb + i < ncand_tile;
-              top2_push(st[tb], ok ? acc[tb][i] * invs[i] : -INFINITY, code0 + i);
-            }
-        }
+        for (int i = 0; i < 4; ++i) top2_push(st[tb], i < left ? c[tb][i] * s.inv[i] : -INFINITY, s.code0 + i);
       }
-      if (more) stage_store(buf ^ 1, regs, nr);
+    };
+    // a step needs no mask if even its last reference is a candidate of the wave's first (lowest) token
+    auto is_full = [&](int ti, int cb) {
+      const int jb0 = (t_begin + ti) * kNT + cb * 16;
+      return (int64_t)(jb0 + 15) * P.stride < pos_first && jb0 + 16 <= ncand_tile;
+    };
+
+    // pipeline prologue: operands of step (0, 0); a dummy "previous step" whose scores are all masked
+    prefetch(0, 0, aop[0], icur);
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) acc[1][tb] = float4v{0.f, 0.f, 0.f, 0.f};
+    iprev.inv[0] = iprev.inv[1] = iprev.inv[2] = iprev.inv[3] = 0.f;
+    iprev.jb = 0x3fffffff;
+    iprev.code0 = 0;
+    bool prev_full = false;
+
+    // one tile: S(ti+3) into `fill`, D(ti+2) from `use`, four steps with the barrier before the last one
+    auto tile_body = [&](int ti, const int (&use)[9], int (&fill)[9]) {
+      // loads are unconditional (past the end they re-load the last tile into a buffer nobody reads), so that
+      // the number of loads in flight -- and with it the wait count below -- is the same in every iteration
+      load_slots(t_begin + min(ti + 3, n_t - 1), fill);
+      issue_tile((ti + 2) % 3, use);
+      auto step = [&](auto CB) {
+        constexpr int cb = decltype(CB)::value, cur = cb & 1, nxt = cur ^ 1;
+        if (cb < 3) prefetch(ti, cb + 1, aop[nxt], inext);
+        else if (ti + 1 < n_t) prefetch(ti + 1, 0, aop[nxt], inext);
+        // one basic block per variant: the MFMAs of this step and the epilogue of the previous one interleave
+        if (prev_full) {
+          mfmas(aop[cur], acc[cur]);
+          epilogue_full(acc[nxt], iprev);
+        } else {
+          mfmas(aop[cur], acc[cur]);
+          epilogue_masked(acc[nxt], iprev);
+        }
+        prev_full = is_full(ti, cb);
+        iprev = icur;
+        icur = inext;
+      };
+      step(std::integral_constant<int, 0>{});
+      step(std::integral_constant<int, 1>{});
+      step(std::integral_constant<int, 2>{});
+      // before step 3 prefetches the first operands of tile ti+1: its direct loads (issued one tile ago) must
+      // have landed in every wave; after it nobody reads tile ti's buffer any more
+      wait_vm(std::integral_constant<int, 18>{});
       __syncthreads();
+      step(std::integral_constant<int, 3>{});
+    };
+    for (int ti = 0; ti < n_t; ti += 2) {
+      tile_body(ti, slot_a, slot_b);
+      if (ti + 1 < n_t) tile_body(ti + 1, slot_b, slot_a);
     }
+    if (prev_full) epilogue_full(acc[1], iprev); else epilogue_masked(acc[1], iprev);
+    wait_vm(std::integral_constant<int, 0>{});               // no LDS write may be in flight when the block ends
   }
   // rebuild ordinals, merge the four lane groups of every token; ties go to the lower ordinal
 #pragma unroll
@@ -524,7 +596,7 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 template <int TB>
 static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
-  const size_t lds = 2 * kNT * kRowPad * 2 + 2 * kNT * 4;
+  const size_t lds = 3 * kNT * 256 * 2 + 3 * kNT * 4;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB>),
