@@ -28,6 +28,20 @@ __device__ inline int seq_len_of(const DecodeParams& P, int b) {
   return clampi(P.seq_lens[b], 0, P.max_seq_len);
 }
 
+// The per-reference weight table is kept in 32-bit fixed point, because the LDS executes integer atomics at
+// full rate while a float atomic add costs about three cycles per active lane on this chip.  A token that
+// points at reference j with latent logit part delta has weight 2^(delta + s_j), s_j = S_ref[j] - m_ref - bias
+// being a constant of the reference (and query head).  Entry (j, g) accumulates the weights divided by
+// 2^floor(s_j), i.e. values 2^(delta + frac(s_j)), in units of 2^-kFixQ; the reference's own token (delta = 0)
+// contributes between 2^kFixQ and 2^(kFixQ+1), so each addend is rounded to 2^-(kFixQ+1) of that token's weight
+// whatever the dynamic range of the softmax.  ref_values multiplies the sums back by 2^floor(s_j).  An entry
+// that wraps, or an addend that does not fit, goes through a small per-block overflow list instead.
+constexpr int kFixQ = 20;
+constexpr int kOvfCap = 256;
+__device__ inline int table_exponent(float sref, float cinit) {
+  return (int)floorf(fminf(fmaxf(sref + cinit, -30000.f), 30000.f));
+}
+
 __device__ inline float wave16_max(float v) {   // max over the 16 lanes that share lane/16
   v = fmaxf(v, __shfl_xor(v, 1));
   v = fmaxf(v, __shfl_xor(v, 2));
@@ -202,8 +216,14 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // scores-operand order) into the value-operand order of the P.z product
   constexpr int TRP = R + 8;
   uint16_t* tr = reinterpret_cast<uint16_t*>(xbuf + NW * 16) + w * 16 * TRP;
-  for (int i = tid; i < n_tab; i += NW * 64) tab[i] = 0.f;
+  // overflow list of the fixed-point table: [0] = number of records, then entry indices, then amounts
+  uint32_t* ovf = reinterpret_cast<uint32_t*>(xbuf + NW * 16) + (JOINT ? NW * 16 * TRP / 2 : 0);
+  uint32_t* ovf_ent = ovf + 4;
+  float* ovf_val = reinterpret_cast<float*>(ovf_ent + kOvfCap);
+  uint32_t* utab = reinterpret_cast<uint32_t*>(tab);
+  for (int i = tid; i < n_tab; i += NW * 64) utab[i] = 0u;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
+  if (tid == 0) ovf[0] = 0u;
 
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const int gq = ln < Gp ? ln : Gp - 1;                   // column of the score table this lane reads
@@ -250,6 +270,26 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     sr[0] = srow[(uint32_t)id.x << gsh]; sr[1] = srow[(uint32_t)id.y << gsh];
     sr[2] = srow[(uint32_t)id.z << gsh]; sr[3] = srow[(uint32_t)id.w << gsh];
   };
+  // Table updates of the previous page whose returned old values have not been looked at yet: an entry that
+  // wrapped, or an addend that did not fit (rare), is recorded in the overflow list.  The check runs one page
+  // late, in the shadow of the next page's score MFMAs, so the atomics' return latency is never waited for.
+  uint32_t pend_old[4] = {0u, 0u, 0u, 0u}, pend_fix[4] = {0u, 0u, 0u, 0u}, pend_ent[2] = {0u, 0u};
+  auto check_pending = [&]() {
+    const bool any = (pend_old[0] > ~pend_fix[0]) | (pend_old[1] > ~pend_fix[1]) | (pend_old[2] > ~pend_fix[2]) |
+                     (pend_old[3] > ~pend_fix[3]);
+    if (any) {      // one branch per page; lanes without a query head keep all-zero state
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (pend_old[e] > ~pend_fix[e]) {
+          const uint32_t slot = atomicAdd(&ovf[0], 1u);
+          if (slot < (uint32_t)kOvfCap) {
+            ovf_ent[slot] = (e & 1) ? pend_ent[e >> 1] >> 16 : pend_ent[e >> 1] & 0xffffu;
+            ovf_val[slot] = __builtin_ldexpf(1.f, 32 - kFixQ);
+          }
+        }
+      }
+    }
+  };
   auto compute = [&](Tile<R>& t, const int4& id, const float (&sr)[4], const int nvalid) {
     float4v d = {cstart, cstart, cstart, cstart};
 #pragma unroll
@@ -257,6 +297,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qbl[kk], d, 0, 0, 0);
       d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qb[kk], d, 0, 0, 0);
     }
+    check_pending();
     const int ids[4] = {id.x, id.y, id.z, id.w};
     float p[4];
     if (nvalid >= kPage) {       // full page: no per-token masking
@@ -276,9 +317,37 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         lsum += p[e];
       }
     }
-    if (ghead) {                   // weights of masked tokens are 0; their (clamped) ordinal is a valid entry
+    // fixed-point table update (weights of masked tokens are 0; their clamped ordinal is a valid entry)
+    if (ghead) {
+      int ex[4];
+      float f[4];
+      uint32_t ent[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) atomicAdd(&tab[((uint32_t)ids[e] << gsh) + ln], p[e]);
+      for (int e = 0; e < 4; ++e) {
+        ex[e] = table_exponent(sr[e], cinit);
+        f[e] = __builtin_ldexpf(p[e], kFixQ - ex[e]) + 0.5f;
+        ent[e] = ((uint32_t)ids[e] << gsh) + ln;
+      }
+      constexpr float kLim = 4294967040.f;     // largest float below 2^32
+      if (!(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])) < kLim)) {   // an addend does not fit (rare): list it whole
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (!(f[e] < kLim)) {
+            const uint32_t slot = atomicAdd(&ovf[0], 1u);
+            if (slot < (uint32_t)kOvfCap) {
+              ovf_ent[slot] = ent[e];
+              ovf_val[slot] = __builtin_ldexpf(p[e], -ex[e]);
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pend_fix[e] = f[e] < kLim ? (uint32_t)f[e] : 0u;
+        pend_old[e] = atomicAdd(&utab[ent[e]], pend_fix[e]);
+      }
+      pend_ent[0] = ent[0] | (ent[1] << 16);
+      pend_ent[1] = ent[2] | (ent[3] << 16);
     }
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
@@ -376,6 +445,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         compute(t[u], id[u], sr[u], valid_of(i + u));
       }
     }
+    check_pending();
   }
 
   // ---- block reduction of the per-wave partials -------------------------------------------------
@@ -403,9 +473,25 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     P.xpart[part * Gp + tid] = xm;
   }
   for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i];
+  // the table leaves the block as floats in units of 2^floor(s_j) (see table_exponent)
   float* wp = P.wpart + part * P.n_ref_max * Gp;
-  for (int i = tid * 4; i < n_tab; i += NW * 64 * 4)
-    *reinterpret_cast<float4*>(wp + i) = *reinterpret_cast<const float4*>(tab + i);
+  const float unit = __builtin_ldexpf(1.f, -kFixQ);
+  const uint32_t n_ovf = ovf[0];
+  if (n_ovf == 0) {
+    for (int i = tid * 4; i < n_tab; i += NW * 64 * 4) {
+      const uint4 u = *reinterpret_cast<const uint4*>(utab + i);
+      *reinterpret_cast<float4*>(wp + i) = make_float4(u.x * unit, u.y * unit, u.z * unit, u.w * unit);
+    }
+  } else {
+    for (int i = tid; i < n_tab; i += NW * 64) tab[i] = (float)utab[i] * unit;
+    __syncthreads();
+    const uint32_t n_rec = n_ovf < (uint32_t)kOvfCap ? n_ovf : (uint32_t)kOvfCap;
+    for (uint32_t i = tid; i < n_rec; i += NW * 64) atomicAdd(&tab[ovf_ent[i]], ovf_val[i]);
+    if (tid == 0 && n_ovf > (uint32_t)kOvfCap) atomicOr(P.status, 2);   // list exhausted: weights were lost
+    __syncthreads();
+    for (int i = tid * 4; i < n_tab; i += NW * 64 * 4)
+      *reinterpret_cast<float4*>(wp + i) = *reinterpret_cast<const float4*>(tab + i);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -428,7 +514,23 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   __shared__ float wsum[kRefChunk][GP];
   __shared__ int slots[kRefChunk];
 
-  // phase 1: thread t sums the split partials of reference j0+t (coalesced across threads) and fetches its slot
+  // exponent offset of each query head (the same value the stream kernel used): -(max chunk maximum + bias)
+  __shared__ float cpart[256];
+  __shared__ float cinit_s[GP];
+  {
+    const int nch = ceil_div(n_ref, kRefChunk);
+    float m = -INFINITY;
+    for (int c = tid / GP; c < nch; c += 256 / GP) m = fmaxf(m, P.cmax[(bh * P.n_chunk_max + c) * GP + tid % GP]);
+    cpart[tid] = m;
+    __syncthreads();
+    if (tid < GP) {
+      for (int k = 1; k < 256 / GP; ++k) m = fmaxf(m, cpart[k * GP + tid]);
+      cinit_s[tid] = -(m + kExpBias);
+    }
+    __syncthreads();
+  }
+  // phase 1: thread t sums the split partials of reference j0+t (coalesced across threads), scales them back
+  // by the power of two the stream kernel divided out, and fetches the reference's slot
   {
     const int j = j0 + tid;
     float wj[GP];
@@ -449,6 +551,17 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
             wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
           }
         }
+      }
+    }
+    if (j < n_ref) {
+      const float* sp_ = P.sref + (bh * P.n_ref_max + j) * GP;
+#pragma unroll
+      for (int g4 = 0; g4 < GP; g4 += 4) {
+        const float4 t = *reinterpret_cast<const float4*>(sp_ + g4);
+        wj[g4] = __builtin_ldexpf(wj[g4], table_exponent(t.x, cinit_s[g4]));
+        wj[g4 + 1] = __builtin_ldexpf(wj[g4 + 1], table_exponent(t.y, cinit_s[g4 + 1]));
+        wj[g4 + 2] = __builtin_ldexpf(wj[g4 + 2], table_exponent(t.z, cinit_s[g4 + 2]));
+        wj[g4 + 3] = __builtin_ldexpf(wj[g4 + 3], table_exponent(t.w, cinit_s[g4 + 3]));
       }
     }
 #pragma unroll
@@ -593,7 +706,8 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int loads_per_page = 1 + NKK + (JOINT ? 0 : NB) + 4;
   constexpr int tile_regs = 4 * NKK + (JOINT ? 0 : 2 * NB);
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinal quads + (LG+1) score quads + ~80 for the rest
-  constexpr int by_regs = ((NW >= 16 ? 110 : 215) - 92 - 2 * tile_regs) / (tile_regs + 12);
+  constexpr int transient = JOINT ? 2 * NB : 0;      // JOINT builds its value operand per page in extra registers
+  constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 92 - 2 * tile_regs) / (tile_regs + 12);
   constexpr int by_counter = 56 / loads_per_page;
   constexpr int lg0 = by_counter < by_regs ? by_counter : by_regs;
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 6 ? 6 : lg0);
@@ -626,6 +740,7 @@ static hipError_t dispatch_stream(const DecodeParams& P, dim3 grid, size_t lds, 
 size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint) {
   size_t b = (size_t)(((n_ref_max * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
   if (joint) b += (size_t)nw * 16 * (R + 8) * 2;
+  b += (size_t)(4 + 2 * kOvfCap) * 4;   // overflow list of the fixed-point table
   return b;
 }
 
