@@ -178,3 +178,63 @@ def test_unsupported_and_workspace_errors_on_device():
                        torch.tensor([64], dtype=torch.int32, device="cuda"), [64], 0.1, torch.empty(8 * 128, dtype=torch.int16, device="cuda"),
                        None, small, check=False)
     assert rc == B.E_WORKSPACE
+
+
+def test_many_tokens_on_one_reference_wrap_the_weight_table():
+    """Every token points at reference 0, so one entry of the fixed-point weight table receives thousands of
+    addends of about 2^20 units and wraps several times; the wraps must be carried, not lost."""
+    from tests.helpers import Case
+    case = Case(7100, [9000], Hkv=1, Hq=4, r=32, n_proto=16)
+    from paper_2602_08005_amd import binding as B
+    case.res[0]["idx"] = np.zeros_like(case.res[0]["idx"])
+    cache = _setup(case)
+    scale = 1.0 / np.sqrt(128)
+    for splits in (1, 0):        # one block sees all 9000 addends (>= 2^33 units in total); then the default plan
+        B.tune("splits", splits)
+        try:
+            got, lse, status = _run(case, cache, scale)
+        finally:
+            B.tune("splits", 0)
+        assert status == 0
+        _compare(case, got, lse, scale)
+
+
+def _boost_tokens(case, tokens, boost_log2, scale):
+    """Rewrite z_K of `tokens` (kv-head 0) so that the latent part of q-head 0's logit is boost_log2 (log2 units)."""
+    from tests.helpers import f64
+    from synthetic import generator as G
+    qlat = (f64(case.W["w_up_k_bf16"]) @ f64(case.q[0, 0])) * scale * 1.4426950408889634
+    z = boost_log2 * qlat / float(qlat @ qlat)
+    zk = case.res[0]["zb_k"].copy()
+    zk[tokens, 0, :] = G.f32_to_bf16_bits(z.astype(np.float32))
+    case.res[0]["zb_k"] = zk
+
+
+def test_weights_far_above_their_reference_take_the_overflow_list():
+    """Tokens whose logit is 2^25 times their reference's do not fit the 32-bit table entries; they are few, so the
+    per-block list holds them and the result is still exact (and of order one: these tokens dominate head 0)."""
+    from tests.helpers import Case
+    case = Case(7200, [3000], Hkv=1, Hq=4, r=64, n_proto=16)
+    scale = 1.0 / np.sqrt(128)
+    _boost_tokens(case, np.arange(37, 3000, 75), 25.0, scale)
+    cache = _setup(case)
+    got, lse, status = _run(case, cache, scale)
+    assert status == 0
+    _compare(case, got, lse, scale)
+    assert np.max(np.abs(got[0, 0])) > 0.3
+
+
+def test_overflow_list_exhaustion_is_reported():
+    """More oversized weights in one block than the list holds: the status word says that weights were lost."""
+    from tests.helpers import Case
+    case = Case(7300, [3000], Hkv=1, Hq=4, r=64, n_proto=16)
+    scale = 1.0 / np.sqrt(128)
+    from paper_2602_08005_amd import binding as B
+    _boost_tokens(case, np.arange(1, 3000, 4), 25.0, scale)
+    cache = _setup(case)
+    B.tune("splits", 1)          # one block per (sequence, kv-head): all 750 oversized weights meet one list
+    try:
+        _, _, status = _run(case, cache, scale)
+    finally:
+        B.tune("splits", 0)
+    assert status & 2
