@@ -26,9 +26,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per k_stream launch at the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a
-# plain copy of known size (profiles/decode_cfg3_k_stream.md): read 2.299 GB + written 0.038 GB.
-MEASURED_STREAM_TRAFFIC_CFG3 = 2_337_000_000
+# HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy
+# of known size (the summaries under profiles/ give the commands and the raw counter values).
+MEASURED_STREAM_TRAFFIC_CFG3 = 2_336_000_000         # SPLIT: read 2.297 GB + written 0.038 GB
+MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_217_000_000   # JOINT: read 1.179 GB + written 0.038 GB
+MEASURED_STREAM_TRAFFIC_RAGGED = 1_247_000_000       # irregular paged batch (SPLIT, rank 48): 1.232 + 0.016 GB
+MEASURED_SIM_TRAFFIC_PREFILL32K = 210_000_000        # similarity kernel, one 32768-token layer: 0.203 + 0.008 GB
 
 
 def log(*a):
@@ -100,7 +103,8 @@ def prefill_workload(args, torch, dk, B, G):
                                f"{args.mode.upper()} latents, references every {s}th earlier token, cosine top-1"},
         "roofline": {"bound": "mfma", "kernel": "k_sim_top2", "achieved": round(tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": None, "flops_per_launch": flops, "avg_launch_ms": round(ms_sim, 4)},
+                     "traffic": MEASURED_SIM_TRAFFIC_PREFILL32K if (L, Hkv, r) == (32768, 8, 64) else None,
+                     "flops_per_launch": flops, "avg_launch_ms": round(ms_sim, 4)},
         "cpu_baseline": {"value": round(nsamp / t_or / NL, 1), "unit": "tokens/s", "cores":
                          int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
                          "sample": f"last {nsamp} tokens of one layer ({t_or:.2f} s), scaled to {NL} layers"},
@@ -195,7 +199,8 @@ def ragged_workload(args, torch, dk, B, G):
                                f"{args.mode.upper()} latents, pages scattered over a pool 1.25x the needed size, 1 layer"},
         "roofline": {"bound": "hbm", "kernel": "k_stream", "achieved": round(stream_bytes / (ms_stream * 1e-3) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(stream_bytes / (ms_stream * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(stream_bytes / (ms_stream * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_STREAM_TRAFFIC_RAGGED if args.mode == "split" and not args.contiguous else None,
                      "algorithmic_bytes_per_launch": stream_bytes, "avg_launch_ms": round(ms_stream, 5)},
         "cpu_baseline": {"value": round(nseq / (t_or * int(lens.sum()) / samp_tokens), 3), "unit": "tokens/s",
                          "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
@@ -429,8 +434,8 @@ def main():
     path_bytes = units * (n_streams * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if (Bt, L, Hkv, Hq, r, joint) == (8, 131072, 8, 32, 64, False):
-        roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3
+    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64):
+        roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
     kernel_ms = {}
     if timing:
         for k, (ms, n) in kern.items():

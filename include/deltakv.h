@@ -180,8 +180,21 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* layout,
  *   out           device bf16 [batch][n_q_heads][head_dim]
  *   lse           device fp32 [batch][n_q_heads] natural-log sum of exp of the
  *                 scaled logits, or NULL
+ *   workspace     device, >= layout->decode_ws_bytes, aligned.  Its first int32 is
+ *                 a status word written by the call (read it after the stream has
+ *                 run the work; 0 = result good):
+ *                   bit 0  a logit lay more than about 41 nats above every
+ *                          reference token's logit, outside the range the fixed
+ *                          exponent offset of the softmax can hold;
+ *                   bit 1  more than 256 softmax weights in one block were at
+ *                          least 2^11 times the weight of the token's own
+ *                          reference, or accumulated past the 32-bit range of an
+ *                          on-chip table entry: some weights were dropped.
+ *                 Neither happens with residuals that are small next to the
+ *                 references they refine; the output is not to be trusted if set.
  * Errors: INVALID_ARG, UNSUPPORTED (a sequence needs more on-chip table space
- * than one compute unit has: roughly seq_len/ref_stride * group size > 36000),
+ * than one compute unit has: roughly seq_len/ref_stride * g > 39000 in SPLIT and
+ * > 34000 in JOINT mode, g = queries per kv-head rounded up to 4, 8 or 16),
  * WORKSPACE, HIP. */
 int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* layout,
                         const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
