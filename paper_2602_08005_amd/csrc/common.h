@@ -43,6 +43,12 @@ __host__ __device__ inline SplitPlan plan_splits(int n_pages, int max_splits, in
   sp.per = ceil_div(n_pages, sp.n_splits);
   return sp;
 }
+// Splits of a sequence that hold at least one page (split s covers pages [s*per, (s+1)*per)).
+__host__ __device__ inline int used_splits(int n_pages, int max_splits, int pages_per_split) {
+  if (n_pages <= 0) return 0;
+  const SplitPlan sp = plan_splits(n_pages, max_splits, pages_per_split);
+  return ceil_div(n_pages, sp.per);
+}
 // Number of reference ordinals that tokens [0, end_tok) can point at.
 __host__ __device__ inline int refs_below(int end_tok, int stride) { return ceil_div(end_tok, stride); }
 
@@ -53,7 +59,8 @@ struct DecodeWs {
   int64_t sref;     // fp32 [B][Hkv][n_ref_max][Gp]  per-reference scores, log2 units
   int64_t cmax;     // fp32 [B][Hkv][n_chunk_max][Gp] per-chunk maxima of sref
   int64_t lpart;    // fp32 [B][Hkv][S][Gp]
-  int64_t xpart;    // fp32 [B][Hkv][S][Gp]          largest exponent argument seen
+  int64_t wflag;    // int32 [B][Hkv][S]             1: this split's weight table is already in plain units
+  int64_t items;    // int32 [1 + B*kMaxSplits]      number of non-empty (sequence, split) items, then the items
   int64_t accpart;  // fp32 [B][Hkv][S][Gp][R]
   int64_t opart;    // fp32 [B][Hkv][n_chunk_max][Gp][128]
   int64_t wpart;    // fp32 [B][Hkv][S][n_ref_max][Gp]
@@ -70,7 +77,8 @@ inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_r
   w.sref = take(BH * n_ref_max * Gp * 4);
   w.cmax = take(BH * nch * Gp * 4);
   w.lpart = take(BH * splits * Gp * 4);
-  w.xpart = take(BH * splits * Gp * 4);
+  w.wflag = take(BH * splits * 4);
+  w.items = take((1 + batch * kMaxSplits) * 4);
   w.accpart = take(BH * splits * Gp * R * 4);
   w.opart = take(BH * nch * Gp * kHeadDim * 4);
   w.wpart = take(BH * splits * n_ref_max * Gp * 4);

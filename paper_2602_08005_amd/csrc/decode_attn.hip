@@ -21,6 +21,8 @@
 #include "common.h"
 #include "launch.h"
 
+#include <type_traits>
+
 namespace dkv {
 
 
@@ -30,17 +32,20 @@ __device__ inline int seq_len_of(const DecodeParams& P, int b) {
 
 // The per-reference weight table is kept in 32-bit fixed point, because the LDS executes integer atomics at
 // full rate while a float atomic add costs about three cycles per active lane on this chip.  A token that
-// points at reference j with latent logit part delta has weight 2^(delta + s_j), s_j = S_ref[j] - m_ref - bias
-// being a constant of the reference (and query head).  Entry (j, g) accumulates the weights divided by
-// 2^floor(s_j), i.e. values 2^(delta + frac(s_j)), in units of 2^-kFixQ; the reference's own token (delta = 0)
-// contributes between 2^kFixQ and 2^(kFixQ+1), so each addend is rounded to 2^-(kFixQ+1) of that token's weight
-// whatever the dynamic range of the softmax.  ref_values multiplies the sums back by 2^floor(s_j).  An entry
-// that wraps, or an addend that does not fit, goes through a small per-block overflow list instead.
+// points at reference j with latent logit part delta has weight p = 2^(delta + s_j), s_j = S_ref[j] - m_ref - bias
+// being a constant of the reference (and query head).  Entry (j, g) accumulates p * 2^k_j with the integer
+// k_j = table_shift(...) within one of kFixQ - s_j, i.e. values near 2^(delta + kFixQ): the reference's own token
+// (delta = 0) contributes about 2^kFixQ, so each addend is rounded to 2^-kFixQ of that token's weight whatever
+// the dynamic range of the softmax.  ref_values multiplies the sums back by 2^-k_j.  An entry that wraps, or a
+// weight too large for an entry (2^11 times its reference token's), is rare: such amounts go, as plain weights,
+// to a small per-block list; a block whose list is not empty converts its whole table to plain weights before
+// it flushes and marks the split, so that ref_values does not scale it again.
 constexpr int kFixQ = 20;
 constexpr int kOvfCap = 256;
-__device__ inline int table_exponent(float sref, float cinit) {
-  return (int)floorf(fminf(fmaxf(sref + cinit, -30000.f), 30000.f));
-}
+// Entry (j, g) is kept in units of 2^-table_shift(S_ref[j][g], base(m_ref[g])): an integer within one of
+// kFixQ - s_j.  Both kernels evaluate exactly these two expressions, so they agree bit for bit.
+__device__ inline float table_shift_base(float mref) { return mref + (kExpBias + (float)kFixQ); }
+__device__ inline int table_shift(float sref, float base) { return (int)fminf(base - sref, 30000.f); }
 
 __device__ inline float wave16_max(float v) {   // max over the 16 lanes that share lane/16
   v = fmaxf(v, __shfl_xor(v, 1));
@@ -57,7 +62,26 @@ __device__ inline float wave16_max(float v) {   // max over the 16 lanes that sh
 __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   // the status word is cleared here rather than by a memset node, so that a caller may capture the call
-  if (chunk == 0 && h == 0 && b == 0 && threadIdx.x == 0) *P.status = 0;
+  if (chunk == 0 && h == 0 && b == 0) {
+    if (threadIdx.x == 0) *P.status = 0;
+    // List of the non-empty (sequence, split) items, in sequence order, for the streaming kernel's grid: thread t
+    // counts the items of its run of sequences, the counts are scanned, and each thread writes its run.
+    __shared__ int run_items[256];
+    const int per = ceil_div(P.batch, 256), b_lo = min((int)threadIdx.x * per, P.batch), b_hi = min(b_lo + per, P.batch);
+    int cnt = 0;
+    for (int bb = b_lo; bb < b_hi; ++bb)
+      cnt += used_splits(ceil_div(seq_len_of(P, bb), kPage), P.S, P.pages_per_split);
+    run_items[threadIdx.x] = cnt;
+    __syncthreads();
+    int at = 0;
+    for (int t = 0; t < (int)threadIdx.x; ++t) at += run_items[t];
+    if (threadIdx.x == 255) P.items[0] = at + cnt;
+    for (int bb = b_lo; bb < b_hi; ++bb) {
+      const int ns = used_splits(ceil_div(seq_len_of(P, bb), kPage), P.S, P.pages_per_split);
+      for (int s = 0; s < ns; ++s) P.items[1 + at + s] = bb * kMaxSplits + s;
+      at += ns;
+    }
+  }
   const int L = seq_len_of(P, b);
   const int n_ref = refs_below(L, P.stride);
   const int j0 = chunk * kRefChunk;
@@ -79,40 +103,48 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;   // K half
   float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  // all loads of the wave's four 16-reference steps are issued before the first MFMA (rows past the end
-  // re-read the last reference and are dropped afterwards)
+  // The wave's four 16-reference steps run as two batches of two: each batch issues its eight 16-byte loads
+  // before its first MFMA (rows past the end re-read the last reference and are dropped afterwards).  Two
+  // steps of registers instead of four keep the kernel at eight waves per SIMD, so the whole grid of a 128k-token
+  // batch is resident at once instead of running as two rounds of blocks.
   constexpr int NSTEP = kRefChunk / 64;
   int slot[NSTEP];
-  uint4 kv[NSTEP][4];
 #pragma unroll
   for (int step = 0; step < NSTEP; ++step) {
     const int j = min(j0 + w * 64 + step * 16 + ln, n_ref - 1);
     slot[step] = P.ref_tables[(int64_t)b * P.rt_stride + j];
   }
 #pragma unroll
-  for (int step = 0; step < NSTEP; ++step) {
-    const uint16_t* krow = kbase + (int64_t)clampi(slot[step], 0, (int)P.n_ref_slots - 1) * kHeadDim;
+  for (int half = 0; half < NSTEP; half += 2) {
+    uint4 kv[2][4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) kv[step][kk] = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
-  }
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const uint16_t* krow = kbase + (int64_t)clampi(slot[half + s2], 0, (int)P.n_ref_slots - 1) * kHeadDim;
 #pragma unroll
-  for (int step = 0; step < NSTEP; ++step) {
-    const int j = j0 + w * 64 + step * 16 + ln;
-    const bool valid = j < n_ref;
-    float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv[step][kk]), acc, 0, 0, 0);
-    // lane holds rows g = 4*lg + i of column j
-    float4 o;
-    o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
-    o.z = acc[2] * P.qk_scale_log2; o.w = acc[3] * P.qk_scale_log2;
-    if (valid && 4 * lg < P.Gp)
-      *reinterpret_cast<float4*>(P.sref + (bh * P.n_ref_max + j) * P.Gp + 4 * lg) = o;
-    if (valid) {
-      mx[0] = fmaxf(mx[0], o.x); mx[1] = fmaxf(mx[1], o.y);
-      mx[2] = fmaxf(mx[2], o.z); mx[3] = fmaxf(mx[3], o.w);
+      for (int kk = 0; kk < 4; ++kk) kv[s2][kk] = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
     }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int step = half + s2;
+      const int j = j0 + w * 64 + step * 16 + ln;
+      const bool valid = j < n_ref;
+      float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv[s2][kk]), acc, 0, 0, 0);
+      // lane holds rows g = 4*lg + i of column j
+      float4 o;
+      o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
+      o.z = acc[2] * P.qk_scale_log2; o.w = acc[3] * P.qk_scale_log2;
+      if (valid && 4 * lg < P.Gp)
+        *reinterpret_cast<float4*>(P.sref + (bh * P.n_ref_max + j) * P.Gp + 4 * lg) = o;
+      if (valid) {
+        mx[0] = fmaxf(mx[0], o.x); mx[1] = fmaxf(mx[1], o.y);
+        mx[2] = fmaxf(mx[2], o.z); mx[3] = fmaxf(mx[3], o.w);
+      }
+    }
+    // keep the second batch's loads behind the first batch's stores in program order
+    __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) mx[i] = wave16_max(mx[i]);
@@ -162,38 +194,50 @@ struct Tile {
   uint2 zv[NB];    // value operand: column l%16 + 16*nb, tokens 4*(l/16)..+3
 };
 
+// Loads of the streaming loop take their address as (uniform 64-bit base of the page) + (32-bit offset of the
+// lane), which the hardware forms itself (scalar base + vector offset): no vector arithmetic per load.
 template <int R, bool JOINT>
-__device__ inline void load_latents(const DecodeParams& P, int page, int h, int l, Tile<R>& t) {
-  const int lg = l >> 4;
-  const uint16_t* base = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+__device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
+                                    uint32_t l, Tile<R>& t) {
+  const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
+  const uint32_t lg = l >> 4;
 #pragma unroll
   for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
     if (4 * kk + lg < R / 8)
-      t.zk[kk] = *reinterpret_cast<const uint4*>(base + (64 * kk + l) * 8);
+      t.zk[kk] = *reinterpret_cast<const uint4*>(base + (l * 16u + kk * 1024u));
     else
       t.zk[kk] = make_uint4(0, 0, 0, 0);
   }
   if (!JOINT) {
-    const uint16_t* vb = base + P.latent_stream_stride;
+    const char* vb = base + stream_bytes;
 #pragma unroll
-    for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (nb * 64 + l) * 4);
+    for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (l * 8u + nb * 512u));
   }
 }
-__device__ inline int4 load_ordinals(const DecodeParams& P, int page, int h, int l) {
-  return *reinterpret_cast<const int4*>(P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride +
-                                        (l >> 4) * 4);
+// One ordinal per lane: lane (row lg = l/16, quad position l%4) holds the ordinal of token 4*lg + l%4, so the four
+// tokens a lane works on sit in the four lanes of its own quad and are fetched with quad-broadcast DPP moves when
+// needed (one register per page in flight instead of four).
+__device__ inline int load_ordinal(const char* idx_h, uint32_t page_bytes, int page, uint32_t l) {
+  return *reinterpret_cast<const int*>(idx_h + (uint64_t)(uint32_t)page * page_bytes + (((l >> 4) * 4u + (l & 3u)) * 4u));
+}
+template <int E>
+__device__ inline int quad_bcast(int v) {   // value held by lane E of the caller's quad
+  return __builtin_amdgcn_update_dpp(0, v, E * 0x55, 0xf, 0xf, true);
 }
 
-// Grid: 1-D.  Workgroups are handed to the eight XCDs round-robin by id, and each XCD has its own L2, so
-// id -> (xcd = id % 8, k = id / 8), (sequence, kv-head) pair = (k / S) * 8 + xcd, split = k % S: every split
-// of a pair runs on the same XCD and shares that L2's copy of the pair's per-reference score table.
+// Grid: 1-D, one block per (item, kv-head) with the head fastest, where the items are the non-empty
+// (sequence, split) pairs listed by ref_scores: no block of the grid is empty, whatever the mix of lengths.  (Empty
+// blocks are not free here: each needs a whole compute unit's LDS before it can start and exit.)  Blocks of the kv-heads
+// of one item run side by side and sweep the same pages; with eight kv-heads, block id % 8 = head, so all splits of a
+// (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
 template <int R, int NW, int PIPE_LG, bool JOINT>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   extern __shared__ float smem[];
-  const int xcd = blockIdx.x & 7, kq = blockIdx.x >> 3;
-  const int pair = (kq / P.S) * 8 + xcd, s = kq % P.S;
-  if (pair >= P.batch * P.Hkv) return;
-  const int b = pair / P.Hkv, h = pair % P.Hkv;
+  const int item_q = blockIdx.x / P.Hkv, h = blockIdx.x % P.Hkv;
+  if (item_q >= P.items[0]) return;
+  const int item = P.items[1 + item_q];
+  const int b = min(item / kMaxSplits, P.batch - 1), s = item % kMaxSplits;
+  const int pair = b * P.Hkv + h;
   const int L = seq_len_of(P, b);
   if (L <= 0) return;
   const int n_pages = ceil_div(L, kPage);
@@ -209,8 +253,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   float* tab = smem;
   float* accbuf = smem + ((n_tab + 3) & ~3);              // [Gp][R]
   float* lbuf = accbuf + Gp * R;                          // [16]
-  float* xbuf = lbuf + 16;                                // [NW][16]
-  const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
+  float* xbuf = lbuf + 16;                                // [NW][16]; the first 16 hold each head's table-unit base
+  const int tid = threadIdx.x;
+  const uint32_t l = tid & 63, ln = l & 15, lg = l >> 4;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   // JOINT: per-wave [16 tokens][R + 8] bf16 scratch used to turn the single latent stream (stored in
   // scores-operand order) into the value-operand order of the P.z product
@@ -218,16 +263,17 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   uint16_t* tr = reinterpret_cast<uint16_t*>(xbuf + NW * 16) + w * 16 * TRP;
   // overflow list of the fixed-point table: [0] = number of records, then entry indices, then amounts
   uint32_t* ovf = reinterpret_cast<uint32_t*>(xbuf + NW * 16) + (JOINT ? NW * 16 * TRP / 2 : 0);
+  uint32_t* pgctr = ovf + 1;            // next undrawn page position of the block
   uint32_t* ovf_ent = ovf + 4;
   float* ovf_val = reinterpret_cast<float*>(ovf_ent + kOvfCap);
   uint32_t* utab = reinterpret_cast<uint32_t*>(tab);
   for (int i = tid; i < n_tab; i += NW * 64) utab[i] = 0u;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
-  if (tid == 0) ovf[0] = 0u;
+  if (tid == 0) { ovf[0] = 0u; pgctr[0] = 0u; }
 
   const int64_t bh = (int64_t)b * P.Hkv + h;
-  const int gq = ln < Gp ? ln : Gp - 1;                   // column of the score table this lane reads
-  const bool ghead = ln < G;
+  const uint32_t gq = ln < (uint32_t)Gp ? ln : Gp - 1;    // column of the score table this lane reads
+  const bool ghead = ln < (uint32_t)G;
   // exponent offset for q-head g = ln: chunk maxima of the per-reference scores
   float mref = -INFINITY;
   {
@@ -235,6 +281,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
   }
   const float cinit = -(mref + kExpBias);
+  const float cshift = table_shift_base(mref);
+  if (tid < 16) xbuf[tid] = cshift;
   // B operand of the score product: (W_uK q) for head g = ln, latent chunk 4*kk + lg
   // (stored as bf16 hi + lo parts, so that the latent part of the logit keeps fp32-like accuracy)
   bf16x8 qb[Tile<R>::NKK], qbl[Tile<R>::NKK];
@@ -251,46 +299,84 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       qbl[kk] = __builtin_bit_cast(bf16x8, vl);
     }
   }
-  const float* srow = P.sref + bh * P.n_ref_max * Gp + gq;
-  const int gsh = group_shift(Gp);
+  // uniform bases of this (sequence, kv-head): score table row block, latent and ordinal pools at head h
+  const char* sref_bh = reinterpret_cast<const char*>(P.sref + bh * P.n_ref_max * Gp);
+  const char* lat_h = reinterpret_cast<const char*>(P.latent + (int64_t)h * P.latent_head_stride);
+  const char* idx_h = reinterpret_cast<const char*>(P.idx + (int64_t)h * P.idx_head_stride);
+  const uint32_t lat_page_bytes = (uint32_t)P.latent_page_stride * 2u, lat_stream_bytes = (uint32_t)P.latent_stream_stride * 2u;
+  const uint32_t idx_page_bytes = (uint32_t)P.idx_page_stride * 4u;
+  const int gsh2 = group_shift(Gp) + 2;                   // ordinal -> byte offset of its table row
+  const uint32_t gq4 = gq * 4u, ln4 = ln * 4u;
   const uint32_t id_hi = (uint32_t)(n_cov - 1);
   __syncthreads();
 
   float4v acc[Tile<R>::NB];
 #pragma unroll
   for (int nb = 0; nb < Tile<R>::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
-  float lsum = 0.f, xmax = -INFINITY;
+  float lsum = 0.f;
   // lanes that hold no query head start their accumulator at -inf, so their weights are exactly 0
   const float cstart = ghead ? cinit : -INFINITY;
 
-  auto gather = [&](int4& id, float (&sr)[4]) {
+  // Per-reference scores of a page: the lane fetches, with ONE 16-byte load, four heads of the row of the token
+  // whose ordinal it holds (token 4*lg + l%4; heads 4*(ln/4)..+3), and compute() turns the quad's 4x4 block
+  // (token x head) around with cross-lane moves so that every lane ends up with its own head for the quad's
+  // four tokens.  Scattered 4-byte gathers -- four per lane and page -- kept the CU's address and data-return
+  // units busy most of the time; quads that hold no query head do not load at all.
+  const uint32_t quad4 = (ln >> 2) * 4u;
+  const bool quad_live = quad4 < (uint32_t)G;
+  const uint32_t quad_off = (quad4 < (uint32_t)Gp ? quad4 : 0u) * 4u;
+  auto gather = [&](int& id, float4& sr) {
     // stored ordinals are clamped (unsigned min: negatives become the last ordinal), never trusted
-    id.x = (int)min((uint32_t)id.x, id_hi); id.y = (int)min((uint32_t)id.y, id_hi);
-    id.z = (int)min((uint32_t)id.z, id_hi); id.w = (int)min((uint32_t)id.w, id_hi);
-    sr[0] = srow[(uint32_t)id.x << gsh]; sr[1] = srow[(uint32_t)id.y << gsh];
-    sr[2] = srow[(uint32_t)id.z << gsh]; sr[3] = srow[(uint32_t)id.w << gsh];
+    id = (int)min((uint32_t)id, id_hi);
+    sr = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (quad_live) sr = *reinterpret_cast<const float4*>(sref_bh + (((uint32_t)id << gsh2) + quad_off));
+  };
+  auto quad_xchg = [](float v, int ctrl_is_pair) {   // value of the lane at position ^1 (pair) or ^2 of the quad
+    const int i = __builtin_bit_cast(int, v);
+    const int r = ctrl_is_pair ? __builtin_amdgcn_update_dpp(0, i, 0xB1, 0xf, 0xf, true)    // quad_perm [1,0,3,2]
+                               : __builtin_amdgcn_update_dpp(0, i, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+    return __builtin_bit_cast(float, r);
+  };
+  const bool pos_odd = (ln & 1u) != 0u, pos_hi = (ln & 2u) != 0u;
+  auto quad_transpose = [&](float4 v, float (&out)[4]) {   // lane q of a quad holds row q -> holds column q
+    const float r0 = quad_xchg(pos_odd ? v.x : v.y, 1);
+    const float r1 = quad_xchg(pos_odd ? v.z : v.w, 1);
+    if (pos_odd) { v.x = r0; v.z = r1; } else { v.y = r0; v.w = r1; }
+    const float r2 = quad_xchg(pos_hi ? v.x : v.z, 0);
+    const float r3 = quad_xchg(pos_hi ? v.y : v.w, 0);
+    if (pos_hi) { v.x = r2; v.y = r3; } else { v.z = r2; v.w = r3; }
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
   };
   // Table updates of the previous page whose returned old values have not been looked at yet: an entry that
-  // wrapped, or an addend that did not fit (rare), is recorded in the overflow list.  The check runs one page
-  // late, in the shadow of the next page's score MFMAs, so the atomics' return latency is never waited for.
-  uint32_t pend_old[4] = {0u, 0u, 0u, 0u}, pend_fix[4] = {0u, 0u, 0u, 0u}, pend_ent[2] = {0u, 0u};
+  // wrapped is recorded in the overflow list (rare).  The check runs one page late, in the shadow of the next
+  // page's score MFMAs, so the atomics' return latency is never waited for.
+  uint32_t pend_old[4] = {0u, 0u, 0u, 0u}, pend_fix[4] = {0u, 0u, 0u, 0u};
+  uint32_t pend_ids[2] = {0u, 0u};      // the page's four ordinals (16 bits each: a table fits the LDS)
+  auto list_push = [&](uint32_t ent, float amount) {
+    const uint32_t slot = atomicAdd(&ovf[0], 1u);
+    if (slot < (uint32_t)kOvfCap) {
+      ovf_ent[slot] = ent;
+      ovf_val[slot] = amount;
+    }
+  };
   auto check_pending = [&]() {
-    const bool any = (pend_old[0] > ~pend_fix[0]) | (pend_old[1] > ~pend_fix[1]) | (pend_old[2] > ~pend_fix[2]) |
-                     (pend_old[3] > ~pend_fix[3]);
+    const bool any = (pend_old[0] + pend_fix[0] < pend_fix[0]) | (pend_old[1] + pend_fix[1] < pend_fix[1]) |
+                     (pend_old[2] + pend_fix[2] < pend_fix[2]) | (pend_old[3] + pend_fix[3] < pend_fix[3]);
     if (any) {      // one branch per page; lanes without a query head keep all-zero state
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (pend_old[e] > ~pend_fix[e]) {
-          const uint32_t slot = atomicAdd(&ovf[0], 1u);
-          if (slot < (uint32_t)kOvfCap) {
-            ovf_ent[slot] = (e & 1) ? pend_ent[e >> 1] >> 16 : pend_ent[e >> 1] & 0xffffu;
-            ovf_val[slot] = __builtin_ldexpf(1.f, 32 - kFixQ);
-          }
-        }
+        const uint32_t j = (e & 1) ? pend_ids[e >> 1] >> 16 : pend_ids[e >> 1] & 0xffffu;
+        // 2^32 table units: marked (top bit) for conversion to a plain weight when the block flushes.  No
+        // memory load may sit on this path: a conditional load in the loop would cost every wait its exact count.
+        if (pend_old[e] + pend_fix[e] < pend_fix[e]) list_push((((j << gsh2) + ln4) >> 2) | 0x80000000u, 4294967296.f);
       }
     }
   };
-  auto compute = [&](Tile<R>& t, const int4& id, const float (&sr)[4], const int nvalid) {
+  // FULL: all 16 tokens of the page are valid (no masking code at all); otherwise nvalid in (-inf, 16].
+  auto compute = [&](auto full_tag, Tile<R>& t, const int id, const float4& srv, const int nvalid) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    float sr[4];
+    quad_transpose(srv, sr);
     float4v d = {cstart, cstart, cstart, cstart};
 #pragma unroll
     for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
@@ -298,56 +384,37 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qb[kk], d, 0, 0, 0);
     }
     check_pending();
-    const int ids[4] = {id.x, id.y, id.z, id.w};
     float p[4];
-    if (nvalid >= kPage) {       // full page: no per-token masking
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x = d[e] + sr[e];
-        xmax = fmaxf(xmax, x);
-        p[e] = __builtin_amdgcn_exp2f(x);
-        lsum += p[e];
-      }
-    } else {                       // tail page, or a pipeline slot past the range (nvalid <= 0)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x = (4 * lg + e < nvalid) ? d[e] + sr[e] : -INFINITY;   // select, not arithmetic:
-        xmax = fmaxf(xmax, x);                                               // garbage slots may hold NaN
-        p[e] = __builtin_amdgcn_exp2f(x);
-        lsum += p[e];
-      }
+    for (int e = 0; e < 4; ++e) {
+      float x = d[e] + sr[e];
+      if (!FULL) x = ((int)(4 * lg) + e < nvalid) ? x : -INFINITY;   // select, not arithmetic: garbage may be NaN
+      p[e] = __builtin_amdgcn_exp2f(x);
+      lsum += p[e];
     }
-    // fixed-point table update (weights of masked tokens are 0; their clamped ordinal is a valid entry)
-    if (ghead) {
-      int ex[4];
+    // (cross-lane moves read 0 from lanes that are switched off, so they stay outside the per-head branch)
+    const int ids[4] = {quad_bcast<0>(id), quad_bcast<1>(id), quad_bcast<2>(id), quad_bcast<3>(id)};
+    if (ghead) {       // fixed-point table update (weights of masked tokens are 0; their clamped ordinal is valid)
+      constexpr float kLim = 4294967040.f;     // largest float below 2^32
       float f[4];
-      uint32_t ent[4];
+      uint32_t off[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        ex[e] = table_exponent(sr[e], cinit);
-        f[e] = __builtin_ldexpf(p[e], kFixQ - ex[e]) + 0.5f;
-        ent[e] = ((uint32_t)ids[e] << gsh) + ln;
+        f[e] = __builtin_ldexpf(p[e], table_shift(sr[e], cshift));
+        off[e] = ((uint32_t)ids[e] << gsh2) + ln4;
       }
-      constexpr float kLim = 4294967040.f;     // largest float below 2^32
-      if (!(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])) < kLim)) {   // an addend does not fit (rare): list it whole
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          if (!(f[e] < kLim)) {
-            const uint32_t slot = atomicAdd(&ovf[0], 1u);
-            if (slot < (uint32_t)kOvfCap) {
-              ovf_ent[slot] = ent[e];
-              ovf_val[slot] = __builtin_ldexpf(p[e], -ex[e]);
-            }
-          }
-        }
+      if (!(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])) < kLim)) {   // an addend does not fit (rare): the whole
+#pragma unroll                                                      // weight goes to the list
+        for (int e = 0; e < 4; ++e)
+          if (!(f[e] < kLim)) list_push(off[e] >> 2, p[e]);
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         pend_fix[e] = f[e] < kLim ? (uint32_t)f[e] : 0u;
-        pend_old[e] = atomicAdd(&utab[ent[e]], pend_fix[e]);
+        pend_old[e] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off[e]), pend_fix[e]);
       }
-      pend_ent[0] = ent[0] | (ent[1] << 16);
-      pend_ent[1] = ent[2] | (ent[3] << 16);
+      pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
+      pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
     }
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
@@ -371,10 +438,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
       __builtin_amdgcn_wave_barrier();
     }
-    if (nvalid < kPage) {    // mask value-operand slots that hold garbage
+    if (!FULL) {             // mask value-operand slots that hold garbage
 #pragma unroll
       for (int nb = 0; nb < Tile<R>::NB; ++nb) {
-        const int left = nvalid - 4 * lg;   // valid tokens among this lane's four
+        const int left = nvalid - (int)(4 * lg);   // valid tokens among this lane's four
         if (left < 4) t.zv[nb].y &= left < 3 ? 0u : 0x0000ffffu;
         if (left < 2) t.zv[nb].x &= left < 1 ? 0u : 0x0000ffffu;
       }
@@ -385,78 +452,97 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   };
 
-  // Software pipeline over this wave's pages p0+w, p0+w+NW, ...  While page i is computed, the ordinals of
+  // Software pipeline over the pages a wave draws.  While page i is computed, the ordinals of
   // page i+LI, the latents of page i+LZ and the per-reference score gather of page i+LG are in flight.  The
   // vector-memory counter retires in order, so a wait for some load is a wait for everything issued before it:
   //   * compute(i) waits for gather(i), issued LG iterations earlier -> LG pages of loads may stay outstanding;
   //   * gather(i+LG) needs the ordinals of page i+LG as addresses; they were issued LI-LG iterations earlier,
   //     so LI-LG >= LG keeps that wait from draining the pipe.
-  // Every load in the loop is unconditional (slots past the wave's range re-read its last page and are
+  // Every load in the loop is unconditional (positions past the block's range re-read its last page and are
   // computed with zero valid tokens), so the compiler can set the wait counts exactly.
-  const int n_my = (p1 - p0 - w + NW - 1) / NW;            // pages of this wave
-  if (n_my > 0) {
+  // The waves of a block draw their pages from a shared counter, ST consecutive pages at a time, instead of owning a
+  // fixed share: with fixed shares the wave that is older on its SIMD ran a third faster than the younger one and
+  // the block waited for the slow half with half-empty SIMDs.  A draw made in one loop iteration is turned into
+  // pool pages in the next and computed two iterations after that, so the counter's latency is never waited for.
+  {
     constexpr int LG = PIPE_LG, LZ = PIPE_LG + 1, LI = 2 * PIPE_LG + 1, ST = LI + 1;
     const int32_t* bt = P.block_tables + (int64_t)b * P.bt_stride;
+    const int n_blk = p1 - p0;                               // pages of this block
     // Blocks start at different points of their (cyclic) page range: ranges of different sequences and splits
     // begin at large power-of-two distances, and blocks that advance in lockstep from such addresses would
-    // keep hitting the same HBM channels.  The order is free because every partial sum simply adds.
-    const int rot = (int)(((uint32_t)pair * 2654435761u + (uint32_t)s * 40503u) >> 8) % n_my;
-    auto slot_of = [&](int i) {                               // i-th page of this wave in rotated order
-      int ii = (i < n_my ? i : n_my - 1) + rot;
-      return ii >= n_my ? ii - n_my : ii;
+    // keep hitting the same HBM channels.  The order is free because every partial sum simply adds.  The block
+    // that holds the sequence's partial last page does not rotate, so that page comes last and every earlier
+    // draw is made of full pages only: the steady-state loop carries no masking code.
+    const bool has_partial = (L & (kPage - 1)) != 0 && p1 == n_pages;
+    const int rot = has_partial ? 0 : (int)(((uint32_t)pair * 2654435761u + (uint32_t)s * 40503u) >> 8) % n_blk;
+    const int n_full = n_blk - (has_partial ? 1 : 0);
+    // Draw c (positions c*ST .. c*ST+ST-1) covers pages c%NW, c%NW + NW, ... of the (c/NW)-th group of NW*ST pages,
+    // so the NW draws that the waves of a block hold at about the same time interleave page by page and the
+    // block sweeps one contiguous region; positions of the last, incomplete group that map past the range are
+    // empty.
+    constexpr int GRP = NW * ST;
+    const int n_pos = ceil_div(n_blk, GRP) * GRP;
+    auto pos_page = [&](int x) {
+      const int c = x / ST, u = x - c * ST;
+      return (c / NW) * GRP + (c % NW) + NW * u;
     };
-    auto valid_of = [&](int i) { return i < n_my ? L - (p0 + w + slot_of(i) * NW) * kPage : 0; };
-    // Pool pages of the wave's pages come from the block table 64 at a time with ONE vector load (lane k holds
-    // the page of the wave's (base + k)-th page) and are handed to the loop with v_readlane.  A scalar load per
-    // iteration would sit in the same out-of-order counter as the LDS atomics and force a full
-    // wait-for-everything each iteration.
+    auto local_page = [&](int x) {                            // page of position x in rotated order
+      const int pgi = pos_page(x);
+      int xx = (pgi < n_blk ? pgi : n_blk - 1) + rot;
+      return xx >= n_blk ? xx - n_blk : xx;
+    };
+    auto valid_of = [&](int x) { return pos_page(x) < n_blk ? L - (p0 + local_page(x)) * kPage : 0; };
+    // Pool pages of a draw come from the block table with ONE vector load (lane u holds the page of position
+    // base + u) and are handed to the stages with v_readlane at a constant lane.  A scalar load per stage would sit
+    // in the same out-of-order counter as the LDS atomics and force a full wait-for-everything each time.
     auto page_vec = [&](int base) {
-      return clampi(bt[p0 + w + slot_of(base + l) * NW], 0, (int)P.n_pages_pool - 1);
+      return clampi(bt[p0 + local_page(base + (int)l)], 0, (int)P.n_pages_pool - 1);
     };
-    int pgv0 = page_vec(0), pgv1 = page_vec(64), base0 = 0;
-    auto page_id = [&](int k) {                               // k in [base0, base0 + 128)
-      const int d = k - base0;
-      return d < 64 ? __builtin_amdgcn_readlane(pgv0, d) : __builtin_amdgcn_readlane(pgv1, d - 64);
+    auto draw = [&]() {                                       // next ST positions of the block (wave-uniform)
+      uint32_t v = 0;
+      if (l == 0) v = atomicAdd(pgctr, (uint32_t)ST);
+      return (int)__builtin_amdgcn_readfirstlane(v);
     };
     Tile<R> t[ST];
-    int4 id[ST];
-    float sr[ST][4];
+    int id[ST];
+    float4 sr[ST];
     int pg[ST];          // pg[k % ST] = pool page of the wave's k-th page, kept LI+1 pages ahead
+    int cb = draw(), cb1 = draw(), cb2 = draw();              // positions of this, the next and the next-but-one draw
+    {
+      const int pv0 = page_vec(cb);
 #pragma unroll
-    for (int u = 0; u < ST; ++u) pg[u] = page_id(u);
+      for (int u = 0; u < ST; ++u) pg[u] = __builtin_amdgcn_readlane(pv0, u);
+    }
+    int pgit_next = page_vec(cb1);
 #pragma unroll
-    for (int u = 0; u < LI; ++u) id[u] = load_ordinals(P, pg[u], h, l);
+    for (int u = 0; u < LI; ++u) id[u] = load_ordinal(idx_h, idx_page_bytes, pg[u], l);
 #pragma unroll
-    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT>(P, pg[u], h, l, t[u]);
+    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
 #pragma unroll
     for (int u = 0; u < LG; ++u) gather(id[u], sr[u]);
-    for (int i = 0; i < n_my; i += ST) {
-      if (i + ST >= base0 + 64) {         // this iteration's lookups k in [i+ST, i+2ST) lie past the first vector
-        pgv0 = pgv1;
-        base0 += 64;
-        pgv1 = page_vec(base0 + 64);
-      }
+    auto body = [&](auto full_tag) {
+      const int pgit = pgit_next;                             // pages of the next draw
+      pgit_next = page_vec(cb2);
+      const int cb3 = draw();
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
-        id[(u + LI) % ST] = load_ordinals(P, pg[(u + LI) % ST], h, l);
-        load_latents<R, JOINT>(P, pg[(u + LZ) % ST], h, l, t[(u + LZ) % ST]);
-        pg[u] = page_id(i + u + ST);
+        id[(u + LI) % ST] = load_ordinal(idx_h, idx_page_bytes, pg[(u + LI) % ST], l);
+        load_latents<R, JOINT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
+        pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
-        compute(t[u], id[u], sr[u], valid_of(i + u));
+        compute(full_tag, t[u], id[u], sr[u], decltype(full_tag)::value ? kPage : valid_of(cb + u));
       }
-    }
+      cb = cb1; cb1 = cb2; cb2 = cb3;
+    };
+    while (cb - cb % GRP + GRP <= n_full) body(std::true_type{});    // the draw's whole group is made of full pages
+    while (cb < n_pos) body(std::false_type{});
     check_pending();
   }
 
   // ---- block reduction of the per-wave partials -------------------------------------------------
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
-  xmax = fmaxf(xmax, __shfl_xor(xmax, 16));
-  xmax = fmaxf(xmax, __shfl_xor(xmax, 32));
-  if (l < 16) {
-    atomicAdd(&lbuf[l], lsum);
-    xbuf[w * 16 + l] = xmax;
-  }
+  if (l < 16) atomicAdd(&lbuf[l], lsum);
 #pragma unroll
   for (int nb = 0; nb < Tile<R>::NB; ++nb)
 #pragma unroll
@@ -466,27 +552,30 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   __syncthreads();
   const int64_t part = bh * P.S + s;
-  if (tid < Gp) {
-    P.lpart[part * Gp + tid] = lbuf[tid];
-    float xm = -INFINITY;
-    for (int ww = 0; ww < NW; ++ww) xm = fmaxf(xm, xbuf[ww * 16 + tid]);
-    P.xpart[part * Gp + tid] = xm;
-  }
+  if (tid < Gp) P.lpart[part * Gp + tid] = lbuf[tid];
+  if (tid == 0) P.wflag[part] = ovf[0] != 0u;
   for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i];
-  // the table leaves the block as floats in units of 2^floor(s_j) (see table_exponent)
+  // the table leaves the block as floats, normally still in the per-entry units of table_shift()
   float* wp = P.wpart + part * P.n_ref_max * Gp;
-  const float unit = __builtin_ldexpf(1.f, -kFixQ);
   const uint32_t n_ovf = ovf[0];
   if (n_ovf == 0) {
     for (int i = tid * 4; i < n_tab; i += NW * 64 * 4) {
       const uint4 u = *reinterpret_cast<const uint4*>(utab + i);
-      *reinterpret_cast<float4*>(wp + i) = make_float4(u.x * unit, u.y * unit, u.z * unit, u.w * unit);
+      *reinterpret_cast<float4*>(wp + i) = make_float4((float)u.x, (float)u.y, (float)u.z, (float)u.w);
     }
   } else {
-    for (int i = tid; i < n_tab; i += NW * 64) tab[i] = (float)utab[i] * unit;
+    // rare: turn the table into plain weights (entry i = (j, g) has the units of score-table element i)
+    const float* sref_tab = P.sref + bh * P.n_ref_max * Gp;
+    for (int i = tid; i < n_tab; i += NW * 64)
+      tab[i] = __builtin_ldexpf((float)utab[i], -table_shift(sref_tab[i], xbuf[i & (Gp - 1)]));
     __syncthreads();
     const uint32_t n_rec = n_ovf < (uint32_t)kOvfCap ? n_ovf : (uint32_t)kOvfCap;
-    for (uint32_t i = tid; i < n_rec; i += NW * 64) atomicAdd(&tab[ovf_ent[i]], ovf_val[i]);
+    for (uint32_t i = tid; i < n_rec; i += NW * 64) {
+      const uint32_t ent = ovf_ent[i] & 0x7fffffffu;
+      float amount = ovf_val[i];
+      if (ovf_ent[i] >> 31) amount = __builtin_ldexpf(amount, -table_shift(sref_tab[ent], xbuf[ent & (Gp - 1)]));
+      atomicAdd(&tab[ent], amount);
+    }
     if (tid == 0 && n_ovf > (uint32_t)kOvfCap) atomicOr(P.status, 2);   // list exhausted: weights were lost
     __syncthreads();
     for (int i = tid * 4; i < n_tab; i += NW * 64 * 4)
@@ -514,9 +603,9 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   __shared__ float wsum[kRefChunk][GP];
   __shared__ int slots[kRefChunk];
 
-  // exponent offset of each query head (the same value the stream kernel used): -(max chunk maximum + bias)
+  // per query head, the base of the table units (the same value the stream kernel used)
   __shared__ float cpart[256];
-  __shared__ float cinit_s[GP];
+  __shared__ float shift_s[GP];
   {
     const int nch = ceil_div(n_ref, kRefChunk);
     float m = -INFINITY;
@@ -525,7 +614,7 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
     __syncthreads();
     if (tid < GP) {
       for (int k = 1; k < 256 / GP; ++k) m = fmaxf(m, cpart[k * GP + tid]);
-      cinit_s[tid] = -(m + kExpBias);
+      shift_s[tid] = table_shift_base(m);
     }
     __syncthreads();
   }
@@ -539,30 +628,36 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
     int slot = 0;
     if (j < n_ref) {
       slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + j], 0, (int)P.n_ref_slots - 1);
+      uint32_t plain = 0;                      // splits whose table already holds plain weights (rare)
 #pragma unroll
-      for (int s = 0; s < kMaxSplits; ++s) {
-        const int p1 = min(n_pages, (s + 1) * sp.per);
-        const int cov = refs_below(min(L, p1 * kPage), P.stride);   // ordinals split s wrote
-        if (s < sp.n_splits && s * sp.per < p1 && j < cov) {
-          const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
+      for (int s = 0; s < kMaxSplits; ++s)
+        if (s < sp.n_splits && P.wflag[bh * P.S + s] != 0) plain |= 1u << s;
+      auto add_splits = [&](bool want_plain) {
 #pragma unroll
-          for (int g4 = 0; g4 < GP; g4 += 4) {
-            const float4 t = *reinterpret_cast<const float4*>(wp + g4);
-            wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
+        for (int s = 0; s < kMaxSplits; ++s) {
+          const int p1 = min(n_pages, (s + 1) * sp.per);
+          const int cov = refs_below(min(L, p1 * kPage), P.stride);   // ordinals split s wrote
+          if (s < sp.n_splits && s * sp.per < p1 && j < cov && (((plain >> s) & 1u) != 0u) == want_plain) {
+            const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
+#pragma unroll
+            for (int g4 = 0; g4 < GP; g4 += 4) {
+              const float4 t = *reinterpret_cast<const float4*>(wp + g4);
+              wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
+            }
           }
         }
-      }
-    }
-    if (j < n_ref) {
+      };
+      add_splits(false);
       const float* sp_ = P.sref + (bh * P.n_ref_max + j) * GP;
 #pragma unroll
       for (int g4 = 0; g4 < GP; g4 += 4) {
         const float4 t = *reinterpret_cast<const float4*>(sp_ + g4);
-        wj[g4] = __builtin_ldexpf(wj[g4], table_exponent(t.x, cinit_s[g4]));
-        wj[g4 + 1] = __builtin_ldexpf(wj[g4 + 1], table_exponent(t.y, cinit_s[g4 + 1]));
-        wj[g4 + 2] = __builtin_ldexpf(wj[g4 + 2], table_exponent(t.z, cinit_s[g4 + 2]));
-        wj[g4 + 3] = __builtin_ldexpf(wj[g4 + 3], table_exponent(t.w, cinit_s[g4 + 3]));
+        wj[g4] = __builtin_ldexpf(wj[g4], -table_shift(t.x, shift_s[g4]));
+        wj[g4 + 1] = __builtin_ldexpf(wj[g4 + 1], -table_shift(t.y, shift_s[g4 + 1]));
+        wj[g4 + 2] = __builtin_ldexpf(wj[g4 + 2], -table_shift(t.z, shift_s[g4 + 2]));
+        wj[g4 + 3] = __builtin_ldexpf(wj[g4 + 3], -table_shift(t.w, shift_s[g4 + 3]));
       }
+      if (plain != 0u) add_splits(true);
     }
 #pragma unroll
     for (int g = 0; g < GP; ++g) wsum[tid][g] = wj[g];
@@ -571,13 +666,13 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   __syncthreads();
 
   // phase 2: lane = (row-in-group lg, 8-wide d chunk ln); a wave reads four 256-byte V rows per load and
-  // keeps eight such loads in flight
+  // keeps UN such loads in flight
   float acc[GP][8];
 #pragma unroll
   for (int g = 0; g < GP; ++g)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  constexpr int UN = 8;
+  constexpr int UN = GP >= 16 ? 2 : (GP == 8 ? 4 : 8);     // row loads in flight per wave
   for (int it0 = 0; it0 < kRefChunk / 16; it0 += UN) {
     uint4 v[UN];
 #pragma unroll
@@ -651,13 +746,10 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   for (int s = 0; s < sp.n_splits; ++s)
     if (s * sp.per < n_pages) n_used = s + 1;
   const int64_t bh = (int64_t)b * P.Hkv + h;
-  float lsum = 0.f, xm = -INFINITY;
+  float lsum = 0.f;
 #pragma unroll
   for (int s = 0; s < kMaxSplits; ++s)
-    if (s < n_used) {
-      lsum += P.lpart[(bh * P.S + s) * Gp + g];
-      xm = fmaxf(xm, P.xpart[(bh * P.S + s) * Gp + g]);
-    }
+    if (s < n_used) lsum += P.lpart[(bh * P.S + s) * Gp + g];
   float mref = -INFINITY;
   for (int c = d; c < nch; c += 128) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
 #pragma unroll
@@ -690,8 +782,9 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   P.out[orow + d] = (uint16_t)f32_to_bf16_bits(o / lsum);
   if (d == 0) {
     if (P.lse) P.lse[(int64_t)b * P.Hq + gh] = (mref + kExpBias + __log2f(lsum)) * kLn2;
-    // exponent arguments above ~60 (relative to the bias) risk overflow of the fp32 sums
-    if (!(xm < 60.0f) || !(lsum > 0.f) || !(lsum < INFINITY)) atomicOr(P.status, 1);
+    // a weight of 2^60 or more (exponent argument ~60 above the biased offset) risks overflow of the fp32 sums;
+    // any such weight makes the sum at least that large
+    if (!(lsum < 0x1p60f) || !(lsum > 0.f)) atomicOr(P.status, 1);
   }
 }
 
@@ -703,14 +796,16 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
-  constexpr int loads_per_page = 1 + NKK + (JOINT ? 0 : NB) + 4;
+  constexpr int lat_loads = NKK + (JOINT ? 0 : NB);       // latent loads per page
   constexpr int tile_regs = 4 * NKK + (JOINT ? 0 : 2 * NB);
-  // live registers ~ (LG+2) latent tiles + (2LG+2) ordinal quads + (LG+1) score quads + ~80 for the rest
+  // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
   constexpr int transient = JOINT ? 2 * NB : 0;      // JOINT builds its value operand per page in extra registers
-  constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 92 - 2 * tile_regs) / (tile_regs + 12);
-  constexpr int by_counter = 56 / loads_per_page;
+  constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6);
+  // loads outstanding at once: (2LG+1) ordinals + (LG+1) pages of latents + LG pages of 4 score gathers (+ the page
+  // vector); the hardware counter has 6 bits
+  constexpr int by_counter = (56 - 1 - lat_loads) / (6 + lat_loads);
   constexpr int lg0 = by_counter < by_regs ? by_counter : by_regs;
-  constexpr int ST = lg0 < 1 ? 1 : (lg0 > 6 ? 6 : lg0);
+  constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT>),
@@ -744,14 +839,14 @@ size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint) {
   return b;
 }
 
-hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st) {
+hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, size_t lds, hipStream_t st) {
   hipError_t e;
   dim3 gchunk(P.n_chunk_max, P.Hkv, batch);
   timing_mark(-1, st);
   hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);
-  dim3 gs(ceil_div(batch * P.Hkv, 8) * 8 * P.S);
+  dim3 gs(n_items > 0 ? n_items * P.Hkv : 1);
   if (P.joint)
     e = (nw == 16) ? dispatch_stream<16, true>(P, gs, lds, st) : dispatch_stream<8, true>(P, gs, lds, st);
   else

@@ -244,8 +244,18 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   const int wave_cap = 32 / nw;
   if (per_cu > wave_cap) per_cu = wave_cap;
   const int64_t slots = (int64_t)device_cu_count() * per_cu;
-  const int64_t pairs = (int64_t)batch * dims->n_kv_heads;
-  int splits = (int)ceil_div64(2 * slots, pairs);
+  // Blocks of at most pages_per_split pages: about one per block slot when all sequences have the same length,
+  // about two when the lengths differ (blocks are handed out as slots free up, so smaller blocks even out a
+  // ragged batch; each block costs several microseconds of set-up and flush, which nothing overlaps).
+  int64_t total_pages = 0;
+  bool uniform = true;
+  for (int b = 0; b < batch; ++b) {
+    total_pages += ceil_div(seq_lens_host[b], P);
+    uniform = uniform && seq_lens_host[b] == seq_lens_host[0];
+  }
+  total_pages *= dims->n_kv_heads;
+  const int64_t pages_target = ceil_div64(total_pages, (uniform ? 1 : 2) * slots);
+  int splits = (int)ceil_div64(max_pages, pages_target > 0 ? pages_target : 1);
   const int split_cap = max_pages / 8 > 1 ? max_pages / 8 : 1;    // at least 8 pages per split
   if (splits > split_cap) splits = split_cap;
   if (splits > kMaxSplits) splits = kMaxSplits;
@@ -303,11 +313,17 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   Pm.sref = reinterpret_cast<float*>(wsb + ws.sref);
   Pm.cmax = reinterpret_cast<float*>(wsb + ws.cmax);
   Pm.lpart = reinterpret_cast<float*>(wsb + ws.lpart);
-  Pm.xpart = reinterpret_cast<float*>(wsb + ws.xpart);
+  Pm.wflag = reinterpret_cast<int32_t*>(wsb + ws.wflag);
+  Pm.items = reinterpret_cast<int32_t*>(wsb + ws.items);
   Pm.accpart = reinterpret_cast<float*>(wsb + ws.accpart);
   Pm.opart = reinterpret_cast<float*>(wsb + ws.opart);
   Pm.wpart = reinterpret_cast<float*>(wsb + ws.wpart);
-  hipError_t e = launch_decode(Pm, batch, nw, lds, static_cast<hipStream_t>(stream));
+  // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
+  // from the device copy of the lengths
+  int64_t n_items = 0;
+  for (int b = 0; b < batch; ++b)
+    n_items += used_splits(ceil_div(seq_lens_host[b], P), Pm.S, Pm.pages_per_split);
+  hipError_t e = launch_decode(Pm, batch, (int)n_items, nw, lds, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 

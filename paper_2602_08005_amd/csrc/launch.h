@@ -36,7 +36,8 @@ struct DecodeParams {
   float* sref;
   float* cmax;
   float* lpart;
-  float* xpart;
+  int32_t* wflag;
+  int32_t* items;           // [0] = number of (sequence, split) items, then item = sequence * kMaxSplits + split
   float* accpart;
   float* opart;
   float* wpart;
@@ -104,6 +105,6 @@ void timing_mark(int kernel_id, hipStream_t st);
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
 size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint);
 // Enqueues the four decode kernels on `st`.
-hipError_t launch_decode(const DecodeParams& P, int batch, int nw, size_t lds, hipStream_t st);
+hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, size_t lds, hipStream_t st);
 
 }  // namespace dkv
