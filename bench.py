@@ -28,9 +28,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy
 # of known size (the summaries under profiles/ give the commands and the raw counter values).
-MEASURED_STREAM_TRAFFIC_CFG3 = 2_336_000_000         # SPLIT: read 2.297 GB + written 0.038 GB
-MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_217_000_000   # JOINT: read 1.179 GB + written 0.038 GB
-MEASURED_STREAM_TRAFFIC_RAGGED = 1_247_000_000       # irregular paged batch (SPLIT, rank 48): 1.232 + 0.016 GB
+MEASURED_STREAM_TRAFFIC_CFG3 = 2_478_000_000         # SPLIT: read 2.457 GB + written 0.021 GB
+MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_295_000_000   # JOINT: read 1.274 GB + written 0.021 GB
+MEASURED_STREAM_TRAFFIC_RAGGED = 1_273_000_000       # irregular paged batch (SPLIT, rank 48): 1.243 + 0.030 GB
 MEASURED_SIM_TRAFFIC_PREFILL32K = 210_000_000        # similarity kernel, one 32768-token layer: 0.203 + 0.008 GB
 
 
