@@ -17,6 +17,8 @@ Long-Range Similarity"):
 * reconstruction KV_hat = f_d(z) + KV_ref with the bias-free
   linear decoder f_d(z) = z W_d                                  -- section 4.1 (reconstruction), section 5.3 (light decompressor)
 * keep-ratio accounting KR                                       -- appendix D, equation (5)
+* attention over a selected subset of the cached tokens
+  (selective decompression under a sparse attention mask)        -- section 4.2, appendix B.2
 
 Readings where the paper is silent or differs from the build target are listed
 in the repository's design notes; the ones that shape this file:
@@ -247,6 +249,18 @@ def decode_attn_direct(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):
     """Reconstruct every cached token, then attend (the definition)."""
     k_hat, v_hat = reconstruct(idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v)
     return dense_attention(q, k_hat, v_hat, scale)
+
+
+def decode_attn_subset(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale, positions):
+    """Attention over the selected cached tokens only: section 4.2 ("Inference with Sparse
+    Attention": selective decompression reconstructs just the KV pairs the sparse attention mask
+    asks for) and appendix B.2 (view construction: index resolution, batch reconstruction).
+    positions: distinct token positions; the definition is reconstruct-those-then-attend.
+    An empty selection gives out = 0 and lse = -inf."""
+    pos = np.asarray(positions, dtype=np.int64).reshape(-1)
+    if pos.size == 0:
+        return np.zeros((q.shape[0], ref_v.shape[-1])), np.full(q.shape[0], -np.inf)
+    return decode_attn_direct(q, idx[pos], z_k[pos], z_v[pos], ref_k, ref_v, w_up_k, w_up_v, scale)
 
 
 def decode_attn_absorbed(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):

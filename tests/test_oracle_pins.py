@@ -344,6 +344,58 @@ def test_lse_merge_of_two_halves_equals_whole():                   # P9
     assert np.max(np.abs(out - whole)) < 1e-12 and np.max(np.abs(lse - lw)) < 1e-12
 
 
+# ---------------------------------------------------------------- subset decode pins
+def test_subset_of_all_tokens_is_the_full_attention_and_order_is_free():
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=43, L=101)
+    full, lf = O.decode_attn_direct(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25)
+    a, la = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25, np.arange(101))
+    assert np.array_equal(a, full) and np.array_equal(la, lf)
+    sel = np.array([5, 99, 17, 64, 3, 42, 8, 0, 77])
+    b, lb = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25, sel)
+    c, lc = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25, np.sort(sel))
+    assert np.max(np.abs(b - c)) < 1e-13 and np.max(np.abs(lb - lc)) < 1e-13
+
+
+def test_subset_equals_explicit_softmax_over_the_reconstructed_rows():
+    """Brute force from the definition: reconstruct everything, keep the selected rows, softmax by hand."""
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=47, L=88)
+    sel = np.array([1, 2, 3, 30, 31, 64, 87])
+    out, lse = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.2, sel)
+    kh, vh = O.reconstruct(res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv)
+    for g in range(6):
+        h = g // 3
+        logit = np.array([0.2 * float(kh[t, h] @ q[g]) for t in sel])
+        w = np.exp(logit - logit.max())
+        want = sum(w[i] * vh[t, h] for i, t in enumerate(sel)) / w.sum()
+        assert np.max(np.abs(out[g] - want)) < 1e-13
+        assert abs(lse[g] - (logit.max() + math.log(w.sum()))) < 1e-13
+
+
+def test_subset_of_reference_tokens_is_dense_attention_over_raw_references():
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=53, L=90, s=4)
+    sel = np.arange(0, 90, 4)[[0, 3, 4, 9, 22]]
+    out, _ = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.25, sel)
+    assert np.max(np.abs(out - _torch_sdpa(q, K[sel], V[sel], 0.25))) < 1e-12
+
+
+def test_subset_single_token_empty_selection_and_merge_of_disjoint_subsets():
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=59, L=75)
+    kh, vh = O.reconstruct(res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv)
+    out, lse = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3, [41])
+    for g in range(6):
+        assert np.max(np.abs(out[g] - vh[41, g // 3])) < 1e-14
+        assert abs(lse[g] - 0.3 * float(kh[41, g // 3] @ q[g])) < 1e-13
+    out0, lse0 = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3, [])
+    assert np.all(out0 == 0) and np.all(np.isneginf(lse0))
+    a_sel, b_sel = np.array([0, 9, 33, 70]), np.array([2, 10, 11, 50, 74])
+    parts = [O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3, x)
+             for x in (a_sel, b_sel)]
+    both, lboth = O.decode_attn_subset(q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3,
+                                       np.concatenate([a_sel, b_sel]))
+    out, lse = O.merge_partials([p[0] for p in parts], [p[1] for p in parts])
+    assert np.max(np.abs(out - both)) < 1e-12 and np.max(np.abs(lse - lboth)) < 1e-12
+
+
 def test_joint_latent_is_sum_of_stream_projections():
     K, V, cls, P = _small_case(seed=43, L=40, H=1, D=16, r=8, s=4, joint=True)
     wk, wv = P["w_down_k_f64"], P["w_down_v_f64"]
