@@ -205,6 +205,36 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* layout,
                         int32_t batch, float scale, void* out, float* lse,
                         void* workspace, int64_t ws_bytes, void* stream);
 
+/* deltakv_decode_attn restricted to selected tokens: the attention of section 4.2
+ * ("Inference with Sparse Attention"), where only the tokens a sparse attention
+ * mask asks for are reconstructed (appendix B.2, view construction: index
+ * resolution and batch reconstruction).  For sequence b the selection is an
+ * ascending list of logical pages (token position / page_tokens) that hold at
+ * least one selected token, and for each listed page a bit mask of its selected
+ * tokens:
+ *   sel_pages   device int32 [batch][sel_stride]  logical pages, ascending, distinct
+ *   sel_masks   device int32 [batch][sel_stride]  bit t set: token page*P + t selected
+ *   n_sel       device int32 [batch] entries used per sequence; n_sel_host: the
+ *               same values on the host (each in [0, sel_stride])
+ * Positions at or past seq_lens[b] are ignored; a sequence with nothing selected
+ * gets out = 0 and lse = -inf.  out / lse are the softmax over the selected tokens
+ * only.  Whole pages are streamed, so a selection costs the traffic of the pages it
+ * touches: it is cheapest when selected tokens share pages.  Every raw reference
+ * is still scored once per call.  The exponent offset of the softmax is the largest
+ * reference score of the sequence; if every selected token's logit lies more than
+ * about 40 nats below it the weights underflow and bit 0 of the status word is set.
+ * Other arguments, workspace, status word and errors as deltakv_decode_attn. */
+int deltakv_decode_attn_subset(const deltakv_dims* dims, const deltakv_layout* layout,
+                               const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
+                               const int32_t* block_tables, int32_t bt_stride,
+                               const int32_t* ref_tables, int32_t rt_stride,
+                               const void* w_up_k, const void* w_up_v, const void* q,
+                               const int32_t* seq_lens, const int32_t* seq_lens_host,
+                               const int32_t* sel_pages, const int32_t* sel_masks, int32_t sel_stride,
+                               const int32_t* n_sel, const int32_t* n_sel_host,
+                               int32_t batch, float scale, void* out, float* lse,
+                               void* workspace, int64_t ws_bytes, void* stream);
+
 const char* deltakv_strerror(int code);
 /* For DELTAKV_E_HIP: which runtime call failed and the runtime's message (calling thread's last failure;
  * empty string if none).  The pointer stays valid until the thread's next failing call. */
@@ -212,7 +242,7 @@ const char* deltakv_last_error_detail(void);
 int deltakv_version(void);
 
 /* Launch-shape overrides for benchmark sweeps (process-wide; value 0 restores the automatic choice):
- *   "stream_waves"  waves per block of the decode streaming kernel (8 or 16)
+ *   "stream_waves"  waves per block of the decode streaming kernel (8)
  *   "splits"        token-range splits per (sequence, kv-head) in decode (1..16)
  *   "sim_tb"        16-token blocks per wave of the similarity kernel (1, 2 or 4)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)

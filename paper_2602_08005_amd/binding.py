@@ -76,6 +76,10 @@ def _load() -> C.CDLL:
     lib.deltakv_decode_attn.restype = C.c_int
     lib.deltakv_decode_attn.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                         vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, i64, vp]
+    lib.deltakv_decode_attn_subset.restype = C.c_int
+    lib.deltakv_decode_attn_subset.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
+                                               vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, C.c_float, vp, vp,
+                                               vp, i64, vp]
     return lib
 
 
@@ -84,7 +88,7 @@ KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", 
                 "project")
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
-           "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn")
+           "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset")
 
 
 def version() -> int:
@@ -188,4 +192,20 @@ def decode_attn(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if check and rc != OK:
         raise DeltaKVError(rc, "deltakv_decode_attn")
+    return rc
+
+
+def decode_attn_subset(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref_tables, w_up_k, w_up_v, q,
+                       seq_lens, seq_lens_host, sel_pages, sel_masks, n_sel, n_sel_host, scale, out, lse, workspace,
+                       stream=None, check=True) -> int:
+    sl_h, ns_h = _host_i32(seq_lens_host), _host_i32(n_sel_host)
+    rc = _lib.deltakv_decode_attn_subset(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_up_k), _dp(w_up_v), _dp(q), _dp(seq_lens), sl_h.ctypes.data,
+        _dp(sel_pages), _dp(sel_masks), sel_pages.shape[1], _dp(n_sel), ns_h.ctypes.data, len(sl_h), float(scale),
+        _dp(out), _dp(lse), _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_decode_attn_subset")
     return rc

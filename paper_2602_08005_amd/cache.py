@@ -152,3 +152,35 @@ class PagedCache:
                       self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host, scale,
                       out, lse, self.decode_ws, stream)
         return out
+
+    def selection(self, positions_per_seq):
+        """Page lists + token masks (device int32 tensors) for per-sequence arrays of selected token positions."""
+        torch = self.torch
+        P = self.dims.page_tokens
+        lists = []
+        for pos in positions_per_seq:
+            pos = np.unique(np.asarray(pos, dtype=np.int64))
+            pages, inv = np.unique(pos // P, return_inverse=True)
+            masks = np.zeros(len(pages), dtype=np.int64)
+            np.bitwise_or.at(masks, inv, 1 << (pos % P))
+            lists.append((pages.astype(np.int32), masks.astype(np.int32)))
+        stride = max(1, max(len(p) for p, _ in lists))
+        sp = np.zeros((len(lists), stride), dtype=np.int32)
+        sm = np.zeros((len(lists), stride), dtype=np.int32)
+        n = np.zeros(len(lists), dtype=np.int32)
+        for b, (p, m) in enumerate(lists):
+            sp[b, :len(p)], sm[b, :len(p)], n[b] = p, m, len(p)
+        return torch.from_numpy(sp).to(self.device), torch.from_numpy(sm).to(self.device), \
+            torch.from_numpy(n).to(self.device), n
+
+    def decode_attn_subset(self, w_up_k, w_up_v, q, seq_lens_host, positions_per_seq, scale, out=None, lse=None,
+                           stream=None):
+        torch = self.torch
+        seq_lens = torch.tensor(np.asarray(seq_lens_host, dtype=np.int32), device=self.device)
+        sp, sm, n_dev, n_host = self.selection(positions_per_seq)
+        if out is None:
+            out = torch.empty_like(q)
+        B.decode_attn_subset(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
+                             self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host,
+                             sp, sm, n_dev, n_host, scale, out, lse, self.decode_ws, stream)
+        return out

@@ -29,6 +29,22 @@ namespace dkv {
 __device__ inline int seq_len_of(const DecodeParams& P, int b) {
   return clampi(P.seq_lens[b], 0, P.max_seq_len);
 }
+// Entries of the page list the blocks of sequence b iterate over: all pages of the sequence, or (subset attention:
+// section 4.2, only the tokens the sparse attention mask asks for are reconstructed) its selected pages.
+__device__ inline int work_pages_of(const DecodeParams& P, int b, int L) {
+  const int n_pages = ceil_div(L, kPage);
+  if (!P.sel_pages) return n_pages;
+  return clampi(P.n_sel[b], 0, min(P.sel_stride, n_pages));
+}
+// Logical page of list entry `pos` of sequence b (L > 0), clamped into the sequence.
+__device__ inline int work_page(const DecodeParams& P, int b, int L, int pos) {
+  if (!P.sel_pages) return pos;
+  return clampi(P.sel_pages[(int64_t)b * P.sel_stride + pos], 0, ceil_div(L, kPage) - 1);
+}
+// Ordinals that list entries [0, p1) of the sequence can point at (p1 >= 1).
+__device__ inline int refs_covered(const DecodeParams& P, int b, int L, int p1) {
+  return refs_below(min(L, (work_page(P, b, L, p1 - 1) + 1) * kPage), P.stride);
+}
 
 // The per-reference weight table is kept in 32-bit fixed point, because the LDS executes integer atomics at
 // full rate while a float atomic add costs about three cycles per active lane on this chip.  A token that
@@ -70,14 +86,14 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
     const int per = ceil_div(P.batch, 256), b_lo = min((int)threadIdx.x * per, P.batch), b_hi = min(b_lo + per, P.batch);
     int cnt = 0;
     for (int bb = b_lo; bb < b_hi; ++bb)
-      cnt += used_splits(ceil_div(seq_len_of(P, bb), kPage), P.S, P.pages_per_split);
+      cnt += used_splits(work_pages_of(P, bb, seq_len_of(P, bb)), P.S, P.pages_per_split);
     run_items[threadIdx.x] = cnt;
     __syncthreads();
     int at = 0;
     for (int t = 0; t < (int)threadIdx.x; ++t) at += run_items[t];
     if (threadIdx.x == 255) P.items[0] = at + cnt;
     for (int bb = b_lo; bb < b_hi; ++bb) {
-      const int ns = used_splits(ceil_div(seq_len_of(P, bb), kPage), P.S, P.pages_per_split);
+      const int ns = used_splits(work_pages_of(P, bb, seq_len_of(P, bb)), P.S, P.pages_per_split);
       for (int s = 0; s < ns; ++s) P.items[1 + at + s] = bb * kMaxSplits + s;
       at += ns;
     }
@@ -230,7 +246,7 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // blocks are not free here: each needs a whole compute unit's LDS before it can start and exit.)  Blocks of the kv-heads
 // of one item run side by side and sweep the same pages; with eight kv-heads, block id % 8 = head, so all splits of a
 // (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
-template <int R, int NW, int PIPE_LG, bool JOINT>
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   extern __shared__ float smem[];
   const int item_q = blockIdx.x / P.Hkv, h = blockIdx.x % P.Hkv;
@@ -240,13 +256,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const int pair = b * P.Hkv + h;
   const int L = seq_len_of(P, b);
   if (L <= 0) return;
-  const int n_pages = ceil_div(L, kPage);
+  const int n_pages = work_pages_of(P, b, L);             // entries of the sequence's page list
+  if (n_pages <= 0) return;
   const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
   if (s >= sp.n_splits) return;
   const int p0 = s * sp.per, p1 = min(n_pages, p0 + sp.per);
   if (p0 >= p1) return;
-  const int end_tok = min(L, p1 * kPage);
-  const int n_cov = refs_below(end_tok, P.stride);      // ordinals this split can touch
+  const int n_cov = refs_covered(P, b, L, p1);          // ordinals this split can touch
   const int n_ref = refs_below(L, P.stride);
   const int Gp = P.Gp, G = P.G;
   const int n_tab = n_cov * Gp;
@@ -372,8 +388,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
     }
   };
-  // FULL: all 16 tokens of the page are valid (no masking code at all); otherwise nvalid in (-inf, 16].
-  auto compute = [&](auto full_tag, Tile<R>& t, const int id, const float4& srv, const int nvalid) {
+  // FULL: all 16 tokens of the page take part (no masking code at all); otherwise bit t of `mask` says whether
+  // token t does (a valid token of the sequence and, in subset attention, a selected one).
+  auto compute = [&](auto full_tag, Tile<R>& t, const int id, const float4& srv, const uint32_t mask) {
     constexpr bool FULL = decltype(full_tag)::value;
     float sr[4];
     quad_transpose(srv, sr);
@@ -388,7 +405,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float x = d[e] + sr[e];
-      if (!FULL) x = ((int)(4 * lg) + e < nvalid) ? x : -INFINITY;   // select, not arithmetic: garbage may be NaN
+      if (!FULL) x = ((mask >> (4 * lg + e)) & 1u) ? x : -INFINITY;   // select, not arithmetic: garbage may be NaN
       p[e] = __builtin_amdgcn_exp2f(x);
       lsum += p[e];
     }
@@ -438,12 +455,14 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
       __builtin_amdgcn_wave_barrier();
     }
-    if (!FULL) {             // mask value-operand slots that hold garbage
+    if (!FULL) {             // zero the value-operand slots of tokens that do not take part (they may hold garbage)
+      const uint32_t m4 = mask >> (4 * lg);       // this lane's four tokens
+      const uint32_t keep_x = ((m4 & 1u) ? 0x0000ffffu : 0u) | ((m4 & 2u) ? 0xffff0000u : 0u);
+      const uint32_t keep_y = ((m4 & 4u) ? 0x0000ffffu : 0u) | ((m4 & 8u) ? 0xffff0000u : 0u);
 #pragma unroll
       for (int nb = 0; nb < Tile<R>::NB; ++nb) {
-        const int left = nvalid - (int)(4 * lg);   // valid tokens among this lane's four
-        if (left < 4) t.zv[nb].y &= left < 3 ? 0u : 0x0000ffffu;
-        if (left < 2) t.zv[nb].x &= left < 1 ? 0u : 0x0000ffffu;
+        t.zv[nb].x &= keep_x;
+        t.zv[nb].y &= keep_y;
       }
     }
 #pragma unroll
@@ -473,9 +492,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     // keep hitting the same HBM channels.  The order is free because every partial sum simply adds.  The block
     // that holds the sequence's partial last page does not rotate, so that page comes last and every earlier
     // draw is made of full pages only: the steady-state loop carries no masking code.
-    const bool has_partial = (L & (kPage - 1)) != 0 && p1 == n_pages;
+    // (Subset attention runs the masked loop body throughout.)
+    const bool has_partial = !SUBSET && (L & (kPage - 1)) != 0 && p1 == n_pages;
     const int rot = has_partial ? 0 : (int)(((uint32_t)pair * 2654435761u + (uint32_t)s * 40503u) >> 8) % n_blk;
-    const int n_full = n_blk - (has_partial ? 1 : 0);
+    const int n_full = SUBSET ? 0 : n_blk - (has_partial ? 1 : 0);
     // Draw c (positions c*ST .. c*ST+ST-1) covers pages c%NW, c%NW + NW, ... of the (c/NW)-th group of NW*ST pages,
     // so the NW draws that the waves of a block hold at about the same time interleave page by page and the
     // block sweeps one contiguous region; positions of the last, incomplete group that map past the range are
@@ -491,12 +511,27 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       int xx = (pgi < n_blk ? pgi : n_blk - 1) + rot;
       return xx >= n_blk ? xx - n_blk : xx;
     };
-    auto valid_of = [&](int x) { return pos_page(x) < n_blk ? L - (p0 + local_page(x)) * kPage : 0; };
+    // list entry -> logical page and the mask of its tokens that take part
+    const int32_t* selp = SUBSET ? P.sel_pages + (int64_t)b * P.sel_stride : nullptr;
+    const int32_t* selm = SUBSET ? P.sel_masks + (int64_t)b * P.sel_stride : nullptr;
+    const int last_logical = ceil_div(L, kPage) - 1;
+    auto logical_of = [&](int entry) { return SUBSET ? clampi(selp[entry], 0, last_logical) : entry; };
+    auto mask_vec = [&](int base) {                           // lane u: mask of position base + u
+      const int x = base + (int)l;
+      const int entry = p0 + local_page(x);
+      const int left = L - logical_of(entry) * kPage;         // valid tokens of the page (>= 1)
+      uint32_t m = left >= kPage ? 0xffffu : (1u << left) - 1u;
+      if (SUBSET) {
+        m &= (uint32_t)selm[entry];
+        if ((uint32_t)selp[entry] > (uint32_t)last_logical) m = 0u;   // a listed page outside the sequence
+      }
+      return (int)(pos_page(x) < n_blk ? m : 0u);
+    };
     // Pool pages of a draw come from the block table with ONE vector load (lane u holds the page of position
     // base + u) and are handed to the stages with v_readlane at a constant lane.  A scalar load per stage would sit
     // in the same out-of-order counter as the LDS atomics and force a full wait-for-everything each time.
     auto page_vec = [&](int base) {
-      return clampi(bt[p0 + local_page(base + (int)l)], 0, (int)P.n_pages_pool - 1);
+      return clampi(bt[logical_of(p0 + local_page(base + (int)l))], 0, (int)P.n_pages_pool - 1);
     };
     auto draw = [&]() {                                       // next ST positions of the block (wave-uniform)
       uint32_t v = 0;
@@ -514,6 +549,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       for (int u = 0; u < ST; ++u) pg[u] = __builtin_amdgcn_readlane(pv0, u);
     }
     int pgit_next = page_vec(cb1);
+    int mk_next = mask_vec(cb);                               // masks of the draw about to be computed
 #pragma unroll
     for (int u = 0; u < LI; ++u) id[u] = load_ordinal(idx_h, idx_page_bytes, pg[u], l);
 #pragma unroll
@@ -523,6 +559,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     auto body = [&](auto full_tag) {
       const int pgit = pgit_next;                             // pages of the next draw
       pgit_next = page_vec(cb2);
+      const int mk = mk_next;                                 // masks of this draw
+      mk_next = mask_vec(cb1);
       const int cb3 = draw();
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
@@ -530,7 +568,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         load_latents<R, JOINT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
         pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
-        compute(full_tag, t[u], id[u], sr[u], decltype(full_tag)::value ? kPage : valid_of(cb + u));
+        compute(full_tag, t[u], id[u], sr[u],
+                decltype(full_tag)::value ? 0xffffu : (uint32_t)__builtin_amdgcn_readlane(mk, u));
       }
       cb = cb1; cb1 = cb2; cb2 = cb3;
     };
@@ -595,7 +634,7 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   const int j0 = chunk * kRefChunk;
   if (j0 >= n_ref) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
-  const int n_pages = ceil_div(L, kPage);
+  const int n_pages = work_pages_of(P, b, L);
   const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;   // V half
@@ -636,8 +675,8 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
 #pragma unroll
         for (int s = 0; s < kMaxSplits; ++s) {
           const int p1 = min(n_pages, (s + 1) * sp.per);
-          const int cov = refs_below(min(L, p1 * kPage), P.stride);   // ordinals split s wrote
-          if (s < sp.n_splits && s * sp.per < p1 && j < cov && (((plain >> s) & 1u) != 0u) == want_plain) {
+          if (s < sp.n_splits && s * sp.per < p1 && j < refs_covered(P, b, L, p1) &&   // ordinals split s wrote
+              (((plain >> s) & 1u) != 0u) == want_plain) {
             const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
 #pragma unroll
             for (int g4 = 0; g4 < GP; g4 += 4) {
@@ -731,7 +770,8 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   const int h = gh / G, g = gh % G;
   const int L = seq_len_of(P, b);
   const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
-  if (L <= 0) {
+  const int n_pages = work_pages_of(P, b, L);
+  if (n_pages <= 0) {         // empty sequence or empty selection
     P.out[orow + d] = 0;
     if (P.lse && d == 0) P.lse[(int64_t)b * P.Hq + gh] = -INFINITY;
     return;
@@ -740,7 +780,6 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   __shared__ float redm[2];
   const int n_ref = refs_below(L, P.stride);
   const int nch = ceil_div(n_ref, kRefChunk);
-  const int n_pages = ceil_div(L, kPage);
   const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
   int n_used = 0;
   for (int s = 0; s < sp.n_splits; ++s)
@@ -791,7 +830,7 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT>
+template <int R, int NW, bool JOINT, bool SUBSET>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
@@ -808,26 +847,26 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 
-template <int NW, bool JOINT>
+template <int NW, bool JOINT, bool SUBSET>
 static hipError_t dispatch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
   switch (P.R) {
-    case 16: return launch_stream<16, NW, JOINT>(P, grid, lds, st);
-    case 32: return launch_stream<32, NW, JOINT>(P, grid, lds, st);
-    case 48: return launch_stream<48, NW, JOINT>(P, grid, lds, st);
-    case 64: return launch_stream<64, NW, JOINT>(P, grid, lds, st);
-    case 80: return launch_stream<80, NW, JOINT>(P, grid, lds, st);
-    case 96: return launch_stream<96, NW, JOINT>(P, grid, lds, st);
-    case 112: return launch_stream<112, NW, JOINT>(P, grid, lds, st);
-    case 128: return launch_stream<128, NW, JOINT>(P, grid, lds, st);
+    case 16: return launch_stream<16, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 32: return launch_stream<32, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 48: return launch_stream<48, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 64: return launch_stream<64, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 80: return launch_stream<80, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 96: return launch_stream<96, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 112: return launch_stream<112, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 128: return launch_stream<128, NW, JOINT, SUBSET>(P, grid, lds, st);
   }
   return hipErrorInvalidValue;
 }
@@ -847,10 +886,11 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);
   dim3 gs(n_items > 0 ? n_items * P.Hkv : 1);
-  if (P.joint)
-    e = (nw == 16) ? dispatch_stream<16, true>(P, gs, lds, st) : dispatch_stream<8, true>(P, gs, lds, st);
+  if (nw != 8) return hipErrorInvalidValue;
+  if (P.sel_pages)
+    e = P.joint ? dispatch_stream<8, true, true>(P, gs, lds, st) : dispatch_stream<8, false, true>(P, gs, lds, st);
   else
-    e = (nw == 16) ? dispatch_stream<16, false>(P, gs, lds, st) : dispatch_stream<8, false>(P, gs, lds, st);
+    e = P.joint ? dispatch_stream<8, true, false>(P, gs, lds, st) : dispatch_stream<8, false, false>(P, gs, lds, st);
   if (e != hipSuccess) return e;
   timing_mark(K_STREAM, st);
   switch (P.Gp) {

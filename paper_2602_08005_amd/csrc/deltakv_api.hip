@@ -101,7 +101,7 @@ const char* deltakv_last_error_detail(void) { return g_detail; }
 int deltakv_tune(const char* name, int32_t value) {
   if (!name || value < 0) return DELTAKV_E_INVALID_ARG;
   if (!strcmp(name, "stream_waves")) {
-    if (value != 0 && value != 8 && value != 16) return DELTAKV_E_INVALID_ARG;
+    if (value != 0 && value != 8) return DELTAKV_E_INVALID_ARG;
     g_tune_stream_waves = value;
   } else if (!strcmp(name, "splits")) {
     if (value > kMaxSplits) return DELTAKV_E_INVALID_ARG;
@@ -205,12 +205,21 @@ double deltakv_keep_ratio(const deltakv_dims* dims) {
   return (rec + (raw + 4.0) / dims->ref_stride) / raw;
 }
 
-int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
-                        const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
-                        int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
-                        const void* w_up_v, const void* q, const int32_t* seq_lens,
-                        const int32_t* seq_lens_host, int32_t batch, float scale, void* out, float* lse,
-                        void* workspace, int64_t ws_bytes, void* stream) {
+// Selection arguments of the subset entry point (all null / 0 for attention over the whole cache).
+struct Selection {
+  const int32_t* pages = nullptr;
+  const int32_t* masks = nullptr;
+  const int32_t* n_sel = nullptr;
+  const int32_t* n_sel_host = nullptr;
+  int32_t stride = 0;
+};
+
+static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                       const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                       int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                       const void* w_up_v, const void* q, const int32_t* seq_lens,
+                       const int32_t* seq_lens_host, const Selection& sel, int32_t batch, float scale, void* out,
+                       float* lse, void* workspace, int64_t ws_bytes, void* stream) {
   int rc = check_dims(dims);
   if (rc != DELTAKV_OK) return rc;
   if (!lay || !latent_pool || !idx_pool || !ref_pool || !block_tables || !ref_tables || !w_up_k || !w_up_v ||
@@ -247,16 +256,26 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   // Blocks of at most pages_per_split pages: about one per block slot when all sequences have the same length,
   // about two when the lengths differ (blocks are handed out as slots free up, so smaller blocks even out a
   // ragged batch; each block costs several microseconds of set-up and flush, which nothing overlaps).
+  // pages a sequence's blocks iterate over: all of its pages, or the selected ones
+  auto work_pages = [&](int b) {
+    const int n_pages = ceil_div(seq_lens_host[b], P);
+    if (!sel.pages) return n_pages;
+    const int n = sel.n_sel_host[b] < sel.stride ? sel.n_sel_host[b] : sel.stride;
+    return n < 0 ? 0 : (n < n_pages ? n : n_pages);
+  };
   int64_t total_pages = 0;
+  int max_work = 1;
   bool uniform = true;
   for (int b = 0; b < batch; ++b) {
-    total_pages += ceil_div(seq_lens_host[b], P);
-    uniform = uniform && seq_lens_host[b] == seq_lens_host[0];
+    const int wp = work_pages(b);
+    total_pages += wp;
+    if (wp > max_work) max_work = wp;
+    uniform = uniform && wp == work_pages(0);
   }
   total_pages *= dims->n_kv_heads;
   const int64_t pages_target = ceil_div64(total_pages, (uniform ? 1 : 2) * slots);
-  int splits = (int)ceil_div64(max_pages, pages_target > 0 ? pages_target : 1);
-  const int split_cap = max_pages / 8 > 1 ? max_pages / 8 : 1;    // at least 8 pages per split
+  int splits = (int)ceil_div64(max_work, pages_target > 0 ? pages_target : 1);
+  const int split_cap = max_work / 8 > 1 ? max_work / 8 : 1;    // at least 8 pages per split
   if (splits > split_cap) splits = split_cap;
   if (splits > kMaxSplits) splits = kMaxSplits;
   if (splits < 1) splits = 1;
@@ -304,7 +323,11 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   Pm.n_ref_max = n_ref_max;
   Pm.n_chunk_max = ceil_div(n_ref_max, kRefChunk);
   Pm.S = splits;
-  Pm.pages_per_split = ceil_div(max_pages, splits);
+  Pm.pages_per_split = ceil_div(max_work, splits);
+  Pm.sel_pages = sel.pages;
+  Pm.sel_masks = sel.masks;
+  Pm.n_sel = sel.n_sel;
+  Pm.sel_stride = sel.stride;
   Pm.qk_scale_log2 = scale * kLog2e;
   char* wsb = static_cast<char*>(workspace);
   Pm.status = reinterpret_cast<int32_t*>(wsb + ws.status);
@@ -321,10 +344,42 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
   // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
   // from the device copy of the lengths
   int64_t n_items = 0;
-  for (int b = 0; b < batch; ++b)
-    n_items += used_splits(ceil_div(seq_lens_host[b], P), Pm.S, Pm.pages_per_split);
+  for (int b = 0; b < batch; ++b) n_items += used_splits(work_pages(b), Pm.S, Pm.pages_per_split);
   hipError_t e = launch_decode(Pm, batch, (int)n_items, nw, lds, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
+}
+
+int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                        const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                        int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                        const void* w_up_v, const void* q, const int32_t* seq_lens,
+                        const int32_t* seq_lens_host, int32_t batch, float scale, void* out, float* lse,
+                        void* workspace, int64_t ws_bytes, void* stream) {
+  return decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
+                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, Selection{}, batch, scale, out, lse, workspace,
+                     ws_bytes, stream);
+}
+
+int deltakv_decode_attn_subset(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                               const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                               int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride,
+                               const void* w_up_k, const void* w_up_v, const void* q, const int32_t* seq_lens,
+                               const int32_t* seq_lens_host, const int32_t* sel_pages, const int32_t* sel_masks,
+                               int32_t sel_stride, const int32_t* n_sel, const int32_t* n_sel_host, int32_t batch,
+                               float scale, void* out, float* lse, void* workspace, int64_t ws_bytes,
+                               void* stream) {
+  if (!sel_pages || !sel_masks || !n_sel || !n_sel_host || sel_stride <= 0) return DELTAKV_E_INVALID_ARG;
+  for (int b = 0; b < batch; ++b)
+    if (n_sel_host[b] < 0 || n_sel_host[b] > sel_stride) return DELTAKV_E_INVALID_ARG;
+  Selection sel;
+  sel.pages = sel_pages;
+  sel.masks = sel_masks;
+  sel.n_sel = n_sel;
+  sel.n_sel_host = n_sel_host;
+  sel.stride = sel_stride;
+  return decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
+                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, sel, batch, scale, out, lse, workspace, ws_bytes,
+                     stream);
 }
 
 int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,

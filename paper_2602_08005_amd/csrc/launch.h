@@ -12,6 +12,12 @@ struct DecodeParams {
   const int32_t* block_tables;
   const int32_t* ref_tables;
   const int32_t* seq_lens;
+  // subset attention (all null for the whole cache): per sequence an ascending list of logical pages that hold a
+  // selected token, and per listed page the 16-bit mask of its selected tokens
+  const int32_t* sel_pages;
+  const int32_t* sel_masks;
+  const int32_t* n_sel;
+  int sel_stride;
   int bt_stride, rt_stride;
   int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
   int64_t idx_page_stride, idx_head_stride;
