@@ -324,6 +324,11 @@ def main():
                          "32768-token prompt over the layers (reports compress tokens/s and the similarity GEMM's "
                          "fraction of the MFMA roofline)")
     ap.add_argument("--contiguous", action="store_true", help="ragged workload: identity page placement (experiment)")
+    ap.add_argument("--select", type=float, default=0.0, metavar="FRACTION",
+                    help="decode128k: attend only a selected subset (deltakv_decode_attn_subset): this fraction of "
+                         "each sequence's pages, drawn at random per layer, all 16 tokens of a drawn page")
+    ap.add_argument("--select-tokens", action="store_true",
+                    help="with --select: draw single tokens instead of whole pages (same number of tokens)")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")
@@ -406,11 +411,35 @@ def main():
     log(f"[bench] setup done in {time.time() - t_setup:.1f} s; "
         f"{torch.cuda.memory_allocated() / 1e9:.1f} GB resident")
 
+    # ---- optional subset attention: one selection per layer (seeded), resident on the device before timing
+    selections = None
+    n_pages_seq = L // 16
+    if args.select > 0:
+        n_pick = max(1, int(round(args.select * n_pages_seq)))
+        selections = []
+        for layer in range(NL):
+            rng = np.random.Generator(np.random.Philox(G.seed_for(3, layer) + 77))
+            pos = []
+            for b in range(Bt):
+                if args.select_tokens:
+                    pos.append(np.sort(rng.choice(L, n_pick * 16, replace=False)))
+                else:
+                    pg = np.sort(rng.choice(n_pages_seq, n_pick, replace=False))
+                    pos.append((pg[:, None] * 16 + np.arange(16)[None, :]).ravel())
+            selections.append(cache.selection(pos) + (pos[0],))
+        sel_pages_touched = float(np.mean([int(sel[3].sum()) for sel in selections])) / Bt
+
     def step():
         for layer in range(NL):
-            B.decode_attn(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
-                          cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, scale, outs[layer],
-                          None, cache.decode_ws)
+            if selections is None:
+                B.decode_attn(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
+                              cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, scale, outs[layer],
+                              None, cache.decode_ws)
+            else:
+                sp, sm, n_dev, n_host, _ = selections[layer]
+                B.decode_attn_subset(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
+                                     cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, sp, sm, n_dev,
+                                     n_host, scale, outs[layer], None, cache.decode_ws)
 
     for _ in range(args.warmup):
         step()
@@ -432,9 +461,14 @@ def main():
     units = Bt * L * Hkv                                  # (token, kv-head) records per launch
     stream_bytes = units * (n_streams * r * 2 + 4)                # bf16 latent stream(s) + int32 ordinal
     path_bytes = units * (n_streams * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
+    if selections is not None:
+        # subset attention: the selected tokens' records (the method's bytes), each raw reference still read once
+        sel_units = Bt * n_pick * 16 * Hkv
+        stream_bytes = sel_units * (n_streams * r * 2 + 4)
+        path_bytes = stream_bytes + units * (2 * D * 2 / s)
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64):
+    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
     kernel_ms = {}
     if timing:
@@ -457,8 +491,12 @@ def main():
         K0, V0 = host_kv0
         qh = f(qs[0][0].cpu().numpy().view(np.uint16))
         t0 = time.perf_counter()
-        want, _ = O.decode_attn_direct(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
-                                       f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
+        if selections is None:
+            want, _ = O.decode_attn_direct(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+                                           f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
+        else:
+            want, _ = O.decode_attn_subset(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+                                           f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale, selections[0][4])
         t_slice = time.perf_counter() - t0
         got = f(outs[0][0].cpu().numpy().view(np.uint16))
         parity = {"what": "layer 0, sequence 0, all query heads vs CPU oracle",
@@ -477,7 +515,11 @@ def main():
         "config": {"workload": f"long-context decode: batch {Bt} x {L} tokens, {NL} layers sequential, "
                                f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents, stride {s}, 16-token pages",
                    "latent_mode": args.mode.upper(), "keep_ratio": round(dk.keep_ratio(dims), 4),
-                   "layers_are_copies_of_layer0": True},
+                   "layers_are_copies_of_layer0": True,
+                   **({} if selections is None else {
+                       "subset": f"{n_pick * 16} of {L} tokens per sequence selected "
+                                 f"({'single tokens' if args.select_tokens else 'whole pages'}, drawn per layer), "
+                                 f"{sel_pages_touched:.0f} pages touched per sequence"})},
         "roofline": roof,
         "cpu_baseline": cpu,
         "path_hbm_frac": round(path_gbs / HBM_PEAK_GBS, 4),
