@@ -255,7 +255,8 @@ int deltakv_tune(const char* name, int32_t value);
  * returns, per kernel, the summed time between the surrounding events in milliseconds (this includes
  * the launch gap in front of the kernel) and the number of launches.  Kernel order:
  *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
- *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress)
+ *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress; a call that appends exactly
+ *     one token to every sequence runs two kernels, reported as 5 (candidate scan) and 8 (finish))
  * Arrays are host memory with n >= DELTAKV_N_KERNELS entries.  Errors: INVALID_ARG, HIP. */
 #define DELTAKV_N_KERNELS 9
 int deltakv_timing_begin(void);

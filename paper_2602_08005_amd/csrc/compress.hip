@@ -592,6 +592,251 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Decode append: every sequence of the call brings exactly one new token.  Two kernels instead of five (the
+// step is bound by launch latency: a few microseconds of work per kernel).
+//   append_scan   grid (NS, Hkv, B), 256 threads: block (s, h, b) scores its share of the token's candidate
+//                 references in fp32 (16 lanes per reference, 16 references per block step) and writes its
+//                 (best, second, arg best, |token|^2); if the token is itself a reference, block s = 0 admits it.
+//   append_finish grid (Hkv, B), 256 threads: merges the NS partial results; re-scores every candidate in fp64 if
+//                 the two best are too close to call (same band as resolve); forms the residual against the chosen
+//                 raw reference, projects it (fp32 FMAs) and writes latent + ordinal.
+// ------------------------------------------------------------------------------------------------
+__device__ inline float group16_sum(float v) {   // sum over the 16 lanes that share lane/16
+  v += __shfl_xor(v, 1);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 8);
+  return v;
+}
+__device__ inline double group16_sum(double v) {
+  v += __shfl_xor(v, 1);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 8);
+  return v;
+}
+__device__ inline void unpack8(const uint4& c, float (&o)[8]) {
+  o[0] = bf16lo(c.x); o[1] = bf16hi(c.x); o[2] = bf16lo(c.y); o[3] = bf16hi(c.y);
+  o[4] = bf16lo(c.z); o[5] = bf16hi(c.z); o[6] = bf16lo(c.w); o[7] = bf16hi(c.w);
+}
+
+__global__ __launch_bounds__(256) void k_append_scan(CompressParams P) {
+  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, sub = l & 15, lg = l >> 4;
+  const int pos = P.len_before[b];
+  const int64_t n = P.cu_new[b];
+  const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
+  const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+  if (pos % P.stride == 0) {          // the new token is a reference: raw copy + inverse norm (first wave of split 0)
+    if (s != 0 || w != 0) return;
+    const int ord = pos / P.stride;
+    if (ord >= P.rt_stride) return;
+    const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
+    const uint32_t kx = reinterpret_cast<const uint32_t*>(kr)[l], vx = reinterpret_cast<const uint32_t*>(vr)[l];
+    uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+    reinterpret_cast<uint32_t*>(rk)[l] = kx;
+    reinterpret_cast<uint32_t*>(rk + P.ref_kv_stride)[l] = vx;
+    float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
+    if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    return;
+  }
+  // the token's K||V chunk of this lane: dims 8*sub..8*sub+7 of K and of V
+  float ak[8], av[8];
+  unpack8(*reinterpret_cast<const uint4*>(kr + sub * 8), ak);
+  unpack8(*reinterpret_cast<const uint4*>(vr + sub * 8), av);
+  float na2 = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) na2 += ak[e] * ak[e] + av[e] * av[e];
+  na2 = group16_sum(na2);
+  const int n_cand = min(refs_below(pos, P.stride), P.rt_stride);
+  const int per = ceil_div(ceil_div(n_cand, P.NS), 16) * 16;       // candidates per split, whole block steps
+  const int j0 = s * per, j1 = min(n_cand, j0 + per);
+  const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;
+  const float* inorm = P.ref_inv_norm + (int64_t)h * P.ref_norm_head_stride;
+  Top2 t2 = {-INFINITY, -INFINITY, -1};
+  constexpr int UN = 4;                                              // block steps of 16 references in flight
+  for (int jb = j0; jb < j1; jb += 16 * UN) {
+    int slot[UN];
+    uint4 ck[UN], cv[UN];
+    float inv[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int j = jb + u * 16 + w * 4 + lg;
+      slot[u] = rtab[min(j, n_cand - 1)];
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int sl = clampi(slot[u], 0, (int)P.n_ref_slots - 1);
+      ck[u] = *reinterpret_cast<const uint4*>(kbase + (int64_t)sl * kHeadDim + sub * 8);
+      cv[u] = *reinterpret_cast<const uint4*>(kbase + P.ref_kv_stride + (int64_t)sl * kHeadDim + sub * 8);
+      inv[u] = inorm[sl];
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int j = jb + u * 16 + w * 4 + lg;
+      float bk[8], bv[8];
+      unpack8(ck[u], bk);
+      unpack8(cv[u], bv);
+      float d = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d += ak[e] * bk[e];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d += av[e] * bv[e];
+      d = group16_sum(d) * inv[u];
+      if (j < j1) top2_push(t2, d, j);          // ascending j within a lane group: strict '>' keeps the lowest
+    }
+  }
+  // merge the four lane groups of the wave, then the four waves
+#pragma unroll
+  for (int o = 16; o < 64; o <<= 1) {
+    const float ob = __shfl_xor(t2.best, o), os = __shfl_xor(t2.second, o);
+    const int oi = __shfl_xor(t2.idx, o);
+    top2_merge(t2, ob, os, oi);
+  }
+  __shared__ float sb[4], ss2[4];
+  __shared__ int si[4];
+  if (l == 0) { sb[w] = t2.best; ss2[w] = t2.second; si[w] = t2.idx; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int ww = 1; ww < 4; ++ww) top2_merge(t2, sb[ww], ss2[ww], si[ww]);
+    reinterpret_cast<float4*>(P.part)[(n * P.Hkv + h) * P.NS + s] =
+        make_float4(t2.best, t2.second, __int_as_float(t2.idx), na2);
+  }
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, sub = l & 15, lg = l >> 4;
+  const int pos = P.len_before[b];
+  const int64_t n = P.cu_new[b];
+  const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
+  const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+  const bool is_ref = pos % P.stride == 0;
+  __shared__ int ord_s;
+  __shared__ double ebest[4];
+  __shared__ int eidx[4];
+  __shared__ float resid[2][kHeadDim];
+  __shared__ float zpart[2][256];
+  if (is_ref) {
+    if (tid == 0) ord_s = pos / P.stride;
+  } else {
+    // merge the partial results (ascending ranges; every thread does the same few loads)
+    float bb = -INFINITY, b2 = -INFINITY, na2 = 0.f;
+    int bi = -1;
+    const float4* pp = reinterpret_cast<const float4*>(P.part) + (n * P.Hkv + h) * P.NS;
+    for (int s = 0; s < P.NS; ++s) {
+      const float4 o = pp[s];
+      na2 = o.w;
+      const int oi = __float_as_int(o.z);
+      if (oi < 0) continue;
+      if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
+      else b2 = fmaxf(b2, o.x);
+    }
+    if (bi >= 0 && bb - b2 > 4e-5f * sqrtf(na2)) {
+      if (tid == 0) ord_s = bi;
+    } else {
+      // too close to call in fp32: every candidate again in fp64, cos = a.b / (|a| |b|), lowest ordinal on ties
+      float akf[8], avf[8];
+      unpack8(*reinterpret_cast<const uint4*>(kr + sub * 8), akf);
+      unpack8(*reinterpret_cast<const uint4*>(vr + sub * 8), avf);
+      double na = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) na += (double)akf[e] * akf[e] + (double)avf[e] * avf[e];
+      na = sqrt(group16_sum(na));
+      const int n_cand = min(refs_below(pos, P.stride), P.rt_stride);
+      const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;
+      double best = -2.0;
+      int besti = 0x7fffffff;
+      for (int jb = 0; jb < n_cand; jb += 16) {
+        const int j = jb + w * 4 + lg;
+        const int sl = clampi(rtab[min(j, n_cand - 1)], 0, (int)P.n_ref_slots - 1);
+        float bk[8], bv[8];
+        unpack8(*reinterpret_cast<const uint4*>(kbase + (int64_t)sl * kHeadDim + sub * 8), bk);
+        unpack8(*reinterpret_cast<const uint4*>(kbase + P.ref_kv_stride + (int64_t)sl * kHeadDim + sub * 8), bv);
+        double d = 0.0, nb = 0.0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          d += (double)akf[e] * bk[e] + (double)avf[e] * bv[e];
+          nb += (double)bk[e] * bk[e] + (double)bv[e] * bv[e];
+        }
+        d = group16_sum(d);
+        nb = sqrt(group16_sum(nb));
+        const double den = na * nb;
+        const double c = den > 0.0 ? d / den : 0.0;
+        if (j < n_cand && (c > best || (c == best && j < besti))) { best = c; besti = j; }
+      }
+#pragma unroll
+      for (int o = 16; o < 64; o <<= 1) {
+        const double ob = __shfl_xor(best, o);
+        const int oi = __shfl_xor(besti, o);
+        if (ob > best || (ob == best && oi < besti)) { best = ob; besti = oi; }
+      }
+      if (l == 0) { ebest[w] = best; eidx[w] = besti; }
+      __syncthreads();
+      if (tid == 0) {
+        for (int ww = 1; ww < 4; ++ww)
+          if (ebest[ww] > best || (ebest[ww] == best && eidx[ww] < besti)) { best = ebest[ww]; besti = eidx[ww]; }
+        ord_s = besti == 0x7fffffff ? 0 : besti;
+      }
+    }
+  }
+  __syncthreads();
+  const int ord = clampi(ord_s, 0, P.rt_stride - 1);
+  // residual against the chosen raw reference (fp32: exact for bf16 inputs); zero for a reference token
+  if (tid < kHeadDim) {
+    const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
+    const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+    const float rkv = __uint_as_float((uint32_t)rk[tid] << 16), rvv = __uint_as_float((uint32_t)rk[P.ref_kv_stride + tid] << 16);
+    const float kx = __uint_as_float((uint32_t)kr[tid] << 16), vx = __uint_as_float((uint32_t)vr[tid] << 16);
+    resid[0][tid] = is_ref ? 0.f : kx - rkv;
+    resid[1][tid] = is_ref ? 0.f : vx - rvv;
+  }
+  __syncthreads();
+  // projection: thread (stream, part, c) sums its share of the 128 dims; R <= 128, 256 threads
+  constexpr int PARTS = 128 / R >= 1 ? 128 / R : 1;        // threads per (stream, c): 128 / R, at least 1
+  {
+    const int st = tid / 128, rem = tid % 128, c = rem % R, part = rem / R;
+    float z = 0.f;
+    if (part < PARTS) {
+      const uint16_t* wd = (st ? P.w_down_v : P.w_down_k) + c;
+      constexpr int DP = kHeadDim / PARTS;
+#pragma unroll 8
+      for (int d = part * DP; d < (part + 1) * DP; ++d) z += resid[st][d] * __uint_as_float((uint32_t)wd[(int64_t)d * R] << 16);
+    }
+    zpart[st][rem] = z;
+  }
+  __syncthreads();
+  const int tok = pos % kPage;
+  const int lp = pos / kPage;
+  const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + min(lp, P.bt_stride - 1)], 0, (int)P.n_pages_pool - 1);
+  uint16_t* lat = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+  if (tid < 2 * R) {
+    const int st = tid / R, c = tid % R;
+    float z = 0.f;
+#pragma unroll
+    for (int pt = 0; pt < PARTS; ++pt) z += zpart[st][pt * R + c];
+    if (P.joint) {
+      if (st == 0) {
+        float zv = 0.f;
+#pragma unroll
+        for (int pt = 0; pt < PARTS; ++pt) zv += zpart[1][pt * R + c];
+        lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z + zv);
+      }
+    } else if (st == 0) {
+      lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z);
+    } else {
+      lat[P.latent_stream_stride + ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3)] = (uint16_t)f32_to_bf16_bits(z);
+    }
+  }
+  if (tid == 0) P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok] = ord;
+}
+
+// ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
 template <int TB>
@@ -660,6 +905,33 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
     case 112: e = launch_project<112>(P, gp, st); break;
     case 128: e = launch_project<128>(P, gp, st); break;
   }
+  timing_mark(K_PROJECT, st);
+  return e;
+}
+
+template <int R>
+static void launch_append_finish(const CompressParams& P, hipStream_t st) {
+  hipLaunchKernelGGL((k_append_finish<R>), dim3(P.Hkv, P.batch), dim3(256), 0, st, P);
+}
+
+hipError_t launch_append(const CompressParams& P, hipStream_t st) {
+  hipError_t e;
+  timing_mark(-1, st);
+  hipLaunchKernelGGL(k_append_scan, dim3(P.NS, P.Hkv, P.batch), dim3(256), 0, st, P);
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of append_scan");
+  timing_mark(K_SIM, st);
+  switch (P.R) {
+    case 16: launch_append_finish<16>(P, st); break;
+    case 32: launch_append_finish<32>(P, st); break;
+    case 48: launch_append_finish<48>(P, st); break;
+    case 64: launch_append_finish<64>(P, st); break;
+    case 80: launch_append_finish<80>(P, st); break;
+    case 96: launch_append_finish<96>(P, st); break;
+    case 112: launch_append_finish<112>(P, st); break;
+    case 128: launch_append_finish<128>(P, st); break;
+    default: return hipErrorInvalidValue;
+  }
+  e = note_hip_error(hipGetLastError(), "launch of append_finish");
   timing_mark(K_PROJECT, st);
   return e;
 }

@@ -484,7 +484,20 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.flag_list = reinterpret_cast<int32_t*>(wsb + cw.flag_list);
   Pm.exact_key = reinterpret_cast<uint64_t*>(wsb + cw.exact_key);
   Pm.part = reinterpret_cast<float*>(wsb + cw.part);
-  hipError_t e = launch_compress(Pm, rb, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
+  // decode append (one new token for every sequence): two small kernels instead of five
+  bool one_each = n_new_total == batch;
+  for (int b = 0; b < batch && one_each; ++b) one_each = cu_new_host[b + 1] - cu_new_host[b] == 1;
+  hipError_t e;
+  if (one_each) {
+    int64_t nsa = ceil_div64(ceil_div64(max_len_after, S), 64);      // about 64 candidates per block
+    const int64_t cap = (ws_bytes - cw.part) / per_split;
+    if (nsa > 64) nsa = 64;
+    if (nsa > cap) nsa = cap;
+    Pm.NS = nsa < 1 ? 1 : (int)nsa;
+    e = launch_append(Pm, static_cast<hipStream_t>(stream));
+  } else {
+    e = launch_compress(Pm, rb, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
+  }
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 

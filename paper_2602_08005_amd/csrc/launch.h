@@ -103,6 +103,10 @@ int sim_tile_rows(int rb);
 hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, int max_new_refs,
                            hipStream_t st);
 
+// Enqueues the two kernels of the decode-append path (every sequence brings exactly one new token; P.NS = blocks
+// per (sequence, kv-head) of the candidate scan).
+hipError_t launch_append(const CompressParams& P, hipStream_t st);
+
 // Optional per-kernel timing (deltakv_timing_begin / deltakv_timing_end): when enabled, launchers call
 // timing_mark(kernel_id, stream) before the first kernel (id -1) and after every kernel.
 enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_RESOLVE, K_EXACT, K_PROJECT, K_COUNT };

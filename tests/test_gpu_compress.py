@@ -165,6 +165,45 @@ def test_exact_and_near_ties_pick_the_oracle_ordinal():
     assert np.array_equal(idx, ref["idx"])
 
 
+@pytest.mark.parametrize("joint,r", [(False, 64), (True, 48), (False, 128), (True, 16)])
+def test_single_token_appends_with_ties_zero_vectors_and_reference_positions(joint, r):
+    """The one-token-per-sequence path (its own two kernels): three sequences grow together token by token through
+    reference positions, exact copies of duplicated references (ties -> lowest ordinal) and a zero vector."""
+    import torch
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    from tests.helpers import dev_bits
+    from oracle import deltakv_oracle as O
+    f = O.bf16_bits_to_f64
+    Hkv, L0, L1, B = 2, 150, 200, 3
+    KV = []
+    for b in range(B):
+        K, V, _ = G.make_kv(600 + b, L1, Hkv, 128, n_proto=8)
+        for j in (2, 5):                       # references 2 and 5 are bit-identical to reference 1
+            K[16 * j], V[16 * j] = K[16], V[16]
+        K[161 + b], V[161 + b] = K[16], V[16]  # appended exact copy: cos = 1 for ordinals 1, 2, 5 -> ordinal 1
+        K[171 + b, 1], V[171 + b, 1] = 0, 0    # appended zero vector on one head -> ordinal 0
+        KV.append((K, V))
+    W = G.make_projections(600, 128, r, joint=joint)
+    pps = -(-L1 // 16)
+    dims = dk.make_dims(Hkv, 8, r, B * pps + 2, B * pps + 2, latent_mode=dk.JOINT if joint else dk.SPLIT)
+    cache = dk.PagedCache(dims, B, B * L0, L1)
+    wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
+    cache.compress(wk, wv, dev_bits(np.concatenate([kv[0][:L0] for kv in KV])),
+                   dev_bits(np.concatenate([kv[1][:L0] for kv in KV])), [0, L0, 2 * L0, 3 * L0], [0, 0, 0])
+    for t in range(L0, L1):
+        cache.compress(wk, wv, dev_bits(np.stack([kv[0][t] for kv in KV])), dev_bits(np.stack([kv[1][t] for kv in KV])),
+                       [0, 1, 2, 3], [t, t, t])
+    torch.cuda.synchronize()
+    for b in range(B):
+        idx, zk, zv = cache.get_sequence(b, 0, L1)
+        assert np.all(idx[161 + b] == 1) and np.all(zk[161 + b] == 0)
+        assert idx[171 + b, 1] == 0
+        _check_against_oracle(KV[b][0], KV[b][1], W, 16, joint, idx, zk, zv)
+        rk, rv, _ = cache.get_refs(b, -(-L1 // 16))
+        assert np.array_equal(rk, KV[b][0][::16]) and np.array_equal(rv, KV[b][1][::16])
+
+
 def test_compress_then_decode_end_to_end():
     """The cache the GPU builds, read by the GPU decode kernel, matches the oracle's own pipeline."""
     import torch
