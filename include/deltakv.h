@@ -244,7 +244,7 @@ int deltakv_version(void);
 /* Launch-shape overrides for benchmark sweeps (process-wide; value 0 restores the automatic choice):
  *   "stream_waves"  waves per block of the decode streaming kernel (8)
  *   "splits"        token-range splits per (sequence, kv-head) in decode (1..16)
- *   "sim_tb"        16-token blocks per wave of the similarity kernel (1, 2 or 4)
+ *   "sim_tb"        16-token blocks per wave of the similarity kernel (1..4)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)
  * Results do not depend on these beyond floating-point summation order.  Errors: INVALID_ARG. */
 int deltakv_tune(const char* name, int32_t value);

@@ -882,6 +882,7 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
   switch (rb) {
     case 1: e = launch_sim<1>(P, gs, st); break;
     case 2: e = launch_sim<2>(P, gs, st); break;
+    case 3: e = launch_sim<3>(P, gs, st); break;
     case 4: e = launch_sim<4>(P, gs, st); break;
     default: return hipErrorInvalidValue;
   }

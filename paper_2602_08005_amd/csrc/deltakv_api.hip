@@ -110,7 +110,7 @@ int deltakv_tune(const char* name, int32_t value) {
     if (value > 64) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_ns = value;
   } else if (!strcmp(name, "sim_tb")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4) return DELTAKV_E_INVALID_ARG;
+    if (value < 0 || value > 4) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_tb = value;
   } else {
     return DELTAKV_E_INVALID_ARG;
@@ -422,7 +422,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   const int n_new_total = cu_new_host[batch];
   if (n_new_total == 0) return DELTAKV_OK;
   if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
-  const int rb = g_tune_sim_tb ? g_tune_sim_tb : (max_new >= 1024 ? 4 : (max_new >= 128 ? 2 : 1));
+  const int rb = g_tune_sim_tb ? g_tune_sim_tb : (max_new >= 1024 ? 3 : (max_new >= 128 ? 2 : 1));
   const int mt = sim_tile_rows(rb);
   const int tiles_max = ceil_div(max_new, mt);
   int64_t tiles_total = 0;
