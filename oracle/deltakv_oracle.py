@@ -23,7 +23,9 @@ Long-Range Similarity"):
 Readings where the paper is silent or differs from the build target are listed
 in the repository's design notes; the ones that shape this file:
   - similarity is cosine over the per-(token, kv-head) vector K||V (256 values
-    for head_dim 128); a zero-norm vector scores 0 against everything;
+    for head_dim 128); a zero-norm vector scores 0 against everything; the
+    paper's own metric, squared L2 distance over the same vector, is the
+    alternative (metric = L2);
   - k = 1, ties go to the lowest reference ordinal;
   - positions are 0-indexed, token 0 is a reference, candidates are strictly
     earlier (ordinal j is token j*s < i);
@@ -134,8 +136,20 @@ def retrieve_one(kv: np.ndarray, i: int, h: int, s: int):
     return j, float(c[j])
 
 
+COSINE = 0
+L2 = 1
+
+
+def l2_scores(a: np.ndarray, refs: np.ndarray) -> np.ndarray:
+    """-||a - refs[j]||^2 for one vector a [n] against refs [m, n]: section 4.1 retrieves the nearest tokens of the
+    reference set by L2 distance (the largest of these scores is the nearest reference)."""
+    a = np.asarray(a, dtype=np.float64)
+    d = np.asarray(refs, dtype=np.float64) - a[None, :]
+    return -np.einsum("jn,jn->j", d, d)
+
+
 def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.ndarray,
-             s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048):
+             s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048, metric: int = COSINE):
     """Compress tokens start..L-1 of one sequence.
 
     K, V: float64 [L, H, D] -- the raw states of the WHOLE sequence so far (the
@@ -144,7 +158,8 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
     Returns a dict of per-token results for tokens start..L-1 (index 0 of each
     array is token `start`):
       idx      int32   [n, H]      reference ordinal (own ordinal for reference tokens)
-      cos      float64 [n, H]      the winning cosine (1.0 stored for reference tokens)
+      cos      float64 [n, H]      the winning score: cosine (1.0 stored for reference tokens), or with
+                                   metric = L2 minus the squared distance to the chosen reference
       z_k, z_v float64 [n, H, r]   unrounded latents (JOINT: z_v is z_k)
       zb_k, zb_v uint16 [n, H, r]  bf16 bits of the stored latents
     and the reference pool of the whole sequence:
@@ -172,16 +187,19 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
             na = np.sqrt(np.einsum("in,in->i", a, a))
             if mmax == 0:
                 continue
-            dots = a @ refs[:mmax, h].T                    # [nb, mmax]
-            den = na[:, None] * ref_norm[None, :mmax, h]
-            c = np.where(den > 0.0, dots / np.where(den > 0.0, den, 1.0), 0.0)
+            if metric == L2:                               # the definition, token by token
+                c = np.stack([l2_scores(a[i], refs[:mmax, h]) for i in range(len(p))])
+            else:
+                dots = a @ refs[:mmax, h].T                # [nb, mmax]
+                den = na[:, None] * ref_norm[None, :mmax, h]
+                c = np.where(den > 0.0, dots / np.where(den > 0.0, den, 1.0), 0.0)
             c = np.where(np.arange(mmax)[None, :] < ncand[:, None], c, -np.inf)
             j = np.argmax(c, axis=1)                       # lowest ordinal among equal maxima
             idx[b0:b1, h] = j
             cos[b0:b1, h] = c[np.arange(b1 - b0), j]
     # reference tokens point at themselves and carry a zero latent
     idx[is_ref] = (pos[is_ref] // s)[:, None]
-    cos[is_ref] = 1.0
+    cos[is_ref] = 0.0 if metric == L2 else 1.0
     tok_ref = idx.astype(np.int64) * s                     # token position of the chosen reference
     hh = np.arange(H)[None, :]
     r_k = K[pos[:, None], hh] - K[tok_ref, hh]             # [n, H, D]

@@ -344,6 +344,52 @@ def test_lse_merge_of_two_halves_equals_whole():                   # P9
     assert np.max(np.abs(out - whole)) < 1e-12 and np.max(np.abs(lse - lw)) < 1e-12
 
 
+# ---------------------------------------------------------------- squared-L2 retrieval pins
+def test_l2_retrieval_equals_brute_force_and_breaks_ties_low():
+    K, V, cls, P = _small_case(seed=61, L=70, H=2, D=16, r=8, s=4)
+    K, V = K.copy(), V.copy()
+    K[12], V[12] = K[4], V[4]                      # reference 3 duplicates reference 1
+    K[41], V[41] = K[4], V[4]                      # token 41 is an exact copy: distance 0 to ordinals 1 and 3
+    res = O.compress(K, V, _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"]), s=4, metric=O.L2)
+    kv = np.concatenate([K, V], axis=2)
+    for i in range(70):
+        for h in range(2):
+            if i % 4 == 0:
+                assert res["idx"][i, h] == i // 4
+                continue
+            best, arg = None, None
+            for j in range((i + 3) // 4):          # strictly earlier references, ascending
+                d = sum((float(kv[i, h, n]) - float(kv[4 * j, h, n])) ** 2 for n in range(32))
+                if best is None or d < best:
+                    best, arg = d, j
+            assert res["idx"][i, h] == arg and abs(res["cos"][i, h] + best) < 1e-12
+    assert np.all(res["idx"][41] == 1) and np.all(res["z_k"][41] == 0)
+
+
+def test_l2_and_cosine_agree_on_unit_norm_references_and_differ_on_a_scaled_copy():
+    rng = np.random.default_rng(7)
+    L, H, D, s = 61, 1, 8, 4
+    K, V = rng.standard_normal((L, H, D)), rng.standard_normal((L, H, D))
+    kv = np.concatenate([K, V], axis=2)
+    kv[0::s] /= np.linalg.norm(kv[0::s], axis=2, keepdims=True)      # every reference has norm 1
+    K, V = kv[..., :D].copy(), kv[..., D:].copy()
+    W = np.eye(D)
+    a = O.compress(K, V, W, W, s=s, metric=O.COSINE)
+    b = O.compress(K, V, W, W, s=s, metric=O.L2)
+    assert np.array_equal(a["idx"], b["idx"])      # ||a-b||^2 = |a|^2 + 1 - 2 a.b: same order as the cosine
+    # a token that is 3x reference 2 has cosine 1 to it, but is nearer to a longer reference pointing elsewhere
+    K2, V2 = K.copy(), V.copy()
+    K2[8], V2[8] = 0.0, 0.0
+    K2[8, 0, 0] = 1.0                              # reference 2 = e0
+    K2[4], V2[4] = 0.0, 0.0
+    K2[4, 0, 0], K2[4, 0, 1] = 2.9, 0.8            # reference 1: close to 3*e0 in distance, not in angle
+    K2[30], V2[30] = 0.0, 0.0
+    K2[30, 0, 0] = 3.0                             # token 30 = 3 * e0
+    ca = O.compress(K2, V2, W, W, s=s, metric=O.COSINE)
+    cb = O.compress(K2, V2, W, W, s=s, metric=O.L2)
+    assert ca["idx"][30, 0] == 2 and cb["idx"][30, 0] == 1
+
+
 # ---------------------------------------------------------------- subset decode pins
 def test_subset_of_all_tokens_is_the_full_attention_and_order_is_free():
     K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=43, L=101)
