@@ -47,8 +47,9 @@ def prefill_workload(args, torch, dk, B, G):
     L, NL, Hkv, Hq, r, D, s = 32768 if args.seq_len == 131072 else args.seq_len, args.layers, args.kv_heads, \
         args.q_heads, args.rank, 128, 16
     joint = args.mode == "joint"
+    l2 = args.metric == "l2"
     dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-L // 16), n_ref_slots=-(-L // s),
-                        latent_mode=dk.JOINT if joint else dk.SPLIT)
+                        latent_mode=dk.JOINT if joint else dk.SPLIT, metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
     cache = dk.PagedCache(dims, 1, L, L)
     W = G.make_projections(G.seed_for(4), D, r, joint=joint)
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
@@ -91,7 +92,7 @@ def prefill_workload(args, torch, dk, B, G):
     t0 = time.perf_counter()
     nsamp = min(L, 4096)
     ref = O.compress(f(Kh), f(Vh), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s,
-                     mode=O.JOINT if joint else O.SPLIT, start=L - nsamp)
+                     mode=O.JOINT if joint else O.SPLIT, start=L - nsamp, metric=O.L2 if l2 else O.COSINE)
     t_or = time.perf_counter() - t0
     mism = int(np.sum(ref["idx"] != idx[L - nsamp:]))
     result = {
@@ -100,7 +101,8 @@ def prefill_workload(args, torch, dk, B, G):
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"prefill compression: 1 x {L} tokens, {NL} layers, {Hkv} kv-heads x {D}, rank {r}, "
-                               f"{args.mode.upper()} latents, references every {s}th earlier token, cosine top-1"},
+                               f"{args.mode.upper()} latents, references every {s}th earlier token, "
+                               f"{'squared-L2' if l2 else 'cosine'} top-1"},
         "roofline": {"bound": "mfma", "kernel": "k_sim_top2", "achieved": round(tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": MEASURED_SIM_TRAFFIC_PREFILL32K if (L, Hkv, r) == (32768, 8, 64) else None,
@@ -220,8 +222,9 @@ def append_workload(args, torch, dk, B, G):
     scale = 1.0 / np.sqrt(D)
     joint = args.mode == "joint"
     Lmax = L0 + nsteps
+    l2 = args.metric == "l2"
     dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-Lmax // 16), n_ref_slots=-(-Lmax // s),
-                        latent_mode=dk.JOINT if joint else dk.SPLIT)
+                        latent_mode=dk.JOINT if joint else dk.SPLIT, metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
     cache = dk.PagedCache(dims, 1, L0, Lmax)
     W = G.make_projections(G.seed_for(2), D, r, joint=joint)
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
@@ -261,7 +264,7 @@ def append_workload(args, torch, dk, B, G):
     from oracle import deltakv_oracle as O
     f = O.bf16_bits_to_f64
     ref = O.compress(f(K), f(V), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s,
-                     mode=O.JOINT if joint else O.SPLIT, start=L0)
+                     mode=O.JOINT if joint else O.SPLIT, start=L0, metric=O.L2 if l2 else O.COSINE)
     idx, zk, zv = cache.get_sequence(0, L0, Lmax)
     mism = int(np.sum(idx != ref["idx"]))
     worst, t_or = 0.0, 0.0
@@ -323,6 +326,8 @@ def main():
                     help="decode128k: the headline long-context decode (default); prefill32k: compression of one "
                          "32768-token prompt over the layers (reports compress tokens/s and the similarity GEMM's "
                          "fraction of the MFMA roofline)")
+    ap.add_argument("--metric", choices=["cosine", "l2"], default="cosine",
+                    help="retrieval metric of the compression workloads (prefill32k, append32k)")
     ap.add_argument("--contiguous", action="store_true", help="ragged workload: identity page placement (experiment)")
     ap.add_argument("--select", type=float, default=0.0, metavar="FRACTION",
                     help="decode128k: attend only a selected subset (deltakv_decode_attn_subset): this fraction of "

@@ -65,7 +65,13 @@ extern "C" {
 #define DELTAKV_SPLIT 0
 #define DELTAKV_JOINT 1
 
+/* Retrieval metric of the reference search (section 4.1): the nearest earlier
+ * reference of a token over the per-head vector K||V, by cosine similarity or by
+ * squared L2 distance (the section's own choice); lowest ordinal on ties.  One
+ * cache uses one metric for its whole life: the per-reference float written at
+ * admission depends on it. */
 #define DELTAKV_METRIC_COSINE 0
+#define DELTAKV_METRIC_L2     1
 
 /* Problem dimensions.  v1 kernels need head_dim == 128, page_tokens == 16,
  * rank a multiple of 16 in [16, 128], 1 <= n_q_heads / n_kv_heads <= 16 and
@@ -78,7 +84,7 @@ typedef struct {
   int32_t latent_mode;  /* DELTAKV_SPLIT or DELTAKV_JOINT                          */
   int32_t ref_stride;   /* s >= 1: every s-th token is a reference                 */
   int32_t page_tokens;  /* P: tokens per page                                      */
-  int32_t metric;       /* DELTAKV_METRIC_COSINE                                   */
+  int32_t metric;       /* DELTAKV_METRIC_COSINE or DELTAKV_METRIC_L2              */
   int64_t n_pages;      /* capacity of the latent / index pools, in pages          */
   int64_t n_ref_slots;  /* capacity of the reference pool, in reference tokens     */
 } deltakv_dims;
@@ -97,7 +103,8 @@ typedef struct {
  *   index pool   int32  [n_pages][n_kv_heads][P]   reference ordinal per token
  *   reference pool bf16 [n_kv_heads][2][n_ref_slots][head_dim]   (0 = K, 1 = V)
  *   reference inverse norms fp32 [n_kv_heads][n_ref_slots]: 1/||K||V|| of the
- *                slot's raw vector (0 for a zero vector), written at admission.
+ *                slot's raw vector (0 for a zero vector), written at admission;
+ *                with DELTAKV_METRIC_L2 the same array holds ||K||V||^2 / 2.
  * Strides are in elements of the pool's type. */
 typedef struct {
   int64_t latent_pool_bytes, idx_pool_bytes, ref_pool_bytes, ref_norm_pool_bytes;

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libdeltakv.so")
 OK, E_INVALID_ARG, E_UNSUPPORTED, E_WORKSPACE, E_HIP = 0, -1, -2, -3, -4
 SPLIT, JOINT = 0, 1
 METRIC_COSINE = 0
+METRIC_L2 = 1
 
 
 class Dims(C.Structure):

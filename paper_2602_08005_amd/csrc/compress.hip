@@ -1,12 +1,15 @@
 // Residual compression of new tokens into the DeltaKV cache, gfx950.
 //
 // Section 4.1: reference set T = {t : t mod s = 0, t < i}; retrieval of the nearest reference
-// (here top-1 by cosine over the per-head vector K||V, lowest ordinal on ties); appendix B.2
+// (top-1 over the per-head vector K||V, by cosine or -- the section's own metric -- by squared L2 distance;
+// lowest ordinal on ties); appendix B.2
 // "lifecycle management": residual against the assigned reference -> down-projection -> write to the
 // latent pool; appendix B.3: the reference search is a dense matrix product.
 //
 // Five kernels per call:
-//   admit_refs : new tokens at multiples of s are copied raw into the reference pool, with 1/||K||V||
+//   admit_refs : new tokens at multiples of s are copied raw into the reference pool, with one float per
+//                reference: 1/||b|| for the cosine, ||b||^2 / 2 for the L2 metric (argmin ||a-b||^2 =
+//                argmax a.b - ||b||^2/2, so both metrics are one product and one per-reference term)
 //   sim_top2   : MFMA GEMM [new tokens x 256] . [references x 256]^T per kv-head with a fused epilogue that
 //                scales by the reference's inverse norm, applies the causal candidate mask and keeps
 //                (best, second best, arg best) per token -- scores never leave the chip
@@ -23,6 +26,33 @@
 #include "launch.h"
 
 namespace dkv {
+
+// the per-reference float of the similarity epilogue from the lane's share of sum b^2 (all 64 lanes call)
+__device__ inline float ref_term(float ss_lane, double dd_lane, int metric) {
+  if (metric) {                       // ||b||^2 / 2, summed in fp64 (exact for bf16 inputs), one rounding to fp32
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) dd_lane += __shfl_xor(dd_lane, o);
+    return (float)(0.5 * dd_lane);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) ss_lane += __shfl_xor(ss_lane, o);
+  return ss_lane > 0.f ? 1.0f / sqrtf(ss_lane) : 0.f;
+}
+
+// Whether the two best fp32 scores of a token are far enough apart to trust their order.
+//   cosine: a score is 256 exact products summed in fp32 times the stored inverse norm: within
+//           256 * 2^-24 |a| = 1.53e-5 |a| of the exact value; pairs closer than twice that (plus slack) fail.
+//   L2:     score = a.b - ||b||^2/2 with error <= 1.53e-5 |a||b| + 2^-24 (||b||^2 + |a||b|).  Any reference that
+//           could still win is at most as far from a as the fp32 winner, so |b| <= |a| + |a - b_best| with
+//           |a - b_best|^2 = |a|^2 - 2 best (5 % slack for the fp32 evaluation of that bound).
+__device__ inline bool gap_is_safe(float best, float second, float na2, int metric) {
+  const float na = sqrtf(na2);
+  if (metric) {
+    const float nb = 1.05f * (na + sqrtf(fmaxf(na2 - 2.f * best, 0.f)));
+    return best - second > 4e-5f * na * nb + 2e-7f * nb * nb;
+  }
+  return best - second > 4e-5f * na;
+}
 
 __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // largest b with cu[b] <= n
   int lo = 0, hi = batch - 1;
@@ -53,10 +83,11 @@ __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
   uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
   reinterpret_cast<uint32_t*>(rk)[l] = kx;
   reinterpret_cast<uint32_t*>(rk + P.ref_kv_stride)[l] = vx;
-  float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
-  if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+  const float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
+  const double dd = (double)bf16lo(kx) * bf16lo(kx) + (double)bf16hi(kx) * bf16hi(kx) + (double)bf16lo(vx) * bf16lo(vx) +
+                    (double)bf16hi(vx) * bf16hi(vx);
+  const float term = ref_term(ss, dd, P.metric);
+  if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = term;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -93,7 +124,7 @@ __device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
 // accumulator sets), software-pipelined by hand: while the 8*TB MFMAs of step q run, the LDS reads of step
 // q+1's operands are in flight and the VALU epilogue of step q-1 (scale, mask, top-2) is issued in the MFMA
 // shadow; reference tiles are staged through three LDS buffers so that one barrier per tile suffices.
-template <int TB>
+template <int TB, bool L2M>
 __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
   constexpr int WM = 16 * TB, MT = 4 * WM;
   constexpr int kTile = kNT * 256;                           // bf16 elements of one staged tile (64 rows x 512 B)
@@ -234,14 +265,15 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], c[tb][i] * s.inv[i], s.code0 + i);
+        for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i], s.code0 + i);
     };
     auto epilogue_masked = [&](const float4v (&c)[TB], const Step& s) {
 #pragma unroll
       for (int tb = 0; tb < TB; ++tb) {
         const int left = ncand_tok[tb] - s.jb;               // this lane's references i < left are candidates
 #pragma unroll
-        for (int i = 0; i < 4; ++i) top2_push(st[tb], i < left ? c[tb][i] * s.inv[i] : -INFINITY, s.code0 + i);
+        for (int i = 0; i < 4; ++i)
+          top2_push(st[tb], i < left ? (L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i]) : -INFINITY, s.code0 + i);
       }
     };
     // a step needs no mask if even its last reference is a candidate of the wave's first (lowest) token
@@ -343,9 +375,7 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
       if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
       else b2 = fmaxf(b2, o.x);
     }
-    // each fp32 score (256 exact products summed in fp32, times the stored inverse norm) is within
-    // 256 * 2^-24 |a| = 1.53e-5 |a| of the exact value; pairs closer than twice that (plus slack) are re-scored
-    if (bi < 0 || !(bb - b2 > 4e-5f * sqrtf(na2))) {
+    if (bi < 0 || !gap_is_safe(bb, b2, na2, P.metric)) {
       const int at = atomicAdd(&P.flag_count[b * P.Hkv + h], 1);
       P.flag_list[(int64_t)h * P.n_new_total + P.cu_new[b] + at] = n;
       P.exact_key[item] = kKeyIdxMask;          // (lowest score, ordinal 0); raised by the exact pass
@@ -364,6 +394,8 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
 // hardware with one-hot inputs): lane (ln, lg) supplies element e of its 8-wide chunk as the k = lg slot of
 // step (kk, e), identically for both operands.  Waves publish their best with a 64-bit atomic max on the key
 // (cosine in 2^-38 steps above -1) << 24 | (2^24-1 - ordinal): the larger cosine wins, then the lower ordinal.
+// With the L2 metric the 40 score bits are the complement of the leading bits of the fp64 squared distance
+// |a|^2 - 2 a.b + |b|^2 (sign, exponent, 28 mantissa bits: distances closer than 2^-28 relative tie).
 // ------------------------------------------------------------------------------------------------
 constexpr int kExactX = 8;    // few blocks: an idle block of this kernel still costs a dispatch with ~240 registers per lane
 constexpr int kExactSplits = 8;
@@ -422,7 +454,10 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
       pos_row[i] = __shfl(pos, 4 * i + lg);
       n_row[i] = __shfl(n, 4 * i + lg);
     }
-    double cbest[4] = {-2.0, -2.0, -2.0, -2.0};
+    double na2_row[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) na2_row[i] = __shfl(na2, 4 * i + lg);
+    double cbest[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     int jbest[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
     for (int rt = lane_tile0; rt * 16 < ncand; rt += tile_step) {
       const int j = rt * 16 + ln;
@@ -449,7 +484,7 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const double den = na_row[i] * nb;
-        const double c = den > 0.0 ? acc[i] / den : 0.0;
+        const double c = P.metric ? -fmax(na2_row[i] - 2.0 * acc[i] + nb2, 0.0) : (den > 0.0 ? acc[i] / den : 0.0);
         const bool ok = j < ncand && (int64_t)j * P.stride < pos_row[i];
         if (ok && c > cbest[i]) { cbest[i] = c; jbest[i] = j; }   // ascending j per lane: strict '>'
       }
@@ -465,7 +500,9 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
       }
       if (ln == 0 && tile * 16 + 4 * i + lg < cnt && jbest[i] != 0x7fffffff) {
         const double cc = fmin(fmax(cbest[i], -1.0), 1.0) + 1.0;                      // [0, 2]
-        const unsigned long long q = (unsigned long long)(cc * 274877906944.0 + 0.5);    // 2^-38 steps, q <= 2^39
+        const unsigned long long q = P.metric
+            ? ((1ull << 40) - 1) - ((unsigned long long)__double_as_longlong(-cbest[i]) >> 24)   // -cbest >= 0
+            : (unsigned long long)(cc * 274877906944.0 + 0.5);                         // 2^-38 steps, q <= 2^39
         const unsigned long long key = (q << 24) | (unsigned long long)(kKeyIdxMask - (jbest[i] & kKeyIdxMask));
         atomicMax(reinterpret_cast<unsigned long long*>(P.exact_key) + ((int64_t)n_row[i] * P.Hkv + h), key);
       }
@@ -637,10 +674,11 @@ __global__ __launch_bounds__(256) void k_append_scan(CompressParams P) {
     uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
     reinterpret_cast<uint32_t*>(rk)[l] = kx;
     reinterpret_cast<uint32_t*>(rk + P.ref_kv_stride)[l] = vx;
-    float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) ss += __shfl_xor(ss, o);
-    if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = ss > 0.f ? 1.0f / sqrtf(ss) : 0.f;
+    const float ss = bf16lo(kx) * bf16lo(kx) + bf16hi(kx) * bf16hi(kx) + bf16lo(vx) * bf16lo(vx) + bf16hi(vx) * bf16hi(vx);
+    const double dd = (double)bf16lo(kx) * bf16lo(kx) + (double)bf16hi(kx) * bf16hi(kx) + (double)bf16lo(vx) * bf16lo(vx) +
+                      (double)bf16hi(vx) * bf16hi(vx);
+    const float term = ref_term(ss, dd, P.metric);
+    if (l == 0) P.ref_inv_norm[(int64_t)h * P.ref_norm_head_stride + slot] = term;
     return;
   }
   // the token's K||V chunk of this lane: dims 8*sub..8*sub+7 of K and of V
@@ -685,7 +723,7 @@ __global__ __launch_bounds__(256) void k_append_scan(CompressParams P) {
       for (int e = 0; e < 8; ++e) d += ak[e] * bk[e];
 #pragma unroll
       for (int e = 0; e < 8; ++e) d += av[e] * bv[e];
-      d = group16_sum(d) * inv[u];
+      d = P.metric ? group16_sum(d) - inv[u] : group16_sum(d) * inv[u];
       if (j < j1) top2_push(t2, d, j);          // ascending j within a lane group: strict '>' keeps the lowest
     }
   }
@@ -737,20 +775,22 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
       if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
       else b2 = fmaxf(b2, o.x);
     }
-    if (bi >= 0 && bb - b2 > 4e-5f * sqrtf(na2)) {
+    if (bi >= 0 && gap_is_safe(bb, b2, na2, P.metric)) {
       if (tid == 0) ord_s = bi;
     } else {
-      // too close to call in fp32: every candidate again in fp64, cos = a.b / (|a| |b|), lowest ordinal on ties
+      // too close to call in fp32: every candidate again in fp64, cos = a.b / (|a| |b|) or -|a - b|^2, lowest
+      // ordinal on ties
       float akf[8], avf[8];
       unpack8(*reinterpret_cast<const uint4*>(kr + sub * 8), akf);
       unpack8(*reinterpret_cast<const uint4*>(vr + sub * 8), avf);
       double na = 0.0;
 #pragma unroll
       for (int e = 0; e < 8; ++e) na += (double)akf[e] * akf[e] + (double)avf[e] * avf[e];
-      na = sqrt(group16_sum(na));
+      const double na2d = group16_sum(na);
+      na = sqrt(na2d);
       const int n_cand = min(refs_below(pos, P.stride), P.rt_stride);
       const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;
-      double best = -2.0;
+      double best = -INFINITY;
       int besti = 0x7fffffff;
       for (int jb = 0; jb < n_cand; jb += 16) {
         const int j = jb + w * 4 + lg;
@@ -765,9 +805,10 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
           nb += (double)bk[e] * bk[e] + (double)bv[e] * bv[e];
         }
         d = group16_sum(d);
-        nb = sqrt(group16_sum(nb));
+        const double nb2 = group16_sum(nb);
+        nb = sqrt(nb2);
         const double den = na * nb;
-        const double c = den > 0.0 ? d / den : 0.0;
+        const double c = P.metric ? -fmax(na2d - 2.0 * d + nb2, 0.0) : (den > 0.0 ? d / den : 0.0);
         if (j < n_cand && (c > best || (c == best && j < besti))) { best = c; besti = j; }
       }
 #pragma unroll
@@ -839,18 +880,22 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int TB>
-static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
+template <int TB, bool L2M>
+static hipError_t launch_sim_m(const CompressParams& P, dim3 grid, hipStream_t st) {
   const size_t lds = 3 * kNT * 256 * 2 + 3 * kNT * 4;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB, L2M>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(similarity kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_sim_top2<TB>), grid, dim3(256), lds, st, P);
+  hipLaunchKernelGGL((k_sim_top2<TB, L2M>), grid, dim3(256), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of sim_top2");
+}
+template <int TB>
+static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
+  return P.metric ? launch_sim_m<TB, true>(P, grid, st) : launch_sim_m<TB, false>(P, grid, st);
 }
 
 template <int R>

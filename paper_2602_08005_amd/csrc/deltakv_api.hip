@@ -22,7 +22,7 @@ int check_dims(const deltakv_dims* d) {
   if (d->n_q_heads / d->n_kv_heads > 16) return DELTAKV_E_UNSUPPORTED;
   if (d->head_dim != kHeadDim || d->page_tokens != kPage) return DELTAKV_E_UNSUPPORTED;
   if (d->rank % 16 != 0 || d->rank < 16 || d->rank > 128) return DELTAKV_E_UNSUPPORTED;
-  if (d->metric != DELTAKV_METRIC_COSINE) return DELTAKV_E_UNSUPPORTED;
+  if (d->metric != DELTAKV_METRIC_COSINE && d->metric != DELTAKV_METRIC_L2) return DELTAKV_E_INVALID_ARG;
   if (d->n_pages > (1ll << 31) - 1 || d->n_ref_slots > (1ll << 31) - 1) return DELTAKV_E_UNSUPPORTED;
   return DELTAKV_OK;
 }
@@ -477,6 +477,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.R = dims->rank;
   Pm.stride = S;
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.metric = dims->metric;
   Pm.NS = (int)ns;
   char* wsb = static_cast<char*>(workspace);
   Pm.ord = reinterpret_cast<int32_t*>(wsb + cw.ord);

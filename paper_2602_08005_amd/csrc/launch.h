@@ -69,6 +69,7 @@ struct CompressParams {
   const int32_t* len_before;
   int batch, n_new_total;
   int Hkv, R, stride, joint;
+  int metric;                       // 0: cosine, 1: squared L2 distance (section 4.1)
   int NS;            // reference-range splits of the similarity search
   float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), |token|^2
   int32_t* ord;        // [n_new_total][Hkv] chosen reference ordinal

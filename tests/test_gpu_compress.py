@@ -12,19 +12,25 @@ def _bf16_ulp(x):
     return 2.0 ** (np.floor(np.log2(ax)) - 7)
 
 
-def _check_against_oracle(K, V, W, s, joint, idx, zk, zv, t0=0):
+def _check_against_oracle(K, V, W, s, joint, idx, zk, zv, t0=0, l2=False):
     """idx/zk/zv: GPU results for tokens t0.. ; K, V: raw bits of the whole sequence."""
     from oracle import deltakv_oracle as O
     f = O.bf16_bits_to_f64
     Kf, Vf = f(K), f(V)
     mode = O.JOINT if joint else O.SPLIT
     wdk, wdv = f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"])
-    ref = O.compress(Kf, Vf, wdk, wdv, s=s, mode=mode, start=t0)
+    ref = O.compress(Kf, Vf, wdk, wdv, s=s, mode=mode, start=t0, metric=O.L2 if l2 else O.COSINE)
     diff = np.argwhere(idx != ref["idx"])
     for (i, h) in diff:                      # allowed only on near-ties of the oracle's own scores
+        assert 0 <= idx[i, h] and idx[i, h] * s < t0 + i
+        if l2:     # squared distances: the exact pass resolves 2^-28 relative (its key) on fp64 arithmetic
+            a = np.concatenate([Kf[t0 + i, h], Vf[t0 + i, h]])
+            b = np.concatenate([Kf[idx[i, h] * s, h], Vf[idx[i, h] * s, h]])
+            d_gpu, d_ref = -O.l2_scores(a, b[None])[0], -ref["cos"][i, h]
+            assert d_gpu <= d_ref * (1 + 1e-8) + 1e-12 * (a @ a), (i, h, idx[i, h], ref["idx"][i, h], d_gpu, d_ref)
+            continue
         c_gpu = O.cosine_of(Kf, Vf, t0 + i, h, int(idx[i, h]), s)
         assert c_gpu >= ref["cos"][i, h] - 1e-6, (i, h, idx[i, h], ref["idx"][i, h], c_gpu, ref["cos"][i, h])
-        assert idx[i, h] * s < t0 + i
     # latents: recompute the oracle residual with the GPU's ordinal where it (legitimately) differs
     z_k, z_v = ref["z_k"].copy(), ref["z_v"] if joint else ref["z_v"].copy()
     for (i, h) in diff:
@@ -45,7 +51,7 @@ def _check_against_oracle(K, V, W, s, joint, idx, zk, zv, t0=0):
 
 
 def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, n_proto=16, perm=None, Hq=None,
-                   capacity=0):
+                   capacity=0, l2=False, edit=None):
     """Build sequences of lens_before+lens_new tokens; prefill `before` and then append `new` on the GPU."""
     import torch
     import paper_2602_08005_amd as dk
@@ -61,12 +67,15 @@ def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, 
         pp, rp = G.page_permutation(perm, B * pps, n_pages), G.page_permutation(perm + 1, B * rps, n_slots)
         page_ids = [pp[b * pps:(b + 1) * pps] for b in range(B)]
         ref_slots = [rp[b * rps:(b + 1) * rps] for b in range(B)]
-    dims = dk.make_dims(Hkv, Hq or 4 * Hkv, r, n_pages, n_slots, ref_stride=s, latent_mode=dk.JOINT if joint else dk.SPLIT)
+    dims = dk.make_dims(Hkv, Hq or 4 * Hkv, r, n_pages, n_slots, ref_stride=s, latent_mode=dk.JOINT if joint else dk.SPLIT,
+                        metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
     cache = dk.PagedCache(dims, B, max(sum(lens_new), sum(lens_before), 1), max_len, page_ids=page_ids, ref_slots=ref_slots)
     cache.latent_pool.fill_(0x7FC0)
     cache.idx_pool.fill_(-7)
     W = G.make_projections(seed, 128, r, joint=joint)
     KV = [G.make_kv(seed + 31 * b, max(total[b], 1, capacity), Hkv, 128, n_proto=n_proto)[:2] for b in range(B)]
+    if edit is not None:
+        edit(KV)
     wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
     for phase, (starts, counts) in enumerate((([0] * B, lens_before), (lens_before, lens_new))):
         if sum(counts) == 0:
@@ -79,20 +88,23 @@ def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, 
     return cache, KV, W, total
 
 
-def _verify(cache, KV, W, total, s, joint):
+def _verify(cache, KV, W, total, s, joint, l2=False):
     n_diff = 0
     for b, L in enumerate(total):
         if L == 0:
             continue
         idx, zk, zv = cache.get_sequence(b, 0, L)
         K, V = KV[b][0][:L], KV[b][1][:L]
-        n_diff += _check_against_oracle(K, V, W, s, joint, idx, zk, zv)
+        n_diff += _check_against_oracle(K, V, W, s, joint, idx, zk, zv, l2=l2)
         n_ref = -(-L // s)
         rk, rv, nrm = cache.get_refs(b, n_ref)
         assert np.array_equal(rk, K[::s]) and np.array_equal(rv, V[::s])
         from oracle import deltakv_oracle as O
         kv = np.concatenate([O.bf16_bits_to_f64(K[::s]), O.bf16_bits_to_f64(V[::s])], axis=2)
-        assert np.allclose(nrm, 1.0 / np.sqrt(np.sum(kv * kv, axis=2)), rtol=1e-5)
+        if l2:
+            assert np.array_equal(nrm, (0.5 * np.sum(kv * kv, axis=2)).astype(np.float32))
+        else:
+            assert np.allclose(nrm, 1.0 / np.sqrt(np.sum(kv * kv, axis=2)), rtol=1e-5)
     return n_diff
 
 
@@ -202,6 +214,53 @@ def test_single_token_appends_with_ties_zero_vectors_and_reference_positions(joi
         _check_against_oracle(KV[b][0], KV[b][1], W, 16, joint, idx, zk, zv)
         rk, rv, _ = cache.get_refs(b, -(-L1 // 16))
         assert np.array_equal(rk, KV[b][0][::16]) and np.array_equal(rv, KV[b][1][::16])
+
+
+# ---------------------------------------------------------------- squared-L2 retrieval (section 4.1's metric)
+def _l2_edit(KV):
+    """Duplicated references, an exact copy of one (distance 0 to all three: lowest ordinal), a zero vector, a
+    token at 3x a reference (cosine 1 to it, yet nearer to others) and a pair of references at almost the same
+    distance from a token (one element differs in the last bf16 bit)."""
+    for K, V in KV:
+        if len(K) < 340:
+            continue
+        for j in (4, 11):
+            K[16 * j], V[16 * j] = K[32], V[32]            # references 4, 11 == reference 2
+        K[263], V[263] = K[32], V[32]
+        K[277, 0], V[277, 0] = 0, 0
+        x = (K[48].astype(np.uint32) << 16).view(np.float32) * np.float32(3.0)
+        u = x.view(np.uint32)
+        K[295] = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+        V[295] = 0
+        K[16 * 7], V[16 * 7] = K[16 * 6].copy(), V[16 * 6].copy()
+        K[16 * 7, :, 5] ^= 1                              # reference 7 = reference 6 up to one last-place bit
+
+
+@pytest.mark.parametrize("joint,r,s", [(False, 64, 16), (True, 32, 16), (False, 128, 8), (True, 96, 32)])
+def test_l2_metric_prefill_and_batched_append(joint, r, s):
+    """Ragged prefill over several similarity tiles, then a batched ragged append, with the L2 metric."""
+    cache, KV, W, total = _compress_case(810, [700, 0, 345, 1100], [333, 420, 0, 77], r=r, s=s, joint=joint, n_proto=12,
+                                         perm=5, l2=True, edit=_l2_edit)
+    _verify(cache, KV, W, total, s, joint, l2=True)
+    if s == 16:
+        idx = cache.get_sequence(0, 0, total[0])[0]
+        assert np.all(idx[263] == 2)
+
+
+def test_l2_metric_single_token_appends():
+    """The one-token-per-sequence kernels with the L2 metric, through reference positions, ties and a zero vector."""
+    import torch
+    cache, KV, W, total = _compress_case(820, [250, 250], [0, 0], r=64, joint=False, n_proto=8, capacity=340, l2=True,
+                                         edit=_l2_edit)
+    import paper_2602_08005_amd as dk
+    from tests.helpers import dev_bits
+    wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
+    for t in range(250, 340):
+        cache.compress(wk, wv, dev_bits(np.stack([kv[0][t] for kv in KV])), dev_bits(np.stack([kv[1][t] for kv in KV])),
+                       [0, 1, 2], [t, t])
+    torch.cuda.synchronize()
+    _verify(cache, KV, W, [340, 340], 16, False, l2=True)
+    assert np.all(cache.get_sequence(1, 0, 340)[0][263] == 2)
 
 
 def test_compress_then_decode_end_to_end():

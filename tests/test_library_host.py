@@ -80,7 +80,7 @@ def test_bad_dims_are_rejected():
     assert rc(n_kv_heads=1, n_q_heads=32) == B.E_UNSUPPORTED
     assert rc(rank=0) == B.E_INVALID_ARG and rc(ref_stride=0) == B.E_INVALID_ARG
     assert rc(latent_mode=7) == B.E_INVALID_ARG
-    assert rc(metric=1) == B.E_UNSUPPORTED
+    assert rc(metric=1) == B.OK and rc(metric=2) == B.E_INVALID_ARG
     out = B.Layout()
     d = dk.make_dims(8, 32, 64, 8, 8)
     assert B._lib.deltakv_paged_layout(None, 1, 16, 16, C.byref(out)) == B.E_INVALID_ARG
