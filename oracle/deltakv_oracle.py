@@ -281,6 +281,22 @@ def decode_attn_subset(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale, po
     return decode_attn_direct(q, idx[pos], z_k[pos], z_v[pos], ref_k, ref_v, w_up_k, w_up_v, scale)
 
 
+def decode_attn_with_raw(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale, raw_k, raw_v, positions=None):
+    """Attention over the cached tokens (all of them, or the selected positions) together with a
+    segment of tokens held raw: appendix B.2 keeps sink and recent tokens at full precision in a
+    pool of their own, and the attention view stitches those static slots together with the
+    reconstructed ones.  raw_k / raw_v [n_raw, Hkv, D] are tokens that are NOT in the cache; the
+    definition is: reconstruct the cached tokens, put the raw rows beside them, attend.
+    Nothing at all to attend gives out = 0 and lse = -inf."""
+    pos = np.arange(idx.shape[0]) if positions is None else np.asarray(positions, dtype=np.int64).reshape(-1)
+    k_hat, v_hat = reconstruct(idx[pos], z_k[pos], z_v[pos], ref_k, ref_v, w_up_k, w_up_v)
+    K = np.concatenate([k_hat, np.asarray(raw_k, dtype=np.float64)], axis=0)
+    V = np.concatenate([v_hat, np.asarray(raw_v, dtype=np.float64)], axis=0)
+    if K.shape[0] == 0:
+        return np.zeros((q.shape[0], ref_v.shape[-1])), np.full(q.shape[0], -np.inf)
+    return dense_attention(q, K, V, scale)
+
+
 def decode_attn_absorbed(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):
     """Same quantity through the linearity of the decoder: the query is pulled
     through W_up once, scores split into a per-reference part and a latent part,

@@ -442,6 +442,53 @@ def test_subset_single_token_empty_selection_and_merge_of_disjoint_subsets():
     assert np.max(np.abs(out - both)) < 1e-12 and np.max(np.abs(lse - lboth)) < 1e-12
 
 
+# ---------------------------------------------------------------- raw (sink / recent) segment pins
+def test_raw_segment_brute_force_and_special_cases():
+    """Cached tokens + raw rows by hand from the definition; no raw rows = the plain call; no cached tokens = dense
+    attention over the raw rows (library routine); the raw rows' place in the concatenation is immaterial."""
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=67, L=60)
+    rng = np.random.default_rng(67)
+    rk, rv = rng.standard_normal((7, 2, K.shape[2])), rng.standard_normal((7, 2, K.shape[2]))
+    args = (q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.22)
+    out, lse = O.decode_attn_with_raw(*args, rk, rv)
+    kh, vh = O.reconstruct(res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv)
+    for g in range(6):
+        h = g // 3
+        logit = [0.22 * float(kh[t, h] @ q[g]) for t in range(60)] + [0.22 * float(rk[t, h] @ q[g]) for t in range(7)]
+        m = max(logit)
+        w = [math.exp(x - m) for x in logit]
+        want = (sum(w[t] * vh[t, h] for t in range(60)) + sum(w[60 + t] * rv[t, h] for t in range(7))) / sum(w)
+        assert np.max(np.abs(out[g] - want)) < 1e-13 and abs(lse[g] - (m + math.log(sum(w)))) < 1e-13
+    a, la = O.decode_attn_with_raw(*args, rk[:0], rv[:0])
+    b, lb = O.decode_attn_direct(*args)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+    c, _ = O.decode_attn_with_raw(*args, rk, rv, positions=[])
+    assert np.max(np.abs(c - _torch_sdpa(q, rk, rv, 0.22))) < 1e-12
+    e, le = O.decode_attn_with_raw(*args, rk[:0], rv[:0], positions=[])
+    assert np.all(e == 0) and np.all(np.isneginf(le))
+
+
+def test_raw_segment_is_the_merge_of_the_two_parts_and_equals_caching_exact_tokens():
+    """(1) LSE merge of the cache-only result with dense attention over the raw rows.  (2) A reference token is
+    reconstructed exactly (z = 0), so serving the reference tokens from the raw segment instead of from the cache
+    changes nothing."""
+    K, V, res, q, zk, zv, wuk, wuv = _decode_case(seed=71, L=64, s=4)
+    rng = np.random.default_rng(71)
+    rk, rv = rng.standard_normal((5, 2, K.shape[2])), rng.standard_normal((5, 2, K.shape[2]))
+    args = (q, res["idx"], zk, zv, res["ref_k"], res["ref_v"], wuk, wuv, 0.3)
+    sel = np.array([1, 4, 9, 10, 33, 63])
+    out, lse = O.decode_attn_with_raw(*args, rk, rv, positions=sel)
+    p0 = O.decode_attn_subset(*args, sel)
+    p1 = O.dense_attention(q, rk, rv, 0.3)
+    want, lwant = O.merge_partials([p0[0], p1[0]], [p0[1], p1[1]])
+    assert np.max(np.abs(out - want)) < 1e-12 and np.max(np.abs(lse - lwant)) < 1e-12
+    refs = np.arange(0, 64, 4)
+    others = np.setdiff1d(np.arange(64), refs)
+    a, la = O.decode_attn_with_raw(*args, K[refs], V[refs], positions=others)
+    b, lb = O.decode_attn_direct(*args)
+    assert np.max(np.abs(a - b)) < 1e-12 and np.max(np.abs(la - lb)) < 1e-12
+
+
 def test_joint_latent_is_sum_of_stream_projections():
     K, V, cls, P = _small_case(seed=43, L=40, H=1, D=16, r=8, s=4, joint=True)
     wk, wv = P["w_down_k_f64"], P["w_down_v_f64"]
