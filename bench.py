@@ -334,6 +334,8 @@ def main():
                          "each sequence's pages, drawn at random per layer, all 16 tokens of a drawn page")
     ap.add_argument("--select-tokens", action="store_true",
                     help="with --select: draw single tokens instead of whole pages (same number of tokens)")
+    ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
+                    help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")
@@ -434,9 +436,21 @@ def main():
             selections.append(cache.selection(pos) + (pos[0],))
         sel_pages_touched = float(np.mean([int(sel[3].sum()) for sel in selections])) / Bt
 
+    # ---- optional raw segment (sink + recent tokens kept uncompressed), the same rows for every layer
+    raw = None
+    if args.raw > 0:
+        rk = np.stack([G.make_kv(G.seed_for(3, 900, b), args.raw, Hkv, D, n_proto=args.protos)[0] for b in range(Bt)])
+        rv = np.stack([G.make_kv(G.seed_for(3, 900, b), args.raw, Hkv, D, n_proto=args.protos)[1] for b in range(Bt)])
+        raw = (dev(rk), dev(rv), torch.full((Bt,), args.raw, dtype=torch.int32, device="cuda"), rk, rv)
+
     def step():
         for layer in range(NL):
-            if selections is None:
+            if raw is not None:
+                sel = None if selections is None else selections[layer][:4]
+                B.decode_attn_raw(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
+                                  cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, raw[0], raw[1],
+                                  raw[2], scale, outs[layer], None, cache.decode_ws, selection=sel)
+            elif selections is None:
                 B.decode_attn(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
                               cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, scale, outs[layer],
                               None, cache.decode_ws)
@@ -471,9 +485,11 @@ def main():
         sel_units = Bt * n_pick * 16 * Hkv
         stream_bytes = sel_units * (n_streams * r * 2 + 4)
         path_bytes = stream_bytes + units * (2 * D * 2 / s)
+    if raw is not None:
+        path_bytes += Bt * args.raw * Hkv * 2 * D * 2             # raw K and V rows, read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:
+    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None and raw is None:
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
     kernel_ms = {}
     if timing:
@@ -496,7 +512,11 @@ def main():
         K0, V0 = host_kv0
         qh = f(qs[0][0].cpu().numpy().view(np.uint16))
         t0 = time.perf_counter()
-        if selections is None:
+        if raw is not None:
+            want, _ = O.decode_attn_with_raw(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+                                             f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale, f(raw[3][0]), f(raw[4][0]),
+                                             positions=None if selections is None else selections[0][4])
+        elif selections is None:
             want, _ = O.decode_attn_direct(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
                                            f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
         else:
@@ -521,6 +541,8 @@ def main():
                                f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents, stride {s}, 16-token pages",
                    "latent_mode": args.mode.upper(), "keep_ratio": round(dk.keep_ratio(dims), 4),
                    "layers_are_copies_of_layer0": True,
+                   **({} if raw is None else {"raw_segment": f"{args.raw} uncompressed tokens per sequence attended "
+                                                                "together with the cache"}),
                    **({} if selections is None else {
                        "subset": f"{n_pick * 16} of {L} tokens per sequence selected "
                                  f"({'single tokens' if args.select_tokens else 'whole pages'}, drawn per layer), "

@@ -242,6 +242,33 @@ int deltakv_decode_attn_subset(const deltakv_dims* dims, const deltakv_layout* l
                                int32_t batch, float scale, void* out, float* lse,
                                void* workspace, int64_t ws_bytes, void* stream);
 
+/* Decode attention over the compressed cache TOGETHER WITH a segment of tokens held raw: appendix B.2 keeps
+ * sink and recent tokens at full precision in a pool of their own, and the attention view puts those static
+ * slots beside the reconstructed tokens.  The result is the softmax attention over the union of
+ *   - the cached tokens (all tokens below seq_lens[b], or, if sel_pages is not NULL, the selected ones exactly as
+ *     in deltakv_decode_attn_subset; with sel_pages NULL the other four selection arguments are ignored), and
+ *   - raw_lens[b] raw tokens of sequence b, which must not also be in the cache (a token in both counts twice).
+ *   raw_k, raw_v  device bf16 [batch][raw_cap][n_kv_heads][head_dim], 16-byte aligned; rows at or past
+ *                 raw_lens[b] are never read.  Not modified; the caller owns them.
+ *   raw_lens      device int32 [batch]; values are clamped to [0, raw_cap]
+ *   raw_cap       host, 0 <= raw_cap <= 4096 (larger: DELTAKV_E_UNSUPPORTED); 0 makes this call
+ *                 deltakv_decode_attn / deltakv_decode_attn_subset and raw_k, raw_v, raw_lens may be NULL
+ * A sequence with neither cached (selected) tokens nor raw tokens gets out = 0 and lse = -inf.  Raw tokens take no
+ * part in the exponent offset of the cached part, so their logits may lie anywhere relative to it: the two parts
+ * are merged at the larger of their offsets.  Everything else (arguments, workspace, status word, errors) as for
+ * deltakv_decode_attn_subset. */
+int deltakv_decode_attn_raw(const deltakv_dims* dims, const deltakv_layout* layout,
+                            const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
+                            const int32_t* block_tables, int32_t bt_stride,
+                            const int32_t* ref_tables, int32_t rt_stride,
+                            const void* w_up_k, const void* w_up_v, const void* q,
+                            const int32_t* seq_lens, const int32_t* seq_lens_host,
+                            const int32_t* sel_pages, const int32_t* sel_masks, int32_t sel_stride,
+                            const int32_t* n_sel, const int32_t* n_sel_host,
+                            const void* raw_k, const void* raw_v, const int32_t* raw_lens, int32_t raw_cap,
+                            int32_t batch, float scale, void* out, float* lse,
+                            void* workspace, int64_t ws_bytes, void* stream);
+
 const char* deltakv_strerror(int code);
 /* For DELTAKV_E_HIP: which runtime call failed and the runtime's message (calling thread's last failure;
  * empty string if none).  The pointer stays valid until the thread's next failing call. */
@@ -264,8 +291,9 @@ int deltakv_tune(const char* name, int32_t value);
  *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
  *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress; a call that appends exactly
  *     one token to every sequence runs two kernels, reported as 5 (candidate scan) and 8 (finish))
+ *   9 raw_attn   (deltakv_decode_attn_raw with a raw segment)
  * Arrays are host memory with n >= DELTAKV_N_KERNELS entries.  Errors: INVALID_ARG, HIP. */
-#define DELTAKV_N_KERNELS 9
+#define DELTAKV_N_KERNELS 10
 int deltakv_timing_begin(void);
 int deltakv_timing_end(float* ms_by_kernel, int32_t* launches_by_kernel, int32_t n);
 

@@ -81,15 +81,20 @@ def _load() -> C.CDLL:
     lib.deltakv_decode_attn_subset.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                                vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, C.c_float, vp, vp,
                                                vp, i64, vp]
+    lib.deltakv_decode_attn_raw.restype = C.c_int
+    lib.deltakv_decode_attn_raw.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
+                                            vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, C.c_float,
+                                            vp, vp, vp, i64, vp]
     return lib
 
 
 _lib = _load()
 KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", "sim_top2", "resolve", "exact",
-                "project")
+                "project", "raw_attn")
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
-           "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset")
+           "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset",
+           "deltakv_decode_attn_raw")
 
 
 def version() -> int:
@@ -209,4 +214,25 @@ def decode_attn_subset(dims, layout, latent_pool, idx_pool, ref_pool, block_tabl
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if check and rc != OK:
         raise DeltaKVError(rc, "deltakv_decode_attn_subset")
+    return rc
+
+
+def decode_attn_raw(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref_tables, w_up_k, w_up_v, q,
+                    seq_lens, seq_lens_host, raw_k, raw_v, raw_lens, scale, out, lse, workspace, selection=None,
+                    stream=None, check=True) -> int:
+    """raw_k / raw_v: [batch, raw_cap, n_kv_heads, head_dim] bf16 bits (or None for no raw segment);
+    selection: None for the whole cache, else (sel_pages, sel_masks, n_sel, n_sel_host)."""
+    sl_h = _host_i32(seq_lens_host)
+    sp, sm, n_dev, n_host = selection if selection is not None else (None, None, None, None)
+    ns_h = _host_i32(n_host) if selection is not None else None
+    rc = _lib.deltakv_decode_attn_raw(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_up_k), _dp(w_up_v), _dp(q), _dp(seq_lens), sl_h.ctypes.data,
+        _dp(sp), _dp(sm), 0 if sp is None else sp.shape[1], _dp(n_dev), None if ns_h is None else ns_h.ctypes.data,
+        _dp(raw_k), _dp(raw_v), _dp(raw_lens), 0 if raw_k is None else raw_k.shape[1], len(sl_h), float(scale),
+        _dp(out), _dp(lse), _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_decode_attn_raw")
     return rc

@@ -184,3 +184,18 @@ class PagedCache:
                              self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host,
                              sp, sm, n_dev, n_host, scale, out, lse, self.decode_ws, stream)
         return out
+
+    def decode_attn_raw(self, w_up_k, w_up_v, q, seq_lens_host, raw_k, raw_v, raw_lens_host, scale,
+                        positions_per_seq=None, out=None, lse=None, stream=None):
+        """Attention over the cache (or the selected positions) plus raw_lens_host[b] raw tokens per sequence;
+        raw_k / raw_v: device bf16 bits [batch, raw_cap, n_kv_heads, head_dim]."""
+        torch = self.torch
+        seq_lens = torch.tensor(np.asarray(seq_lens_host, dtype=np.int32), device=self.device)
+        raw_lens = torch.tensor(np.asarray(raw_lens_host, dtype=np.int32), device=self.device)
+        sel = self.selection(positions_per_seq) if positions_per_seq is not None else None
+        if out is None:
+            out = torch.empty_like(q)
+        B.decode_attn_raw(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool, self.block_tables,
+                          self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host, raw_k, raw_v, raw_lens, scale,
+                          out, lse, self.decode_ws, selection=sel, stream=stream)
+        return out

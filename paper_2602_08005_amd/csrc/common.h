@@ -12,6 +12,8 @@ constexpr int kHeadDim = 128;
 constexpr int kPage = 16;          // tokens per page
 constexpr int kRefChunk = 256;     // reference ordinals handled by one block of the per-reference kernels
 constexpr int kMaxSplits = 16;     // upper bound on token-range splits of one (sequence, kv-head)
+constexpr int kRawChunk = 256;     // raw-segment tokens handled by one block
+constexpr int kRawMaxChunks = 16;  // a raw segment holds at most kRawChunk * kRawMaxChunks tokens per sequence
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // Softmax weights are 2^(x - m_ref - kExpBias) with m_ref the largest per-reference score; every
@@ -64,6 +66,8 @@ struct DecodeWs {
   int64_t accpart;  // fp32 [B][Hkv][S][Gp][R]
   int64_t opart;    // fp32 [B][Hkv][n_chunk_max][Gp][128]
   int64_t wpart;    // fp32 [B][Hkv][S][n_ref_max][Gp]
+  int64_t rawo;     // fp32 [B][Hkv][kRawMaxChunks][Gp][128]  raw-segment partial outputs
+  int64_t rawml;    // fp32 [B][Hkv][kRawMaxChunks][Gp][2]    their (largest logit, weight sum)
   int64_t total;
 };
 inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_ref_max, int splits) {
@@ -82,6 +86,8 @@ inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_r
   w.accpart = take(BH * splits * Gp * R * 4);
   w.opart = take(BH * nch * Gp * kHeadDim * 4);
   w.wpart = take(BH * splits * n_ref_max * Gp * 4);
+  w.rawo = take(BH * kRawMaxChunks * Gp * kHeadDim * 4);
+  w.rawml = take(BH * kRawMaxChunks * Gp * 2 * 4);
   w.total = o;
   return w;
 }

@@ -14,6 +14,7 @@
 //                 w_j accumulated in an LDS table with hardware float atomics, one partial set per split
 //   ref_values  : sum_j w_j V_ref[j] per reference chunk
 //   finalize    : merges splits/chunks, up-projects the latent sum through W_uV, normalises, writes bf16
+// (a fifth, raw_attn, runs first when the call brings a segment of uncompressed sink / recent tokens)
 // All softmax weights use one fixed exponent offset per (sequence, q-head): m_ref = max_j S_ref[j].  A
 // reference token is cached with idx = own ordinal and z = 0, so its logit IS S_ref[j]; the true maximum
 // is therefore >= m_ref, partial sums from different waves/splits add without rescaling, and the sum of
@@ -762,6 +763,146 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// raw_attn: grid (chunks of the longest raw segment, Hkv, B), 256 threads.  Appendix B.2 keeps sink and recent
+// tokens uncompressed in a pool of their own and attends them together with the reconstructed ones.  A block
+// takes kRawChunk raw tokens of one (sequence, kv-head): scores of the group's query heads on the matrix unit
+// (as ref_scores), weights 2^(x - m) against the chunk's own largest logit m, then sum_t w_t V_t in fp32 (as
+// ref_values).  It depends on nothing the other kernels compute; finalize merges its (m, sum w, sum w V).
+// ------------------------------------------------------------------------------------------------
+template <int GP>
+__global__ __launch_bounds__(256) void k_raw_attn(DecodeParams P) {
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int n_raw = clampi(P.raw_lens[b], 0, P.raw_cap);
+  const int t0 = chunk * kRawChunk;
+  if (t0 >= n_raw) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  __shared__ float sc[kRawChunk][GP];          // scores, then weights
+  __shared__ float red[4][GP][kHeadDim];
+  __shared__ float mred[4][16];
+  __shared__ float msh[GP];
+  const int64_t row_stride = (int64_t)P.Hkv * kHeadDim;
+  const uint16_t* kseg = P.raw_k + ((int64_t)b * P.raw_cap * P.Hkv + h) * kHeadDim;
+  const uint16_t* vseg = P.raw_v + ((int64_t)b * P.raw_cap * P.Hkv + h) * kHeadDim;
+
+  bf16x8 qa[4];
+  {
+    const uint16_t* qrow = P.q + ((int64_t)b * P.Hq + (int64_t)h * P.G + (ln < P.G ? ln : 0)) * kHeadDim;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 v = *reinterpret_cast<const uint4*>(qrow + (4 * kk + lg) * 8);
+      if (ln >= P.G) v = make_uint4(0, 0, 0, 0);
+      qa[kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+  // scores: wave w, step st <-> tokens t0 + 64 w + 16 st + ln (rows past the end re-read the last token)
+  float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+  for (int st = 0; st < 4; ++st) {
+    const int tl = w * 64 + st * 16 + ln;
+    const bool valid = t0 + tl < n_raw;
+    const uint16_t* krow = kseg + (int64_t)min(t0 + tl, n_raw - 1) * row_stride;
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint4 kv = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv), acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float x = valid ? acc[i] * P.qk_scale_log2 : -INFINITY;
+      if (4 * lg + i < GP) sc[tl][4 * lg + i] = x;      // lane holds heads 4*lg + i of token ln
+      mx[i] = fmaxf(mx[i], x);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) mx[i] = wave16_max(mx[i]);
+  if (ln == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) mred[w][4 * lg + i] = mx[i];
+  }
+  __syncthreads();
+  if (tid < GP) msh[tid] = fmaxf(fmaxf(mred[0][tid], mred[1][tid]), fmaxf(mred[2][tid], mred[3][tid]));
+  __syncthreads();
+  // weights of token tid (the chunk holds a valid token, so every m is finite; rows past the end get 0)
+  float lsum[GP];
+#pragma unroll
+  for (int g = 0; g < GP; ++g) {
+    const float p = __builtin_amdgcn_exp2f(sc[tid][g] - msh[g]);
+    sc[tid][g] = p;
+    lsum[g] = p;
+  }
+#pragma unroll
+  for (int g = 0; g < GP; ++g) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) lsum[g] += __shfl_xor(lsum[g], o);
+  }
+  __syncthreads();                                   // all weights written; mred is free again
+  if (l == 0) {
+#pragma unroll
+    for (int g = 0; g < GP; ++g) mred[w][g] = lsum[g];
+  }
+  // values: lane = (row-in-group lg, 8-wide d chunk ln); a wave reads four 256-byte V rows per load
+  float acc[GP][8];
+#pragma unroll
+  for (int g = 0; g < GP; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  constexpr int UN = GP >= 16 ? 2 : (GP == 8 ? 4 : 8);
+  for (int it0 = 0; it0 < kRawChunk / 16; it0 += UN) {
+    uint4 v[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int row = w * (kRawChunk / 4) + (it0 + u) * 4 + lg;
+      v[u] = *reinterpret_cast<const uint4*>(vseg + (int64_t)min(t0 + row, n_raw - 1) * row_stride + ln * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int row = w * (kRawChunk / 4) + (it0 + u) * 4 + lg;
+      float wj[GP];
+#pragma unroll
+      for (int g = 0; g < GP; ++g) wj[g] = sc[row][g];
+      const uint32_t vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float lo = bf16lo(vv[e2]), hi = bf16hi(vv[e2]);
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+          acc[g][2 * e2] += wj[g] * lo;
+          acc[g][2 * e2 + 1] += wj[g] * hi;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < GP; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[g][e];
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      acc[g][e] = v;
+    }
+  if (lg == 0) {
+#pragma unroll
+    for (int g = 0; g < GP; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[w][g][ln * 8 + e] = acc[g][e];
+  }
+  __syncthreads();
+  const int64_t part = ((int64_t)b * P.Hkv + h) * kRawMaxChunks + chunk;
+  float* op = P.rawo + part * GP * kHeadDim;
+  for (int i = tid; i < GP * kHeadDim; i += 256) {
+    const int g = i / kHeadDim, d = i % kHeadDim;
+    op[i] = red[0][g][d] + red[1][g][d] + red[2][g][d] + red[3][g][d];
+  }
+  if (tid < GP) {
+    float* ml = P.rawml + (part * GP + tid) * 2;
+    ml[0] = msh[tid];
+    ml[1] = mred[0][tid] + mred[1][tid] + mred[2][tid] + mred[3][tid];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // finalize: grid (Hq, B), 128 threads (thread = output dim d); one block per query head.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
@@ -771,60 +912,78 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   const int L = seq_len_of(P, b);
   const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
   const int n_pages = work_pages_of(P, b, L);
-  if (n_pages <= 0) {         // empty sequence or empty selection
+  const int n_raw = P.raw_k ? clampi(P.raw_lens[b], 0, P.raw_cap) : 0;
+  if (n_pages <= 0 && n_raw <= 0) {         // nothing to attend: empty sequence or selection, no raw tokens
     P.out[orow + d] = 0;
     if (P.lse && d == 0) P.lse[(int64_t)b * P.Hq + gh] = -INFINITY;
     return;
   }
   __shared__ float zsum[128];
   __shared__ float redm[2];
-  const int n_ref = refs_below(L, P.stride);
-  const int nch = ceil_div(n_ref, kRefChunk);
-  const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
-  int n_used = 0;
-  for (int s = 0; s < sp.n_splits; ++s)
-    if (s * sp.per < n_pages) n_used = s + 1;
   const int64_t bh = (int64_t)b * P.Hkv + h;
-  float lsum = 0.f;
-#pragma unroll
-  for (int s = 0; s < kMaxSplits; ++s)
-    if (s < n_used) lsum += P.lpart[(bh * P.S + s) * Gp + g];
-  float mref = -INFINITY;
-  for (int c = d; c < nch; c += 128) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) mref = fmaxf(mref, __shfl_xor(mref, o));
-  if ((d & 63) == 0) redm[d >> 6] = mref;
-  if (d < R) {
-    float a = 0.f;
+  // the cached tokens: weights 2^(x - frame), frame = m_ref + kExpBias
+  float lsum = 0.f, o = 0.f, frame = -INFINITY;
+  if (n_pages > 0) {                        // uniform over the block
+    const int n_ref = refs_below(L, P.stride);
+    const int nch = ceil_div(n_ref, kRefChunk);
+    const SplitPlan sp = plan_splits(n_pages, P.S, P.pages_per_split);
+    int n_used = 0;
+    for (int s = 0; s < sp.n_splits; ++s)
+      if (s * sp.per < n_pages) n_used = s + 1;
 #pragma unroll
     for (int s = 0; s < kMaxSplits; ++s)
-      if (s < n_used) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
-    zsum[d] = a;
-  }
-  __syncthreads();
-  mref = fmaxf(redm[0], redm[1]);
-  float o = 0.f;
-  const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
-  const int64_t cstride = (int64_t)Gp * kHeadDim;
-  int c = 0;
-  for (; c + 8 <= nch; c += 8) {
-    float t[8];
+      if (s < n_used) lsum += P.lpart[(bh * P.S + s) * Gp + g];
+    float mref = -INFINITY;
+    for (int c = d; c < nch; c += 128) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) t[u] = op[(c + u) * cstride];
+    for (int o2 = 1; o2 < 64; o2 <<= 1) mref = fmaxf(mref, __shfl_xor(mref, o2));
+    if ((d & 63) == 0) redm[d >> 6] = mref;
+    if (d < R) {
+      float a = 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) o += t[u];
-  }
-  for (; c < nch; ++c) o += op[c * cstride];
-  const uint16_t* wv = P.w_up_v + d;
+      for (int s = 0; s < kMaxSplits; ++s)
+        if (s < n_used) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
+      zsum[d] = a;
+    }
+    __syncthreads();
+    frame = fmaxf(redm[0], redm[1]) + kExpBias;
+    const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
+    const int64_t cstride = (int64_t)Gp * kHeadDim;
+    int c = 0;
+    for (; c + 8 <= nch; c += 8) {
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = op[(c + u) * cstride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) o += t[u];
+    }
+    for (; c < nch; ++c) o += op[c * cstride];
+    const uint16_t* wv = P.w_up_v + d;
 #pragma unroll 16
-  for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wv[(int64_t)cc * kHeadDim]);
-  P.out[orow + d] = (uint16_t)f32_to_bf16_bits(o / lsum);
-  if (d == 0) {
-    if (P.lse) P.lse[(int64_t)b * P.Hq + gh] = (mref + kExpBias + __log2f(lsum)) * kLn2;
+    for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wv[(int64_t)cc * kHeadDim]);
     // a weight of 2^60 or more (exponent argument ~60 above the biased offset) risks overflow of the fp32 sums;
     // any such weight makes the sum at least that large
-    if (!(lsum < 0x1p60f) || !(lsum > 0.f)) atomicOr(P.status, 1);
+    if (d == 0 && (!(lsum < 0x1p60f) || !(lsum > 0.f))) atomicOr(P.status, 1);
   }
+  if (n_raw > 0) {
+    // merge the raw chunks: everything is brought to the largest frame, so no factor exceeds 1
+    const int nrc = ceil_div(n_raw, kRawChunk);
+    const float* ml = P.rawml + ((bh * kRawMaxChunks) * Gp + g) * 2;
+    float top = lsum > 0.f ? frame : -INFINITY;
+    for (int c = 0; c < nrc; ++c) top = fmaxf(top, ml[(int64_t)c * Gp * 2]);
+    const float fc = lsum > 0.f ? __builtin_amdgcn_exp2f(frame - top) : 0.f;
+    lsum *= fc;
+    o *= fc;
+    const float* ro = P.rawo + ((bh * kRawMaxChunks) * Gp + g) * kHeadDim + d;
+    for (int c = 0; c < nrc; ++c) {
+      const float f = __builtin_amdgcn_exp2f(ml[(int64_t)c * Gp * 2] - top);
+      lsum += f * ml[(int64_t)c * Gp * 2 + 1];
+      o += f * ro[(int64_t)c * Gp * kHeadDim];
+    }
+    frame = top;
+  }
+  P.out[orow + d] = (uint16_t)f32_to_bf16_bits(o / lsum);
+  if (d == 0 && P.lse) P.lse[(int64_t)b * P.Hq + gh] = (frame + __log2f(lsum)) * kLn2;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -882,6 +1041,17 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
   hipError_t e;
   dim3 gchunk(P.n_chunk_max, P.Hkv, batch);
   timing_mark(-1, st);
+  if (P.raw_k && P.raw_cap > 0) {
+    dim3 graw(ceil_div(P.raw_cap, kRawChunk), P.Hkv, batch);
+    switch (P.Gp) {
+      case 4: hipLaunchKernelGGL(k_raw_attn<4>, graw, dim3(256), 0, st, P); break;
+      case 8: hipLaunchKernelGGL(k_raw_attn<8>, graw, dim3(256), 0, st, P); break;
+      case 16: hipLaunchKernelGGL(k_raw_attn<16>, graw, dim3(256), 0, st, P); break;
+      default: return hipErrorInvalidValue;
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of raw_attn");
+    timing_mark(K_RAW, st);
+  }
   hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);

@@ -214,18 +214,29 @@ struct Selection {
   int32_t stride = 0;
 };
 
+// Raw segment of the third entry point (all null / 0 for none).
+struct RawSegment {
+  const void* k = nullptr;
+  const void* v = nullptr;
+  const int32_t* lens = nullptr;
+  int32_t cap = 0;
+};
+
 static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
                        const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
                        int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
                        const void* w_up_v, const void* q, const int32_t* seq_lens,
-                       const int32_t* seq_lens_host, const Selection& sel, int32_t batch, float scale, void* out,
-                       float* lse, void* workspace, int64_t ws_bytes, void* stream) {
+                       const int32_t* seq_lens_host, const Selection& sel, const RawSegment& raw, int32_t batch,
+                       float scale, void* out, float* lse, void* workspace, int64_t ws_bytes, void* stream) {
   int rc = check_dims(dims);
   if (rc != DELTAKV_OK) return rc;
   if (!lay || !latent_pool || !idx_pool || !ref_pool || !block_tables || !ref_tables || !w_up_k || !w_up_v ||
       !q || !seq_lens || !seq_lens_host || !out || batch < 0 || bt_stride <= 0 || rt_stride <= 0 ||
       !(scale == scale))
     return DELTAKV_E_INVALID_ARG;
+  if (raw.cap < 0 || (raw.cap > 0 && (!raw.k || !raw.v || !raw.lens))) return DELTAKV_E_INVALID_ARG;
+  if (raw.cap > 0 && (!aligned(raw.k, 16) || !aligned(raw.v, 16))) return DELTAKV_E_INVALID_ARG;
+  if (raw.cap > kRawChunk * kRawMaxChunks) return DELTAKV_E_UNSUPPORTED;
   if (batch == 0) return DELTAKV_OK;
   if (batch > 65535) return DELTAKV_E_UNSUPPORTED;
   if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
@@ -341,6 +352,14 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   Pm.accpart = reinterpret_cast<float*>(wsb + ws.accpart);
   Pm.opart = reinterpret_cast<float*>(wsb + ws.opart);
   Pm.wpart = reinterpret_cast<float*>(wsb + ws.wpart);
+  Pm.rawo = reinterpret_cast<float*>(wsb + ws.rawo);
+  Pm.rawml = reinterpret_cast<float*>(wsb + ws.rawml);
+  if (raw.cap > 0) {
+    Pm.raw_k = static_cast<const uint16_t*>(raw.k);
+    Pm.raw_v = static_cast<const uint16_t*>(raw.v);
+    Pm.raw_lens = raw.lens;
+    Pm.raw_cap = raw.cap;
+  }
   // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
   // from the device copy of the lengths
   int64_t n_items = 0;
@@ -356,7 +375,7 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* lay, con
                         const int32_t* seq_lens_host, int32_t batch, float scale, void* out, float* lse,
                         void* workspace, int64_t ws_bytes, void* stream) {
   return decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
-                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, Selection{}, batch, scale, out, lse, workspace,
+                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, Selection{}, RawSegment{}, batch, scale, out, lse, workspace,
                      ws_bytes, stream);
 }
 
@@ -378,8 +397,37 @@ int deltakv_decode_attn_subset(const deltakv_dims* dims, const deltakv_layout* l
   sel.n_sel_host = n_sel_host;
   sel.stride = sel_stride;
   return decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
-                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, sel, batch, scale, out, lse, workspace, ws_bytes,
-                     stream);
+                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, sel, RawSegment{}, batch, scale, out, lse, workspace,
+                     ws_bytes, stream);
+}
+
+int deltakv_decode_attn_raw(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                            const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                            int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                            const void* w_up_v, const void* q, const int32_t* seq_lens,
+                            const int32_t* seq_lens_host, const int32_t* sel_pages, const int32_t* sel_masks,
+                            int32_t sel_stride, const int32_t* n_sel, const int32_t* n_sel_host, const void* raw_k,
+                            const void* raw_v, const int32_t* raw_lens, int32_t raw_cap, int32_t batch, float scale,
+                            void* out, float* lse, void* workspace, int64_t ws_bytes, void* stream) {
+  Selection sel;
+  if (sel_pages) {
+    if (!sel_masks || !n_sel || !n_sel_host || sel_stride <= 0) return DELTAKV_E_INVALID_ARG;
+    for (int b = 0; b < batch; ++b)
+      if (n_sel_host[b] < 0 || n_sel_host[b] > sel_stride) return DELTAKV_E_INVALID_ARG;
+    sel.pages = sel_pages;
+    sel.masks = sel_masks;
+    sel.n_sel = n_sel;
+    sel.n_sel_host = n_sel_host;
+    sel.stride = sel_stride;
+  }
+  RawSegment raw;
+  raw.k = raw_k;
+  raw.v = raw_v;
+  raw.lens = raw_lens;
+  raw.cap = raw_cap;
+  return decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
+                     w_up_k, w_up_v, q, seq_lens, seq_lens_host, sel, raw, batch, scale, out, lse, workspace,
+                     ws_bytes, stream);
 }
 
 int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,

@@ -18,6 +18,12 @@ struct DecodeParams {
   const int32_t* sel_masks;
   const int32_t* n_sel;
   int sel_stride;
+  // raw segment (null for none): tokens kept uncompressed beside the cache (sink / recent tokens), attended
+  // together with the cached ones; bf16 [batch][raw_cap][Hkv][128] each, raw_lens[b] <= raw_cap of them valid
+  const uint16_t* raw_k;
+  const uint16_t* raw_v;
+  const int32_t* raw_lens;
+  int raw_cap;
   int bt_stride, rt_stride;
   int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
   int64_t idx_page_stride, idx_head_stride;
@@ -47,6 +53,8 @@ struct DecodeParams {
   float* accpart;
   float* opart;
   float* wpart;
+  float* rawo;              // fp32 [B][Hkv][kRawMaxChunks][Gp][128]: sum_t 2^(x_t - m) V_t of one raw chunk
+  float* rawml;             // fp32 [B][Hkv][kRawMaxChunks][Gp][2]: the chunk's m (largest logit, log2 units) and sum of weights
 };
 
 struct CompressParams {
@@ -110,7 +118,7 @@ hipError_t launch_append(const CompressParams& P, hipStream_t st);
 
 // Optional per-kernel timing (deltakv_timing_begin / deltakv_timing_end): when enabled, launchers call
 // timing_mark(kernel_id, stream) before the first kernel (id -1) and after every kernel.
-enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_RESOLVE, K_EXACT, K_PROJECT, K_COUNT };
+enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_RESOLVE, K_EXACT, K_PROJECT, K_RAW, K_COUNT };
 void timing_mark(int kernel_id, hipStream_t st);
 
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
