@@ -14,7 +14,8 @@
 //                scales by the reference's inverse norm, applies the causal candidate mask and keeps
 //                (best, second best, arg best) per token -- scores never leave the chip
 //   resolve    : merges reference-range splits; a token whose two best fp32 scores are closer than the fp32
-//                error bound is queued for exact re-scoring, every other token gets its ordinal
+//                error bound is queued for exact re-scoring, every other token gets its ordinal (with a single
+//                split the similarity kernel does this itself and the kernel is not launched)
 //   exact      : queued tokens, 16 at a time, against all their candidates on the fp64 matrix unit
 //                (v_mfma_f64_16x16x4) with the definition's formula, so the stored ordinal is the exact
 //                arg-max with lowest-ordinal tie-break
@@ -54,6 +55,18 @@ __device__ inline bool gap_is_safe(float best, float second, float na2, int metr
   return best - second > 4e-5f * na;
 }
 
+constexpr int kKeyIdxMask = 0xFFFFFF;   // low 24 bits of an exact-pass key hold (2^24 - 1 - ordinal)
+
+// The ordinal of a non-reference token from its merged fp32 result, or -1 after queueing it for the exact pass.
+__device__ inline int decide_ordinal(const CompressParams& P, int64_t n, int b, int h, float best, float second, int arg,
+                                     float na2) {
+  if (arg >= 0 && gap_is_safe(best, second, na2, P.metric)) return arg;
+  const int at = atomicAdd(&P.flag_count[b * P.Hkv + h], 1);
+  P.flag_list[(int64_t)h * P.n_new_total + P.cu_new[b] + at] = (int)n;
+  P.exact_key[n * P.Hkv + h] = kKeyIdxMask;          // (lowest score, ordinal 0); raised by the exact pass
+  return -1;
+}
+
 __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // largest b with cu[b] <= n
   int lo = 0, hi = batch - 1;
   while (lo < hi) {
@@ -91,10 +104,9 @@ __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// sim_top2: grid (tiles_max, NS, B*Hkv), 256 threads = 4 waves, wave tile (16*TB) tokens x 64 references.
+// sim_top2: grid (B*Hkv, NS, tiles_max), 4 or 8 waves, wave tile (16*TB) tokens x 64 references.
 // ------------------------------------------------------------------------------------------------
 constexpr int kNT = 64;                 // references per LDS tile
-constexpr int kKeyIdxMask = 0xFFFFFF;   // low 24 bits of an exact-pass key hold (2^24 - 1 - ordinal)
 constexpr int kRowPad = 264;            // bf16 elements per staged reference row (256 + 8: shifts banks)
 
 struct Top2 {
@@ -124,16 +136,19 @@ __device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
 // accumulator sets), software-pipelined by hand: while the 8*TB MFMAs of step q run, the LDS reads of step
 // q+1's operands are in flight and the VALU epilogue of step q-1 (scale, mask, top-2) is issued in the MFMA
 // shadow; reference tiles are staged through three LDS buffers so that one barrier per tile suffices.
-template <int TB, bool L2M>
-__global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
-  constexpr int WM = 16 * TB, MT = 4 * WM;
+template <int TB, bool L2M, int NW>
+__global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
+  constexpr int WM = 16 * TB, MT = NW * WM;
+  constexpr int LPW = 32 / NW;                                // direct loads of reference rows per wave and tile
   constexpr int kTile = kNT * 256;                           // bf16 elements of one staged tile (64 rows x 512 B)
   extern __shared__ uint16_t lds_raw[];
   float* nrm = reinterpret_cast<float*>(lds_raw + 3 * kTile);   // [3][kNT]
 
-  // token tiles with the most candidate references are scheduled first (the causal search gets longer with position)
-  const int tt = (int)gridDim.x - 1 - (int)blockIdx.x, split = blockIdx.y;
-  const int b = blockIdx.z / P.Hkv, h = blockIdx.z % P.Hkv;
+  // Blocks are handed out in the order of their linear index, x fastest: (sequence, kv-head) runs fastest and the
+  // token tile slowest, last tile first, so the tiles with the most candidate references (the causal search gets
+  // longer with position) of ALL heads start first and the short ones fill the gaps at the end.
+  const int tt = (int)gridDim.z - 1 - (int)blockIdx.z, split = blockIdx.y;
+  const int b = blockIdx.x / P.Hkv, h = blockIdx.x % P.Hkv;
   const int n_new = P.cu_new[b + 1] - P.cu_new[b];
   if (tt * MT >= n_new) return;
   const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
@@ -194,25 +209,25 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
   // Every wave also copies the 64 inverse norms (same values to the same place: keeps all waves' load counts equal).
   const int my_row = l >> 5;                                  // which of the two rows of a load this lane fills
   const int my_pos = l & 31;                                  // position inside the row
-  auto load_slots = [&](int t, int (&slot)[9]) {              // pool slots of the rows this lane will fill
+  auto load_slots = [&](int t, int (&slot)[LPW + 1]) {        // pool slots of the rows this lane will fill
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = 2 * (8 * w + i) + my_row;
+    for (int i = 0; i < LPW; ++i) {
+      const int r = 2 * (LPW * w + i) + my_row;
       slot[i] = rtab[min(t * kNT + r, ncand_tile - 1)];       // rows past the end repeat the last reference
     }                                                          // (they are masked by the candidate count)
-    slot[8] = rtab[min(t * kNT + l, ncand_tile - 1)];
+    slot[LPW] = rtab[min(t * kNT + l, ncand_tile - 1)];
   };
-  auto issue_tile = [&](int buf, const int (&slot)[9]) {
+  auto issue_tile = [&](int buf, const int (&slot)[LPW + 1]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = 2 * (8 * w + i) + my_row;
+    for (int i = 0; i < LPW; ++i) {
+      const int r = 2 * (LPW * w + i) + my_row;
       const int c = my_pos ^ (r & 7);
       const uint16_t* src = (c < 16 ? refk : refv) + (int64_t)clampi(slot[i], 0, (int)P.n_ref_slots - 1) * kHeadDim + (c & 15) * 8;
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                       (void __attribute__((address_space(3)))*)(lds_raw + buf * kTile + (8 * w + i) * 512),
+                                       (void __attribute__((address_space(3)))*)(lds_raw + buf * kTile + (LPW * w + i) * 512),
                                        16, 0, 0);
     }
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rnorm + clampi(slot[8], 0, (int)P.n_ref_slots - 1)),
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rnorm + clampi(slot[LPW], 0, (int)P.n_ref_slots - 1)),
                                      (void __attribute__((address_space(3)))*)(nrm + buf * kNT), 4, 0, 0);
   };
   // s_waitcnt for the vector-memory counter only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
@@ -222,16 +237,16 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
   };
 
   if (n_t > 0) {
-    // Per tile and wave: 9 slot loads (S) then 9 direct loads (D).  Order of issue: S(0) S(1) D(0) S(2) D(1) |
+    // Per tile and wave: LPW + 1 (= 9 with four waves) slot loads (S) then as many direct loads (D).  Order of issue: S(0) S(1) D(0) S(2) D(1) |
     // tile ti: S(ti+3) D(ti+2) ... so D(ti+1), needed at the end of tile ti, has two tiles of work to land in,
     // and everything issued after it is S(ti+3), D(ti+2): 18 loads.
-    int slot_a[9], slot_b[9];                                 // slots of tiles ti+2 (a) and ti+3 (b)
+    int slot_a[LPW + 1], slot_b[LPW + 1];                     // slots of tiles ti+2 (a) and ti+3 (b)
     load_slots(t_begin, slot_a);
     load_slots(t_begin + (n_t > 1 ? 1 : 0), slot_b);
     issue_tile(0, slot_a);
     load_slots(t_begin + min(2, n_t - 1), slot_a);
     issue_tile(1, slot_b);
-    wait_vm(std::integral_constant<int, 18>{});              // D(0) has landed (S(2), D(1) may be outstanding)
+    wait_vm(std::integral_constant<int, 2 * (LPW + 1)>{});   // D(0) has landed (S(2), D(1) may be outstanding)
     __syncthreads();
     const int pos_first = lb + row0;                         // smallest position in this wave's rows
 
@@ -292,7 +307,7 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
     bool prev_full = false;
 
     // one tile: S(ti+3) into `fill`, D(ti+2) from `use`, four steps with the barrier before the last one
-    auto tile_body = [&](int ti, const int (&use)[9], int (&fill)[9]) {
+    auto tile_body = [&](int ti, const int (&use)[LPW + 1], int (&fill)[LPW + 1]) {
       // loads are unconditional (past the end they re-load the last tile into a buffer nobody reads), so that
       // the number of loads in flight -- and with it the wait count below -- is the same in every iteration
       load_slots(t_begin + min(ti + 3, n_t - 1), fill);
@@ -318,7 +333,7 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
       step(std::integral_constant<int, 2>{});
       // before step 3 prefetches the first operands of tile ti+1: its direct loads (issued one tile ago) must
       // have landed in every wave; after it nobody reads tile ti's buffer any more
-      wait_vm(std::integral_constant<int, 18>{});
+      wait_vm(std::integral_constant<int, 2 * (LPW + 1)>{});
       __syncthreads();
       step(std::integral_constant<int, 3>{});
     };
@@ -342,10 +357,16 @@ __global__ __launch_bounds__(256) void k_sim_top2(CompressParams P) {
     }
     const int r = row0 + tb * 16 + ln;
     if (lg == 0 && r < n_new) {
-      float4 o;
-      o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = na2[tb];
       const int64_t n = P.cu_new[b] + r;
-      *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
+      if (P.NS == 1) {        // the whole reference range was this block's: decide here, no resolve kernel
+        const int pos = lb + r;
+        P.ord[n * P.Hkv + h] = pos % P.stride == 0 ? pos / P.stride
+                                                   : decide_ordinal(P, n, b, h, t.best, t.second, t.idx, na2[tb]);
+      } else {
+        float4 o;
+        o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = na2[tb];
+        *reinterpret_cast<float4*>(P.part + ((n * P.Hkv + h) * P.NS + split) * 4) = o;
+      }
     }
   }
 }
@@ -375,14 +396,7 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
       if (o.x > bb) { b2 = fmaxf(bb, o.y); bb = o.x; bi = oi; }
       else b2 = fmaxf(b2, o.x);
     }
-    if (bi < 0 || !gap_is_safe(bb, b2, na2, P.metric)) {
-      const int at = atomicAdd(&P.flag_count[b * P.Hkv + h], 1);
-      P.flag_list[(int64_t)h * P.n_new_total + P.cu_new[b] + at] = n;
-      P.exact_key[item] = kKeyIdxMask;          // (lowest score, ordinal 0); raised by the exact pass
-      ord = -1;
-    } else {
-      ord = bi;
-    }
+    ord = decide_ordinal(P, n, b, h, bb, b2, bi, na2);
   }
   P.ord[item] = ord;
 }
@@ -880,22 +894,25 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int TB, bool L2M>
+template <int TB, bool L2M, int NW>
 static hipError_t launch_sim_m(const CompressParams& P, dim3 grid, hipStream_t st) {
   const size_t lds = 3 * kNT * 256 * 2 + 3 * kNT * 4;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB, L2M>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB, L2M, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(similarity kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_sim_top2<TB, L2M>), grid, dim3(256), lds, st, P);
+  hipLaunchKernelGGL((k_sim_top2<TB, L2M, NW>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of sim_top2");
 }
 template <int TB>
-static hipError_t launch_sim(const CompressParams& P, dim3 grid, hipStream_t st) {
-  return P.metric ? launch_sim_m<TB, true>(P, grid, st) : launch_sim_m<TB, false>(P, grid, st);
+static hipError_t launch_sim(const CompressParams& P, int nw, dim3 grid, hipStream_t st) {
+  if constexpr (TB <= 2) {
+    if (nw == 8) return P.metric ? launch_sim_m<TB, true, 8>(P, grid, st) : launch_sim_m<TB, false, 8>(P, grid, st);
+  }
+  return P.metric ? launch_sim_m<TB, true, 4>(P, grid, st) : launch_sim_m<TB, false, 4>(P, grid, st);
 }
 
 template <int R>
@@ -912,9 +929,9 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
   return note_hip_error(hipGetLastError(), "launch of project");
 }
 
-int sim_tile_rows(int rb) { return 64 * rb; }
+int sim_tile_rows(int rb, int nw) { return (nw == 8 && rb <= 2 ? 8 : 4) * 16 * rb; }
 
-hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, int max_new_refs,
+hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_max, int page_tiles_max, int max_new_refs,
                            hipStream_t st) {
   hipError_t e;
   const int items = P.n_new_total * P.Hkv;
@@ -923,19 +940,21 @@ hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int p
                      dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of admit_refs");
   timing_mark(K_ADMIT, st);
-  dim3 gs(tiles_max, P.NS, P.batch * P.Hkv);
+  dim3 gs(P.batch * P.Hkv, P.NS, tiles_max);
   switch (rb) {
-    case 1: e = launch_sim<1>(P, gs, st); break;
-    case 2: e = launch_sim<2>(P, gs, st); break;
-    case 3: e = launch_sim<3>(P, gs, st); break;
-    case 4: e = launch_sim<4>(P, gs, st); break;
+    case 1: e = launch_sim<1>(P, nw, gs, st); break;
+    case 2: e = launch_sim<2>(P, nw, gs, st); break;
+    case 3: e = launch_sim<3>(P, nw, gs, st); break;
+    case 4: e = launch_sim<4>(P, nw, gs, st); break;
     default: return hipErrorInvalidValue;
   }
   if (e != hipSuccess) return e;
   timing_mark(K_SIM, st);
-  hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
-  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
-  timing_mark(K_RESOLVE, st);
+  if (P.NS > 1) {           // with one reference-range split the similarity kernel has decided already
+    hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
+    if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
+    timing_mark(K_RESOLVE, st);
+  }
   hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
   timing_mark(K_EXACT, st);

@@ -49,6 +49,7 @@ int g_tune_stream_waves = 0;
 int g_tune_splits = 0;
 int g_tune_sim_tb = 0;
 int g_tune_sim_ns = 0;
+int g_tune_sim_waves = 0;
 
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
@@ -109,6 +110,9 @@ int deltakv_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "sim_ns")) {
     if (value > 64) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_ns = value;
+  } else if (!strcmp(name, "sim_waves")) {
+    if (value != 0 && value != 4 && value != 8) return DELTAKV_E_INVALID_ARG;
+    g_tune_sim_waves = value;
   } else if (!strcmp(name, "sim_tb")) {
     if (value < 0 || value > 4) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_tb = value;
@@ -470,8 +474,11 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   const int n_new_total = cu_new_host[batch];
   if (n_new_total == 0) return DELTAKV_OK;
   if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
-  const int rb = g_tune_sim_tb ? g_tune_sim_tb : (max_new >= 1024 ? 3 : (max_new >= 128 ? 2 : 1));
-  const int mt = sim_tile_rows(rb);
+  // long calls: eight waves (two per SIMD, so one wave's top-2 arithmetic runs under the other's matrix
+  // instructions) of two 16-token blocks each; short calls: four waves, smaller tiles
+  const int rb = g_tune_sim_tb ? g_tune_sim_tb : (max_new >= 128 ? 2 : 1);
+  const int sim_nw = g_tune_sim_waves ? g_tune_sim_waves : (max_new >= 1024 ? 8 : 4);
+  const int mt = sim_tile_rows(rb, sim_nw);
   const int tiles_max = ceil_div(max_new, mt);
   int64_t tiles_total = 0;
   int64_t max_len_after = 0;
@@ -491,7 +498,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   if (ws_bytes < cw.part + per_split) return DELTAKV_E_WORKSPACE;
   if (ns > (ws_bytes - cw.part) / per_split) ns = (ws_bytes - cw.part) / per_split;
   if (ns < 1) return DELTAKV_E_WORKSPACE;
-  if (tiles_max > 65535 * 32768ll || page_tiles_max <= 0) return DELTAKV_E_UNSUPPORTED;
+  if (tiles_max > 65535 || page_tiles_max <= 0) return DELTAKV_E_UNSUPPORTED;   // grid z of the similarity kernel
 
   CompressParams Pm;
   memset(&Pm, 0, sizeof(Pm));
@@ -545,7 +552,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
     Pm.NS = nsa < 1 ? 1 : (int)nsa;
     e = launch_append(Pm, static_cast<hipStream_t>(stream));
   } else {
-    e = launch_compress(Pm, rb, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
+    e = launch_compress(Pm, rb, sim_nw, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }

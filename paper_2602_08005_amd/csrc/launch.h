@@ -107,9 +107,9 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
 }
 
 // Token rows per block of the similarity kernel for row-block factor rb (1, 2 or 4).
-int sim_tile_rows(int rb);
+int sim_tile_rows(int rb, int nw);
 // Enqueues the three compress kernels on `st`.
-hipError_t launch_compress(const CompressParams& P, int rb, int tiles_max, int page_tiles_max, int max_new_refs,
+hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_max, int page_tiles_max, int max_new_refs,
                            hipStream_t st);
 
 // Enqueues the two kernels of the decode-append path (every sequence brings exactly one new token; P.NS = blocks
