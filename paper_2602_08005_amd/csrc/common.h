@@ -12,6 +12,7 @@ constexpr int kHeadDim = 128;
 constexpr int kPage = 16;          // tokens per page
 constexpr int kRefChunk = 256;     // reference ordinals handled by one block of the per-reference kernels
 constexpr int kMaxSplits = 16;     // upper bound on token-range splits of one (sequence, kv-head)
+constexpr int kWPad = 136;         // bf16 elements per staged W_down^T row (128 + 8: shifts LDS banks)
 constexpr int kRawChunk = 256;     // raw-segment tokens handled by one block
 constexpr int kRawMaxChunks = 16;  // a raw segment holds at most kRawChunk * kRawMaxChunks tokens per sequence
 constexpr float kLog2e = 1.4426950408889634f;

@@ -82,6 +82,13 @@ __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // large
 __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
   if (blockIdx.x == 0 && blockIdx.y == 0)   // queue counters of the exact pass (cleared here, not by a memset node)
     for (int i = threadIdx.x; i < P.batch * P.Hkv; i += 256) P.flag_count[i] = 0;
+  // W_down^T of both streams with padded rows, the form the projection kernel stages into LDS with wide copies:
+  // element (stream, c, d) <- w_down[d][c]; the pad columns are zeroed
+  if (blockIdx.y == 0)
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < 2 * P.R * kWPad; i += gridDim.x * 256) {
+      const int st = i / (P.R * kWPad), rem = i % (P.R * kWPad), c = rem / kWPad, d = rem % kWPad;
+      P.wt[i] = d < kHeadDim ? (st ? P.w_down_v : P.w_down_k)[d * P.R + c] : (uint16_t)0;
+    }
   const int b = blockIdx.y;
   const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int l = threadIdx.x & 63;
@@ -411,8 +418,8 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
 // With the L2 metric the 40 score bits are the complement of the leading bits of the fp64 squared distance
 // |a|^2 - 2 a.b + |b|^2 (sign, exponent, 28 mantissa bits: distances closer than 2^-28 relative tie).
 // ------------------------------------------------------------------------------------------------
-constexpr int kExactX = 8;    // few blocks: an idle block of this kernel still costs a dispatch with ~240 registers per lane
-constexpr int kExactSplits = 8;
+constexpr int kExactX = 2;    // few blocks: an idle block of this kernel still costs a dispatch with ~240 registers per lane
+constexpr int kExactSplits = 32;  // each wave then scores one 16-reference tile per 2048 candidates
 typedef double double4v __attribute__((ext_vector_type(4)));
 
 __device__ inline double bf16_elem_f64(const uint4& c, int e) {
@@ -528,7 +535,6 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
 // project: grid (page_tiles_max, B), 256 threads; wave w handles kv-heads w, w+4, ...
 // A wave owns one page of one sequence: lane (ln, lg) <-> token slot ln of the page, 8-wide chunk.
 // ------------------------------------------------------------------------------------------------
-constexpr int kWPad = 136;   // bf16 elements per staged W_down^T row (128 + 8)
 
 template <int R>
 __global__ __launch_bounds__(256) void k_project(CompressParams P) {
@@ -542,11 +548,9 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   const int lp = page_first + blockIdx.x;         // logical page of the sequence
   if (n_new <= 0 || lp * kPage >= la) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
-  // stage W_down^T (both streams): element (c, d) <- w_down[d][c]
-  for (int i = tid; i < 2 * R * kHeadDim; i += 256) {
-    const int st = i / (R * kHeadDim), rem = i % (R * kHeadDim), d = rem / R, c = rem % R;
-    wlds[(st * R + c) * kWPad + d] = (st ? P.w_down_v : P.w_down_k)[d * R + c];
-  }
+  // stage W_down^T of both streams (transposed and padded by admit_refs) with 16-byte copies
+  for (int i = tid; i < 2 * R * kWPad / 8; i += 256)
+    reinterpret_cast<uint4*>(wlds)[i] = reinterpret_cast<const uint4*>(P.wt)[i];
   __syncthreads();
   const int pos = lp * kPage + ln;
   const bool tok_ok = pos >= lb && pos < la;
@@ -556,14 +560,25 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   page = clampi(page, 0, (int)P.n_pages_pool - 1);
   const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
 
+  // ordinal and reference slot of the lane's token for kv-head h: the fp32 decision, or (negative) the exact pass's
+  // key; both are loaded unconditionally (no load behind a branch), and one head ahead of their use, so that the
+  // chain ordinal -> table entry -> reference row of the next head runs under the current head's arithmetic
+  auto fetch_ord = [&](int h) {
+    const int hh = min(h, P.Hkv - 1);
+    const int o = P.ord[n * P.Hkv + hh];
+    const int oe = kKeyIdxMask - (int)(P.exact_key[n * P.Hkv + hh] & kKeyIdxMask);
+    return clampi(o < 0 ? oe : o, 0, P.rt_stride - 1);
+  };
+  int ord_next = fetch_ord(w);
+  int slot_next = rtab[ord_next];
   for (int h = w; h < P.Hkv; h += 4) {
     const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
     const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
-    int ord = P.ord[n * P.Hkv + h];
-    if (ord < 0) ord = kKeyIdxMask - (int)(P.exact_key[n * P.Hkv + h] & kKeyIdxMask);   // decided by the exact pass
-    ord = clampi(ord, 0, P.rt_stride - 1);
+    const int ord = ord_next;
     // residual against the chosen raw reference, fp32 (exact for bf16 inputs), split into bf16 hi + lo
-    const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
+    const int slot = clampi(slot_next, 0, (int)P.n_ref_slots - 1);
+    ord_next = fetch_ord(h + 4);
+    slot_next = rtab[ord_next];
     const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
     const uint16_t* rv = rk + P.ref_kv_stride;
     const bool zero = !tok_ok || is_ref;

@@ -540,6 +540,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.flag_list = reinterpret_cast<int32_t*>(wsb + cw.flag_list);
   Pm.exact_key = reinterpret_cast<uint64_t*>(wsb + cw.exact_key);
   Pm.part = reinterpret_cast<float*>(wsb + cw.part);
+  Pm.wt = reinterpret_cast<uint16_t*>(wsb + cw.wt);
   // decode append (one new token for every sequence): two small kernels instead of five
   bool one_each = n_new_total == batch;
   for (int b = 0; b < batch && one_each; ++b) one_each = cu_new_host[b + 1] - cu_new_host[b] == 1;

@@ -84,10 +84,11 @@ struct CompressParams {
   int32_t* flag_count; // [batch][Hkv] tokens queued for exact re-scoring
   int32_t* flag_list;  // [Hkv][n_new_total] queued token indices, sequence b's segment starts at cu_new[b]
   uint64_t* exact_key; // [n_new_total][Hkv] result keys of the exact pass (valid for queued tokens)
+  uint16_t* wt;        // bf16 [2][R][kWPad]: W_dK^T and W_dV^T, rows padded, written by admit_refs for project
 };
 
 struct CompressWs {
-  int64_t ord, flag_count, flag_list, exact_key, part;   // byte offsets; `part` takes everything from its offset on
+  int64_t ord, flag_count, flag_list, exact_key, wt, part;   // byte offsets; `part` takes everything from its offset on
   int64_t total;
 };
 // Offsets for a call with n_new tokens in total; `total` leaves room for 8 reference-range splits of a large
@@ -98,6 +99,7 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
   auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
   w.ord = take(n_new * d.n_kv_heads * 4);
   w.flag_count = take(batch * d.n_kv_heads * 4);
+  w.wt = take(2 * (int64_t)d.rank * kWPad * 2);
   w.flag_list = take(n_new * d.n_kv_heads * 4);
   w.exact_key = take(n_new * d.n_kv_heads * 8);
   w.part = o;
