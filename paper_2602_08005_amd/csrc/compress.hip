@@ -220,21 +220,22 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
       const int r = 2 * (LPW * w + i) + my_row;
-      slot[i] = rtab[min(t * kNT + r, ncand_tile - 1)];       // rows past the end repeat the last reference
-    }                                                          // (they are masked by the candidate count)
-    slot[LPW] = rtab[min(t * kNT + l, ncand_tile - 1)];
+      slot[i] = rtab[(uint32_t)min(t * kNT + r, ncand_tile - 1)];   // rows past the end repeat the last reference
+    }                                                                // (they are masked by the candidate count)
+    slot[LPW] = rtab[(uint32_t)min(t * kNT + l, ncand_tile - 1)];
   };
   auto issue_tile = [&](int buf, const int (&slot)[LPW + 1]) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
       const int r = 2 * (LPW * w + i) + my_row;
       const int c = my_pos ^ (r & 7);
-      const uint16_t* src = (c < 16 ? refk : refv) + (int64_t)clampi(slot[i], 0, (int)P.n_ref_slots - 1) * kHeadDim + (c & 15) * 8;
+      // unsigned clamp (a negative table entry lands on the last slot): one instruction, zero-extended address
+      const uint16_t* src = (c < 16 ? refk : refv) + (uint64_t)min((uint32_t)slot[i], (uint32_t)P.n_ref_slots - 1u) * kHeadDim + (c & 15) * 8;
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                        (void __attribute__((address_space(3)))*)(lds_raw + buf * kTile + (LPW * w + i) * 512),
                                        16, 0, 0);
     }
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rnorm + clampi(slot[LPW], 0, (int)P.n_ref_slots - 1)),
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(rnorm + min((uint32_t)slot[LPW], (uint32_t)P.n_ref_slots - 1u)),
                                      (void __attribute__((address_space(3)))*)(nrm + buf * kNT), 4, 0, 0);
   };
   // s_waitcnt for the vector-memory counter only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
