@@ -279,6 +279,7 @@ int deltakv_version(void);
  *   "stream_waves"  waves per block of the decode streaming kernel (8)
  *   "splits"        token-range splits per (sequence, kv-head) in decode (1..16)
  *   "sim_tb"        16-token blocks per wave of the similarity kernel (1..4)
+ *   "sim_waves"     waves per block of the similarity kernel (4 or 8; 8 needs sim_tb <= 2)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)
  * Results do not depend on these beyond floating-point summation order.  Errors: INVALID_ARG. */
 int deltakv_tune(const char* name, int32_t value);
