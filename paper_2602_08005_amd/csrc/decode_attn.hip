@@ -81,18 +81,31 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   // the status word is cleared here rather than by a memset node, so that a caller may capture the call
   if (chunk == 0 && h == 0 && b == 0) {
     if (threadIdx.x == 0) *P.status = 0;
-    // List of the non-empty (sequence, split) items, in sequence order, for the streaming kernel's grid: thread t
-    // counts the items of its run of sequences, the counts are scanned, and each thread writes its run.
+    // List of the non-empty (sequence, split) items for the streaming kernel's grid.  Blocks start in list order,
+    // so the list goes from the sequences with the largest splits to those with the smallest (longest processing
+    // time first: the short blocks fill the gaps at the end of a ragged batch); a batch of more than 256
+    // sequences keeps sequence order.  Thread t counts the items of its run of sequences, finds how many items
+    // come before its run, and writes its run.
     __shared__ int run_items[256];
+    __shared__ int run_size[256];
     const int per = ceil_div(P.batch, 256), b_lo = min((int)threadIdx.x * per, P.batch), b_hi = min(b_lo + per, P.batch);
-    int cnt = 0;
-    for (int bb = b_lo; bb < b_hi; ++bb)
-      cnt += used_splits(work_pages_of(P, bb, seq_len_of(P, bb)), P.S, P.pages_per_split);
+    int cnt = 0, size = 0;
+    for (int bb = b_lo; bb < b_hi; ++bb) {
+      const int wp = work_pages_of(P, bb, seq_len_of(P, bb));
+      cnt += used_splits(wp, P.S, P.pages_per_split);
+      size = wp > 0 ? plan_splits(wp, P.S, P.pages_per_split).per : 0;     // pages per split (used when per == 1)
+    }
     run_items[threadIdx.x] = cnt;
+    run_size[threadIdx.x] = per == 1 ? size : 0;      // all equal: sequence order
     __syncthreads();
-    int at = 0;
-    for (int t = 0; t < (int)threadIdx.x; ++t) at += run_items[t];
-    if (threadIdx.x == 255) P.items[0] = at + cnt;
+    int at = 0, total = 0;
+    for (int t = 0; t < 256; ++t) {
+      const int n = run_items[t], sz = run_size[t];
+      const bool before = sz > run_size[threadIdx.x] || (sz == run_size[threadIdx.x] && t < (int)threadIdx.x);
+      at += before ? n : 0;
+      total += n;
+    }
+    if (threadIdx.x == 0) P.items[0] = total;
     for (int bb = b_lo; bb < b_hi; ++bb) {
       const int ns = used_splits(work_pages_of(P, bb, seq_len_of(P, bb)), P.S, P.pages_per_split);
       for (int s = 0; s < ns; ++s) P.items[1 + at + s] = bb * kMaxSplits + s;

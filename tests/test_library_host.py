@@ -144,3 +144,45 @@ def test_entry_points_reject_null_and_inconsistent_arguments_without_a_device():
     assert comp(lbh=far.ctypes.data) == B.E_INVALID_ARG
     empty = np.array([0, 0, 0], dtype=np.int32)
     assert comp(cuh=empty.ctypes.data, ws=None) == B.OK
+
+
+def test_subset_and_raw_entry_points_reject_bad_arguments_without_a_device():
+    d = dk.make_dims(2, 8, 64, 8, 8)
+    L = dk.paged_layout(d, 2, 64, 128)
+    buf = np.zeros(4096, dtype=np.uint8)
+    p = buf.ctypes.data + (256 - buf.ctypes.data % 256) % 256      # aligned host address, never dereferenced
+    sl = np.array([40, 128], dtype=np.int32)
+    ns = np.array([2, 3], dtype=np.int32)
+    lib = B._lib
+    def subset(**kw):
+        a = dict(sp=p, sm=p, ss=4, nd=p, nh=ns.ctypes.data, batch=2, ws=p)
+        a.update(kw)
+        return lib.deltakv_decode_attn_subset(C.byref(d), C.byref(L), p, p, p, p, 8, p, 8, p, p, p, p, sl.ctypes.data,
+                                              a["sp"], a["sm"], a["ss"], a["nd"], a["nh"], a["batch"], 0.1, p, None,
+                                              a["ws"], L.decode_ws_bytes, None)
+    assert subset(sp=None) == B.E_INVALID_ARG
+    assert subset(sm=None) == B.E_INVALID_ARG
+    assert subset(nh=None) == B.E_INVALID_ARG
+    assert subset(ss=0) == B.E_INVALID_ARG
+    assert subset(ss=2) == B.E_INVALID_ARG            # a sequence lists 3 pages, the rows hold 2
+    neg = np.array([2, -1], dtype=np.int32)
+    assert subset(nh=neg.ctypes.data) == B.E_INVALID_ARG
+    assert subset(batch=0) == B.OK
+    assert subset(ws=None) == B.E_WORKSPACE
+
+    def raw(**kw):
+        a = dict(sp=None, sm=None, ss=0, nd=None, nh=None, rk=p, rv=p, rl=p, cap=16, batch=2, ws=p)
+        a.update(kw)
+        return lib.deltakv_decode_attn_raw(C.byref(d), C.byref(L), p, p, p, p, 8, p, 8, p, p, p, p, sl.ctypes.data,
+                                           a["sp"], a["sm"], a["ss"], a["nd"], a["nh"], a["rk"], a["rv"], a["rl"],
+                                           a["cap"], a["batch"], 0.1, p, None, a["ws"], L.decode_ws_bytes, None)
+    assert raw(rk=None) == B.E_INVALID_ARG
+    assert raw(rv=None) == B.E_INVALID_ARG
+    assert raw(rl=None) == B.E_INVALID_ARG
+    assert raw(cap=-1) == B.E_INVALID_ARG
+    assert raw(rk=p + 8) == B.E_INVALID_ARG           # misaligned rows
+    assert raw(cap=4097) == B.E_UNSUPPORTED
+    assert raw(sp=p, sm=None) == B.E_INVALID_ARG      # a selection needs all of its arguments
+    assert raw(batch=0) == B.OK
+    assert raw(ws=None) == B.E_WORKSPACE
+    assert raw(cap=0, rk=None, rv=None, rl=None, batch=0) == B.OK
