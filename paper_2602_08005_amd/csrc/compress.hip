@@ -790,6 +790,17 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
   __shared__ int eidx[4];
   __shared__ float resid[2][kHeadDim];
   __shared__ float zpart[2][256];
+  // projection: thread (stream, part, c) sums its share of the 128 dims; R <= 128, 256 threads.  Its W_down column
+  // does not depend on the retrieval, so all of its loads are issued here, under the latency of everything below.
+  constexpr int PARTS = 128 / R >= 1 ? 128 / R : 1;        // threads per (stream, c): 128 / R, at least 1
+  constexpr int DP = kHeadDim / PARTS;
+  const int pst = tid / 128, prem = tid % 128, pc = prem % R, ppart = prem / R;
+  uint16_t wcol[DP];
+  {
+    const uint16_t* wd = (pst ? P.w_down_v : P.w_down_k) + pc;
+#pragma unroll
+    for (int i = 0; i < DP; ++i) wcol[i] = wd[(int64_t)(min(ppart, PARTS - 1) * DP + i) * R];
+  }
   if (is_ref) {
     if (tid == 0) ord_s = pos / P.stride;
   } else {
@@ -868,18 +879,13 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
     resid[1][tid] = is_ref ? 0.f : vx - rvv;
   }
   __syncthreads();
-  // projection: thread (stream, part, c) sums its share of the 128 dims; R <= 128, 256 threads
-  constexpr int PARTS = 128 / R >= 1 ? 128 / R : 1;        // threads per (stream, c): 128 / R, at least 1
   {
-    const int st = tid / 128, rem = tid % 128, c = rem % R, part = rem / R;
     float z = 0.f;
-    if (part < PARTS) {
-      const uint16_t* wd = (st ? P.w_down_v : P.w_down_k) + c;
-      constexpr int DP = kHeadDim / PARTS;
-#pragma unroll 8
-      for (int d = part * DP; d < (part + 1) * DP; ++d) z += resid[st][d] * __uint_as_float((uint32_t)wd[(int64_t)d * R] << 16);
+    if (ppart < PARTS) {
+#pragma unroll
+      for (int i = 0; i < DP; ++i) z += resid[pst][ppart * DP + i] * __uint_as_float((uint32_t)wcol[i] << 16);
     }
-    zpart[st][rem] = z;
+    zpart[pst][prem] = z;
   }
   __syncthreads();
   const int tok = pos % kPage;

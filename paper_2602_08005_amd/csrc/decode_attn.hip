@@ -99,7 +99,8 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
     run_size[threadIdx.x] = per == 1 ? size : 0;      // all equal: sequence order
     __syncthreads();
     int at = 0, total = 0;
-    for (int t = 0; t < 256; ++t) {
+    const int n_runs = ceil_div(P.batch, per);          // threads beyond hold no sequence
+    for (int t = 0; t < n_runs; ++t) {
       const int n = run_items[t], sz = run_size[t];
       const bool before = sz > run_size[threadIdx.x] || (sz == run_size[threadIdx.x] && t < (int)threadIdx.x);
       at += before ? n : 0;
@@ -656,6 +657,51 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   __shared__ float wsum[kRefChunk][GP];
   __shared__ int slots[kRefChunk];
 
+  // phase 1a: thread t loads the split partials of reference j0+t (coalesced across threads), its scores and its
+  // slot.  All loads are issued before the reduction below needs its own, so the two latencies overlap.  The loads
+  // of a split's entries are unconditional within the splits in use (an entry the split did not write holds stale
+  // values and is dropped by the select): behind a per-thread branch each load would wait for the one before it.
+  const int j = j0 + tid;
+  float wfix[GP], wplain[GP], sj[GP];          // fixed-point sums, sums of tables already in plain units, scores
+#pragma unroll
+  for (int g = 0; g < GP; ++g) { wfix[g] = 0.f; wplain[g] = 0.f; sj[g] = 0.f; }
+  int slot = 0;
+  if (j < n_ref) {
+    slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + j], 0, (int)P.n_ref_slots - 1);
+    uint32_t plain = 0;                        // splits whose table already holds plain weights (rare)
+    uint32_t wrote = 0;                        // splits whose table covers ordinal j
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+      const int p1 = min(n_pages, (s + 1) * sp.per);
+      if (s < sp.n_splits && s * sp.per < p1) {
+        if (P.wflag[bh * P.S + s] != 0) plain |= 1u << s;
+        if (j < refs_covered(P, b, L, p1)) wrote |= 1u << s;
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+      if (s < sp.n_splits) {                   // uniform over the block
+        const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
+        const bool on = (wrote >> s) & 1u, pl = (plain >> s) & 1u;
+#pragma unroll
+        for (int g4 = 0; g4 < GP; g4 += 4) {
+          const float4 t = *reinterpret_cast<const float4*>(wp + g4);
+          const float tt[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            wfix[g4 + e] += on && !pl ? tt[e] : 0.f;
+            wplain[g4 + e] += on && pl ? tt[e] : 0.f;
+          }
+        }
+      }
+    }
+    const float* sp_ = P.sref + (bh * P.n_ref_max + j) * GP;
+#pragma unroll
+    for (int g4 = 0; g4 < GP; g4 += 4) {
+      const float4 t = *reinterpret_cast<const float4*>(sp_ + g4);
+      sj[g4] = t.x; sj[g4 + 1] = t.y; sj[g4 + 2] = t.z; sj[g4 + 3] = t.w;
+    }
+  }
   // per query head, the base of the table units (the same value the stream kernel used)
   __shared__ float cpart[256];
   __shared__ float shift_s[GP];
@@ -671,51 +717,11 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
     }
     __syncthreads();
   }
-  // phase 1: thread t sums the split partials of reference j0+t (coalesced across threads), scales them back
-  // by the power of two the stream kernel divided out, and fetches the reference's slot
-  {
-    const int j = j0 + tid;
-    float wj[GP];
+  // phase 1b: the fixed-point sums are scaled back by the power of two the stream kernel divided out
 #pragma unroll
-    for (int g = 0; g < GP; ++g) wj[g] = 0.f;
-    int slot = 0;
-    if (j < n_ref) {
-      slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + j], 0, (int)P.n_ref_slots - 1);
-      uint32_t plain = 0;                      // splits whose table already holds plain weights (rare)
-#pragma unroll
-      for (int s = 0; s < kMaxSplits; ++s)
-        if (s < sp.n_splits && P.wflag[bh * P.S + s] != 0) plain |= 1u << s;
-      auto add_splits = [&](bool want_plain) {
-#pragma unroll
-        for (int s = 0; s < kMaxSplits; ++s) {
-          const int p1 = min(n_pages, (s + 1) * sp.per);
-          if (s < sp.n_splits && s * sp.per < p1 && j < refs_covered(P, b, L, p1) &&   // ordinals split s wrote
-              (((plain >> s) & 1u) != 0u) == want_plain) {
-            const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
-#pragma unroll
-            for (int g4 = 0; g4 < GP; g4 += 4) {
-              const float4 t = *reinterpret_cast<const float4*>(wp + g4);
-              wj[g4] += t.x; wj[g4 + 1] += t.y; wj[g4 + 2] += t.z; wj[g4 + 3] += t.w;
-            }
-          }
-        }
-      };
-      add_splits(false);
-      const float* sp_ = P.sref + (bh * P.n_ref_max + j) * GP;
-#pragma unroll
-      for (int g4 = 0; g4 < GP; g4 += 4) {
-        const float4 t = *reinterpret_cast<const float4*>(sp_ + g4);
-        wj[g4] = __builtin_ldexpf(wj[g4], -table_shift(t.x, shift_s[g4]));
-        wj[g4 + 1] = __builtin_ldexpf(wj[g4 + 1], -table_shift(t.y, shift_s[g4 + 1]));
-        wj[g4 + 2] = __builtin_ldexpf(wj[g4 + 2], -table_shift(t.z, shift_s[g4 + 2]));
-        wj[g4 + 3] = __builtin_ldexpf(wj[g4 + 3], -table_shift(t.w, shift_s[g4 + 3]));
-      }
-      if (plain != 0u) add_splits(true);
-    }
-#pragma unroll
-    for (int g = 0; g < GP; ++g) wsum[tid][g] = wj[g];
-    slots[tid] = slot;
-  }
+  for (int g = 0; g < GP; ++g)
+    wsum[tid][g] = __builtin_ldexpf(wfix[g], -table_shift(sj[g], shift_s[g])) + wplain[g];
+  slots[tid] = slot;
   __syncthreads();
 
   // phase 2: lane = (row-in-group lg, 8-wide d chunk ln); a wave reads four 256-byte V rows per load and
@@ -918,9 +924,15 @@ __global__ __launch_bounds__(256) void k_raw_attn(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // finalize: grid (Hq, B), 128 threads (thread = output dim d); one block per query head.
 // ------------------------------------------------------------------------------------------------
+template <int R>
 __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   const int gh = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-  const int G = P.G, Gp = P.Gp, R = P.R;
+  const int G = P.G, Gp = P.Gp;
+  // the thread's column of W_uV does not depend on anything computed here: all R loads are issued first and land
+  // under the latency of the partial-sum loads below
+  uint16_t wcol[R];
+#pragma unroll
+  for (int cc = 0; cc < R; ++cc) wcol[cc] = P.w_up_v[(int64_t)cc * kHeadDim + d];
   const int h = gh / G, g = gh % G;
   const int L = seq_len_of(P, b);
   const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
@@ -943,20 +955,29 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
     int n_used = 0;
     for (int s = 0; s < sp.n_splits; ++s)
       if (s * sp.per < n_pages) n_used = s + 1;
+    // loads of all split slots are unconditional (slots past the used ones hold stale values and are dropped
+    // afterwards): behind a branch each load would wait for the one before it
+    {
+      float lp[kMaxSplits];
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s)
-      if (s < n_used) lsum += P.lpart[(bh * P.S + s) * Gp + g];
+      for (int s = 0; s < kMaxSplits; ++s) lp[s] = P.lpart[(bh * P.S + min(s, P.S - 1)) * Gp + g];
+#pragma unroll
+      for (int s = 0; s < kMaxSplits; ++s) lsum += s < n_used ? lp[s] : 0.f;
+    }
     float mref = -INFINITY;
     for (int c = d; c < nch; c += 128) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + g]);
 #pragma unroll
     for (int o2 = 1; o2 < 64; o2 <<= 1) mref = fmaxf(mref, __shfl_xor(mref, o2));
     if ((d & 63) == 0) redm[d >> 6] = mref;
-    if (d < R) {
+    {
+      const int dd = d < R ? d : R - 1;
+      float ap[kMaxSplits];
+#pragma unroll
+      for (int s = 0; s < kMaxSplits; ++s) ap[s] = P.accpart[((bh * P.S + min(s, P.S - 1)) * Gp + g) * R + dd];
       float a = 0.f;
 #pragma unroll
-      for (int s = 0; s < kMaxSplits; ++s)
-        if (s < n_used) a += P.accpart[((bh * P.S + s) * Gp + g) * R + d];
-      zsum[d] = a;
+      for (int s = 0; s < kMaxSplits; ++s) a += s < n_used ? ap[s] : 0.f;
+      if (d < R) zsum[d] = a;
     }
     __syncthreads();
     frame = fmaxf(redm[0], redm[1]) + kExpBias;
@@ -971,9 +992,8 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
       for (int u = 0; u < 8; ++u) o += t[u];
     }
     for (; c < nch; ++c) o += op[c * cstride];
-    const uint16_t* wv = P.w_up_v + d;
-#pragma unroll 16
-    for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wv[(int64_t)cc * kHeadDim]);
+#pragma unroll
+    for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wcol[cc]);
     // a weight of 2^60 or more (exponent argument ~60 above the biased offset) risks overflow of the fp32 sums;
     // any such weight makes the sum at least that large
     if (d == 0 && (!(lsum < 0x1p60f) || !(lsum > 0.f))) atomicOr(P.status, 1);
@@ -1084,7 +1104,17 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
   }
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_values");
   timing_mark(K_REF_VALUES, st);
-  hipLaunchKernelGGL(k_finalize, dim3(P.Hq, batch), dim3(128), 0, st, P);
+  switch (P.R) {
+    case 16: hipLaunchKernelGGL(k_finalize<16>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 32: hipLaunchKernelGGL(k_finalize<32>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 48: hipLaunchKernelGGL(k_finalize<48>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 64: hipLaunchKernelGGL(k_finalize<64>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 80: hipLaunchKernelGGL(k_finalize<80>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 96: hipLaunchKernelGGL(k_finalize<96>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 112: hipLaunchKernelGGL(k_finalize<112>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    case 128: hipLaunchKernelGGL(k_finalize<128>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
+    default: return hipErrorInvalidValue;
+  }
   e = note_hip_error(hipGetLastError(), "launch of finalize");
   timing_mark(K_FINALIZE, st);
   return e;
