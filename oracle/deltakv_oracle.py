@@ -94,6 +94,14 @@ def keep_ratio_eq5(n_full_layers: int, n_layers: int, s: int, dc_over_2dk: float
     return n_full_layers / n_layers + n_sparse / n_layers * per_layer
 
 
+def compute_ratio_eq6(n_full_layers: int, n_layers: int, budget: float) -> float:
+    """CR = L_full/L * 100 % + L_sparse/L * r (appendix D, equation (6)): the dense layers attend every
+    token, the compressed layers the fraction r that the sparse attention selects.  (The appendix's own
+    worked table prints r itself -- 30.0 and 20.0 -- in its CR column, which is the second term's factor,
+    not the value of the equation; the equation is what this function evaluates.)"""
+    return n_full_layers / n_layers + (n_layers - n_full_layers) / n_layers * budget
+
+
 def dense_kv_bytes(batch: int, seq_len: int, n_layers: int, n_kv_heads: int, head_dim: int,
                    bytes_per_value: int = 2) -> int:
     return batch * seq_len * n_layers * 2 * n_kv_heads * head_dim * bytes_per_value

@@ -41,6 +41,17 @@ def test_keep_ratio_matches_paper_rows(row):
     assert abs(got - want) <= tol, (got, want)
 
 
+def test_compute_ratio_equation_closed_forms():
+    """Equation (6): no dense layers -> the budget itself (the figure the appendix's table prints, 30.0 / 20.0);
+    all layers dense -> 100 %; budget 1 -> 100 %; linear in the budget; and the table's two layer splits by hand."""
+    assert O.compute_ratio_eq6(0, 32, 0.3) == pytest.approx(0.3) and O.compute_ratio_eq6(0, 32, 0.2) == pytest.approx(0.2)
+    assert O.compute_ratio_eq6(32, 32, 0.3) == 1.0 and O.compute_ratio_eq6(5, 32, 1.0) == pytest.approx(1.0)
+    assert O.compute_ratio_eq6(5, 32, 0.3) == pytest.approx(5 / 32 + 27 / 32 * 0.3)        # 40.9 %
+    assert O.compute_ratio_eq6(4, 32, 0.2) == pytest.approx(0.125 + 0.875 * 0.2)            # 30.0 %
+    a, b, c = (O.compute_ratio_eq6(5, 32, x) for x in (0.1, 0.2, 0.3))
+    assert (b - a) == pytest.approx(c - b)
+
+
 def test_dense_kv_size_statement():
     b, L, nl, hkv, d, bpv, lo, hi = _rows("dense_kv_size.txt")[0]
     gb = O.dense_kv_bytes(int(b), int(L), int(nl), int(hkv), int(d), int(bpv)) / 1e9
