@@ -107,6 +107,16 @@ def dense_kv_bytes(batch: int, seq_len: int, n_layers: int, n_kv_heads: int, hea
     return batch * seq_len * n_layers * 2 * n_kv_heads * head_dim * bytes_per_value
 
 
+def record_keep_ratio_4bit(mode: int, rank: int, head_dim: int, s: int) -> float:
+    """As record_keep_ratio for 4-bit token-wise latents: rank/2 bytes of codes plus a bf16 scale and a
+    bf16 zero point per latent, an int32 ordinal per token, and the raw bf16 reference (+ its fp32
+    float) every s-th token."""
+    streams = 1 if mode == JOINT else 2
+    rec = streams * (rank / 2 + 4) + 4
+    raw = 2 * head_dim * 2
+    return (rec + (raw + 4) / s) / raw
+
+
 def record_keep_ratio(mode: int, rank: int, head_dim: int, s: int, idx_bytes: int = 4,
                       value_bytes: int = 2, norm_bytes: int = 0) -> float:
     """Bytes kept per (token, kv-head) over the dense 2*head_dim values when every
@@ -156,8 +166,35 @@ def l2_scores(a: np.ndarray, refs: np.ndarray) -> np.ndarray:
     return -np.einsum("jn,jn->j", d, d)
 
 
+def quantize_tokenwise_4bit(z: np.ndarray):
+    """Token-wise asymmetric 4-bit quantisation of latent vectors (section 5.3, "Compatibility with
+    Quantization": the token-wise scheme of KIVI applied to the compressed residuals only).  One group
+    = the r values of one (token, head) latent.  The stored record is 16 levels per value plus a scale
+    and a zero point kept as bf16:
+        scale = bf16((max - min) / 15)      zero = bf16(min)
+        code  = clamp(round_half_even((z - zero) / scale), 0, 15)        (all codes 0 if scale = 0)
+        value read back = scale * code + zero
+    The code is an integer decided by floating point, so it is decided in the precision the kernel
+    has: z, the subtraction, the reciprocal of the scale and the product are float32.
+    z: [..., r].  Returns codes uint8 [..., r], scale bits uint16 [...], zero bits uint16 [...], and
+    the values read back, float64 [..., r]."""
+    z32 = np.asarray(z, dtype=np.float64).astype(np.float32)
+    mn, mx = z32.min(axis=-1), z32.max(axis=-1)
+    scale_b = f64_to_bf16_bits(((mx - mn) * np.float32(1.0 / 15.0)).astype(np.float64))
+    zero_b = f64_to_bf16_bits(mn.astype(np.float64))
+    scale = bf16_bits_to_f64(scale_b).astype(np.float32)
+    zero = bf16_bits_to_f64(zero_b).astype(np.float32)
+    with np.errstate(divide="ignore"):
+        inv = np.where(scale > 0, np.float32(1.0) / np.where(scale > 0, scale, np.float32(1.0)), np.float32(0.0))
+    q = np.rint((z32 - zero[..., None]) * inv[..., None].astype(np.float32))
+    codes = np.clip(q, 0, 15).astype(np.uint8)
+    back = scale.astype(np.float64)[..., None] * codes.astype(np.float64) + zero.astype(np.float64)[..., None]
+    return codes, scale_b, zero_b, back
+
+
 def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.ndarray,
-             s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048, metric: int = COSINE):
+             s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048, metric: int = COSINE,
+             latent_bits: int = 16):
     """Compress tokens start..L-1 of one sequence.
 
     K, V: float64 [L, H, D] -- the raw states of the WHOLE sequence so far (the
@@ -170,6 +207,9 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
                                    metric = L2 minus the squared distance to the chosen reference
       z_k, z_v float64 [n, H, r]   unrounded latents (JOINT: z_v is z_k)
       zb_k, zb_v uint16 [n, H, r]  bf16 bits of the stored latents
+    with latent_bits = 4 (4-bit token-wise latents) additionally
+      q_k, q_v   uint8  [n, H, r]  codes;  qs_*, qz_* uint16 [n, H]: bf16 bits of scale and zero point
+      zq_k, zq_v float64 [n, H, r] the latents as read back from the 4-bit record (what decode uses)
     and the reference pool of the whole sequence:
       ref_k, ref_v float64 [ceil(L/s), H, D]
     """
@@ -227,6 +267,12 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
         "mode": mode, "s": s, "start": start,
     }
     out["zb_v"] = out["zb_k"] if mode == JOINT else f64_to_bf16_bits(z_v)
+    if latent_bits == 4:
+        out["q_k"], out["qs_k"], out["qz_k"], out["zq_k"] = quantize_tokenwise_4bit(z_k)
+        if mode == JOINT:
+            out["q_v"], out["qs_v"], out["qz_v"], out["zq_v"] = out["q_k"], out["qs_k"], out["qz_k"], out["zq_k"]
+        else:
+            out["q_v"], out["qs_v"], out["qz_v"], out["zq_v"] = quantize_tokenwise_4bit(z_v)
     return out
 
 

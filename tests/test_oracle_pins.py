@@ -453,6 +453,62 @@ def test_subset_single_token_empty_selection_and_merge_of_disjoint_subsets():
     assert np.max(np.abs(out - both)) < 1e-12 and np.max(np.abs(lse - lboth)) < 1e-12
 
 
+# ---------------------------------------------------------------- 4-bit token-wise latents
+def test_4bit_quantiser_exact_on_a_16_level_grid_and_degenerate_vectors():
+    """Values that already sit on 16 levels with a bf16-representable origin and step come back exactly and their
+    codes are the level numbers (the textbook affine quantiser); a constant vector and the zero vector are exact."""
+    rng = np.random.default_rng(5)
+    lv = rng.integers(0, 16, size=(7, 3, 32))
+    lv[..., 0], lv[..., 1] = 0, 15                          # both ends present in every vector
+    z = -1.5 + 0.25 * lv                                    # origin -1.5, step 0.25: exact in bf16 and fp32
+    codes, sb, zb, back = O.quantize_tokenwise_4bit(z)
+    assert np.array_equal(codes, lv) and np.array_equal(back, z)
+    assert np.all(O.bf16_bits_to_f64(sb) == 0.25) and np.all(O.bf16_bits_to_f64(zb) == -1.5)
+    c2, s2, z2, b2 = O.quantize_tokenwise_4bit(np.full((2, 8), 0.375))
+    assert np.all(c2 == 0) and np.all(O.bf16_bits_to_f64(s2) == 0) and np.all(b2 == 0.375)
+    c3, s3, z3, b3 = O.quantize_tokenwise_4bit(np.zeros((4, 16)))
+    assert np.all(c3 == 0) and np.all(s3 == 0) and np.all(z3 == 0) and np.all(b3 == 0)
+
+
+def test_4bit_quantiser_error_bound_monotonicity_and_record_accounting():
+    """|read back - z| <= half a step plus the bf16 rounding of scale and zero point; codes are monotone in z; the
+    smallest value gets code 0 and the largest 15; keep ratio of the 4-bit record in closed form."""
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal((500, 64)) * rng.uniform(0.01, 30.0, size=(500, 1))
+    codes, sb, zb, back = O.quantize_tokenwise_4bit(z)
+    step = O.bf16_bits_to_f64(sb)
+    rng_ = z.max(-1) - z.min(-1)
+    assert np.all(np.abs(step - rng_ / 15) <= rng_ / 15 * 2.0 ** -8)
+    slack = 15 * step * 2.0 ** -8 + np.abs(z.min(-1)) * 2.0 ** -8 + 1e-6
+    assert np.all(np.abs(back - z) <= (0.5 * step + slack)[:, None])
+    order = np.argsort(z, axis=-1)
+    sorted_codes = np.take_along_axis(codes, order, axis=-1).astype(int)
+    assert np.all(np.diff(sorted_codes, axis=-1) >= 0)
+    assert np.all(sorted_codes[:, 0] == 0) and np.all(sorted_codes[:, -1] == 15)
+    assert O.record_keep_ratio_4bit(O.JOINT, 64, 128, 16) == pytest.approx((32 + 4 + 4 + 516 / 16) / 512)
+    assert O.record_keep_ratio_4bit(O.SPLIT, 64, 128, 16) == pytest.approx((2 * 36 + 4 + 516 / 16) / 512)
+
+
+def test_4bit_compress_keeps_ordinals_and_decodes_close_to_the_bf16_cache():
+    """Quantisation touches the latents only: ordinals and references are those of the bf16 path, reference tokens
+    keep an exactly zero latent, and attention over the 4-bit cache stays within the quantiser's error of the bf16
+    one (a loose sanity bound; the GPU is compared with this oracle, not with the bf16 result)."""
+    K, V, cls, P = _small_case(seed=73, L=120, H=2, D=16, r=8, s=4, joint=True)
+    wk, wv = _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"])
+    a = O.compress(K, V, wk, wv, s=4, mode=O.JOINT)
+    b = O.compress(K, V, wk, wv, s=4, mode=O.JOINT, latent_bits=4)
+    assert np.array_equal(a["idx"], b["idx"]) and np.array_equal(a["zb_k"], b["zb_k"])
+    assert np.all(b["zq_k"][::4] == 0) and np.all(b["q_k"][::4] == 0)
+    assert b["zq_v"] is b["zq_k"]
+    step = O.bf16_bits_to_f64(b["qs_k"])
+    assert np.all(np.abs(b["zq_k"] - b["z_k"]) <= 0.52 * step[..., None] + 1e-3 * np.abs(b["z_k"]).max())
+    q = np.random.default_rng(1).standard_normal((6, 16))
+    wuk, wuv = _f64(P["w_up_k_bf16"]), _f64(P["w_up_v_bf16"])
+    o16, _ = O.decode_attn_direct(q, a["idx"], _f64(a["zb_k"]), _f64(a["zb_k"]), a["ref_k"], a["ref_v"], wuk, wuv, 0.25)
+    o4, _ = O.decode_attn_direct(q, b["idx"], b["zq_k"], b["zq_v"], b["ref_k"], b["ref_v"], wuk, wuv, 0.25)
+    assert np.max(np.abs(o16 - o4)) < 0.25 * np.abs(o16).max() + 0.05
+
+
 # ---------------------------------------------------------------- raw (sink / recent) segment pins
 def test_raw_segment_brute_force_and_special_cases():
     """Cached tokens + raw rows by hand from the definition; no raw rows = the plain call; no cached tokens = dense
