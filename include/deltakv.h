@@ -87,6 +87,8 @@ typedef struct {
   int32_t metric;       /* DELTAKV_METRIC_COSINE or DELTAKV_METRIC_L2              */
   int64_t n_pages;      /* capacity of the latent / index pools, in pages          */
   int64_t n_ref_slots;  /* capacity of the reference pool, in reference tokens     */
+  int32_t latent_bits;  /* 16 (or 0): bf16 latents; 4: 4-bit token-wise latents    */
+  int32_t reserved;     /* must be 0                                               */
 } deltakv_dims;
 
 /* Filled by deltakv_paged_layout; the only source of sizes and strides.
@@ -100,6 +102,15 @@ typedef struct {
  *                  stream 1 (value operand, SPLIT mode only):
  *                    value (tok, c) at ((c/16)*64 + (tok/4)*16 + c%16)*4 + tok%4
  *                deltakv_latent_block_offsets returns these as a table.
+ *                With latent_bits = 4 (section 5.3: token-wise 4-bit quantisation
+ *                of the compressed residuals; JOINT mode only in this version,
+ *                SPLIT returns DELTAKV_E_UNSUPPORTED) a (page, head) block is
+ *                8*r + 64 bytes: first r/8 x P dwords of codes, the dword of
+ *                (chunk c/8, tok) at byte 4*((c/8)*P + tok), the code of value c in
+ *                bits [s, s+3] with s = 4*((c%8)/2) + 16*(c%2); then, for each
+ *                group of four tokens, 4 bf16 scales followed by 4 bf16 zero
+ *                points (16 bytes per group).  A value reads back as
+ *                scale * code + zero.  Strides stay in 2-byte elements.
  *   index pool   int32  [n_pages][n_kv_heads][P]   reference ordinal per token
  *   reference pool bf16 [n_kv_heads][2][n_ref_slots][head_dim]   (0 = K, 1 = V)
  *   reference inverse norms fp32 [n_kv_heads][n_ref_slots]: 1/||K||V|| of the

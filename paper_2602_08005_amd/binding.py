@@ -27,7 +27,8 @@ class Dims(C.Structure):
     _fields_ = [("n_kv_heads", C.c_int32), ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("rank", C.c_int32), ("latent_mode", C.c_int32), ("ref_stride", C.c_int32),
                 ("page_tokens", C.c_int32), ("metric", C.c_int32),
-                ("n_pages", C.c_int64), ("n_ref_slots", C.c_int64)]
+                ("n_pages", C.c_int64), ("n_ref_slots", C.c_int64),
+                ("latent_bits", C.c_int32), ("reserved", C.c_int32)]
 
 
 class Layout(C.Structure):
@@ -128,9 +129,9 @@ def timing_end() -> dict:
 
 
 def make_dims(n_kv_heads, n_q_heads, rank, n_pages, n_ref_slots, latent_mode=SPLIT, ref_stride=16,
-              head_dim=128, page_tokens=16, metric=METRIC_COSINE) -> Dims:
+              head_dim=128, page_tokens=16, metric=METRIC_COSINE, latent_bits=16) -> Dims:
     return Dims(n_kv_heads, n_q_heads, head_dim, rank, latent_mode, ref_stride, page_tokens, metric,
-                n_pages, n_ref_slots)
+                n_pages, n_ref_slots, latent_bits, 0)
 
 
 def paged_layout(dims: Dims, max_batch: int, max_new_tokens: int, max_seq_len: int) -> Layout:

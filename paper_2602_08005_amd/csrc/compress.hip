@@ -57,6 +57,25 @@ __device__ inline bool gap_is_safe(float best, float second, float na2, int metr
 
 constexpr int kKeyIdxMask = 0xFFFFFF;   // low 24 bits of an exact-pass key hold (2^24 - 1 - ordinal)
 
+// 4-bit token-wise latents (section 5.3): scale = bf16((max - min) / 15), zero = bf16(min), code =
+// clamp(round_half_even((z - zero) / scale), 0, 15), all in fp32 (the decision precision of the format).
+struct Q4Params {
+  uint32_t scale_bits, zero_bits;
+  float zero, inv;
+};
+__device__ inline Q4Params q4_params(float mn, float mx) {
+  Q4Params q;
+  q.scale_bits = f32_to_bf16_bits((mx - mn) * (1.0f / 15.0f));
+  q.zero_bits = f32_to_bf16_bits(mn);
+  const float scale = __uint_as_float(q.scale_bits << 16);
+  q.zero = __uint_as_float(q.zero_bits << 16);
+  q.inv = scale > 0.f ? 1.0f / scale : 0.f;
+  return q;
+}
+__device__ inline uint32_t q4_code(float z, const Q4Params& q) {
+  return (uint32_t)fminf(fmaxf(rintf((z - q.zero) * q.inv), 0.f), 15.f);
+}
+
 // The ordinal of a non-reference token from its merged fp32 result, or -1 after queueing it for the exact pass.
 __device__ inline int decide_ordinal(const CompressParams& P, int64_t n, int b, int h, float best, float second, int arg,
                                      float na2) {
@@ -604,6 +623,7 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
       }
     uint16_t* lat = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
     // stream 0 (scores-operand order): D^T[c][token], lane holds 4 consecutive c of token ln
+    float4v q4acc[NB];                 // 4-bit latents: the token's whole latent is needed before any of it is stored
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float4v acc = {0.f, 0.f, 0.f, 0.f};
@@ -618,12 +638,40 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, res[1][kk][1], acc, 0, 0, 0);
         }
       }
-      if (tok_ok) {
+      q4acc[nb] = acc;
+      if (tok_ok && !P.q4) {
         const int c = nb * 16 + 4 * lg;
         uint2 o;
         o.x = pack_bf16(acc[0], acc[1]);
         o.y = pack_bf16(acc[2], acc[3]);
         *reinterpret_cast<uint2*>(lat + ((c >> 3) * kPage + ln) * 8 + (c & 7)) = o;
+      }
+    }
+    if (P.q4) {
+      // the token's values sit in the four lanes (ln, lg = 0..3); value c = 16 nb + 4 lg + i is element
+      // e = 4 (lg & 1) + i of chunk 2 nb + lg / 2 and goes to bits 4 (e / 2) + 16 (e & 1) of the chunk's dword
+      float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { mn = fminf(mn, q4acc[nb][i]); mx = fmaxf(mx, q4acc[nb][i]); }
+      mn = fminf(mn, __shfl_xor(mn, 16)); mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mn = fminf(mn, __shfl_xor(mn, 32)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const Q4Params qp = q4_params(mn, mx);
+      char* blk = reinterpret_cast<char*>(lat);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        uint32_t part = q4_code(q4acc[nb][0], qp) | (q4_code(q4acc[nb][1], qp) << 16) |
+                        (q4_code(q4acc[nb][2], qp) << 4) | (q4_code(q4acc[nb][3], qp) << 20);
+        part <<= 8 * (lg & 1);
+        part |= __shfl_xor(part, 16);
+        if (tok_ok && (lg & 1) == 0)
+          *reinterpret_cast<uint32_t*>(blk + 4 * ((2 * nb + (lg >> 1)) * kPage + ln)) = part;
+      }
+      if (tok_ok && lg == 0) {
+        uint16_t* sz = reinterpret_cast<uint16_t*>(blk + 8 * R + (ln >> 2) * 16 + (ln & 3) * 2);
+        sz[0] = (uint16_t)qp.scale_bits;
+        sz[4] = (uint16_t)qp.zero_bits;
       }
     }
     if (!P.joint) {
@@ -790,6 +838,8 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
   __shared__ int eidx[4];
   __shared__ float resid[2][kHeadDim];
   __shared__ float zpart[2][256];
+  __shared__ float zfin[128];           // 4-bit latents: the token's final latent
+  __shared__ uint32_t qcode[128];
   // projection: thread (stream, part, c) sums its share of the 128 dims; R <= 128, 256 threads.  Its W_down column
   // does not depend on the retrieval, so all of its loads are issued here, under the latency of everything below.
   constexpr int PARTS = 128 / R >= 1 ? 128 / R : 1;        // threads per (stream, c): 128 / R, at least 1
@@ -902,12 +952,33 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
         float zv = 0.f;
 #pragma unroll
         for (int pt = 0; pt < PARTS; ++pt) zv += zpart[1][pt * R + c];
-        lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z + zv);
+        if (P.q4) zfin[c] = z + zv;
+        else lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z + zv);
       }
     } else if (st == 0) {
       lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z);
     } else {
       lat[P.latent_stream_stride + ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3)] = (uint16_t)f32_to_bf16_bits(z);
+    }
+  }
+  if (P.q4) {                 // 4-bit record of the token (single stream): codes of value c by thread c
+    __syncthreads();
+    float mn = INFINITY, mx = -INFINITY;
+    for (int c = 0; c < R; ++c) { mn = fminf(mn, zfin[c]); mx = fmaxf(mx, zfin[c]); }
+    const Q4Params qp = q4_params(mn, mx);
+    if (tid < R) qcode[tid] = q4_code(zfin[tid], qp);
+    __syncthreads();
+    char* blk = reinterpret_cast<char*>(lat);
+    if (tid < R / 8) {
+      uint32_t wd = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) wd |= qcode[tid * 8 + e] << (4 * (e >> 1) + 16 * (e & 1));
+      *reinterpret_cast<uint32_t*>(blk + 4 * (tid * kPage + tok)) = wd;
+    }
+    if (tid == 0) {
+      uint16_t* sz = reinterpret_cast<uint16_t*>(blk + 8 * R + (tok >> 2) * 16 + (tok & 3) * 2);
+      sz[0] = (uint16_t)qp.scale_bits;
+      sz[4] = (uint16_t)qp.zero_bits;
     }
   }
   if (tid == 0) P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok] = ord;

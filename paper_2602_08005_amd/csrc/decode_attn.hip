@@ -217,23 +217,47 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // stream: grid (S, Hkv, B), NW waves.  Dynamic LDS: [n_tab] w table, then small reduction buffers.
 // ------------------------------------------------------------------------------------------------
-template <int R>
+template <int R, bool Q4>
 struct Tile {
   static constexpr int NKK = (R + 31) / 32;
   static constexpr int NB = R / 16;
   uint4 zk[NKK];   // scores operand: token l%16, latent chunk l/16 + 4*kk
   uint2 zv[NB];    // value operand: column l%16 + 16*nb, tokens 4*(l/16)..+3
 };
+// 4-bit token-wise latents (section 5.3; one stream, JOINT mode): eight codes per dword instead of eight bf16
+// values per 16 bytes, plus the bf16 scales and zero points of the lane's four tokens 4*(l/16)..+3.
+template <int R>
+struct Tile<R, true> {
+  static constexpr int NKK = (R + 31) / 32;
+  static constexpr int NB = R / 16;
+  uint32_t zc[NKK];   // codes of token l%16, latent chunk l/16 + 4*kk (value c%8 at bits 4*((c%8)/2) + 16*(c%2))
+  uint4 sz;           // scales of tokens 4*(l/16)..+3 (x, y), their zero points (z, w), bf16 pairs
+  uint2 zv[NB];       // value operand, built on chip
+};
 
 // Loads of the streaming loop take their address as (uniform 64-bit base of the page) + (32-bit offset of the
 // lane), which the hardware forms itself (scalar base + vector offset): no vector arithmetic per load.
 template <int R, bool JOINT>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
-                                    uint32_t l, Tile<R>& t) {
+                                    uint32_t l, Tile<R, true>& t) {
   const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
   const uint32_t lg = l >> 4;
 #pragma unroll
-  for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
+  for (int kk = 0; kk < Tile<R, true>::NKK; ++kk) {
+    if (4 * kk + lg < R / 8)
+      t.zc[kk] = *reinterpret_cast<const uint32_t*>(base + (l * 4u + kk * 256u));
+    else
+      t.zc[kk] = 0u;
+  }
+  t.sz = *reinterpret_cast<const uint4*>(base + (8u * R + lg * 16u));
+}
+template <int R, bool JOINT>
+__device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
+                                    uint32_t l, Tile<R, false>& t) {
+  const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
+  const uint32_t lg = l >> 4;
+#pragma unroll
+  for (int kk = 0; kk < Tile<R, false>::NKK; ++kk) {
     if (4 * kk + lg < R / 8)
       t.zk[kk] = *reinterpret_cast<const uint4*>(base + (l * 16u + kk * 1024u));
     else
@@ -242,7 +266,7 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
   if (!JOINT) {
     const char* vb = base + stream_bytes;
 #pragma unroll
-    for (int nb = 0; nb < Tile<R>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (l * 8u + nb * 512u));
+    for (int nb = 0; nb < Tile<R, false>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (l * 8u + nb * 512u));
   }
 }
 // One ordinal per lane: lane (row lg = l/16, quad position l%4) holds the ordinal of token 4*lg + l%4, so the four
@@ -261,8 +285,10 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // blocks are not free here: each needs a whole compute unit's LDS before it can start and exit.)  Blocks of the kv-heads
 // of one item run side by side and sweep the same pages; with eight kv-heads, block id % 8 = head, so all splits of a
 // (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
-template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET>
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
+  static_assert(!Q4 || JOINT, "4-bit latents are built for the single-stream layout");
+  typedef Tile<R, Q4> TileT;
   extern __shared__ float smem[];
   const int item_q = blockIdx.x / P.Hkv, h = blockIdx.x % P.Hkv;
   if (item_q >= P.items[0]) return;
@@ -313,14 +339,15 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   }
   const float cinit = -(mref + kExpBias);
   const float cshift = table_shift_base(mref);
-  if (tid < 16) xbuf[tid] = cshift;
+  if (tid < 16) { xbuf[tid] = cshift; xbuf[16 + tid] = 0.f; }
+  float* zbuf = xbuf + 16;                                // [16] 4-bit latents: sum of weight x zero-point term per head
   // B operand of the score product: (W_uK q) for head g = ln, latent chunk 4*kk + lg
   // (stored as bf16 hi + lo parts, so that the latent part of the logit keeps fp32-like accuracy)
-  bf16x8 qb[Tile<R>::NKK], qbl[Tile<R>::NKK];
+  bf16x8 qb[TileT::NKK], qbl[TileT::NKK];
   {
     const uint16_t* qrow = P.qlat + ((int64_t)b * P.Hq + (int64_t)h * G + (ghead ? ln : 0)) * R;
 #pragma unroll
-    for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
+    for (int kk = 0; kk < TileT::NKK; ++kk) {
       uint4 v = make_uint4(0, 0, 0, 0), vl = v;
       if (ghead && 4 * kk + lg < R / 8) {
         v = *reinterpret_cast<const uint4*>(qrow + (4 * kk + lg) * 8);
@@ -330,6 +357,23 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       qbl[kk] = __builtin_bit_cast(bf16x8, vl);
     }
   }
+  // 4-bit latents: a value reads back as scale * code + zero; the operand holds 16 + code (exact in bf16), so
+  //   q . z = scale * (q . (16 + code)) + (zero - 16 * scale) * sum(q)        and
+  //   sum_t p_t z_t = sum_t (p_t scale_t) (16 + code_t) + (sum_t p_t (zero_t - 16 scale_t)) * (1, ..., 1)
+  // qsum = sum over the latent dims of this lane's query head
+  float qsum = 0.f;
+  if (Q4) {
+#pragma unroll
+    for (int kk = 0; kk < TileT::NKK; ++kk) {
+      const uint4 a = __builtin_bit_cast(uint4, qb[kk]), c = __builtin_bit_cast(uint4, qbl[kk]);
+      const uint32_t u[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qsum += bf16lo(u[e]) + bf16hi(u[e]);
+    }
+    qsum += __shfl_xor(qsum, 16);
+    qsum += __shfl_xor(qsum, 32);
+  }
+  float zacc = 0.f;
   // uniform bases of this (sequence, kv-head): score table row block, latent and ordinal pools at head h
   const char* sref_bh = reinterpret_cast<const char*>(P.sref + bh * P.n_ref_max * Gp);
   const char* lat_h = reinterpret_cast<const char*>(P.latent + (int64_t)h * P.latent_head_stride);
@@ -341,9 +385,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const uint32_t id_hi = (uint32_t)(n_cov - 1);
   __syncthreads();
 
-  float4v acc[Tile<R>::NB];
+  float4v acc[TileT::NB];
 #pragma unroll
-  for (int nb = 0; nb < Tile<R>::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+  for (int nb = 0; nb < TileT::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
   float lsum = 0.f;
   // lanes that hold no query head start their accumulator at -inf, so their weights are exactly 0
   const float cstart = ghead ? cinit : -INFINITY;
@@ -405,21 +449,48 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   };
   // FULL: all 16 tokens of the page take part (no masking code at all); otherwise bit t of `mask` says whether
   // token t does (a valid token of the sequence and, in subset attention, a selected one).
-  auto compute = [&](auto full_tag, Tile<R>& t, const int id, const float4& srv, const uint32_t mask) {
+  auto compute = [&](auto full_tag, TileT& t, const int id, const float4& srv, const uint32_t mask) {
     constexpr bool FULL = decltype(full_tag)::value;
     float sr[4];
     quad_transpose(srv, sr);
-    float4v d = {cstart, cstart, cstart, cstart};
+    uint4 zk[TileT::NKK];                      // the scores operand as bf16
+    float sc[4] = {1.f, 1.f, 1.f, 1.f}, zf[4] = {0.f, 0.f, 0.f, 0.f};   // 4-bit: scale, zero - 16 * scale per token
+    if constexpr (Q4) {
 #pragma unroll
-    for (int kk = 0; kk < Tile<R>::NKK; ++kk) {
-      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qbl[kk], d, 0, 0, 0);
-      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.zk[kk]), qb[kk], d, 0, 0, 0);
+      for (int kk = 0; kk < TileT::NKK; ++kk) {
+        const uint32_t wd = t.zc[kk];            // bf16 (16 + code) = 0x4180 | code << 3
+        zk[kk].x = ((wd << 3) & 0x00780078u) | 0x41804180u;
+        zk[kk].y = ((wd >> 1) & 0x00780078u) | 0x41804180u;
+        zk[kk].z = ((wd >> 5) & 0x00780078u) | 0x41804180u;
+        zk[kk].w = ((wd >> 9) & 0x00780078u) | 0x41804180u;
+      }
+      sc[0] = bf16lo(t.sz.x); sc[1] = bf16hi(t.sz.x); sc[2] = bf16lo(t.sz.y); sc[3] = bf16hi(t.sz.y);
+      zf[0] = bf16lo(t.sz.z) - 16.f * sc[0]; zf[1] = bf16hi(t.sz.z) - 16.f * sc[1];
+      zf[2] = bf16lo(t.sz.w) - 16.f * sc[2]; zf[3] = bf16hi(t.sz.w) - 16.f * sc[3];
+      if (!FULL) {                               // records of tokens that do not take part may hold anything
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool on = (mask >> (4 * lg + e)) & 1u;
+          sc[e] = on ? sc[e] : 0.f;
+          zf[e] = on ? zf[e] : 0.f;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < TileT::NKK; ++kk) zk[kk] = t.zk[kk];
+    }
+    const float d0 = Q4 ? 0.f : cstart;
+    float4v d = {d0, d0, d0, d0};
+#pragma unroll
+    for (int kk = 0; kk < TileT::NKK; ++kk) {
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, zk[kk]), qbl[kk], d, 0, 0, 0);
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, zk[kk]), qb[kk], d, 0, 0, 0);
     }
     check_pending();
     float p[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float x = d[e] + sr[e];
+      float x = Q4 ? cstart + (sr[e] + (sc[e] * d[e] + zf[e] * qsum)) : d[e] + sr[e];
       if (!FULL) x = ((mask >> (4 * lg + e)) & 1u) ? x : -INFINITY;   // select, not arithmetic: garbage may be NaN
       p[e] = __builtin_amdgcn_exp2f(x);
       lsum += p[e];
@@ -448,21 +519,28 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
       pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
     }
+    if constexpr (Q4) {       // the value product takes p * scale; the zero-point term is a scalar per head
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        zacc += p[e] * zf[e];
+        p[e] *= sc[e];
+      }
+    }
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
     pk.y = pack_bf16(p[2], p[3]);
     const short4v pa = __builtin_bit_cast(short4v, pk);
     if (JOINT) {
 #pragma unroll
-      for (int kk = 0; kk < Tile<R>::NKK; ++kk)
-        if (4 * kk + lg < R / 8) *reinterpret_cast<uint4*>(tr + ln * TRP + (4 * kk + lg) * 8) = t.zk[kk];
+      for (int kk = 0; kk < TileT::NKK; ++kk)
+        if (4 * kk + lg < R / 8) *reinterpret_cast<uint4*>(tr + ln * TRP + (4 * kk + lg) * 8) = zk[kk];
       __builtin_amdgcn_wave_barrier();
       // LDS transpose load (ds_read_b64_tr_b16; behaviour checked on the hardware): within each 16-lane group
       // lane j supplies the address of a 4-element chunk and lane i receives element i%4 of the chunks
       // supplied by lanes i/4, i/4+4, i/4+8, i/4+12.  Lane j of group lg points at token 4*lg + j/4, columns
       // 16*nb + 4*(j%4)..+3, so lane i ends up with tokens 4*lg..4*lg+3 of column 16*nb + i: the value operand.
 #pragma unroll
-      for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+      for (int nb = 0; nb < TileT::NB; ++nb) {
         typedef short s4 __attribute__((ext_vector_type(4)));
         const uint16_t* src = tr + (4 * lg + (ln >> 2)) * TRP + nb * 16 + (ln & 3) * 4;
         const s4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s4 __attribute__((address_space(3)))*)src);
@@ -475,13 +553,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       const uint32_t keep_x = ((m4 & 1u) ? 0x0000ffffu : 0u) | ((m4 & 2u) ? 0xffff0000u : 0u);
       const uint32_t keep_y = ((m4 & 4u) ? 0x0000ffffu : 0u) | ((m4 & 8u) ? 0xffff0000u : 0u);
 #pragma unroll
-      for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+      for (int nb = 0; nb < TileT::NB; ++nb) {
         t.zv[nb].x &= keep_x;
         t.zv[nb].y &= keep_y;
       }
     }
 #pragma unroll
-    for (int nb = 0; nb < Tile<R>::NB; ++nb) {
+    for (int nb = 0; nb < TileT::NB; ++nb) {
       acc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, __builtin_bit_cast(short4v, t.zv[nb]), acc[nb], 0, 0, 0);
     }
   };
@@ -553,7 +631,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       if (l == 0) v = atomicAdd(pgctr, (uint32_t)ST);
       return (int)__builtin_amdgcn_readfirstlane(v);
     };
-    Tile<R> t[ST];
+    TileT t[ST];
     int id[ST];
     float4 sr[ST];
     int pg[ST];          // pg[k % ST] = pool page of the wave's k-th page, kept LI+1 pages ahead
@@ -597,8 +675,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
   if (l < 16) atomicAdd(&lbuf[l], lsum);
+  if (Q4) {
+    zacc += __shfl_xor(zacc, 16);
+    zacc += __shfl_xor(zacc, 32);
+    if (l < 16) atomicAdd(&zbuf[l], zacc);
+  }
 #pragma unroll
-  for (int nb = 0; nb < Tile<R>::NB; ++nb)
+  for (int nb = 0; nb < TileT::NB; ++nb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int g = 4 * lg + i;
@@ -608,7 +691,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const int64_t part = bh * P.S + s;
   if (tid < Gp) P.lpart[part * Gp + tid] = lbuf[tid];
   if (tid == 0) P.wflag[part] = ovf[0] != 0u;
-  for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i];
+  for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i] + (Q4 ? zbuf[i / R] : 0.f);
   // the table leaves the block as floats, normally still in the per-entry units of table_shift()
   float* wp = P.wpart + part * P.n_ref_max * Gp;
   const uint32_t n_ovf = ovf[0];
@@ -1022,15 +1105,15 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT, bool SUBSET>
+template <int R, int NW, bool JOINT, bool SUBSET, bool Q4>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
-  constexpr int lat_loads = NKK + (JOINT ? 0 : NB);       // latent loads per page
-  constexpr int tile_regs = 4 * NKK + (JOINT ? 0 : 2 * NB);
+  constexpr int lat_loads = Q4 ? NKK + 1 : NKK + (JOINT ? 0 : NB);       // latent loads per page
+  constexpr int tile_regs = Q4 ? NKK + 4 : 4 * NKK + (JOINT ? 0 : 2 * NB);
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
-  constexpr int transient = JOINT ? 2 * NB : 0;      // JOINT builds its value operand per page in extra registers
+  constexpr int transient = (JOINT ? 2 * NB : 0) + (Q4 ? 4 * NKK + 40 : 0);   // operands built per page in extra registers
   constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6);
   // loads outstanding at once: (2LG+1) ordinals + (LG+1) pages of latents + LG pages of 4 score gathers (+ the page
   // vector); the hardware counter has 6 bits
@@ -1039,26 +1122,26 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 
-template <int NW, bool JOINT, bool SUBSET>
+template <int NW, bool JOINT, bool SUBSET, bool Q4 = false>
 static hipError_t dispatch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
   switch (P.R) {
-    case 16: return launch_stream<16, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 32: return launch_stream<32, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 48: return launch_stream<48, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 64: return launch_stream<64, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 80: return launch_stream<80, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 96: return launch_stream<96, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 112: return launch_stream<112, NW, JOINT, SUBSET>(P, grid, lds, st);
-    case 128: return launch_stream<128, NW, JOINT, SUBSET>(P, grid, lds, st);
+    case 16: return launch_stream<16, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 32: return launch_stream<32, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 48: return launch_stream<48, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 64: return launch_stream<64, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 80: return launch_stream<80, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 96: return launch_stream<96, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 112: return launch_stream<112, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
+    case 128: return launch_stream<128, NW, JOINT, SUBSET, Q4>(P, grid, lds, st);
   }
   return hipErrorInvalidValue;
 }
@@ -1090,7 +1173,10 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
   timing_mark(K_REF_SCORES, st);
   dim3 gs(n_items > 0 ? n_items * P.Hkv : 1);
   if (nw != 8) return hipErrorInvalidValue;
-  if (P.sel_pages)
+  if (P.q4) {
+    if (!P.joint) return hipErrorInvalidValue;
+    e = P.sel_pages ? dispatch_stream<8, true, true, true>(P, gs, lds, st) : dispatch_stream<8, true, false, true>(P, gs, lds, st);
+  } else if (P.sel_pages)
     e = P.joint ? dispatch_stream<8, true, true>(P, gs, lds, st) : dispatch_stream<8, false, true>(P, gs, lds, st);
   else
     e = P.joint ? dispatch_stream<8, true, false>(P, gs, lds, st) : dispatch_stream<8, false, false>(P, gs, lds, st);

@@ -24,6 +24,9 @@ int check_dims(const deltakv_dims* d) {
   if (d->rank % 16 != 0 || d->rank < 16 || d->rank > 128) return DELTAKV_E_UNSUPPORTED;
   if (d->metric != DELTAKV_METRIC_COSINE && d->metric != DELTAKV_METRIC_L2) return DELTAKV_E_INVALID_ARG;
   if (d->n_pages > (1ll << 31) - 1 || d->n_ref_slots > (1ll << 31) - 1) return DELTAKV_E_UNSUPPORTED;
+  if (d->reserved != 0) return DELTAKV_E_INVALID_ARG;
+  if (d->latent_bits != 0 && d->latent_bits != 16 && d->latent_bits != 4) return DELTAKV_E_INVALID_ARG;
+  if (d->latent_bits == 4 && d->latent_mode != DELTAKV_JOINT) return DELTAKV_E_UNSUPPORTED;
   return DELTAKV_OK;
 }
 
@@ -169,7 +172,7 @@ int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t ma
   const int64_t H = dims->n_kv_heads, P = dims->page_tokens, R = dims->rank, D = dims->head_dim;
   out->n_streams = dims->latent_mode == DELTAKV_JOINT ? 1 : 2;
   out->alignment = 256;
-  out->latent_stream_stride = P * R;
+  out->latent_stream_stride = dims->latent_bits == 4 ? 4 * R + 32 : P * R;   // 2-byte elements
   out->latent_head_stride = out->n_streams * out->latent_stream_stride;
   out->latent_page_stride = H * out->latent_head_stride;
   out->latent_pool_bytes = dims->n_pages * out->latent_page_stride * 2;
@@ -193,6 +196,7 @@ int deltakv_latent_block_offsets(const deltakv_dims* dims, int32_t stream, int32
   if (rc != DELTAKV_OK) return rc;
   if (!out || stream < 0 || stream > 1) return DELTAKV_E_INVALID_ARG;
   if (stream == 1 && dims->latent_mode == DELTAKV_JOINT) return DELTAKV_E_INVALID_ARG;
+  if (dims->latent_bits == 4) return DELTAKV_E_UNSUPPORTED;     // codes are not 2-byte elements
   const int P = dims->page_tokens, R = dims->rank;
   for (int tok = 0; tok < P; ++tok)
     for (int c = 0; c < R; ++c)
@@ -205,7 +209,7 @@ double deltakv_keep_ratio(const deltakv_dims* dims) {
   if (check_dims(dims) != DELTAKV_OK) return -1.0;
   const double streams = dims->latent_mode == DELTAKV_JOINT ? 1.0 : 2.0;
   const double raw = 2.0 * dims->head_dim * 2.0;
-  const double rec = streams * dims->rank * 2.0 + 4.0;
+  const double rec = streams * (dims->latent_bits == 4 ? dims->rank / 2.0 + 4.0 : dims->rank * 2.0) + 4.0;
   return (rec + (raw + 4.0) / dims->ref_stride) / raw;
 }
 
@@ -334,6 +338,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   Pm.R = R;
   Pm.stride = S;
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.q4 = dims->latent_bits == 4;
   Pm.max_seq_len = max_len;
   Pm.n_ref_max = n_ref_max;
   Pm.n_chunk_max = ceil_div(n_ref_max, kRefChunk);
@@ -532,6 +537,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.R = dims->rank;
   Pm.stride = S;
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.q4 = dims->latent_bits == 4;
   Pm.metric = dims->metric;
   Pm.NS = (int)ns;
   char* wsb = static_cast<char*>(workspace);

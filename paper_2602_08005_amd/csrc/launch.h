@@ -37,6 +37,7 @@ struct DecodeParams {
   float* lse;
   // shape
   int batch, Hkv, Hq, G, Gp, R, stride, joint;
+  int q4;                   // 4-bit token-wise latents (single stream)
   int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)
   int n_ref_max, n_chunk_max;
   int S, pages_per_split;   // split grid
@@ -77,6 +78,7 @@ struct CompressParams {
   const int32_t* len_before;
   int batch, n_new_total;
   int Hkv, R, stride, joint;
+  int q4;                           // 4-bit token-wise latents (single stream)
   int metric;                       // 0: cosine, 1: squared L2 distance (section 4.1)
   int NS;            // reference-range splits of the similarity search
   float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), |token|^2

@@ -1,0 +1,163 @@
+"""GPU parity for 4-bit token-wise latents (single-stream layout): decode attention over a cache of 4-bit records
+against the oracle's attention over the values those records read back as (max-abs <= 2e-2, relative L2 <= 1e-2),
+and the compression kernels' records against the oracle's quantiser."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+class Q4Case:
+    """Sequences compressed by the oracle into 4-bit records (JOINT latents)."""
+
+    def __init__(self, seed, lens, Hkv=2, Hq=8, r=64, s=16, n_proto=32):
+        from oracle import deltakv_oracle as O
+        from synthetic import generator as G
+        from tests.helpers import f64
+        self.lens, self.Hkv, self.Hq, self.r, self.s = list(lens), Hkv, Hq, r, s
+        self.W = G.make_projections(seed, 128, r, joint=True)
+        self.K, self.V, self.res = [], [], []
+        for b, L in enumerate(self.lens):
+            K, V, _ = G.make_kv(seed + 17 * b, max(L, 1), Hkv, 128, n_proto=n_proto)
+            self.K.append(K[:L])
+            self.V.append(V[:L])
+            self.res.append(O.compress(f64(K[:L]), f64(V[:L]), f64(self.W["w_down_k_bf16"]), f64(self.W["w_down_v_bf16"]),
+                                       s=s, mode=O.JOINT, latent_bits=4) if L else None)
+        self.q = G.make_queries(seed, len(self.lens), Hq, 128)
+
+
+def _setup(case, perm=None):
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    B = len(case.lens)
+    max_len = max(max(case.lens), 1)
+    pps, rps = -(-max_len // 16), -(-max_len // case.s)
+    n_pages, n_slots = B * pps + 5, B * rps + 5
+    page_ids = ref_slots = None
+    if perm is not None:
+        pp, rp = G.page_permutation(perm, B * pps, n_pages), G.page_permutation(perm + 1, B * rps, n_slots)
+        page_ids = [pp[b * pps:(b + 1) * pps] for b in range(B)]
+        ref_slots = [rp[b * rps:(b + 1) * rps] for b in range(B)]
+    dims = dk.make_dims(case.Hkv, case.Hq, case.r, n_pages, n_slots, ref_stride=case.s, latent_mode=dk.JOINT,
+                        latent_bits=4)
+    cache = dk.PagedCache(dims, B, 16, max_len, page_ids=page_ids, ref_slots=ref_slots)
+    cache.latent_pool.fill_(0x7FC0)            # bf16 NaN in every scale / zero point that is not written
+    cache.idx_pool.fill_(0x7FFFFFF0)
+    for b, L in enumerate(case.lens):
+        if L:
+            r = case.res[b]
+            cache.put_sequence_q4(b, r["idx"], r["q_k"], r["qs_k"], r["qz_k"], case.K[b][::case.s], case.V[b][::case.s])
+    return cache
+
+
+def _check_decode(case, cache, scale, positions=None):
+    import torch
+    from oracle import deltakv_oracle as O
+    from tests.helpers import dev_bits, out_f64, f64, check_attention
+    wuk, wuv, q = dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(case.q)
+    lse = torch.zeros((len(case.lens), case.Hq), dtype=torch.float32, device="cuda")
+    if positions is None:
+        out = cache.decode_attn(wuk, wuv, q, case.lens, scale, lse=lse)
+    else:
+        out = cache.decode_attn_subset(wuk, wuv, q, case.lens, positions, scale, lse=lse)
+    torch.cuda.synchronize()
+    assert int(cache.decode_ws[:4].view(torch.int32)[0].item()) == 0
+    got, lse = out_f64(out), lse.cpu().numpy().astype(np.float64)
+    for b, L in enumerate(case.lens):
+        if L == 0:
+            assert np.all(got[b] == 0)
+            continue
+        r = case.res[b]
+        args = (f64(case.q[b]), r["idx"], r["zq_k"], r["zq_v"], r["ref_k"], r["ref_v"], f64(case.W["w_up_k_bf16"]),
+                f64(case.W["w_up_v_bf16"]), scale)
+        want, wl = O.decode_attn_direct(*args) if positions is None else O.decode_attn_subset(*args, positions[b])
+        check_attention(got[b], want, f"seq {b}")
+        assert np.max(np.abs(lse[b] - wl)) <= 2e-2
+
+
+@pytest.mark.parametrize("r,Hkv,Hq", [(64, 2, 8), (48, 4, 28), (16, 1, 16), (128, 2, 4)])
+def test_decode_over_4bit_records_ragged(r, Hkv, Hq):
+    case = Q4Case(9100 + r, [3000, 777, 0, 1601], Hkv=Hkv, Hq=Hq, r=r)
+    _check_decode(case, _setup(case, perm=7), 1.0 / np.sqrt(128))
+
+
+def test_decode_over_4bit_records_long_sequence_and_selection():
+    case = Q4Case(9200, [36000], Hkv=1, Hq=4, r=64, n_proto=64)
+    cache = _setup(case)
+    _check_decode(case, cache, 1.0 / np.sqrt(128))
+    rng = np.random.default_rng(3)
+    _check_decode(case, cache, 1.0 / np.sqrt(128), positions=[np.sort(rng.choice(36000, 9000, replace=False))])
+
+
+def _compare_records(case, cache, b, t0, t1):
+    """GPU-written 4-bit records of tokens t0..t1-1 against the oracle's.  The codes are integers decided by fp32
+    arithmetic on latents that the two sides accumulate in different orders, so: scale and zero point equal in all
+    but a few tokens (and then within one bf16 step), codes equal in nearly all values and never more than one
+    level apart where the token's scale and zero point agree, values read back within one quantisation step."""
+    from oracle import deltakv_oracle as O
+    r = case.res[b]
+    idx, codes, sb, zb = cache.get_sequence_q4(b, t0, t1)
+    assert np.array_equal(idx, r["idx"][t0:t1])
+    want_c, want_s, want_z = r["q_k"][t0:t1], r["qs_k"][t0:t1], r["qz_k"][t0:t1]
+    same = (sb == want_s) & (zb == want_z)
+    assert same.mean() > 0.99, same.mean()
+    assert np.all(np.abs(sb.astype(np.int64) - want_s.astype(np.int64)) <= 1)
+    assert np.all(np.abs(zb.astype(np.int64) - want_z.astype(np.int64)) <= 1)
+    dc = np.abs(codes.astype(np.int64) - want_c.astype(np.int64))
+    assert np.all(dc[same] <= 1) and (dc[same] == 0).mean() > 0.99, ((dc[same] == 0).mean(), dc.max())
+    back = O.bf16_bits_to_f64(sb)[..., None] * codes + O.bf16_bits_to_f64(zb)[..., None]
+    step = O.bf16_bits_to_f64(want_s)[..., None]
+    assert np.all(np.abs(back - r["zq_k"][t0:t1]) <= 1.01 * step + 1e-6)
+    return idx, back
+
+
+@pytest.mark.parametrize("r", [64, 32, 128])
+def test_compress_writes_the_oracles_4bit_records_prefill_append_and_single_tokens(r):
+    import torch
+    import paper_2602_08005_amd as dk
+    from oracle import deltakv_oracle as O
+    from tests.helpers import dev_bits, out_f64, f64, check_attention
+    case = Q4Case(9300 + r, [2500, 1203], Hkv=2, Hq=8, r=r, n_proto=16)
+    B, max_len = 2, 2500
+    pps = -(-max_len // 16)
+    dims = dk.make_dims(2, 8, r, B * pps + 3, B * pps + 3, latent_mode=dk.JOINT, latent_bits=4)
+    cache = dk.PagedCache(dims, B, 4000, max_len)
+    cache.latent_pool.fill_(0x7FC0)
+    wk, wv = dev_bits(case.W["w_down_k_bf16"]), dev_bits(case.W["w_down_v_bf16"])
+    first = [1700, 900]                        # prefill, then a batched ragged append, then single-token appends
+    second = [2490, 1193]
+    for lo, hi in (([0, 0], first), (first, second)):
+        kn = np.concatenate([case.K[b][lo[b]:hi[b]] for b in range(B)])
+        vn = np.concatenate([case.V[b][lo[b]:hi[b]] for b in range(B)])
+        cu = np.concatenate([[0], np.cumsum([hi[b] - lo[b] for b in range(B)])]).astype(np.int32)
+        cache.compress(wk, wv, dev_bits(kn), dev_bits(vn), cu, np.asarray(lo, dtype=np.int32))
+    for step in range(10):
+        t = [second[0] + step, second[1] + step]
+        cache.compress(wk, wv, dev_bits(np.stack([case.K[b][t[b]] for b in range(B)])),
+                       dev_bits(np.stack([case.V[b][t[b]] for b in range(B)])), [0, 1, 2], t)
+    torch.cuda.synchronize()
+    backs = []
+    for b in range(B):
+        backs.append(_compare_records(case, cache, b, 0, case.lens[b]))
+    # attention over the GPU-built cache against the oracle's attention over the values ITS records read back as
+    scale = 1.0 / np.sqrt(128)
+    out = out_f64(cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(case.q),
+                                    case.lens, scale))
+    torch.cuda.synchronize()
+    for b in range(B):
+        idx, back = backs[b]
+        res = case.res[b]
+        want, _ = O.decode_attn_direct(f64(case.q[b]), idx, back, back, res["ref_k"], res["ref_v"],
+                                       f64(case.W["w_up_k_bf16"]), f64(case.W["w_up_v_bf16"]), scale)
+        check_attention(out[b], want, f"seq {b}")
+
+
+def test_4bit_latents_need_the_single_stream_layout():
+    import paper_2602_08005_amd as dk
+    from paper_2602_08005_amd import binding as B
+    with pytest.raises(dk.DeltaKVError) as e:
+        dk.paged_layout(dk.make_dims(2, 8, 64, 8, 8, latent_mode=dk.SPLIT, latent_bits=4), 1, 16, 16)
+    assert e.value.code == B.E_UNSUPPORTED
+    with pytest.raises(dk.DeltaKVError) as e:
+        dk.paged_layout(dk.make_dims(2, 8, 64, 8, 8, latent_mode=dk.JOINT, latent_bits=8), 1, 16, 16)
+    assert e.value.code == B.E_INVALID_ARG
