@@ -335,6 +335,8 @@ def main():
                          "each sequence's pages, drawn at random per layer, all 16 tokens of a drawn page")
     ap.add_argument("--select-tokens", action="store_true",
                     help="with --select: draw single tokens instead of whole pages (same number of tokens)")
+    ap.add_argument("--latent-bits", type=int, choices=[16, 4], default=16,
+                    help="decode128k: 4 = 4-bit token-wise latents (needs --mode joint)")
     ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
                     help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
@@ -376,8 +378,13 @@ def main():
     pages_per_seq, refs_per_seq = -(-L // 16), -(-L // s)
     joint = args.mode == "joint"
     n_streams = 1 if joint else 2
+    q4 = args.latent_bits == 4
+    if q4 and not joint:
+        sys.exit("bench.py: 4-bit latents are built for the single-stream layout: add --mode joint")
     dims = dk.make_dims(Hkv, Hq, r, n_pages=Bt * pages_per_seq, n_ref_slots=Bt * refs_per_seq,
-                        latent_mode=dk.JOINT if joint else dk.SPLIT)
+                        latent_mode=dk.JOINT if joint else dk.SPLIT, latent_bits=args.latent_bits)
+    rec_bytes = (r // 2 + 4 if q4 else n_streams * r * 2) + 4   # latent record (codes + bf16 scale and zero, or bf16
+                                                                # latents) + int32 ordinal, per (token, kv-head)
     t_setup = time.time()
     cache = dk.PagedCache(dims, Bt, L, L)
     W = G.make_projections(G.seed_for(3), D, r, joint=joint)
@@ -479,18 +486,20 @@ def main():
 
     # ---- roofline of the dominant kernel (the streaming pass over latents + indices)
     units = Bt * L * Hkv                                  # (token, kv-head) records per launch
-    stream_bytes = units * (n_streams * r * 2 + 4)                # bf16 latent stream(s) + int32 ordinal
-    path_bytes = units * (n_streams * r * 2 + 4 + 2 * D * 2 / s)  # + each raw reference K and V read once
+    stream_bytes = units * rec_bytes                              # latent record(s) + int32 ordinal
+    path_bytes = units * (rec_bytes + 2 * D * 2 / s)              # + each raw reference K and V read once
     if selections is not None:
         # subset attention: the selected tokens' records (the method's bytes), each raw reference still read once
         sel_units = Bt * n_pick * 16 * Hkv
-        stream_bytes = sel_units * (n_streams * r * 2 + 4)
+        stream_bytes = sel_units * rec_bytes
         path_bytes = stream_bytes + units * (2 * D * 2 / s)
     if raw is not None:
         path_bytes += Bt * args.raw * Hkv * 2 * D * 2             # raw K and V rows, read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:   # a raw segment does not touch k_stream
+    if q4:
+        pass                                                                     # no counter run recorded for this variant
+    elif (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:   # a raw segment does not touch k_stream
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
     elif (Bt, L, Hkv, Hq, r, joint) == (8, 131072, 8, 32, 64, False) and args.select == 0.25 and not args.select_tokens:
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_SELECT25
@@ -511,19 +520,24 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import deltakv_oracle as O
         f = O.bf16_bits_to_f64
-        i0, zk0, zv0 = cache.get_sequence(0, 0, L)
+        if q4:      # the values the GPU's own 4-bit records read back as (scale * code + zero)
+            i0, c0, s0, z0 = cache.get_sequence_q4(0, 0, L)
+            zkf = zvf = f(s0)[..., None] * c0 + f(z0)[..., None]
+        else:
+            i0, zk0, zv0 = cache.get_sequence(0, 0, L)
+            zkf, zvf = f(zk0), f(zv0)
         K0, V0 = host_kv0
         qh = f(qs[0][0].cpu().numpy().view(np.uint16))
         t0 = time.perf_counter()
         if raw is not None:
-            want, _ = O.decode_attn_with_raw(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+            want, _ = O.decode_attn_with_raw(qh, i0, zkf, zvf, f(K0[::s]), f(V0[::s]),
                                              f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale, f(raw[3][0]), f(raw[4][0]),
                                              positions=None if selections is None else selections[0][4])
         elif selections is None:
-            want, _ = O.decode_attn_direct(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+            want, _ = O.decode_attn_direct(qh, i0, zkf, zvf, f(K0[::s]), f(V0[::s]),
                                            f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale)
         else:
-            want, _ = O.decode_attn_subset(qh, i0, f(zk0), f(zv0), f(K0[::s]), f(V0[::s]),
+            want, _ = O.decode_attn_subset(qh, i0, zkf, zvf, f(K0[::s]), f(V0[::s]),
                                            f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), scale, selections[0][4])
         t_slice = time.perf_counter() - t0
         got = f(outs[0][0].cpu().numpy().view(np.uint16))
@@ -541,8 +555,10 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"long-context decode: batch {Bt} x {L} tokens, {NL} layers sequential, "
-                               f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents, stride {s}, 16-token pages",
-                   "latent_mode": args.mode.upper(), "keep_ratio": round(dk.keep_ratio(dims), 4),
+                               f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents"
+                               f"{' (4-bit token-wise)' if q4 else ''}, stride {s}, 16-token pages",
+                   "latent_mode": args.mode.upper(), "latent_bits": args.latent_bits,
+                   "keep_ratio": round(dk.keep_ratio(dims), 4),
                    "layers_are_copies_of_layer0": True,
                    **({} if raw is None else {"raw_segment": f"{args.raw} uncompressed tokens per sequence attended "
                                                                 "together with the cache"}),

@@ -75,7 +75,10 @@ extern "C" {
 
 /* Problem dimensions.  v1 kernels need head_dim == 128, page_tokens == 16,
  * rank a multiple of 16 in [16, 128], 1 <= n_q_heads / n_kv_heads <= 16 and
- * n_q_heads % n_kv_heads == 0; anything else returns DELTAKV_E_UNSUPPORTED. */
+ * n_q_heads % n_kv_heads == 0; anything else returns DELTAKV_E_UNSUPPORTED.
+ * latent_bits = 4 stores the latents as 4-bit codes with a bf16 scale and zero
+ * point per (token, kv-head) (section 5.3; format with the pool layout below);
+ * compress writes such records and every decode entry point reads them. */
 typedef struct {
   int32_t n_kv_heads;
   int32_t n_q_heads;

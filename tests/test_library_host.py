@@ -64,6 +64,11 @@ def test_keep_ratio_matches_record_accounting():
             assert dk.keep_ratio(d) == pytest.approx(O.record_keep_ratio(om, r, 128, s, norm_bytes=4), rel=1e-12)
     # the figures quoted for this build's two modes (index and norm included)
     assert dk.keep_ratio(dk.make_dims(8, 32, 64, 8, 8)) == pytest.approx((256 + 4 + 516 / 16) / 512)
+    for r in (16, 64, 128):                    # 4-bit token-wise latents, single-stream layout
+        d4 = dk.make_dims(8, 32, r, 8, 8, latent_mode=dk.JOINT, latent_bits=4)
+        assert dk.keep_ratio(d4) == pytest.approx(O.record_keep_ratio_4bit(O.JOINT, r, 128, 16), rel=1e-12)
+        L4 = dk.paged_layout(d4, 1, 16, 16)
+        assert L4.latent_head_stride * 2 == 8 * r + 64 and L4.latent_pool_bytes == 8 * 8 * (8 * r + 64)
 
 
 def test_bad_dims_are_rejected():
