@@ -33,6 +33,7 @@ MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_295_000_000   # JOINT: read 1.274 GB + wr
 MEASURED_STREAM_TRAFFIC_RAGGED = 1_284_000_000       # irregular paged batch (SPLIT, rank 48): 1.255 + 0.030 GB
 MEASURED_SIM_TRAFFIC_PREFILL32K = 160_700_000        # similarity kernel, one 32768-token layer: 0.152 + 0.008 GB
 MEASURED_STREAM_TRAFFIC_CFG3_SELECT25 = 647_000_000  # SPLIT, a quarter of the pages selected: 0.626 + 0.021 GB
+MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4 = 468_000_000  # JOINT, 4-bit latents: 0.447 + 0.021 GB
 
 
 def log(*a):
@@ -498,7 +499,8 @@ def main():
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
     if q4:
-        pass                                                                     # no counter run recorded for this variant
+        if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:
+            roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4
     elif (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:   # a raw segment does not touch k_stream
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
     elif (Bt, L, Hkv, Hq, r, joint) == (8, 131072, 8, 32, 64, False) and args.select == 0.25 and not args.select_tokens:
