@@ -337,7 +337,7 @@ def main():
     ap.add_argument("--select-tokens", action="store_true",
                     help="with --select: draw single tokens instead of whole pages (same number of tokens)")
     ap.add_argument("--latent-bits", type=int, choices=[16, 4], default=16,
-                    help="decode128k: 4 = 4-bit token-wise latents (needs --mode joint)")
+                    help="decode128k: 4 = 4-bit token-wise latents")
     ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
                     help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
@@ -380,12 +380,10 @@ def main():
     joint = args.mode == "joint"
     n_streams = 1 if joint else 2
     q4 = args.latent_bits == 4
-    if q4 and not joint:
-        sys.exit("bench.py: 4-bit latents are built for the single-stream layout: add --mode joint")
     dims = dk.make_dims(Hkv, Hq, r, n_pages=Bt * pages_per_seq, n_ref_slots=Bt * refs_per_seq,
                         latent_mode=dk.JOINT if joint else dk.SPLIT, latent_bits=args.latent_bits)
-    rec_bytes = (r // 2 + 4 if q4 else n_streams * r * 2) + 4   # latent record (codes + bf16 scale and zero, or bf16
-                                                                # latents) + int32 ordinal, per (token, kv-head)
+    # latent record(s) (codes + bf16 scale and zero point, or bf16 latents) + int32 ordinal, per (token, kv-head)
+    rec_bytes = n_streams * (r // 2 + 4 if q4 else r * 2) + 4
     t_setup = time.time()
     cache = dk.PagedCache(dims, Bt, L, L)
     W = G.make_projections(G.seed_for(3), D, r, joint=joint)
@@ -499,7 +497,7 @@ def main():
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
     if q4:
-        if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:
+        if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None and joint:
             roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4
     elif (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:   # a raw segment does not touch k_stream
         roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
@@ -525,6 +523,9 @@ def main():
         if q4:      # the values the GPU's own 4-bit records read back as (scale * code + zero)
             i0, c0, s0, z0 = cache.get_sequence_q4(0, 0, L)
             zkf = zvf = f(s0)[..., None] * c0 + f(z0)[..., None]
+            if not joint:
+                _, c1, s1, z1 = cache.get_sequence_q4(0, 0, L, stream=1)
+                zvf = f(s1)[..., None] * c1 + f(z1)[..., None]
         else:
             i0, zk0, zv0 = cache.get_sequence(0, 0, L)
             zkf, zvf = f(zk0), f(zv0)

@@ -106,14 +106,18 @@ typedef struct {
  *                    value (tok, c) at ((c/16)*64 + (tok/4)*16 + c%16)*4 + tok%4
  *                deltakv_latent_block_offsets returns these as a table.
  *                With latent_bits = 4 (section 5.3: token-wise 4-bit quantisation
- *                of the compressed residuals; JOINT mode only in this version,
- *                SPLIT returns DELTAKV_E_UNSUPPORTED) a (page, head) block is
- *                8*r + 64 bytes: first r/8 x P dwords of codes, the dword of
- *                (chunk c/8, tok) at byte 4*((c/8)*P + tok), the code of value c in
- *                bits [s, s+3] with s = 4*((c%8)/2) + 16*(c%2); then, for each
- *                group of four tokens, 4 bf16 scales followed by 4 bf16 zero
- *                points (16 bytes per group).  A value reads back as
- *                scale * code + zero.  Strides stay in 2-byte elements.
+ *                of the compressed residuals) a (page, head, stream) block is
+ *                8*r + 64 bytes: 8*r bytes of codes, then, for each group of
+ *                four tokens, 4 bf16 scales followed by 4 bf16 zero points (16
+ *                bytes per group).  A value reads back as scale * code + zero.
+ *                  stream 0: the dword of (chunk c/8, tok) at byte 4*((c/8)*P + tok),
+ *                    the code of value c in bits [s, s+3], s = 4*((c%8)/2) + 16*(c%2)
+ *                  stream 1 (SPLIT mode; needs rank 64 or 128, other ranks return
+ *                    DELTAKV_E_UNSUPPORTED): an 8-byte pair of dwords per (c/64,
+ *                    tok/4, c%16) at byte 8*((c/64)*64 + (tok/4)*16 + c%16); tokens
+ *                    tok%4 = 0, 1 in the first dword and 2, 3 in the second; the
+ *                    code of value c in bits [s, s+3], s = 4*((c/16)%4) + 16*(tok%2)
+ *                Strides stay in 2-byte elements.
  *   index pool   int32  [n_pages][n_kv_heads][P]   reference ordinal per token
  *   reference pool bf16 [n_kv_heads][2][n_ref_slots][head_dim]   (0 = K, 1 = V)
  *   reference inverse norms fp32 [n_kv_heads][n_ref_slots]: 1/||K||V|| of the

@@ -119,26 +119,31 @@ class PagedCache:
         return idx, out[0], out[1]
 
     # -- 4-bit latents (format stated with the pool layout in the library header) -------------------
-    def _q4_index(self, b: int, t0: int, t1: int):
+    def _q4_index(self, b: int, t0: int, t1: int, stream: int = 0):
         """2-byte element indices of the code half-words [n, H, r] (+ nibble shifts [r]) and of the scale and zero
-        point [n, H] of tokens t0..t1-1."""
+        point [n, H] of tokens t0..t1-1 in latent stream `stream` (0: scores-operand order; 1: value-operand order)."""
         d, L = self.dims, self.layout
         t = np.arange(t0, t1)
         page = self.block_tables_host[b, t // d.page_tokens].astype(np.int64)
-        base = page[:, None] * L.latent_page_stride + np.arange(d.n_kv_heads)[None, :] * L.latent_head_stride
+        base = page[:, None] * L.latent_page_stride + np.arange(d.n_kv_heads)[None, :] * L.latent_head_stride \
+            + stream * L.latent_stream_stride
         tok = (t % d.page_tokens)[:, None, None]
         c = np.arange(d.rank)[None, None, :]
-        code_el = base[:, :, None] + 2 * ((c >> 3) * d.page_tokens + tok) + (c & 1)
-        shift = 4 * ((np.arange(d.rank) & 7) >> 1)
+        if stream == 0:
+            code_el = base[:, :, None] + 2 * ((c >> 3) * d.page_tokens + tok) + (c & 1)
+            shift = 4 * ((np.arange(d.rank) & 7) >> 1)
+        else:
+            code_el = base[:, :, None] + 4 * ((c >> 6) * 64 + (tok >> 2) * 16 + (c & 15)) + 2 * ((tok & 3) >> 1) + (tok & 1)
+            shift = 4 * ((np.arange(d.rank) >> 4) & 3)
         tk = (t % d.page_tokens)[:, None]
         sc_el = base + 4 * d.rank + (tk >> 2) * 8 + (tk & 3)
         return code_el, shift, sc_el, sc_el + 4
 
-    def get_sequence_q4(self, b: int, t0: int, t1: int):
-        """Token-major copies of the 4-bit records of tokens t0..t1-1: idx [n, H], codes uint8 [n, H, r], bf16 bits
-        of scale and zero point [n, H]."""
+    def get_sequence_q4(self, b: int, t0: int, t1: int, stream: int = 0):
+        """Token-major copies of the 4-bit records of tokens t0..t1-1 in one latent stream: idx [n, H], codes uint8
+        [n, H, r], bf16 bits of scale and zero point [n, H]."""
         torch = self.torch
-        code_el, shift, sc_el, zp_el = self._q4_index(b, t0, t1)
+        code_el, shift, sc_el, zp_el = self._q4_index(b, t0, t1, stream)
         ii = torch.from_numpy(self._idx_index(b, t0, t1).ravel()).to(self.device)
         idx = self.idx_pool[ii].cpu().numpy().reshape(t1 - t0, self.dims.n_kv_heads)
         take = lambda el: self.latent_pool[torch.from_numpy(el.ravel()).to(self.device)].cpu().numpy().view(np.uint16) \
@@ -146,22 +151,25 @@ class PagedCache:
         codes = ((take(code_el) >> shift[None, None, :].astype(np.uint16)) & 0xF).astype(np.uint8)
         return idx, codes, take(sc_el), take(zp_el)
 
-    def put_sequence_q4(self, b: int, idx, codes, scale_bits, zero_bits, ref_k_bits, ref_v_bits, t0: int = 0):
-        """Copy token-major 4-bit records (tokens t0..t0+n-1, whole pages are rebuilt from the arrays given, so t0
-        and n should cover whole pages except at the sequence's end) and the references into the pools."""
+    def put_sequence_q4(self, b: int, idx, codes, scale_bits, zero_bits, ref_k_bits, ref_v_bits, t0: int = 0,
+                        codes_v=None, scale_bits_v=None, zero_bits_v=None):
+        """Copy token-major 4-bit records (tokens t0..t0+n-1; t0 and n should cover whole pages except at the
+        sequence's end: the half-words that hold the codes are rebuilt from the arrays given) and the references into
+        the pools.  The *_v arrays are the value stream of the two-stream layout."""
         torch = self.torch
         n = idx.shape[0]
-        code_el, shift, sc_el, zp_el = self._q4_index(b, t0, t0 + n)
-        # assemble the half-words: four codes each
-        flat = code_el.ravel()
-        vals = (codes.astype(np.uint16) << shift[None, None, :].astype(np.uint16)).ravel()
-        uniq, inv = np.unique(flat, return_inverse=True)
-        words = np.zeros(len(uniq), dtype=np.uint16)
-        np.bitwise_or.at(words, inv, vals)
-        self.latent_pool[torch.from_numpy(uniq).to(self.device)] = torch.from_numpy(words.view(np.int16)).to(self.device)
-        for el, bits in ((sc_el, scale_bits), (zp_el, zero_bits)):
-            self.latent_pool[torch.from_numpy(el.ravel()).to(self.device)] = \
-                torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.int16).ravel()).to(self.device)
+        streams = [(codes, scale_bits, zero_bits)] + ([(codes_v, scale_bits_v, zero_bits_v)] if codes_v is not None else [])
+        for stream, (cd, sb, zb) in enumerate(streams):
+            code_el, shift, sc_el, zp_el = self._q4_index(b, t0, t0 + n, stream)
+            flat = code_el.ravel()
+            vals = (cd.astype(np.uint16) << shift[None, None, :].astype(np.uint16)).ravel()
+            uniq, inv = np.unique(flat, return_inverse=True)
+            words = np.zeros(len(uniq), dtype=np.uint16)
+            np.bitwise_or.at(words, inv, vals)
+            self.latent_pool[torch.from_numpy(uniq).to(self.device)] = torch.from_numpy(words.view(np.int16)).to(self.device)
+            for el, bits in ((sc_el, sb), (zp_el, zb)):
+                self.latent_pool[torch.from_numpy(el.ravel()).to(self.device)] = \
+                    torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.int16).ravel()).to(self.device)
         self.put_sequence(b, idx, None, None, ref_k_bits, ref_v_bits, t0=t0)
 
     def get_refs(self, b: int, n_ref: int):

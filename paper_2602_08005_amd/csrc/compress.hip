@@ -679,6 +679,7 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
       uint16_t* latv = lat + P.latent_stream_stride;
       const int t0 = lp * kPage + 4 * lg;                    // position of this lane's first token
       const bool all4 = t0 >= lb && t0 + 3 < la;
+      float4v q4v[NB];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         float4v acc = {0.f, 0.f, 0.f, 0.f};
@@ -688,6 +689,8 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(res[1][kk][0], wv, acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(res[1][kk][1], wv, acc, 0, 0, 0);
         }
+        q4v[nb] = acc;
+        if (P.q4) continue;
         uint16_t* dst = latv + (nb * 64 + l) * 4;
         if (all4) {
           uint2 o;
@@ -698,6 +701,53 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             if (t0 + i >= lb && t0 + i < la) dst[i] = (uint16_t)f32_to_bf16_bits(acc[i]);
+        }
+      }
+      if (P.q4) {
+        // Value stream, 4-bit: token 4 lg + i has its values in the 16 lanes (ln = 0..15, this lg) x NB registers.
+        // The lane's codes for columns ln + 16 nb of its four tokens fill its own dword pair (.x: first and second
+        // token at bits 4 (nb % 4) and 16 + 4 (nb % 4), .y: third and fourth) of column group nb / 4; tokens that
+        // were written by an earlier call share those dwords and keep their bits.
+        Q4Params qv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float mn = INFINITY, mx = -INFINITY;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) { mn = fminf(mn, q4v[nb][i]); mx = fmaxf(mx, q4v[nb][i]); }
+#pragma unroll
+          for (int o = 1; o < 16; o <<= 1) { mn = fminf(mn, __shfl_xor(mn, o)); mx = fmaxf(mx, __shfl_xor(mx, o)); }
+          qv[i] = q4_params(mn, mx);
+        }
+        bool fresh[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fresh[i] = t0 + i >= lb && t0 + i < la;
+        const uint32_t keep_x = (fresh[0] ? 0u : 0x0000ffffu) | (fresh[1] ? 0u : 0xffff0000u);
+        const uint32_t keep_y = (fresh[2] ? 0u : 0x0000ffffu) | (fresh[3] ? 0u : 0xffff0000u);
+        char* vblk = reinterpret_cast<char*>(latv);
+#pragma unroll
+        for (int q = 0; q < (NB + 3) / 4; ++q) {
+          uint2 w = make_uint2(0u, 0u);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int nb = 4 * q + j;
+            if (nb < NB) {
+              w.x |= (q4_code(q4v[nb][0], qv[0]) << (4 * j)) | (q4_code(q4v[nb][1], qv[1]) << (16 + 4 * j));
+              w.y |= (q4_code(q4v[nb][2], qv[2]) << (4 * j)) | (q4_code(q4v[nb][3], qv[3]) << (16 + 4 * j));
+            }
+          }
+          uint2* dst = reinterpret_cast<uint2*>(vblk + (q * 64 + l) * 8);
+          if (!all4) {
+            const uint2 old = *dst;
+            w.x = (w.x & ~keep_x) | (old.x & keep_x);
+            w.y = (w.y & ~keep_y) | (old.y & keep_y);
+          }
+          if (fresh[0] || fresh[1] || fresh[2] || fresh[3]) *dst = w;
+        }
+        if (ln == 0) {
+          uint16_t* sz = reinterpret_cast<uint16_t*>(vblk + 8 * R + lg * 16);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (fresh[i]) { sz[i] = (uint16_t)qv[i].scale_bits; sz[4 + i] = (uint16_t)qv[i].zero_bits; }
         }
       }
     }
@@ -838,8 +888,8 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
   __shared__ int eidx[4];
   __shared__ float resid[2][kHeadDim];
   __shared__ float zpart[2][256];
-  __shared__ float zfin[128];           // 4-bit latents: the token's final latent
-  __shared__ uint32_t qcode[128];
+  __shared__ float zfin[256];           // 4-bit latents: the token's final latent(s)
+  __shared__ uint32_t qcode[256];
   // projection: thread (stream, part, c) sums its share of the 128 dims; R <= 128, 256 threads.  Its W_down column
   // does not depend on the retrieval, so all of its loads are issued here, under the latency of everything below.
   constexpr int PARTS = 128 / R >= 1 ? 128 / R : 1;        // threads per (stream, c): 128 / R, at least 1
@@ -955,6 +1005,8 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
         if (P.q4) zfin[c] = z + zv;
         else lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z + zv);
       }
+    } else if (P.q4) {
+      zfin[st * 128 + c] = z;
     } else if (st == 0) {
       lat[((c >> 3) * kPage + tok) * 8 + (c & 7)] = (uint16_t)f32_to_bf16_bits(z);
     } else {
@@ -979,6 +1031,28 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
       uint16_t* sz = reinterpret_cast<uint16_t*>(blk + 8 * R + (tok >> 2) * 16 + (tok & 3) * 2);
       sz[0] = (uint16_t)qp.scale_bits;
       sz[4] = (uint16_t)qp.zero_bits;
+    }
+    if (!P.joint) {           // value stream: columns c, c+16, c+32, c+48 of the token share a dword with one neighbour token
+      float mnv = INFINITY, mxv = -INFINITY;
+      for (int c = 0; c < R; ++c) { mnv = fminf(mnv, zfin[128 + c]); mxv = fmaxf(mxv, zfin[128 + c]); }
+      const Q4Params qv = q4_params(mnv, mxv);
+      if (tid < R) qcode[128 + tid] = q4_code(zfin[128 + tid], qv);
+      __syncthreads();
+      char* vblk = blk + P.latent_stream_stride * 2;
+      if (tid < R / 4) {
+        const int q = tid >> 4, c15 = tid & 15;
+        uint32_t nib = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) nib |= qcode[128 + 64 * q + 16 * j + c15] << (4 * j);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(vblk + (q * 64 + (tok >> 2) * 16 + c15) * 8) + ((tok & 3) >> 1);
+        const int sh = 16 * (tok & 1);
+        *dst = (*dst & ~(0xffffu << sh)) | (nib << sh);
+      }
+      if (tid == 0) {
+        uint16_t* sz = reinterpret_cast<uint16_t*>(vblk + 8 * R + (tok >> 2) * 16 + (tok & 3) * 2);
+        sz[0] = (uint16_t)qv.scale_bits;
+        sz[4] = (uint16_t)qv.zero_bits;
+      }
     }
   }
   if (tid == 0) P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok] = ord;

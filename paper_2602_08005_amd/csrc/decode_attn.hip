@@ -230,9 +230,14 @@ template <int R>
 struct Tile<R, true> {
   static constexpr int NKK = (R + 31) / 32;
   static constexpr int NB = R / 16;
+  static constexpr int NQ = (NB + 3) / 4;
   uint32_t zc[NKK];   // codes of token l%16, latent chunk l/16 + 4*kk (value c%8 at bits 4*((c%8)/2) + 16*(c%2))
   uint4 sz;           // scales of tokens 4*(l/16)..+3 (x, y), their zero points (z, w), bf16 pairs
   uint2 zv[NB];       // value operand, built on chip
+  // two-stream layout only: codes of the value stream, columns l%16 + 16*nb of tokens 4*(l/16)..+3 (.x: first and
+  // second token at bits 4*(nb%4) and 16 + 4*(nb%4), .y: third and fourth), and that stream's scales / zero points
+  uint2 zvc[NQ];
+  uint4 szv;
 };
 
 // Loads of the streaming loop take their address as (uniform 64-bit base of the page) + (32-bit offset of the
@@ -250,6 +255,12 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
       t.zc[kk] = 0u;
   }
   t.sz = *reinterpret_cast<const uint4*>(base + (8u * R + lg * 16u));
+  if (!JOINT) {
+    const char* vb = base + stream_bytes;
+#pragma unroll
+    for (int q = 0; q < Tile<R, true>::NQ; ++q) t.zvc[q] = *reinterpret_cast<const uint2*>(vb + (l * 8u + q * 512u));
+    t.szv = *reinterpret_cast<const uint4*>(vb + (8u * R + lg * 16u));
+  }
 }
 template <int R, bool JOINT>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
@@ -287,7 +298,7 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
 template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
-  static_assert(!Q4 || JOINT, "4-bit latents are built for the single-stream layout");
+  static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
   extern __shared__ float smem[];
   const int item_q = blockIdx.x / P.Hkv, h = blockIdx.x % P.Hkv;
@@ -519,11 +530,29 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
       pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
     }
-    if constexpr (Q4) {       // the value product takes p * scale; the zero-point term is a scalar per head
+    if constexpr (Q4 && JOINT) {   // the value product takes p * scale; the zero-point term is a scalar per head
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         zacc += p[e] * zf[e];
         p[e] *= sc[e];
+      }
+    }
+    if constexpr (Q4 && !JOINT) {  // the same with the value stream's own scales and zero points
+      float sv[4] = {bf16lo(t.szv.x), bf16hi(t.szv.x), bf16lo(t.szv.y), bf16hi(t.szv.y)};
+      float zv0[4] = {bf16lo(t.szv.z), bf16hi(t.szv.z), bf16lo(t.szv.w), bf16hi(t.szv.w)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool on = FULL || ((mask >> (4 * lg + e)) & 1u);
+        const float sve = on ? sv[e] : 0.f, zve = on ? zv0[e] - 16.f * sv[e] : 0.f;
+        zacc += p[e] * zve;
+        p[e] *= sve;
+      }
+#pragma unroll
+      for (int nb = 0; nb < TileT::NB; ++nb) {
+        const uint2 wv = t.zvc[nb >> 2];
+        const int j = nb & 3;                       // bf16 (16 + code) = 0x4180 | code << 3
+        t.zv[nb].x = ((j == 0 ? wv.x << 3 : wv.x >> (4 * j - 3)) & 0x00780078u) | 0x41804180u;
+        t.zv[nb].y = ((j == 0 ? wv.y << 3 : wv.y >> (4 * j - 3)) & 0x00780078u) | 0x41804180u;
       }
     }
     uint2 pk;
@@ -1110,10 +1139,12 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
-  constexpr int lat_loads = Q4 ? NKK + 1 : NKK + (JOINT ? 0 : NB);       // latent loads per page
-  constexpr int tile_regs = Q4 ? NKK + 4 : 4 * NKK + (JOINT ? 0 : 2 * NB);
+  constexpr int NQ = (NB + 3) / 4;
+  constexpr int lat_loads = Q4 ? NKK + 1 + (JOINT ? 0 : NQ + 1) : NKK + (JOINT ? 0 : NB);       // latent loads per page
+  constexpr int tile_regs = Q4 ? NKK + 4 + (JOINT ? 0 : 2 * NQ + 4) : 4 * NKK + (JOINT ? 0 : 2 * NB);
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
-  constexpr int transient = (JOINT ? 2 * NB : 0) + (Q4 ? 4 * NKK + 40 : 0);   // operands built per page in extra registers
+  // operands built per page in extra registers (the constants are fitted to what the compiler keeps without spilling)
+  constexpr int transient = (JOINT || Q4 ? 2 * NB : 0) + (Q4 ? 4 * NKK + (JOINT ? 40 : 16) : 0);
   constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6);
   // loads outstanding at once: (2LG+1) ordinals + (LG+1) pages of latents + LG pages of 4 score gathers (+ the page
   // vector); the hardware counter has 6 bits
@@ -1173,9 +1204,15 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
   timing_mark(K_REF_SCORES, st);
   dim3 gs(n_items > 0 ? n_items * P.Hkv : 1);
   if (nw != 8) return hipErrorInvalidValue;
-  if (P.q4) {
-    if (!P.joint) return hipErrorInvalidValue;
+  if (P.q4 && P.joint) {
     e = P.sel_pages ? dispatch_stream<8, true, true, true>(P, gs, lds, st) : dispatch_stream<8, true, false, true>(P, gs, lds, st);
+  } else if (P.q4) {        // two streams: ranks 64 and 128
+    if (P.R == 64)
+      e = P.sel_pages ? launch_stream<64, 8, false, true, true>(P, gs, lds, st) : launch_stream<64, 8, false, false, true>(P, gs, lds, st);
+    else if (P.R == 128)
+      e = P.sel_pages ? launch_stream<128, 8, false, true, true>(P, gs, lds, st) : launch_stream<128, 8, false, false, true>(P, gs, lds, st);
+    else
+      return hipErrorInvalidValue;
   } else if (P.sel_pages)
     e = P.joint ? dispatch_stream<8, true, true>(P, gs, lds, st) : dispatch_stream<8, false, true>(P, gs, lds, st);
   else

@@ -26,7 +26,7 @@ int check_dims(const deltakv_dims* d) {
   if (d->n_pages > (1ll << 31) - 1 || d->n_ref_slots > (1ll << 31) - 1) return DELTAKV_E_UNSUPPORTED;
   if (d->reserved != 0) return DELTAKV_E_INVALID_ARG;
   if (d->latent_bits != 0 && d->latent_bits != 16 && d->latent_bits != 4) return DELTAKV_E_INVALID_ARG;
-  if (d->latent_bits == 4 && d->latent_mode != DELTAKV_JOINT) return DELTAKV_E_UNSUPPORTED;
+  if (d->latent_bits == 4 && d->latent_mode != DELTAKV_JOINT && d->rank % 64 != 0) return DELTAKV_E_UNSUPPORTED;
   return DELTAKV_OK;
 }
 

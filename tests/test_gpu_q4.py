@@ -8,21 +8,21 @@ pytestmark = pytest.mark.gpu
 
 
 class Q4Case:
-    """Sequences compressed by the oracle into 4-bit records (JOINT latents)."""
+    """Sequences compressed by the oracle into 4-bit records (JOINT latents, or the two streams of SPLIT)."""
 
-    def __init__(self, seed, lens, Hkv=2, Hq=8, r=64, s=16, n_proto=32):
+    def __init__(self, seed, lens, Hkv=2, Hq=8, r=64, s=16, n_proto=32, joint=True):
         from oracle import deltakv_oracle as O
         from synthetic import generator as G
         from tests.helpers import f64
-        self.lens, self.Hkv, self.Hq, self.r, self.s = list(lens), Hkv, Hq, r, s
-        self.W = G.make_projections(seed, 128, r, joint=True)
+        self.lens, self.Hkv, self.Hq, self.r, self.s, self.joint = list(lens), Hkv, Hq, r, s, joint
+        self.W = G.make_projections(seed, 128, r, joint=joint)
         self.K, self.V, self.res = [], [], []
         for b, L in enumerate(self.lens):
             K, V, _ = G.make_kv(seed + 17 * b, max(L, 1), Hkv, 128, n_proto=n_proto)
             self.K.append(K[:L])
             self.V.append(V[:L])
             self.res.append(O.compress(f64(K[:L]), f64(V[:L]), f64(self.W["w_down_k_bf16"]), f64(self.W["w_down_v_bf16"]),
-                                       s=s, mode=O.JOINT, latent_bits=4) if L else None)
+                                       s=s, mode=O.JOINT if joint else O.SPLIT, latent_bits=4) if L else None)
         self.q = G.make_queries(seed, len(self.lens), Hq, 128)
 
 
@@ -38,15 +38,17 @@ def _setup(case, perm=None):
         pp, rp = G.page_permutation(perm, B * pps, n_pages), G.page_permutation(perm + 1, B * rps, n_slots)
         page_ids = [pp[b * pps:(b + 1) * pps] for b in range(B)]
         ref_slots = [rp[b * rps:(b + 1) * rps] for b in range(B)]
-    dims = dk.make_dims(case.Hkv, case.Hq, case.r, n_pages, n_slots, ref_stride=case.s, latent_mode=dk.JOINT,
-                        latent_bits=4)
+    dims = dk.make_dims(case.Hkv, case.Hq, case.r, n_pages, n_slots, ref_stride=case.s,
+                        latent_mode=dk.JOINT if case.joint else dk.SPLIT, latent_bits=4)
     cache = dk.PagedCache(dims, B, 16, max_len, page_ids=page_ids, ref_slots=ref_slots)
     cache.latent_pool.fill_(0x7FC0)            # bf16 NaN in every scale / zero point that is not written
     cache.idx_pool.fill_(0x7FFFFFF0)
     for b, L in enumerate(case.lens):
         if L:
             r = case.res[b]
-            cache.put_sequence_q4(b, r["idx"], r["q_k"], r["qs_k"], r["qz_k"], case.K[b][::case.s], case.V[b][::case.s])
+            extra = {} if case.joint else dict(codes_v=r["q_v"], scale_bits_v=r["qs_v"], zero_bits_v=r["qz_v"])
+            cache.put_sequence_q4(b, r["idx"], r["q_k"], r["qs_k"], r["qz_k"], case.K[b][::case.s], case.V[b][::case.s],
+                                  **extra)
     return cache
 
 
@@ -81,24 +83,32 @@ def test_decode_over_4bit_records_ragged(r, Hkv, Hq):
     _check_decode(case, _setup(case, perm=7), 1.0 / np.sqrt(128))
 
 
-def test_decode_over_4bit_records_long_sequence_and_selection():
-    case = Q4Case(9200, [36000], Hkv=1, Hq=4, r=64, n_proto=64)
+@pytest.mark.parametrize("r,Hkv,Hq", [(64, 2, 8), (128, 1, 7), (64, 4, 28)])
+def test_decode_over_4bit_records_two_streams(r, Hkv, Hq):
+    case = Q4Case(9150 + r + Hq, [2900, 0, 811, 1601], Hkv=Hkv, Hq=Hq, r=r, joint=False)
+    _check_decode(case, _setup(case, perm=9), 1.0 / np.sqrt(128))
+
+
+@pytest.mark.parametrize("joint", [True, False])
+def test_decode_over_4bit_records_long_sequence_and_selection(joint):
+    case = Q4Case(9200, [36000], Hkv=1, Hq=4, r=64, n_proto=64, joint=joint)
     cache = _setup(case)
     _check_decode(case, cache, 1.0 / np.sqrt(128))
     rng = np.random.default_rng(3)
     _check_decode(case, cache, 1.0 / np.sqrt(128), positions=[np.sort(rng.choice(36000, 9000, replace=False))])
 
 
-def _compare_records(case, cache, b, t0, t1):
+def _compare_records(case, cache, b, t0, t1, stream=0):
     """GPU-written 4-bit records of tokens t0..t1-1 against the oracle's.  The codes are integers decided by fp32
     arithmetic on latents that the two sides accumulate in different orders, so: scale and zero point equal in all
     but a few tokens (and then within one bf16 step), codes equal in nearly all values and never more than one
     level apart where the token's scale and zero point agree, values read back within one quantisation step."""
     from oracle import deltakv_oracle as O
     r = case.res[b]
-    idx, codes, sb, zb = cache.get_sequence_q4(b, t0, t1)
+    idx, codes, sb, zb = cache.get_sequence_q4(b, t0, t1, stream)
     assert np.array_equal(idx, r["idx"][t0:t1])
-    want_c, want_s, want_z = r["q_k"][t0:t1], r["qs_k"][t0:t1], r["qz_k"][t0:t1]
+    sfx = "_v" if stream else "_k"
+    want_c, want_s, want_z = r["q" + sfx][t0:t1], r["qs" + sfx][t0:t1], r["qz" + sfx][t0:t1]
     same = (sb == want_s) & (zb == want_z)
     assert same.mean() > 0.99, same.mean()
     assert np.all(np.abs(sb.astype(np.int64) - want_s.astype(np.int64)) <= 1)
@@ -107,25 +117,25 @@ def _compare_records(case, cache, b, t0, t1):
     assert np.all(dc[same] <= 1) and (dc[same] == 0).mean() > 0.99, ((dc[same] == 0).mean(), dc.max())
     back = O.bf16_bits_to_f64(sb)[..., None] * codes + O.bf16_bits_to_f64(zb)[..., None]
     step = O.bf16_bits_to_f64(want_s)[..., None]
-    assert np.all(np.abs(back - r["zq_k"][t0:t1]) <= 1.01 * step + 1e-6)
+    assert np.all(np.abs(back - r["zq" + sfx][t0:t1]) <= 1.01 * step + 1e-6)
     return idx, back
 
 
-@pytest.mark.parametrize("r", [64, 32, 128])
-def test_compress_writes_the_oracles_4bit_records_prefill_append_and_single_tokens(r):
+@pytest.mark.parametrize("r,joint", [(64, True), (32, True), (128, True), (64, False), (128, False)])
+def test_compress_writes_the_oracles_4bit_records_prefill_append_and_single_tokens(r, joint):
     import torch
     import paper_2602_08005_amd as dk
     from oracle import deltakv_oracle as O
     from tests.helpers import dev_bits, out_f64, f64, check_attention
-    case = Q4Case(9300 + r, [2500, 1203], Hkv=2, Hq=8, r=r, n_proto=16)
+    case = Q4Case(9300 + r, [2500, 1203], Hkv=2, Hq=8, r=r, n_proto=16, joint=joint)
     B, max_len = 2, 2500
     pps = -(-max_len // 16)
-    dims = dk.make_dims(2, 8, r, B * pps + 3, B * pps + 3, latent_mode=dk.JOINT, latent_bits=4)
+    dims = dk.make_dims(2, 8, r, B * pps + 3, B * pps + 3, latent_mode=dk.JOINT if joint else dk.SPLIT, latent_bits=4)
     cache = dk.PagedCache(dims, B, 4000, max_len)
     cache.latent_pool.fill_(0x7FC0)
     wk, wv = dev_bits(case.W["w_down_k_bf16"]), dev_bits(case.W["w_down_v_bf16"])
-    first = [1700, 900]                        # prefill, then a batched ragged append, then single-token appends
-    second = [2490, 1193]
+    first = [1701, 903]                        # prefill, then a batched ragged append that starts inside a page (and
+    second = [2490, 1193]                      # inside a token pair of the value stream), then single-token appends
     for lo, hi in (([0, 0], first), (first, second)):
         kn = np.concatenate([case.K[b][lo[b]:hi[b]] for b in range(B)])
         vn = np.concatenate([case.V[b][lo[b]:hi[b]] for b in range(B)])
@@ -138,26 +148,29 @@ def test_compress_writes_the_oracles_4bit_records_prefill_append_and_single_toke
     torch.cuda.synchronize()
     backs = []
     for b in range(B):
-        backs.append(_compare_records(case, cache, b, 0, case.lens[b]))
+        bk = _compare_records(case, cache, b, 0, case.lens[b])
+        bv = bk if joint else _compare_records(case, cache, b, 0, case.lens[b], stream=1)
+        backs.append((bk[0], bk[1], bv[1]))
     # attention over the GPU-built cache against the oracle's attention over the values ITS records read back as
     scale = 1.0 / np.sqrt(128)
     out = out_f64(cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(case.q),
                                     case.lens, scale))
     torch.cuda.synchronize()
     for b in range(B):
-        idx, back = backs[b]
+        idx, back, back_v = backs[b]
         res = case.res[b]
-        want, _ = O.decode_attn_direct(f64(case.q[b]), idx, back, back, res["ref_k"], res["ref_v"],
+        want, _ = O.decode_attn_direct(f64(case.q[b]), idx, back, back_v, res["ref_k"], res["ref_v"],
                                        f64(case.W["w_up_k_bf16"]), f64(case.W["w_up_v_bf16"]), scale)
         check_attention(out[b], want, f"seq {b}")
 
 
-def test_4bit_latents_need_the_single_stream_layout():
+def test_4bit_two_stream_layout_needs_rank_64_or_128():
     import paper_2602_08005_amd as dk
     from paper_2602_08005_amd import binding as B
     with pytest.raises(dk.DeltaKVError) as e:
-        dk.paged_layout(dk.make_dims(2, 8, 64, 8, 8, latent_mode=dk.SPLIT, latent_bits=4), 1, 16, 16)
+        dk.paged_layout(dk.make_dims(2, 8, 48, 8, 8, latent_mode=dk.SPLIT, latent_bits=4), 1, 16, 16)
     assert e.value.code == B.E_UNSUPPORTED
+    assert dk.paged_layout(dk.make_dims(2, 8, 64, 8, 8, latent_mode=dk.SPLIT, latent_bits=4), 1, 16, 16).n_streams == 2
     with pytest.raises(dk.DeltaKVError) as e:
         dk.paged_layout(dk.make_dims(2, 8, 64, 8, 8, latent_mode=dk.JOINT, latent_bits=8), 1, 16, 16)
     assert e.value.code == B.E_INVALID_ARG
