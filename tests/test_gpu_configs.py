@@ -11,8 +11,8 @@ def _dev(bits):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
 
 
-@pytest.mark.parametrize("joint", [False, True])
-def test_long_context_decode_launch_configuration(joint):
+@pytest.mark.parametrize("joint,bits", [(False, 16), (True, 16), (False, 4), (True, 4)])
+def test_long_context_decode_launch_configuration(joint, bits):
     """Config 3's launch shape: batch 8 x 131072 tokens, 8 kv-heads, 32 q-heads, rank 64 -- the same split count,
     wave count and LDS table size bench.py times.  One sequence is compressed for real; all 8 batch rows map to its
     pages (block tables may alias), each with its own query, and two rows are checked against the oracle."""
@@ -22,7 +22,8 @@ def test_long_context_decode_launch_configuration(joint):
     from synthetic import generator as G
     from tests.helpers import check_attention
     B, L, Hkv, Hq, r, s = 8, 131072, 8, 32, 64, 16
-    dims = dk.make_dims(Hkv, Hq, r, n_pages=L // 16, n_ref_slots=L // s, latent_mode=dk.JOINT if joint else dk.SPLIT)
+    dims = dk.make_dims(Hkv, Hq, r, n_pages=L // 16, n_ref_slots=L // s, latent_mode=dk.JOINT if joint else dk.SPLIT,
+                        latent_bits=bits)
     ids = [np.arange(L // 16, dtype=np.int32)] * B
     cache = dk.PagedCache(dims, B, L, L, page_ids=ids, ref_slots=ids)
     W = G.make_projections(G.seed_for(3), 128, r, joint=joint)
@@ -35,11 +36,19 @@ def test_long_context_decode_launch_configuration(joint):
     torch.cuda.synchronize()
     assert int(cache.decode_ws[:4].view(torch.int32)[0].item()) == 0
     f = O.bf16_bits_to_f64
-    idx, zk, zv = cache.get_sequence(0, 0, L)
+    if bits == 4:          # the values the GPU's 4-bit records read back as
+        idx, c0, s0, z0 = cache.get_sequence_q4(0, 0, L)
+        zkf = zvf = f(s0)[..., None] * c0 + f(z0)[..., None]
+        if not joint:
+            _, c1, s1, z1 = cache.get_sequence_q4(0, 0, L, stream=1)
+            zvf = f(s1)[..., None] * c1 + f(z1)[..., None]
+    else:
+        idx, zk, zv = cache.get_sequence(0, 0, L)
+        zkf, zvf = f(zk), f(zv)
     got = f(out.cpu().numpy().view(np.uint16))
     for b in (2, 5):
         Lb = lens[b]
-        want, _ = O.decode_attn_direct(f(q_bits[b]), idx[:Lb], f(zk[:Lb]), f(zv[:Lb]), f(K[:Lb:s]), f(V[:Lb:s]),
+        want, _ = O.decode_attn_direct(f(q_bits[b]), idx[:Lb], zkf[:Lb], zvf[:Lb], f(K[:Lb:s]), f(V[:Lb:s]),
                                        f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), 1 / np.sqrt(128))
         check_attention(got[b], want, f"row {b}")
     # ordinals of a sample of tokens against the oracle's own retrieval (prefill at 131072 tokens)
