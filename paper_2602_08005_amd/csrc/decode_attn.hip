@@ -62,7 +62,9 @@ constexpr int kOvfCap = 256;
 // Entry (j, g) is kept in units of 2^-table_shift(S_ref[j][g], base(m_ref[g])): an integer within one of
 // kFixQ - s_j.  Both kernels evaluate exactly these two expressions, so they agree bit for bit.
 __device__ inline float table_shift_base(float mref) { return mref + (kExpBias + (float)kFixQ); }
-__device__ inline int table_shift(float sref, float base) { return (int)fminf(base - sref, 30000.f); }
+// (base - sref >= kExpBias + kFixQ; the conversion saturates and the scaling by a power of two takes any exponent, so
+// no clamp is needed: an absurdly distant score just turns its weights into overflow-list records or zeros)
+__device__ inline int table_shift(float sref, float base) { return (int)(base - sref); }
 
 __device__ inline float wave16_max(float v) {   // max over the 16 lanes that share lane/16
   v = fmaxf(v, __shfl_xor(v, 1));
@@ -385,6 +387,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     qsum += __shfl_xor(qsum, 32);
   }
   float zacc = 0.f;
+  // bf16 pair (16.0, 16.0); kept in a vector register (opaque to the compiler) so that (x & mask) | c16 is a single
+  // and-or instruction: such an instruction can take only one literal constant
+  uint32_t c16 = 0x41804180u;
+  if (Q4) asm volatile("" : "+v"(c16));
   // uniform bases of this (sequence, kv-head): score table row block, latent and ordinal pools at head h
   const char* sref_bh = reinterpret_cast<const char*>(P.sref + bh * P.n_ref_max * Gp);
   const char* lat_h = reinterpret_cast<const char*>(P.latent + (int64_t)h * P.latent_head_stride);
@@ -470,10 +476,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
       for (int kk = 0; kk < TileT::NKK; ++kk) {
         const uint32_t wd = t.zc[kk];            // bf16 (16 + code) = 0x4180 | code << 3
-        zk[kk].x = ((wd << 3) & 0x00780078u) | 0x41804180u;
-        zk[kk].y = ((wd >> 1) & 0x00780078u) | 0x41804180u;
-        zk[kk].z = ((wd >> 5) & 0x00780078u) | 0x41804180u;
-        zk[kk].w = ((wd >> 9) & 0x00780078u) | 0x41804180u;
+        zk[kk].x = ((wd << 3) & 0x00780078u) | c16;
+        zk[kk].y = ((wd >> 1) & 0x00780078u) | c16;
+        zk[kk].z = ((wd >> 5) & 0x00780078u) | c16;
+        zk[kk].w = ((wd >> 9) & 0x00780078u) | c16;
       }
       sc[0] = bf16lo(t.sz.x); sc[1] = bf16hi(t.sz.x); sc[2] = bf16lo(t.sz.y); sc[3] = bf16hi(t.sz.y);
       zf[0] = bf16lo(t.sz.z) - 16.f * sc[0]; zf[1] = bf16hi(t.sz.z) - 16.f * sc[1];
@@ -551,8 +557,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       for (int nb = 0; nb < TileT::NB; ++nb) {
         const uint2 wv = t.zvc[nb >> 2];
         const int j = nb & 3;                       // bf16 (16 + code) = 0x4180 | code << 3
-        t.zv[nb].x = ((j == 0 ? wv.x << 3 : wv.x >> (4 * j - 3)) & 0x00780078u) | 0x41804180u;
-        t.zv[nb].y = ((j == 0 ? wv.y << 3 : wv.y >> (4 * j - 3)) & 0x00780078u) | 0x41804180u;
+        t.zv[nb].x = ((j == 0 ? wv.x << 3 : wv.x >> (4 * j - 3)) & 0x00780078u) | c16;
+        t.zv[nb].y = ((j == 0 ? wv.y << 3 : wv.y >> (4 * j - 3)) & 0x00780078u) | c16;
       }
     }
     uint2 pk;
