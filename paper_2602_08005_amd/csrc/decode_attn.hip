@@ -536,10 +536,16 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
       pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
     }
-    if constexpr (Q4 && JOINT) {   // the value product takes p * scale; the zero-point term is a scalar per head
+    // 4-bit: the value product takes p * scale (rounded to bf16 for the matrix unit) against 16 + code; the scalar
+    // that takes the offset back out must use the SAME rounded weights, or the two large terms would not cancel
+    // exactly and the bf16 rounding of the weights would show the latent's whole range in every output.  The offset
+    // taken out is 23.5, the centre of 16 + code, so that what the rounding of a weight multiplies is the centred
+    // code (-7.5 .. 7.5), as it multiplies a centred latent in the bf16 layouts; the 7.5 scale goes with the zero point.
+    float pzero = 0.f;                           // sum_e p[e] * (zero[e] + 7.5 scale[e])
+    if constexpr (Q4 && JOINT) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        zacc += p[e] * zf[e];
+        pzero += p[e] * (zf[e] + 23.5f * sc[e]); // zf = zero - 16 scale
         p[e] *= sc[e];
       }
     }
@@ -549,9 +555,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const bool on = FULL || ((mask >> (4 * lg + e)) & 1u);
-        const float sve = on ? sv[e] : 0.f, zve = on ? zv0[e] - 16.f * sv[e] : 0.f;
-        zacc += p[e] * zve;
-        p[e] *= sve;
+        pzero += p[e] * (on ? zv0[e] + 7.5f * sv[e] : 0.f);
+        p[e] *= on ? sv[e] : 0.f;
       }
 #pragma unroll
       for (int nb = 0; nb < TileT::NB; ++nb) {
@@ -564,6 +569,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
     pk.y = pack_bf16(p[2], p[3]);
+    if constexpr (Q4) zacc += pzero - 23.5f * ((bf16lo(pk.x) + bf16hi(pk.x)) + (bf16lo(pk.y) + bf16hi(pk.y)));
     const short4v pa = __builtin_bit_cast(short4v, pk);
     if (JOINT) {
 #pragma unroll

@@ -1,0 +1,106 @@
+"""Randomised cross-feature parity: batches of random shape (kv-heads, group size, rank, layout, latent bits, lengths
+including empty and ragged ones, scattered pages) decoded with a random mix of the optional inputs (a selection, a raw
+segment) against the oracle's definition.  Seeds are fixed; every case is a few thousand tokens."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed):
+    rng = np.random.default_rng(seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16]))
+    joint = bool(rng.integers(0, 2))
+    bits = int(rng.choice([16, 4]))
+    r = int(rng.choice([64, 128])) if (bits == 4 and not joint) else int(rng.choice([16, 32, 48, 64, 80, 96, 112, 128]))
+    s = int(rng.choice([8, 16, 32]))
+    B = int(rng.integers(1, 5))
+    lens = [int(x) for x in rng.choice([0, 1, 15, 16, 17, 250, 999, 1600, 2777, 4100], size=B)]
+    if max(lens) == 0:
+        lens[0] = 333
+    return dict(Hkv=Hkv, Hq=Hkv * G, joint=joint, bits=bits, r=r, s=s, lens=lens,
+                use_sel=bool(rng.integers(0, 2)), use_raw=bool(rng.integers(0, 2)), rng=rng)
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_random_shape_and_feature_mix(seed):
+    import torch
+    import paper_2602_08005_amd as dk
+    from oracle import deltakv_oracle as O
+    from synthetic import generator as G
+    from tests.helpers import dev_bits, out_f64, f64, check_attention
+    c = _case(1000 + seed)
+    rng, Hkv, Hq, r, s, lens, joint, bits = c["rng"], c["Hkv"], c["Hq"], c["r"], c["s"], c["lens"], c["joint"], c["bits"]
+    B = len(lens)
+    W = G.make_projections(seed, 128, r, joint=joint)
+    max_len = max(max(lens), 1)
+    pps, rps = -(-max_len // 16), -(-max_len // s)
+    n_pages, n_slots = B * pps + 4, B * rps + 4
+    pp, rp = G.page_permutation(seed, B * pps, n_pages), G.page_permutation(seed + 1, B * rps, n_slots)
+    dims = dk.make_dims(Hkv, Hq, r, n_pages, n_slots, ref_stride=s, latent_mode=dk.JOINT if joint else dk.SPLIT,
+                        latent_bits=bits)
+    cache = dk.PagedCache(dims, B, 16, max_len, page_ids=[pp[b * pps:(b + 1) * pps] for b in range(B)],
+                          ref_slots=[rp[b * rps:(b + 1) * rps] for b in range(B)])
+    cache.latent_pool.fill_(0x7FC0)
+    cache.idx_pool.fill_(0x7FFFFFF0)
+    res, Ks, Vs = [], [], []
+    for b, L in enumerate(lens):
+        K, V, _ = G.make_kv(seed * 100 + b, max(L, 1), Hkv, 128, n_proto=12)
+        K, V = K[:L], V[:L]
+        Ks.append(K)
+        Vs.append(V)
+        if L == 0:
+            res.append(None)
+            continue
+        rr = O.compress(f64(K), f64(V), f64(W["w_down_k_bf16"]), f64(W["w_down_v_bf16"]), s=s,
+                        mode=O.JOINT if joint else O.SPLIT, latent_bits=bits)
+        res.append(rr)
+        if bits == 4:
+            extra = {} if joint else dict(codes_v=rr["q_v"], scale_bits_v=rr["qs_v"], zero_bits_v=rr["qz_v"])
+            cache.put_sequence_q4(b, rr["idx"], rr["q_k"], rr["qs_k"], rr["qz_k"], K[::s], V[::s], **extra)
+        else:
+            cache.put_sequence(b, rr["idx"], rr["zb_k"], rr["zb_v"], K[::s], V[::s])
+    q_bits = G.make_queries(seed, B, Hq, 128)
+    positions = None
+    if c["use_sel"]:
+        positions = [np.sort(rng.choice(L, max(L // 3, 1), replace=False)) if L else np.array([], dtype=np.int64)
+                     for L in lens]
+    raw_lens = [int(x) for x in rng.choice([0, 1, 70, 300], size=B)] if c["use_raw"] else [0] * B
+    cap = max(max(raw_lens), 1)
+    rawK = np.full((B, cap, Hkv, 128), 0x7FC0, dtype=np.uint16)
+    rawV = rawK.copy()
+    for b in range(B):
+        if raw_lens[b]:
+            k, v, _ = G.make_kv(seed * 100 + 50 + b, raw_lens[b], Hkv, 128, n_proto=6)
+            rawK[b, :raw_lens[b]], rawV[b, :raw_lens[b]] = k, v
+    scale = float(rng.choice([0.05, 1.0 / np.sqrt(128), 0.15]))
+    wuk, wuv, q = dev_bits(W["w_up_k_bf16"]), dev_bits(W["w_up_v_bf16"]), dev_bits(q_bits)
+    lse = torch.zeros((B, Hq), dtype=torch.float32, device="cuda")
+    if c["use_raw"]:
+        out = cache.decode_attn_raw(wuk, wuv, q, lens, dev_bits(rawK), dev_bits(rawV), raw_lens, scale,
+                                    positions_per_seq=positions, lse=lse)
+    elif positions is not None:
+        out = cache.decode_attn_subset(wuk, wuv, q, lens, positions, scale, lse=lse)
+    else:
+        out = cache.decode_attn(wuk, wuv, q, lens, scale, lse=lse)
+    torch.cuda.synchronize()
+    got, lse = out_f64(out), lse.cpu().numpy().astype(np.float64)
+    for b, L in enumerate(lens):
+        if L:
+            rr = res[b]
+            zk, zv = (rr["zq_k"], rr["zq_v"]) if bits == 4 else (f64(rr["zb_k"]), f64(rr["zb_v"]))
+            idx, rk, rv = rr["idx"], rr["ref_k"], rr["ref_v"]
+        else:
+            idx = np.zeros((0, Hkv), dtype=np.int64)
+            zk = zv = np.zeros((0, Hkv, r))
+            rk = rv = np.zeros((1, Hkv, 128))
+        want, wl = O.decode_attn_with_raw(f64(q_bits[b]), idx, zk, zv, rk, rv, f64(W["w_up_k_bf16"]),
+                                          f64(W["w_up_v_bf16"]), scale, f64(rawK[b, :raw_lens[b]]),
+                                          f64(rawV[b, :raw_lens[b]]), positions=None if positions is None else positions[b])
+        what = f"seed {seed} seq {b} {dict((k, v) for k, v in c.items() if k != 'rng')}"
+        if np.all(np.isneginf(wl)):
+            assert np.all(got[b] == 0) and np.all(np.isneginf(lse[b])), what
+            continue
+        check_attention(got[b], want, what)
+        assert np.max(np.abs(lse[b] - wl)) <= 2e-2, what
