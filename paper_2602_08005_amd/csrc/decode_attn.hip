@@ -27,6 +27,9 @@
 namespace dkv {
 
 
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));   // operand types of the non-temporal load builtin
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+
 __device__ inline int seq_len_of(const DecodeParams& P, int b) {
   return clampi(P.seq_lens[b], 0, P.max_seq_len);
 }
@@ -243,8 +246,13 @@ struct Tile<R, true> {
 };
 
 // Loads of the streaming loop take their address as (uniform 64-bit base of the page) + (32-bit offset of the
-// lane), which the hardware forms itself (scalar base + vector offset): no vector arithmetic per load.
-template <int R, bool JOINT>
+// lane), which the hardware forms itself (scalar base + vector offset): no vector arithmetic per load.  The bf16
+// latent loads are non-temporal: every record is read once, and letting two gigabytes of them flow through the L2
+// as ordinary lines kept evicting the per-reference score rows that the gathers come back to (11 % of the
+// kernel's time).  The same hint on the ordinals, or on the small 4-bit records, changed nothing; and a cache that
+// fits the chip's last-level cache and is read again by the next call (a single sequence's decode loop) is better
+// off with ordinary loads, so the host picks the variant (NT) by the size of what the call streams.
+template <int R, bool JOINT, bool NT>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
                                     uint32_t l, Tile<R, true>& t) {
   const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
@@ -264,7 +272,7 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
     t.szv = *reinterpret_cast<const uint4*>(vb + (8u * R + lg * 16u));
   }
 }
-template <int R, bool JOINT>
+template <int R, bool JOINT, bool NT>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
                                     uint32_t l, Tile<R, false>& t) {
   const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
@@ -272,14 +280,17 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
 #pragma unroll
   for (int kk = 0; kk < Tile<R, false>::NKK; ++kk) {
     if (4 * kk + lg < R / 8)
-      t.zk[kk] = *reinterpret_cast<const uint4*>(base + (l * 16u + kk * 1024u));
+      t.zk[kk] = NT ? __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(base + (l * 16u + kk * 1024u))))
+                    : *reinterpret_cast<const uint4*>(base + (l * 16u + kk * 1024u));
     else
       t.zk[kk] = make_uint4(0, 0, 0, 0);
   }
   if (!JOINT) {
     const char* vb = base + stream_bytes;
 #pragma unroll
-    for (int nb = 0; nb < Tile<R, false>::NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(vb + (l * 8u + nb * 512u));
+    for (int nb = 0; nb < Tile<R, false>::NB; ++nb)
+      t.zv[nb] = NT ? __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const uint2v*>(vb + (l * 8u + nb * 512u))))
+                    : *reinterpret_cast<const uint2*>(vb + (l * 8u + nb * 512u));
   }
 }
 // One ordinal per lane: lane (row lg = l/16, quad position l%4) holds the ordinal of token 4*lg + l%4, so the four
@@ -298,7 +309,7 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // blocks are not free here: each needs a whole compute unit's LDS before it can start and exit.)  Blocks of the kv-heads
 // of one item run side by side and sweep the same pages; with eight kv-heads, block id % 8 = head, so all splits of a
 // (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
-template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4>
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
@@ -687,7 +698,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
     for (int u = 0; u < LI; ++u) id[u] = load_ordinal(idx_h, idx_page_bytes, pg[u], l);
 #pragma unroll
-    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
+    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
 #pragma unroll
     for (int u = 0; u < LG; ++u) gather(id[u], sr[u]);
     auto body = [&](auto full_tag) {
@@ -699,7 +710,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
         id[(u + LI) % ST] = load_ordinal(idx_h, idx_page_bytes, pg[(u + LI) % ST], l);
-        load_latents<R, JOINT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
+        load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
         pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
         compute(full_tag, t[u], id[u], sr[u],
@@ -1146,8 +1157,11 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT, bool SUBSET, bool Q4>
+template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  if constexpr (!Q4 && !NT) {
+    if (P.nt) return launch_stream<R, NW, JOINT, SUBSET, Q4, true>(P, grid, lds, st);
+  }
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
@@ -1165,12 +1179,12 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 

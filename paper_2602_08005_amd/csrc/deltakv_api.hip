@@ -369,6 +369,9 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
     Pm.raw_lens = raw.lens;
     Pm.raw_cap = raw.cap;
   }
+  // latent bytes the call streams (pages x heads x page block); beyond what the last-level cache (256 MB) can keep
+  // for the next call, the records go through the caches as non-temporal loads
+  Pm.nt = total_pages * lay->latent_head_stride * 2 > (192ll << 20);
   // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
   // from the device copy of the lengths
   int64_t n_items = 0;
