@@ -28,12 +28,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy
 # of known size (the summaries under profiles/ give the commands and the raw counter values).
-MEASURED_STREAM_TRAFFIC_CFG3 = 2_478_000_000         # SPLIT: read 2.457 GB + written 0.021 GB
-MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_295_000_000   # JOINT: read 1.274 GB + written 0.021 GB
-MEASURED_STREAM_TRAFFIC_RAGGED = 1_284_000_000       # irregular paged batch (SPLIT, rank 48): 1.255 + 0.030 GB
+MEASURED_STREAM_TRAFFIC_CFG3 = 2_271_000_000         # SPLIT: read 2.250 GB + written 0.021 GB
+MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_189_000_000   # JOINT: read 1.168 GB + written 0.021 GB
+MEASURED_STREAM_TRAFFIC_RAGGED = 1_226_000_000       # irregular paged batch (SPLIT, rank 48): 1.196 + 0.030 GB
 MEASURED_SIM_TRAFFIC_PREFILL32K = 160_700_000        # similarity kernel, one 32768-token layer: 0.152 + 0.008 GB
-MEASURED_STREAM_TRAFFIC_CFG3_SELECT25 = 647_000_000  # SPLIT, a quarter of the pages selected: 0.626 + 0.021 GB
-MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4 = 468_000_000  # JOINT, 4-bit latents: 0.447 + 0.021 GB
+MEASURED_STREAM_TRAFFIC_CFG3_SELECT25 = 596_000_000  # SPLIT, a quarter of the pages selected: 0.575 + 0.021 GB
+MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4 = 476_000_000  # JOINT, 4-bit latents: 0.451 + 0.025 GB
 
 
 def log(*a):
