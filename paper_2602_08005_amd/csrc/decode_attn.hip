@@ -750,7 +750,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   if (n_ovf == 0) {
     for (int i = tid * 4; i < n_tab; i += NW * 64 * 4) {
       const uint4 u = *reinterpret_cast<const uint4*>(utab + i);
-      *reinterpret_cast<float4*>(wp + i) = make_float4((float)u.x, (float)u.y, (float)u.z, (float)u.w);
+      typedef float float4n __attribute__((ext_vector_type(4)));
+      const float4n o = {(float)u.x, (float)u.y, (float)u.z, (float)u.w};
+      if (NT) __builtin_nontemporal_store(o, reinterpret_cast<float4n*>(wp + i));   // large calls: keep the flush out of L2 too
+      else *reinterpret_cast<float4n*>(wp + i) = o;
     }
   } else {
     // rare: turn the table into plain weights (entry i = (j, g) has the units of score-table element i)
