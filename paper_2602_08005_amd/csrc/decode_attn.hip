@@ -78,13 +78,19 @@ __device__ inline float wave16_max(float v) {   // max over the 16 lanes that sh
 }
 
 // ------------------------------------------------------------------------------------------------
-// ref_scores: grid (n_chunk_max, Hkv, B), 256 threads.  Each wave scores 16 references per MFMA step:
-// D[g][j] = sum_d q[g][d] K_ref[j][d].
+// ref_scores: grid (ceil(n_chunk_max / CPB), Hkv, B), 256 threads; a block scores CPB consecutive chunks of
+// kRefChunk references.  Each wave scores 16 references per MFMA step: D[g][j] = sum_d q[g][d] K_ref[j][d].
+// A wave's life is a chain of dependent round trips to memory (q and slots, reference rows, stores), about 10 us
+// whatever the load of the machine, and blocks are handed to the compute units at a limited rate; a grid of
+// thousands of one-chunk blocks therefore spends most of its time being dispatched, with a quarter of the wave
+// slots occupied.  Large calls over sequences of about equal length use CPB = 4: a quarter of the blocks, each with
+// the rows of its next chunk in flight while it scores the current one (chosen by the host).
 // ------------------------------------------------------------------------------------------------
+template <int CPB>
 __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
-  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int chunk0 = blockIdx.x * CPB, h = blockIdx.y, b = blockIdx.z;
   // the status word is cleared here rather than by a memset node, so that a caller may capture the call
-  if (chunk == 0 && h == 0 && b == 0) {
+  if (chunk0 == 0 && h == 0 && b == 0) {
     if (threadIdx.x == 0) *P.status = 0;
     // List of the non-empty (sequence, split) items for the streaming kernel's grid.  Blocks start in list order,
     // so the list goes from the sequences with the largest splits to those with the smallest (longest processing
@@ -120,10 +126,9 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   }
   const int L = seq_len_of(P, b);
   const int n_ref = refs_below(L, P.stride);
-  const int j0 = chunk * kRefChunk;
-  if (j0 >= n_ref) return;
+  if (chunk0 * kRefChunk >= n_ref) return;
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63, ln = l & 15, lg = l >> 4;
-  __shared__ float red[4][16];
+  __shared__ float red[2][4][16];
 
   // A operand: q rows of this kv-head's group (rows >= G are zero)
   bf16x8 qa[4];
@@ -138,36 +143,43 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
   }
   const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint16_t* kbase = P.ref + (int64_t)h * P.ref_head_stride;   // K half
-  float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  // The wave's four 16-reference steps run as two batches of two: each batch issues its eight 16-byte loads
-  // before its first MFMA (rows past the end re-read the last reference and are dropped afterwards).  Two
-  // steps of registers instead of four keep the kernel at eight waves per SIMD, so the whole grid of a 128k-token
-  // batch is resident at once instead of running as two rounds of blocks.
+  // A wave owns 64 references of every chunk: four 16-reference steps.  The pool slots of all the block's chunks
+  // are fetched first; the sixteen 16-byte row loads of chunk c+1 are issued before chunk c is scored (rows past
+  // the end re-read the last reference and are dropped afterwards).
   constexpr int NSTEP = kRefChunk / 64;
-  int slot[NSTEP];
+  constexpr int NBUF = CPB > 1 ? 2 : 1;
+  int slot[CPB][NSTEP];
 #pragma unroll
-  for (int step = 0; step < NSTEP; ++step) {
-    const int j = min(j0 + w * 64 + step * 16 + ln, n_ref - 1);
-    slot[step] = P.ref_tables[(int64_t)b * P.rt_stride + j];
-  }
+  for (int cc = 0; cc < CPB; ++cc)
 #pragma unroll
-  for (int half = 0; half < NSTEP; half += 2) {
-    uint4 kv[2][4];
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      const uint16_t* krow = kbase + (int64_t)clampi(slot[half + s2], 0, (int)P.n_ref_slots - 1) * kHeadDim;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) kv[s2][kk] = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
+    for (int step = 0; step < NSTEP; ++step) {
+      const int j = min((chunk0 + cc) * kRefChunk + w * 64 + step * 16 + ln, n_ref - 1);
+      slot[cc][step] = P.ref_tables[(int64_t)b * P.rt_stride + j];
     }
+  uint4 kv[NBUF][NSTEP][4];
+  auto issue = [&](const int (&sl)[NSTEP], uint4 (&dst)[NSTEP][4]) {
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) {
-      const int step = half + s2;
+    for (int step = 0; step < NSTEP; ++step) {
+      const uint16_t* krow = kbase + (int64_t)clampi(sl[step], 0, (int)P.n_ref_slots - 1) * kHeadDim;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) dst[step][kk] = *reinterpret_cast<const uint4*>(krow + (4 * kk + lg) * 8);
+    }
+  };
+  issue(slot[0], kv[0]);
+#pragma unroll
+  for (int cc = 0; cc < CPB; ++cc) {
+    const int chunk = chunk0 + cc, j0 = chunk * kRefChunk;
+    if (j0 >= n_ref) break;                                  // uniform over the block
+    if (cc + 1 < CPB) issue(slot[cc + 1 < CPB ? cc + 1 : cc], kv[(cc + 1) % NBUF]);
+    float mx[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+    for (int step = 0; step < NSTEP; ++step) {
       const int j = j0 + w * 64 + step * 16 + ln;
       const bool valid = j < n_ref;
       float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv[s2][kk]), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kv[cc % NBUF][step][kk]), acc, 0, 0, 0);
       // lane holds rows g = 4*lg + i of column j
       float4 o;
       o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
@@ -179,24 +191,24 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
         mx[2] = fmaxf(mx[2], o.z); mx[3] = fmaxf(mx[3], o.w);
       }
     }
-    // keep the second batch's loads behind the first batch's stores in program order
-    __builtin_amdgcn_sched_barrier(0);
-  }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) mx[i] = wave16_max(mx[i]);
-  if (ln == 0) {
+    for (int i = 0; i < 4; ++i) mx[i] = wave16_max(mx[i]);
+    if (ln == 0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) red[w][4 * lg + i] = mx[i];
-  }
-  __syncthreads();
-  if (threadIdx.x < P.Gp) {
-    float m = fmaxf(fmaxf(red[0][threadIdx.x], red[1][threadIdx.x]), fmaxf(red[2][threadIdx.x], red[3][threadIdx.x]));
-    P.cmax[(bh * P.n_chunk_max + chunk) * P.Gp + threadIdx.x] = m;
+      for (int i = 0; i < 4; ++i) red[cc & 1][w][4 * lg + i] = mx[i];
+    }
+    __syncthreads();      // (the buffer written two chunks later was read before the barrier in between)
+    if (threadIdx.x < P.Gp) {
+      const float (&r)[4][16] = red[cc & 1];
+      float m = fmaxf(fmaxf(r[0][threadIdx.x], r[1][threadIdx.x]), fmaxf(r[2][threadIdx.x], r[3][threadIdx.x]));
+      P.cmax[(bh * P.n_chunk_max + chunk) * P.Gp + threadIdx.x] = m;
+    }
   }
 
-  // chunk 0, last wave: q_lat[g][c] = scale*log2e * sum_d q[g][d] W_uK[c][d], stored bf16
-  if (chunk == 0 && w == 3) {
-    for (int nb = 0; nb < P.R / 16; ++nb) {
+  // first block of the pair: q_lat[g][c] = scale*log2e * sum_d q[g][d] W_uK[c][d], stored bf16; the 16-column
+  // blocks go round the four waves (each block is a round trip to memory of its own)
+  if (chunk0 == 0) {
+    for (int nb = w; nb < P.R / 16; nb += 4) {
       const uint16_t* wrow = P.w_up_k + (int64_t)(nb * 16 + ln) * kHeadDim;
       float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1228,7 +1240,10 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
     if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of raw_attn");
     timing_mark(K_RAW, st);
   }
-  hipLaunchKernelGGL(k_ref_scores, gchunk, dim3(256), 0, st, P);
+  if (P.ref_cpb == 4)
+    hipLaunchKernelGGL(k_ref_scores<4>, dim3(ceil_div(P.n_chunk_max, 4), P.Hkv, batch), dim3(256), 0, st, P);
+  else
+    hipLaunchKernelGGL(k_ref_scores<1>, gchunk, dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of ref_scores");
   timing_mark(K_REF_SCORES, st);
   dim3 gs(n_items > 0 ? n_items * P.Hkv : 1);

@@ -372,6 +372,14 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   // latent bytes the call streams (pages x heads x page block); beyond what the last-level cache (256 MB) can keep
   // for the next call, the records go through the caches as non-temporal loads
   Pm.nt = total_pages * lay->latent_head_stride * 2 > (192ll << 20);
+  // ref_scores: four reference chunks per block when that still leaves two blocks per compute unit and the sequences
+  // are about equally long (blocks of four chunks balance badly over a ragged batch)
+  {
+    int64_t chunks = 0;
+    for (int b = 0; b < batch; ++b) chunks += ceil_div(ceil_div(seq_lens_host[b], S), kRefChunk);
+    const int64_t grid1 = (int64_t)Pm.n_chunk_max * batch;
+    Pm.ref_cpb = grid1 * dims->n_kv_heads >= 2048 && Pm.n_chunk_max >= 4 && chunks * 10 >= grid1 * 9 ? 4 : 1;
+  }
   // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
   // from the device copy of the lengths
   int64_t n_items = 0;

@@ -39,6 +39,7 @@ struct DecodeParams {
   int batch, Hkv, Hq, G, Gp, R, stride, joint;
   int q4;                   // 4-bit token-wise latents
   int nt;                   // the call streams more than the last-level cache holds: non-temporal latent loads
+  int ref_cpb;              // reference chunks scored per block of ref_scores (1 or 4)
   int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)
   int n_ref_max, n_chunk_max;
   int S, pages_per_split;   // split grid
