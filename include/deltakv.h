@@ -299,6 +299,8 @@ int deltakv_version(void);
  *   "sim_tb"        16-token blocks per wave of the similarity kernel (1..4)
  *   "sim_waves"     waves per block of the similarity kernel (4 or 8; 8 needs sim_tb <= 2)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)
+ *   "timing_period" timed regions record events for every value-th call only (0 or 1 = every call): an event costs
+ *                   a few microseconds of stream time, which a benchmark may not want in front of every kernel
  * Results do not depend on these beyond floating-point summation order.  Errors: INVALID_ARG. */
 int deltakv_tune(const char* name, int32_t value);
 
@@ -306,7 +308,8 @@ int deltakv_tune(const char* name, int32_t value);
  * compress / decode call records a HIP event on its stream before its first kernel and after each
  * kernel (use one stream, call from one thread).  deltakv_timing_end waits for the last event and
  * returns, per kernel, the summed time between the surrounding events in milliseconds (this includes
- * the launch gap in front of the kernel) and the number of launches.  Kernel order:
+ * the launch gap in front of the kernel) and the number of launches (with "timing_period" p set through
+ * deltakv_tune, of the calls 0, p, 2p, ... of the region).  Kernel order:
  *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
  *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress; a call that appends exactly
  *     one token to every sequence runs two kernels, reported as 5 (candidate scan) and 8 (finish))

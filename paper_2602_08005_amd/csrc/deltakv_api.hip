@@ -57,6 +57,9 @@ int g_tune_sim_waves = 0;
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
 bool g_timing = false;
+int g_timing_period = 1;       // events are recorded for calls 0, p, 2p, ... of a timed region
+int g_timing_calls = 0;
+bool g_timing_this_call = true;
 std::vector<Mark> g_marks;
 std::vector<hipEvent_t> g_event_pool;
 
@@ -69,6 +72,8 @@ hipError_t note_hip_error(hipError_t e, const char* what) {
 }
 void timing_mark(int kernel_id, hipStream_t st) {
   if (!g_timing) return;
+  if (kernel_id < 0) g_timing_this_call = g_timing_calls++ % g_timing_period == 0;   // the mark that opens a call
+  if (!g_timing_this_call) return;
   hipEvent_t ev;
   if (!g_event_pool.empty()) {
     ev = g_event_pool.back();
@@ -116,6 +121,8 @@ int deltakv_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "sim_waves")) {
     if (value != 0 && value != 4 && value != 8) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_waves = value;
+  } else if (!strcmp(name, "timing_period")) {
+    g_timing_period = value > 1 ? value : 1;
   } else if (!strcmp(name, "sim_tb")) {
     if (value < 0 || value > 4) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_tb = value;
@@ -128,6 +135,8 @@ int deltakv_tune(const char* name, int32_t value) {
 int deltakv_timing_begin(void) {
   for (auto& m : g_marks) g_event_pool.push_back(m.ev);
   g_marks.clear();
+  g_timing_calls = 0;
+  g_timing_this_call = true;
   g_timing = true;
   return DELTAKV_OK;
 }
