@@ -53,6 +53,7 @@ int g_tune_splits = 0;
 int g_tune_sim_tb = 0;
 int g_tune_sim_ns = 0;
 int g_tune_sim_waves = 0;
+int g_tune_ref_chunks = 0;
 
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
@@ -121,6 +122,9 @@ int deltakv_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "sim_waves")) {
     if (value != 0 && value != 4 && value != 8) return DELTAKV_E_INVALID_ARG;
     g_tune_sim_waves = value;
+  } else if (!strcmp(name, "ref_chunks")) {
+    if (value != 0 && value != 1 && value != 4) return DELTAKV_E_INVALID_ARG;
+    g_tune_ref_chunks = value;
   } else if (!strcmp(name, "timing_period")) {
     g_timing_period = value > 1 ? value : 1;
   } else if (!strcmp(name, "sim_tb")) {
@@ -388,6 +392,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
     for (int b = 0; b < batch; ++b) chunks += ceil_div(ceil_div(seq_lens_host[b], S), kRefChunk);
     const int64_t grid1 = (int64_t)Pm.n_chunk_max * batch;
     Pm.ref_cpb = grid1 * dims->n_kv_heads >= 2048 && Pm.n_chunk_max >= 4 && chunks * 10 >= grid1 * 9 ? 4 : 1;
+    if (g_tune_ref_chunks) Pm.ref_cpb = g_tune_ref_chunks;
   }
   // the streaming kernel runs one block per non-empty (sequence, split, kv-head); the kernels derive the same list
   // from the device copy of the lengths

@@ -199,6 +199,24 @@ def test_many_tokens_on_one_reference_wrap_the_weight_table():
         _compare(case, got, lse, scale)
 
 
+def test_four_reference_chunks_per_block_on_ragged_lengths():
+    """Large uniform batches score four 256-reference chunks per block of the first kernel.  Forced on a small ragged
+    batch: sequences that end inside a block's first, second and last chunk, one that fills its chunks exactly, one
+    with a single reference and an empty one."""
+    from tests.helpers import Case
+    from paper_2602_08005_amd import binding as B
+    case = Case(7150, [16 * 1100 + 5, 16 * 300, 16 * 257 - 3, 16 * 1024, 9, 0, 16 * 600 + 1], Hkv=2, Hq=8, r=32, n_proto=16)
+    cache = _setup(case)
+    scale = 1.0 / np.sqrt(128)
+    B.tune("ref_chunks", 4)
+    try:
+        got, lse, status = _run(case, cache, scale)
+    finally:
+        B.tune("ref_chunks", 0)
+    assert status == 0
+    _compare(case, got, lse, scale)
+
+
 def _boost_tokens(case, tokens, boost_log2, scale):
     """Rewrite z_K of `tokens` (kv-head 0) so that the latent part of q-head 0's logit is boost_log2 (log2 units)."""
     from tests.helpers import f64
