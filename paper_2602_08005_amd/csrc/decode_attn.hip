@@ -360,18 +360,34 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   uint32_t* ovf_ent = ovf + 4;
   float* ovf_val = reinterpret_cast<float*>(ovf_ent + kOvfCap);
   uint32_t* utab = reinterpret_cast<uint32_t*>(tab);
+  // The chunk maxima of the per-reference scores (n_cm floats, at most a few hundred) are fetched with one load
+  // per thread and staged in the still unused overflow list; read one after the other from global memory they cost a
+  // round trip each, 32 in a row at 131072 tokens, which was most of a block's set-up time.
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const int n_cm = ceil_div(n_ref, kRefChunk) * Gp;
+  const bool cm_staged = n_cm <= kOvfCap;
+  float cm_mine = -INFINITY;
+  if (cm_staged && tid < n_cm) cm_mine = P.cmax[bh * P.n_chunk_max * Gp + tid];
   for (int i = tid; i < n_tab; i += NW * 64) utab[i] = 0u;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
   if (tid == 0) { ovf[0] = 0u; pgctr[0] = 0u; }
+  if (cm_staged) {
+    if (tid < n_cm) ovf_val[tid] = cm_mine;
+    __syncthreads();
+  }
 
-  const int64_t bh = (int64_t)b * P.Hkv + h;
   const uint32_t gq = ln < (uint32_t)Gp ? ln : Gp - 1;    // column of the score table this lane reads
   const bool ghead = ln < (uint32_t)G;
-  // exponent offset for q-head g = ln: chunk maxima of the per-reference scores
+  // exponent offset for q-head g = ln: the largest chunk maximum (the staged copy is free again after the barrier
+  // that ends the set-up)
   float mref = -INFINITY;
   {
     const int nch = ceil_div(n_ref, kRefChunk);
-    for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
+    if (cm_staged) {
+      for (int c = 0; c < nch; ++c) mref = fmaxf(mref, ovf_val[c * Gp + gq]);
+    } else {
+      for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
+    }
   }
   const float cinit = -(mref + kExpBias);
   const float cshift = table_shift_base(mref);
