@@ -299,6 +299,7 @@ int deltakv_version(void);
  *   "sim_tb"        16-token blocks per wave of the similarity kernel (1..4)
  *   "sim_waves"     waves per block of the similarity kernel (4 or 8; 8 needs sim_tb <= 2)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)
+ *   "project_pages" consecutive pages per block of the projection kernel (1..16)
  *   "ref_chunks"    reference chunks scored per block of the decode call's first kernel (1 or 4)
  *   "timing_period" timed regions record events for every value-th call only (0 or 1 = every call): an event costs
  *                   a few microseconds of stream time, which a benchmark may not want in front of every kernel

@@ -552,7 +552,7 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// project: grid (page_tiles_max, B), 256 threads; wave w handles kv-heads w, w+4, ...
+// project: grid (ceil(page_tiles_max / pages per block), B), 256 threads; wave w handles kv-heads w, w+4, ...
 // A wave owns one page of one sequence: lane (ln, lg) <-> token slot ln of the page, 8-wide chunk.
 // ------------------------------------------------------------------------------------------------
 
@@ -565,13 +565,15 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   const int n_new = P.cu_new[b + 1] - P.cu_new[b];
   const int la = lb + n_new;
   const int page_first = lb / kPage;
-  const int lp = page_first + blockIdx.x;         // logical page of the sequence
-  if (n_new <= 0 || lp * kPage >= la) return;
+  const int lp0 = page_first + blockIdx.x * P.proj_ppb;   // first logical page of the block
+  if (n_new <= 0 || lp0 * kPage >= la) return;
   const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
-  // stage W_down^T of both streams (transposed and padded by admit_refs) with 16-byte copies
+  // stage W_down^T of both streams (transposed and padded by admit_refs) with 16-byte copies; a block of a long
+  // call takes several consecutive pages, so that the staging (half as many bytes as a page brings) is shared
   for (int i = tid; i < 2 * R * kWPad / 8; i += 256)
     reinterpret_cast<uint4*>(wlds)[i] = reinterpret_cast<const uint4*>(P.wt)[i];
   __syncthreads();
+  for (int lp = lp0; lp < lp0 + P.proj_ppb && lp * kPage < la; ++lp) {
   const int pos = lp * kPage + ln;
   const bool tok_ok = pos >= lb && pos < la;
   const int64_t n = P.cu_new[b] + (tok_ok ? pos - lb : 0);
@@ -753,6 +755,7 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
     }
     if (tok_ok && lg == 0)
       P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + ln] = ord;
+  }
   }
 }
 
@@ -1125,7 +1128,7 @@ hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_ma
   hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
   timing_mark(K_EXACT, st);
-  dim3 gp(page_tiles_max, P.batch);
+  dim3 gp(ceil_div(page_tiles_max, P.proj_ppb), P.batch);
   e = hipErrorInvalidValue;
   switch (P.R) {
     case 16: e = launch_project<16>(P, gp, st); break;

@@ -82,6 +82,7 @@ struct CompressParams {
   int Hkv, R, stride, joint;
   int q4;                           // 4-bit token-wise latents (single stream)
   int metric;                       // 0: cosine, 1: squared L2 distance (section 4.1)
+  int proj_ppb;                     // consecutive pages a block of the projection kernel takes
   int NS;            // reference-range splits of the similarity search
   float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), |token|^2
   int32_t* ord;        // [n_new_total][Hkv] chosen reference ordinal

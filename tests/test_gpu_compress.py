@@ -134,6 +134,21 @@ def test_append_after_prefill_batched_and_paged():
     _verify(cache, KV, W, total, 16, False)
 
 
+@pytest.mark.parametrize("pages,joint", [(2, False), (3, True), (4, False)])
+def test_projection_blocks_of_several_pages(pages, joint):
+    """Long calls give a block of the projection kernel up to four consecutive pages.  Forced on a small ragged batch
+    whose appends start inside a page, end inside a block's first, middle and last page, bring fewer pages than a
+    block takes, or nothing at all."""
+    from paper_2602_08005_amd import binding as B
+    B.tune("project_pages", pages)
+    try:
+        cache, KV, W, total = _compress_case(330 + pages, [500, 0, 37, 1024, 64, 9], [130, 3, 40, 16 * pages * 3, 0, 16 * pages + 1],
+                                             Hkv=4, r=48, joint=joint, perm=7, Hq=16)
+    finally:
+        B.tune("project_pages", 0)
+    _verify(cache, KV, W, total, 16, joint)
+
+
 def test_decode_appends_one_token_at_a_time():
     import torch
     from tests.helpers import dev_bits
