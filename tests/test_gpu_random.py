@@ -80,6 +80,10 @@ def test_random_shape_and_feature_mix(seed):
     scale = float(rng.choice([0.05, 1.0 / np.sqrt(128), 0.15]))
     wuk, wuv, q = dev_bits(W["w_up_k_bf16"]), dev_bits(W["w_up_v_bf16"]), dev_bits(q_bits)
     lse = torch.zeros((B, Hq), dtype=torch.float32, device="cuda")
+    # every other case runs the reference-score kernel in its four-chunks-per-block form (a launch shape the library
+    # otherwise picks for large uniform batches only); a generator of its own keeps the cases above as they were
+    from paper_2602_08005_amd import binding as Bd
+    Bd.tune("ref_chunks", 4 if np.random.default_rng(5000 + seed).integers(0, 2) else 0)
     if c["use_raw"]:
         out = cache.decode_attn_raw(wuk, wuv, q, lens, dev_bits(rawK), dev_bits(rawV), raw_lens, scale,
                                     positions_per_seq=positions, lse=lse)
@@ -88,6 +92,7 @@ def test_random_shape_and_feature_mix(seed):
     else:
         out = cache.decode_attn(wuk, wuv, q, lens, scale, lse=lse)
     torch.cuda.synchronize()
+    Bd.tune("ref_chunks", 0)
     got, lse = out_f64(out), lse.cpu().numpy().astype(np.float64)
     for b, L in enumerate(lens):
         if L:
@@ -146,6 +151,9 @@ def test_random_compress_shapes_metrics_and_record_formats(seed):
     W = G.make_projections(seed, 128, r, joint=joint)
     KV = [G.make_kv(seed * 50 + b, max(total[b], 1), Hkv, 128, n_proto=10)[:2] for b in range(B)]
     wk, wv = dev_bits(W["w_down_k_bf16"]), dev_bits(W["w_down_v_bf16"])
+    # pages per block of the projection kernel: the library's choice (one, at these sizes) or a forced 2..4
+    from paper_2602_08005_amd import binding as Bd
+    Bd.tune("project_pages", int(np.random.default_rng(6000 + seed).choice([0, 2, 3, 4])))
     for starts, counts in (([0] * B, before), (before, new)):
         if sum(counts) == 0:
             continue
@@ -154,6 +162,7 @@ def test_random_compress_shapes_metrics_and_record_formats(seed):
         cu = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
         cache.compress(wk, wv, dev_bits(kn), dev_bits(vn), cu, np.asarray(starts, dtype=np.int32))
     torch.cuda.synchronize()
+    Bd.tune("project_pages", 0)
     what = dict(Hkv=Hkv, joint=joint, bits=bits, r=r, s=s, l2=l2, before=before, new=new)
     for b, L in enumerate(total):
         if L == 0:
