@@ -130,6 +130,13 @@ void timing_mark(int kernel_id, hipStream_t st);
 
 // LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
 size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint);
+// The streaming kernel, one function per family of template variants (stream_*.hip); each picks the rank.
+hipError_t stream_split_full(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+hipError_t stream_split_subset(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+hipError_t stream_joint_full(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+hipError_t stream_joint_subset(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+hipError_t stream_q4_joint(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+hipError_t stream_q4_split(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
 // Enqueues the four decode kernels on `st`.
 hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, size_t lds, hipStream_t st);
 

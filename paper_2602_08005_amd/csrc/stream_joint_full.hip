@@ -1,0 +1,10 @@
+// Streaming-kernel variants: one bf16 latent stream, whole cache (all ranks).
+#include "stream_kernel.h"
+
+namespace dkv {
+
+hipError_t stream_joint_full(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  return dispatch_stream<8, true, false>(P, grid, lds, st);
+}
+
+}  // namespace dkv
