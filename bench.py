@@ -71,7 +71,7 @@ def prefill_workload(args, torch, dk, B, G):
     dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-L // 16), n_ref_slots=-(-L // s),
                         latent_mode=dk.JOINT if joint else dk.SPLIT, metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
     cache = dk.PagedCache(dims, 1, L, L)
-    W = G.make_projections(G.seed_for(4), D, r, joint=joint)
+    W = G.make_projections(G.seed_for(4), D, r, joint=joint, recipe="baseline")
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv = dev(W["w_down_k_bf16"]), dev(W["w_down_v_bf16"])
     n_in = 4                                                     # distinct input sets, used round-robin
@@ -169,7 +169,7 @@ def ragged_workload(args, torch, dk, B, G):
     Lmax = int(lens.max())
     cache = dk.PagedCache(dims, nseq, Lmax, Lmax, page_ids=[pp[cp[b]:cp[b + 1]] for b in range(nseq)],
                           ref_slots=[rp[cr[b]:cr[b + 1]] for b in range(nseq)])
-    W = G.make_projections(G.seed_for(5), D, r, joint=joint)
+    W = G.make_projections(G.seed_for(5), D, r, joint=joint, recipe="baseline")
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv, wuk, wuv = (dev(W[k]) for k in ("w_down_k_bf16", "w_down_v_bf16", "w_up_k_bf16", "w_up_v_bf16"))
     order = np.argsort(lens)
@@ -249,7 +249,7 @@ def append_workload(args, torch, dk, B, G):
     dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-Lmax // 16), n_ref_slots=-(-Lmax // s),
                         latent_mode=dk.JOINT if joint else dk.SPLIT, metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
     cache = dk.PagedCache(dims, 1, L0, Lmax)
-    W = G.make_projections(G.seed_for(2), D, r, joint=joint)
+    W = G.make_projections(G.seed_for(2), D, r, joint=joint, recipe="baseline")
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv, wuk, wuv = (dev(W[k]) for k in ("w_down_k_bf16", "w_down_v_bf16", "w_up_k_bf16", "w_up_v_bf16"))
     K, V, _ = G.make_kv(G.seed_for(2), Lmax, Hkv, D, n_proto=args.protos, threads=16)
@@ -407,7 +407,7 @@ def main():
     rec_bytes = n_streams * (r // 2 + 4 if q4 else r * 2) + 4
     t_setup = time.time()
     cache = dk.PagedCache(dims, Bt, L, L)
-    W = G.make_projections(G.seed_for(3), D, r, joint=joint)
+    W = G.make_projections(G.seed_for(3), D, r, joint=joint, recipe="baseline")
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv = dev(W["w_down_k_bf16"]), dev(W["w_down_v_bf16"])
     wuk, wuv = dev(W["w_up_k_bf16"]), dev(W["w_up_v_bf16"])

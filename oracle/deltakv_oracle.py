@@ -166,29 +166,33 @@ def l2_scores(a: np.ndarray, refs: np.ndarray) -> np.ndarray:
     return -np.einsum("jn,jn->j", d, d)
 
 
+def code_positions_4bit(z: np.ndarray, scale_bits: np.ndarray, zero_bits: np.ndarray) -> np.ndarray:
+    """Unrounded level positions (z - zero) / scale of latents z [..., r] on the 16-level grid of a stored
+    record (bf16 scale and zero point, [...]); 0 where the scale is 0.  float64."""
+    scale = bf16_bits_to_f64(scale_bits)[..., None]
+    zero = bf16_bits_to_f64(zero_bits)[..., None]
+    z = np.asarray(z, dtype=np.float64)
+    return np.where(scale > 0.0, (z - zero) / np.where(scale > 0.0, scale, 1.0), 0.0)
+
+
 def quantize_tokenwise_4bit(z: np.ndarray):
     """Token-wise asymmetric 4-bit quantisation of latent vectors (section 5.3, "Compatibility with
     Quantization": the token-wise scheme of KIVI applied to the compressed residuals only).  One group
-    = the r values of one (token, head) latent.  The stored record is 16 levels per value plus a scale
-    and a zero point kept as bf16:
-        scale = bf16((max - min) / 15)      zero = bf16(min)
-        code  = clamp(round_half_even((z - zero) / scale), 0, 15)        (all codes 0 if scale = 0)
+    = the r values of one (token, head) latent; 16 levels between the group's smallest and largest value:
+        scale = (max - min) / 15          zero = min             (both then stored as bf16)
+        code  = clamp(round((z - zero) / scale), 0, 15)          (all codes 0 if scale = 0)
         value read back = scale * code + zero
-    The code is an integer decided by floating point, so it is decided in the precision the kernel
-    has: z, the subtraction, the reciprocal of the scale and the product are float32.
+    evaluated in float64 with the stored (bf16) scale and zero point, which are what a reader of the record
+    has; round = to nearest, halves to the even level.
     z: [..., r].  Returns codes uint8 [..., r], scale bits uint16 [...], zero bits uint16 [...], and
     the values read back, float64 [..., r]."""
-    z32 = np.asarray(z, dtype=np.float64).astype(np.float32)
-    mn, mx = z32.min(axis=-1), z32.max(axis=-1)
-    scale_b = f64_to_bf16_bits(((mx - mn) * np.float32(1.0 / 15.0)).astype(np.float64))
-    zero_b = f64_to_bf16_bits(mn.astype(np.float64))
-    scale = bf16_bits_to_f64(scale_b).astype(np.float32)
-    zero = bf16_bits_to_f64(zero_b).astype(np.float32)
-    with np.errstate(divide="ignore"):
-        inv = np.where(scale > 0, np.float32(1.0) / np.where(scale > 0, scale, np.float32(1.0)), np.float32(0.0))
-    q = np.rint((z32 - zero[..., None]) * inv[..., None].astype(np.float32))
-    codes = np.clip(q, 0, 15).astype(np.uint8)
-    back = scale.astype(np.float64)[..., None] * codes.astype(np.float64) + zero.astype(np.float64)[..., None]
+    z = np.asarray(z, dtype=np.float64)
+    mn, mx = z.min(axis=-1), z.max(axis=-1)
+    scale_b = f64_to_bf16_bits((mx - mn) / 15.0)
+    zero_b = f64_to_bf16_bits(mn)
+    pos = code_positions_4bit(z, scale_b, zero_b)
+    codes = np.clip(np.rint(pos), 0, 15).astype(np.uint8)          # np.rint: halves to even
+    back = bf16_bits_to_f64(scale_b)[..., None] * codes.astype(np.float64) + bf16_bits_to_f64(zero_b)[..., None]
     return codes, scale_b, zero_b, back
 
 

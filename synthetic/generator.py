@@ -104,17 +104,25 @@ def make_queries(seed: int, batch: int, n_q_heads: int, head_dim: int = 128) -> 
     return f32_to_bf16_bits(g.standard_normal((batch, n_q_heads, head_dim), dtype=np.float32))
 
 
-def make_projections(seed: int, head_dim: int, rank: int, joint: bool = False):
-    """Random orthonormal down-projection(s) and their transposes as up-projection(s).
+def make_projections(seed: int, head_dim: int, rank: int, joint: bool = False, recipe: str = "independent"):
+    """Random orthonormal down-projections and up-projections.
 
-    SPLIT (joint=False): one orthonormal head_dim x rank matrix used for both
-    streams (W_dK = W_dV), W_u = W_d^T.
-    JOINT (joint=True): an orthonormal (2*head_dim) x rank matrix; its top half
-    is W_dK and its bottom half W_dV, and W_uK / W_uV are their transposes.
+    recipe:
+      "independent" (default; what the parity tests feed both sides): the four matrices are separate draws, so a
+                   path that read one of them in place of another gives a different result.  SPLIT: W_dK and W_dV
+                   are two orthonormal head_dim x rank draws and W_uK, W_uV the transposes of two further draws;
+                   JOINT: [W_dK; W_dV] is one orthonormal (2*head_dim) x rank draw and [W_uK | W_uV] the transpose
+                   of another.
+      "paired"     distinct streams, each with W_u = W_d^T (reconstruction is the orthogonal projection of the
+                   residual): SPLIT two draws, JOINT the two halves of one (2*head_dim) x rank draw.
+      "baseline"   the benchmark's stated weights: SPLIT one orthonormal head_dim x rank matrix used for both
+                   streams (W_dK = W_dV), W_u = W_d^T; JOINT as "paired".
 
     Returns a dict with fp64 ("*_f64", unrounded) and bf16-bit ("*_bf16")
     versions of w_down_k, w_down_v [head_dim, rank] and w_up_k, w_up_v [rank, head_dim].
     """
+    if recipe not in ("independent", "paired", "baseline"):
+        raise ValueError(recipe)
     g = _rng(seed, 7_000_002)
     D = head_dim
     if joint:
@@ -122,9 +130,16 @@ def make_projections(seed: int, head_dim: int, rank: int, joint: bool = False):
         wdk, wdv = w[:D].copy(), w[D:].copy()
     else:
         wdk = orthonormal(g, D, rank)
-        wdv = wdk.copy()
-    out = {"w_down_k_f64": wdk, "w_down_v_f64": wdv,
-           "w_up_k_f64": wdk.T.copy(), "w_up_v_f64": wdv.T.copy()}
+        wdv = wdk.copy() if recipe == "baseline" else orthonormal(g, D, rank)
+    if recipe == "independent":
+        if joint:
+            u = orthonormal(g, 2 * D, rank)
+            wuk, wuv = u[:D].T.copy(), u[D:].T.copy()
+        else:
+            wuk, wuv = orthonormal(g, D, rank).T.copy(), orthonormal(g, D, rank).T.copy()
+    else:
+        wuk, wuv = wdk.T.copy(), wdv.T.copy()
+    out = {"w_down_k_f64": wdk, "w_down_v_f64": wdv, "w_up_k_f64": wuk, "w_up_v_f64": wuv}
     for k in ("w_down_k", "w_down_v", "w_up_k", "w_up_v"):
         out[k + "_bf16"] = f32_to_bf16_bits(out[k + "_f64"].astype(np.float32))
     return out

@@ -55,3 +55,32 @@ def check_attention(got, want, what="", scale_with_magnitude=False):
     assert err <= bar, f"{what}: max-abs {err}"
     assert rel <= 1e-2, f"{what}: relative L2 {rel}"
     return err, rel
+
+
+def check_q4_records(z, d, codes, sb, zb):
+    """Validity of 4-bit token-wise records (codes [..., r], bf16 bits of scale and zero point [...]) for latents
+    whose float64 values are z [..., r] and whose computed values lie within d [..., r] of them.  A record passes iff
+    it is what the definition (scale = (max - min)/15 and zero = min stored as bf16; code = the nearest level of
+    (z - zero)/scale, halves to even, clamped to 0..15) gives for SOME latent inside that error bound:
+      * zero point: a bf16 value between bf16(min - dmax) and bf16(min + dmax) -- one value, two only where the minimum
+        sits at a bf16 rounding boundary; scale likewise from (max - min -/+ 2 dmax)/15, with 2^-21 relative for an
+        fp32 product with 1/15;
+      * every code c, on the grid of the record's OWN scale and zero point: the unrounded position x = (z - zero)/scale
+        has |x - c| <= 1/2 + eps (or lies beyond the end level that c clamps to), eps = d/scale + 2^-17 (a position
+        formed in fp32 from a reciprocal: three roundings of a number below 16);
+      * scale 0 (constant latent): all codes 0.
+    A code one level off anywhere but at a half-way point fails."""
+    f, bits = O.bf16_bits_to_f64, O.f64_to_bf16_bits
+    dmax = d.max(axis=-1)
+    mn, mx = z.min(axis=-1), z.max(axis=-1)
+    zero, scale = f(zb), f(sb)
+    assert np.all((zero >= f(bits(mn - dmax))) & (zero <= f(bits(mn + dmax)))), "zero point outside its rounding window"
+    lo = np.maximum(mx - mn - 2 * dmax, 0.0) / 15.0 * (1 - 2.0 ** -21)
+    hi = (mx - mn + 2 * dmax) / 15.0 * (1 + 2.0 ** -21)
+    assert np.all((scale >= f(bits(lo))) & (scale <= f(bits(hi)))), "scale outside its rounding window"
+    x = O.code_positions_4bit(z, sb, zb)
+    c = codes.astype(np.float64)
+    eps = d / np.where(scale > 0, scale, 1.0)[..., None] + 2.0 ** -17
+    ok = (np.abs(x - c) <= 0.5 + eps) | ((c == 0) & (x <= 0.5 + eps)) | ((c == 15) & (x >= 14.5 - eps))
+    ok = np.where((scale > 0)[..., None], ok, c == 0)
+    assert np.all(ok), f"{int((~ok).sum())} codes off their level (worst |x - c| = {float(np.abs(x - c)[~ok].max())})"

@@ -98,26 +98,44 @@ def test_decode_over_4bit_records_long_sequence_and_selection(joint):
     _check_decode(case, cache, 1.0 / np.sqrt(128), positions=[np.sort(rng.choice(36000, 9000, replace=False))])
 
 
+def _latent_error_bound(case, b, stream):
+    """Bound on |z_gpu - z_oracle| per latent value, [L, H, r].  The kernels form the residual exactly in fp32, feed
+    it to the matrix unit as bf16 hi + lo parts (what is dropped is below 2^-18 of the element) or to fp32 FMAs, and
+    accumulate at most 2 x 256 products in fp32 (each addition rounds to 2^-24 of the running sum, itself at most the
+    sum of the terms' magnitudes): (2^-18 + 512 * 2^-24) * sum_i |r_i| |W_ic| < 2^-14 * sum_i |r_i| |W_ic|."""
+    from tests.helpers import f64
+    res, s = case.res[b], case.s
+    K, V = f64(case.K[b]), f64(case.V[b])
+    tok_ref = res["idx"].astype(np.int64) * s
+    hh = np.arange(case.Hkv)[None, :]
+    t = np.arange(K.shape[0])[:, None]
+    ak, av = np.abs(K[t, hh] - K[tok_ref, hh]), np.abs(V[t, hh] - V[tok_ref, hh])
+    wk, wv = np.abs(f64(case.W["w_down_k_bf16"])), np.abs(f64(case.W["w_down_v_bf16"]))
+    if case.joint:
+        mag = ak @ wk + av @ wv
+    else:
+        mag = av @ wv if stream else ak @ wk
+    return 2.0 ** -14 * mag + 1e-30
+
+
 def _compare_records(case, cache, b, t0, t1, stream=0):
-    """GPU-written 4-bit records of tokens t0..t1-1 against the oracle's.  The codes are integers decided by fp32
-    arithmetic on latents that the two sides accumulate in different orders, so: scale and zero point equal in all
-    but a few tokens (and then within one bf16 step), codes equal in nearly all values and never more than one
-    level apart where the token's scale and zero point agree, values read back within one quantisation step."""
+    """GPU-written 4-bit records of tokens t0..t1-1 against the oracle's definition: accepted iff they are what
+    the definition gives for some latent within the kernels' arithmetic error of the oracle's float64 latent
+    (tests.helpers.check_q4_records); the oracle's own record is the outcome in nearly all tokens."""
     from oracle import deltakv_oracle as O
     r = case.res[b]
     idx, codes, sb, zb = cache.get_sequence_q4(b, t0, t1, stream)
     assert np.array_equal(idx, r["idx"][t0:t1])
     sfx = "_v" if stream else "_k"
-    want_c, want_s, want_z = r["q" + sfx][t0:t1], r["qs" + sfx][t0:t1], r["qz" + sfx][t0:t1]
-    same = (sb == want_s) & (zb == want_z)
-    assert same.mean() > 0.99, same.mean()
-    assert np.all(np.abs(sb.astype(np.int64) - want_s.astype(np.int64)) <= 1)
-    assert np.all(np.abs(zb.astype(np.int64) - want_z.astype(np.int64)) <= 1)
-    dc = np.abs(codes.astype(np.int64) - want_c.astype(np.int64))
-    assert np.all(dc[same] <= 1) and (dc[same] == 0).mean() > 0.99, ((dc[same] == 0).mean(), dc.max())
-    back = O.bf16_bits_to_f64(sb)[..., None] * codes + O.bf16_bits_to_f64(zb)[..., None]
-    step = O.bf16_bits_to_f64(want_s)[..., None]
-    assert np.all(np.abs(back - r["zq" + sfx][t0:t1]) <= 1.01 * step + 1e-6)
+    z = r["z" + sfx][t0:t1]
+    d = _latent_error_bound(case, b, stream)[t0:t1]
+    from tests.helpers import check_q4_records
+    check_q4_records(z, d, codes, sb, zb)
+    scale, zero = O.bf16_bits_to_f64(sb), O.bf16_bits_to_f64(zb)
+    # and the oracle's own record is the usual outcome: identical in nearly all tokens
+    same = (sb == r["qs" + sfx][t0:t1]) & (zb == r["qz" + sfx][t0:t1])
+    assert same.mean() > 0.99 and (codes[same] == r["q" + sfx][t0:t1][same]).mean() > 0.99
+    back = scale[..., None] * codes + zero[..., None]
     return idx, back
 
 

@@ -29,7 +29,7 @@ def _f64(bits):
 
 def _small_case(seed=1, L=96, H=2, D=16, r=8, s=4, n_proto=6, joint=False):
     K, V, cls = G.make_kv(seed, L, H, D, n_proto=n_proto, basis_dim=4)
-    P = G.make_projections(seed, D, r, joint=joint)
+    P = G.make_projections(seed, D, r, joint=joint, recipe="paired")
     return _f64(K), _f64(V), cls, P
 
 
@@ -184,10 +184,8 @@ def test_full_rank_orthonormal_reconstructs_exactly(joint):
     D = 16
     r = 2 * D if joint else D
     K, V, cls, _ = _small_case(seed=13, L=80, H=2, D=D, r=8, s=4)
-    P = G.make_projections(99, D, r, joint=joint)
-    if not joint:      # distinct projections per stream, so that swapping them is caught
-        P2 = G.make_projections(100, D, r)
-        P["w_down_v_f64"], P["w_up_v_f64"] = P2["w_down_k_f64"], P2["w_up_k_f64"]
+    P = G.make_projections(99, D, r, joint=joint, recipe="paired")   # distinct per stream: swapping them is caught
+    assert joint or np.max(np.abs(P["w_down_k_f64"] - P["w_down_v_f64"])) > 0.1
     mode = O.JOINT if joint else O.SPLIT
     res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4, mode=mode)
     kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
@@ -302,7 +300,7 @@ def test_zero_residual_equals_dense_attention_over_gathered_references():   # P5
 def test_full_rank_decode_equals_dense_attention_over_raw_kv():
     D = 16
     K, V, cls, _ = _small_case(seed=31, L=70, H=2, D=D, r=8, s=4)
-    P = G.make_projections(5, D, D)
+    P = G.make_projections(5, D, D, recipe="paired")
     res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4)
     q = _f64(G.make_queries(31, 1, 4, D))[0]
     out, _ = O.decode_attn_direct(q, res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
@@ -470,6 +468,25 @@ def test_4bit_quantiser_exact_on_a_16_level_grid_and_degenerate_vectors():
     assert np.all(c3 == 0) and np.all(s3 == 0) and np.all(z3 == 0) and np.all(b3 == 0)
 
 
+def test_4bit_quantiser_halfway_points_go_to_the_even_level_and_are_decided_in_fp64():
+    """Values exactly half-way between two levels of a bf16-exact grid take the even level (0.5 -> 0, 1.5 -> 2,
+    2.5 -> 2, ... 14.5 -> 14): round-half-up or round-half-away would give 1, 2, 3, ... 15.  A value a hair under a
+    half-way point (2^-30 of the step, far below fp32 resolution) stays on the lower level although it rounds to the
+    half-way point -- and from there up, when the lower level is odd -- once it is squeezed into fp32: the decision
+    is taken on the float64 latent."""
+    half = np.arange(15) + 0.5
+    z = -2.0 + 0.125 * np.concatenate([[0.0, 15.0], half])          # origin -2, step 1/8: exact in bf16
+    codes, sb, zb, back = O.quantize_tokenwise_4bit(z[None, :])
+    assert O.bf16_bits_to_f64(sb)[0] == 0.125 and O.bf16_bits_to_f64(zb)[0] == -2.0
+    assert codes[0, :2].tolist() == [0, 15]
+    assert codes[0, 2:].tolist() == [0, 2, 2, 4, 4, 6, 6, 8, 8, 10, 10, 12, 12, 14, 14]
+    assert np.array_equal(O.code_positions_4bit(z[None, :], sb, zb)[0, 2:], half)
+    under = -2.0 + 0.125 * (half * (1.0 - 2.0 ** -30))
+    assert np.all(under.astype(np.float32).astype(np.float64) == -2.0 + 0.125 * half)   # fp32 cannot tell them apart
+    c2 = O.quantize_tokenwise_4bit(np.concatenate([[-2.0, -0.125], under])[None, :])[0]
+    assert c2[0, 2:].tolist() == list(range(15))
+
+
 def test_4bit_quantiser_error_bound_monotonicity_and_record_accounting():
     """|read back - z| <= half a step plus the bf16 rounding of scale and zero point; codes are monotone in z; the
     smallest value gets code 0 and the largest 15; keep ratio of the 4-bit record in closed form."""
@@ -588,3 +605,46 @@ def test_generator_recipe_statistics():
     assert abs(np.mean([cs(i, i - 1) for i in range(1, 400) if cls[i, 0] != cls[i - 1, 0]])) < 0.1
     # per-token energy: 128 (prototype) + 32 (basis part, variance 2 x 16) + 0.32 (noise)
     assert abs(np.mean(np.sum(Kf * Kf, -1)) - 160.3) < 4.0
+
+
+def test_4bit_record_validity_criterion_accepts_fp32_decisions_and_rejects_planted_mistakes():
+    """The criterion the GPU records are held to (tests.helpers.check_q4_records), exercised on the CPU: records
+    produced from latents perturbed inside the error bound, with the decisions taken in fp32, pass; a code moved one
+    level away from a point that is not half-way, a scale or zero point one bf16 step off where no rounding boundary
+    is near, a code two levels from an exact half-way point, and a non-zero code under a zero scale all fail.  (At an
+    exact half-way point of the float64 latent either neighbour passes: the computed latent may lie on either side.
+    That the definition itself takes the even one is pinned on the oracle above.)"""
+    from tests.helpers import check_q4_records
+    rng = np.random.default_rng(11)
+    z = rng.standard_normal((400, 3, 32)) * rng.uniform(0.05, 8.0, size=(400, 3, 1))
+    d = np.full(z.shape, 1e-5) * np.abs(z).max(-1, keepdims=True)
+    z32 = (z + rng.uniform(-1, 1, size=z.shape) * d).astype(np.float32)
+    mn, mx = z32.min(-1), z32.max(-1)
+    sb = O.f64_to_bf16_bits(((mx - mn) * np.float32(1 / 15)).astype(np.float64))
+    zb = O.f64_to_bf16_bits(mn.astype(np.float64))
+    sc, zp = O.bf16_bits_to_f64(sb).astype(np.float32), O.bf16_bits_to_f64(zb).astype(np.float32)
+    codes = np.clip(np.rint((z32 - zp[..., None]) * (np.float32(1) / sc)[..., None]), 0, 15).astype(np.uint8)
+    check_q4_records(z, d, codes, sb, zb)
+    x = O.code_positions_4bit(z, sb, zb)
+    i = np.unravel_index(np.argmin(np.abs(x - np.rint(x)) + (np.rint(x) > 14) + (np.rint(x) < 1)), x.shape)
+    bad = codes.copy()
+    bad[i] += 1                                              # a value sitting on a level, moved one level up
+    with pytest.raises(AssertionError):
+        check_q4_records(z, d, bad, sb, zb)
+    for arr in (sb, zb):                                     # a stored parameter one bf16 step off, everywhere
+        off = arr.copy()
+        off += 1
+        with pytest.raises(AssertionError):
+            check_q4_records(z, d, codes, off if arr is sb else sb, off if arr is zb else zb)
+    zg = (-2.0 + 0.125 * np.concatenate([[0.0, 15.0], np.arange(15) + 0.5]))[None, :]
+    cg, sg, zg_b, _ = O.quantize_tokenwise_4bit(zg)
+    tiny = np.full(zg.shape, 1e-12)
+    check_q4_records(zg, tiny, cg, sg, zg_b)
+    up = np.concatenate([[0, 15], np.arange(15) + 1]).astype(np.uint8)[None, :]
+    check_q4_records(zg, tiny, up, sg, zg_b)                 # at an exact half-way point both neighbours are within eps
+    with pytest.raises(AssertionError):
+        check_q4_records(zg, tiny, (up + 1).clip(0, 15).astype(np.uint8), sg, zg_b)
+    const = np.full((1, 8), 0.375)
+    with pytest.raises(AssertionError):
+        check_q4_records(const, np.full(const.shape, 1e-12), np.ones((1, 8), np.uint8), np.zeros(1, np.uint16),
+                         O.f64_to_bf16_bits(np.array([0.375])))
