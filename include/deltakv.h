@@ -207,16 +207,22 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* layout,
  *                 scaled logits, or NULL
  *   workspace     device, >= layout->decode_ws_bytes, aligned.  Its first int32 is
  *                 a status word written by the call (read it after the stream has
- *                 run the work; 0 = result good):
- *                   bit 0  a logit lay more than about 41 nats above every
- *                          reference token's logit, outside the range the fixed
- *                          exponent offset of the softmax can hold;
- *                   bit 1  more than 256 softmax weights in one block were at
- *                          least 2^11 times the weight of the token's own
- *                          reference, or accumulated past the 32-bit range of an
- *                          on-chip table entry: some weights were dropped.
- *                 Neither happens with residuals that are small next to the
- *                 references they refine; the output is not to be trusted if set.
+ *                 run the work).  It is diagnostic only -- out and lse are the attention
+ *                 defined above whatever it says: the main kernels keep every softmax
+ *                 weight in one fixed exponent frame per (sequence, q-head) around the
+ *                 largest reference score, and an output row that leaves the frame is
+ *                 recomputed inside the same call by a slow kernel that takes the row's
+ *                 own largest logit as its offset.  The word says that this happened:
+ *                   bit 0  a row left the frame: a logit 86 nats or more above every
+ *                          reference token's logit (55 nats in a call with a selection),
+ *                          or a selection whose tokens all lie 55 nats or more below the
+ *                          largest reference score of the sequence;
+ *                   bit 1  more than 256 softmax weights in one block were at least 2^11
+ *                          times the weight of the token's own reference, or accumulated
+ *                          past the 32-bit range of an on-chip table entry.
+ *                 Neither happens with residuals that are small next to the references
+ *                 they refine; a set bit means the call took milliseconds instead of
+ *                 microseconds for the rows concerned.
  * Errors: INVALID_ARG, UNSUPPORTED (a sequence needs more on-chip table space
  * than one compute unit has: roughly seq_len/ref_stride * g > 39000 in SPLIT and
  * > 34000 in JOINT mode, g = queries per kv-head rounded up to 4, 8 or 16),
@@ -245,9 +251,9 @@ int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* layout,
  * gets out = 0 and lse = -inf.  out / lse are the softmax over the selected tokens
  * only.  Whole pages are streamed, so a selection costs the traffic of the pages it
  * touches: it is cheapest when selected tokens share pages.  Every raw reference
- * is still scored once per call.  The exponent offset of the softmax is the largest
- * reference score of the sequence; if every selected token's logit lies more than
- * about 40 nats below it the weights underflow and bit 0 of the status word is set.
+ * is still scored once per call.  The exponent frame of the softmax hangs on the largest
+ * reference score of the sequence, selected or not; rows whose selected tokens all lie far
+ * below it are recomputed by the slow kernel (bit 0 of the status word).
  * Other arguments, workspace, status word and errors as deltakv_decode_attn. */
 int deltakv_decode_attn_subset(const deltakv_dims* dims, const deltakv_layout* layout,
                                const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
@@ -293,7 +299,10 @@ const char* deltakv_strerror(int code);
 const char* deltakv_last_error_detail(void);
 int deltakv_version(void);
 
-/* Launch-shape overrides for benchmark sweeps (process-wide; value 0 restores the automatic choice):
+/* The library keeps process-wide state without locks (the launch-shape overrides below, the timing marks, the
+ * first-call kernel attributes): call it from one thread at a time.
+ *
+ * Launch-shape overrides for benchmark sweeps (process-wide; value 0 restores the automatic choice):
  *   "stream_waves"  waves per block of the decode streaming kernel (8)
  *   "splits"        token-range splits per (sequence, kv-head) in decode (1..16)
  *   "sim_tb"        16-token blocks per wave of the similarity kernel (1..4)
@@ -312,7 +321,7 @@ int deltakv_tune(const char* name, int32_t value);
  * returns, per kernel, the summed time between the surrounding events in milliseconds (this includes
  * the launch gap in front of the kernel) and the number of launches (with "timing_period" p set through
  * deltakv_tune, of the calls 0, p, 2p, ... of the region).  Kernel order:
- *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize   (deltakv_decode_attn)
+ *   0 ref_scores, 1 stream, 2 ref_values, 3 finalize + rescue   (deltakv_decode_attn)
  *   4 admit_refs, 5 sim_top2, 6 resolve, 7 exact, 8 project   (deltakv_compress; a call that appends exactly
  *     one token to every sequence runs two kernels, reported as 5 (candidate scan) and 8 (finish))
  *   9 raw_attn   (deltakv_decode_attn_raw with a raw segment)

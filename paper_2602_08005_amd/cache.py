@@ -185,6 +185,12 @@ class PagedCache:
             .reshape(n_ref, self.dims.n_kv_heads)
         return res[0], res[1], nrm
 
+    def status(self) -> int:
+        """Status word of the last decode call on this cache's workspace (synchronises the device).  Diagnostic:
+        non-zero means some output rows were recomputed by the library's slow exact kernel."""
+        self.torch.cuda.synchronize()
+        return int(self.decode_ws[:4].view(self.torch.int32)[0].item())
+
     # -- calls ------------------------------------------------------------------------------------
     def compress(self, w_down_k, w_down_v, k_new, v_new, cu_new_host, len_before_host, stream=None,
                  first_seq: int = 0):

@@ -17,10 +17,15 @@ constexpr int kRawChunk = 256;     // raw-segment tokens handled by one block
 constexpr int kRawMaxChunks = 16;  // a raw segment holds at most kRawChunk * kRawMaxChunks tokens per sequence
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-// Softmax weights are 2^(x - m_ref - kExpBias) with m_ref the largest per-reference score; every
-// reference token is itself attended with a zero latent, so the true maximum is >= m_ref and the
-// weights cannot all underflow.  The bias leaves 2^(127-kExpBias) of headroom above m_ref.
+// Softmax weights are 2^(x - m_ref - bias) with m_ref the largest per-reference score.  Attention over the whole
+// cache: every reference token is itself attended with a zero latent, so the true maximum is >= m_ref, the weight
+// sum is >= 2^-64 and only the room above m_ref matters: 124 log2 units (86 nats) before a sum reaches 2^60.
+// Attention over a selection: the selected tokens may lie anywhere below m_ref, so the frame is centred: 80 log2
+// units (55 nats) either way before the sum leaves [2^-100, 2^60).  Rows outside go to the rescue kernel.
 constexpr float kExpBias = 64.0f;
+constexpr float kExpBiasSubset = 20.0f;
+__host__ __device__ inline float exp_bias(bool subset) { return subset ? kExpBiasSubset : kExpBias; }
+constexpr float kSumLo = 0x1p-100f, kSumHi = 0x1p60f;      // sums of weights a streaming result is accepted with
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
@@ -58,6 +63,7 @@ __host__ __device__ inline int refs_below(int end_tok, int stride) { return ceil
 // ---- decode workspace carving (host computes, kernels receive pointers) -------------------------
 struct DecodeWs {
   int64_t status;   // int32[4]   bit 0: a logit left the range the biased exponent can hold
+  int64_t rescue;   // int32 [B][Hq]  rows to be recomputed by the rescue kernel
   int64_t qlat;     // bf16 [2][B][Hq][R]         (W_uK q) * scale * log2(e), split into bf16 hi + lo parts
   int64_t sref;     // fp32 [B][Hkv][n_ref_max][Gp]  per-reference scores, log2 units
   int64_t cmax;     // fp32 [B][Hkv][n_chunk_max][Gp] per-chunk maxima of sref
@@ -78,6 +84,7 @@ inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_r
   int64_t o = 0;
   auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
   w.status = take(16);
+  w.rescue = take(batch * d.n_q_heads * 4);
   w.qlat = take(2 * batch * d.n_q_heads * R * 2);
   w.sref = take(BH * n_ref_max * Gp * 4);
   w.cmax = take(BH * nch * Gp * 4);

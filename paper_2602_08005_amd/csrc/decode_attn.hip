@@ -11,14 +11,15 @@
 // work is two small contractions against the latent streams.  Four kernels per call:
 //   ref_scores  : S_ref for every reference ordinal (MFMA, q x K_ref tiles), chunk maxima, W_uK q
 //   stream      : the HBM-bound pass over latents + indices; scores and the weighted latent sum on MFMA,
-//                 w_j accumulated in an LDS table with hardware float atomics, one partial set per split
+//                 w_j accumulated in a 32-bit fixed-point LDS table with integer atomics (plus a short list for the
+//                 rare amounts that do not fit an entry), one partial set per (sequence, split) item
 //   ref_values  : sum_j w_j V_ref[j] per reference chunk
 //   finalize    : merges splits/chunks, up-projects the latent sum through W_uV, normalises, writes bf16
 // (a fifth, raw_attn, runs first when the call brings a segment of uncompressed sink / recent tokens)
 // All softmax weights use one fixed exponent offset per (sequence, q-head): m_ref = max_j S_ref[j].  A
 // reference token is cached with idx = own ordinal and z = 0, so its logit IS S_ref[j]; the true maximum
 // is therefore >= m_ref, partial sums from different waves/splits add without rescaling, and the sum of
-// weights is >= 2^-kExpBias > 0.
+// weights is >= 2^-64 > 0 (attention over a selection has no such floor: see the rescue kernel).
 #include "decode_common.h"
 
 namespace dkv {
@@ -72,6 +73,8 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
       at += ns;
     }
   }
+  // (as are the rescue flags of this pair's query heads, by the pair's first block)
+  if (chunk0 == 0 && (int)threadIdx.x < P.G) P.rescue[(int64_t)b * P.Hq + (int64_t)h * P.G + threadIdx.x] = 0;
   const int L = seq_len_of(P, b);
   const int n_ref = refs_below(L, P.stride);
   if (chunk0 * kRefChunk >= n_ref) return;
@@ -208,9 +211,10 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   float wfix[GP], wplain[GP], sj[GP];          // fixed-point sums, sums of tables already in plain units, scores
 #pragma unroll
   for (int g = 0; g < GP; ++g) { wfix[g] = 0.f; wplain[g] = 0.f; sj[g] = 0.f; }
-  int slot = 0;
+  // rows past the sequence's last reference carry weight 0; they re-read the last valid reference's row (never a
+  // slot the caller did not admit: 0 * garbage could be NaN)
+  const int slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + min(j, n_ref - 1)], 0, (int)P.n_ref_slots - 1);
   if (j < n_ref) {
-    slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + j], 0, (int)P.n_ref_slots - 1);
     uint32_t plain = 0;                        // splits whose table already holds plain weights (rare)
     uint32_t wrote = 0;                        // splits whose table covers ordinal j
 #pragma unroll
@@ -256,7 +260,7 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
     __syncthreads();
     if (tid < GP) {
       for (int k = 1; k < 256 / GP; ++k) m = fmaxf(m, cpart[k * GP + tid]);
-      shift_s[tid] = table_shift_base(m);
+      shift_s[tid] = table_shift_base(m, exp_bias(P.sel_pages != nullptr));
     }
     __syncthreads();
   }
@@ -464,6 +468,35 @@ __global__ __launch_bounds__(256) void k_raw_attn(DecodeParams P) {
   }
 }
 
+// Last step of an output row (thread = output dim d): the cached part arrives as (sum of weights lsum, weighted value
+// sum o, both in units of 2^frame); the raw-segment chunks are merged at the largest of all frames, so no factor
+// exceeds 1; then normalise and store.  Nothing to attend (no weight anywhere) gives out = 0 and lse = -inf.
+__device__ inline void finish_output(const DecodeParams& P, int b, int gh, int h, int g, int d, float lsum, float o,
+                                     float frame, int n_raw) {
+  const int Gp = P.Gp;
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
+  if (n_raw > 0) {
+    const int nrc = ceil_div(n_raw, kRawChunk);
+    const float* ml = P.rawml + ((bh * kRawMaxChunks) * Gp + g) * 2;
+    float top = lsum > 0.f ? frame : -INFINITY;
+    for (int c = 0; c < nrc; ++c) top = fmaxf(top, ml[(int64_t)c * Gp * 2]);
+    const float fc = lsum > 0.f ? __builtin_amdgcn_exp2f(frame - top) : 0.f;
+    lsum *= fc;
+    o *= fc;
+    const float* ro = P.rawo + ((bh * kRawMaxChunks) * Gp + g) * kHeadDim + d;
+    for (int c = 0; c < nrc; ++c) {
+      const float f = __builtin_amdgcn_exp2f(ml[(int64_t)c * Gp * 2] - top);
+      lsum += f * ml[(int64_t)c * Gp * 2 + 1];
+      o += f * ro[(int64_t)c * Gp * kHeadDim];
+    }
+    frame = top;
+  }
+  const bool any = lsum > 0.f;
+  P.out[orow + d] = any ? (uint16_t)f32_to_bf16_bits(o / lsum) : (uint16_t)0;
+  if (d == 0 && P.lse) P.lse[(int64_t)b * P.Hq + gh] = any ? (frame + __log2f(lsum)) * kLn2 : -INFINITY;
+}
+
 // ------------------------------------------------------------------------------------------------
 // finalize: grid (Hq, B), 128 threads (thread = output dim d); one block per query head.
 // ------------------------------------------------------------------------------------------------
@@ -489,7 +522,7 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   __shared__ float zsum[128];
   __shared__ float redm[2];
   const int64_t bh = (int64_t)b * P.Hkv + h;
-  // the cached tokens: weights 2^(x - frame), frame = m_ref + kExpBias
+  // the cached tokens: weights 2^(x - frame), frame = m_ref + bias
   float lsum = 0.f, o = 0.f, frame = -INFINITY;
   if (n_pages > 0) {                        // uniform over the block
     const int n_ref = refs_below(L, P.stride);
@@ -523,7 +556,7 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
       if (d < R) zsum[d] = a;
     }
     __syncthreads();
-    frame = fmaxf(redm[0], redm[1]) + kExpBias;
+    frame = fmaxf(redm[0], redm[1]) + exp_bias(P.sel_pages != nullptr);
     const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
     const int64_t cstride = (int64_t)Gp * kHeadDim;
     int c = 0;
@@ -537,29 +570,145 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
     for (; c < nch; ++c) o += op[c * cstride];
 #pragma unroll
     for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wcol[cc]);
-    // a weight of 2^60 or more (exponent argument ~60 above the biased offset) risks overflow of the fp32 sums;
-    // any such weight makes the sum at least that large
-    if (d == 0 && (!(lsum < 0x1p60f) || !(lsum > 0.f))) atomicOr(P.status, 1);
-  }
-  if (n_raw > 0) {
-    // merge the raw chunks: everything is brought to the largest frame, so no factor exceeds 1
-    const int nrc = ceil_div(n_raw, kRawChunk);
-    const float* ml = P.rawml + ((bh * kRawMaxChunks) * Gp + g) * 2;
-    float top = lsum > 0.f ? frame : -INFINITY;
-    for (int c = 0; c < nrc; ++c) top = fmaxf(top, ml[(int64_t)c * Gp * 2]);
-    const float fc = lsum > 0.f ? __builtin_amdgcn_exp2f(frame - top) : 0.f;
-    lsum *= fc;
-    o *= fc;
-    const float* ro = P.rawo + ((bh * kRawMaxChunks) * Gp + g) * kHeadDim + d;
-    for (int c = 0; c < nrc; ++c) {
-      const float f = __builtin_amdgcn_exp2f(ml[(int64_t)c * Gp * 2] - top);
-      lsum += f * ml[(int64_t)c * Gp * 2 + 1];
-      o += f * ro[(int64_t)c * Gp * kHeadDim];
+    // The fixed exponent frame holds weights between 2^-126 and 2^127.  A weight of 2^60 or more (any such weight
+    // makes the sum at least that large) risks overflow of the fp32 sums; a sum below 2^-100 means every attended
+    // token lies so far under the largest reference score that weights of some weight may have been flushed to
+    // zero (only a selection can do that: a reference token of the full cache weighs 2^-64 or more; with the sum
+    // at 2^-100 or more a flushed weight is below 2^-26 of it).  Such a row is recomputed by the rescue kernel
+    // with the row's exact maximum as its offset.
+    if (d == 0 && !(lsum >= kSumLo && lsum < kSumHi)) {
+      atomicOr(P.status, 1);
+      P.rescue[(int64_t)b * P.Hq + gh] = 1;
     }
-    frame = top;
   }
-  P.out[orow + d] = (uint16_t)f32_to_bf16_bits(o / lsum);
-  if (d == 0 && P.lse) P.lse[(int64_t)b * P.Hq + gh] = (frame + __log2f(lsum)) * kLn2;
+  finish_output(P, b, gh, h, g, d, lsum, o, frame, n_raw);
+}
+
+// ------------------------------------------------------------------------------------------------
+// rescue: grid (Hq, B), 256 threads.  The streaming path keeps every softmax weight in one fixed frame per
+// (sequence, q-head), 2^(x - m_ref - bias) with m_ref the largest per-reference score; that holds logits up to 86
+// nats above m_ref (55 nats either way for a selection), which is where reconstructed keys of small residuals live.
+// A row whose weights left that range (finalize saw a sum at or beyond 2^60, or below 2^-100), or whose block ran out of room for oversized table
+// amounts, is flagged, and this kernel -- launched with every call, a few microseconds when no row is flagged --
+// recomputes the flagged rows from the cache by the definition: pass 1 finds the exact largest logit of the row,
+// pass 2 accumulates weights against it (all <= 1), sum_t p_t V_ref[idx_t] and sum_t p_t z_V,t directly.  Slow
+// (every latent value is fetched on its own) and always right; logits use the same operands as the streaming
+// kernel (per-reference scores and W_uK q of ref_scores, in log2 units).
+// ------------------------------------------------------------------------------------------------
+// Latent value c of token `tok` in the (page, head, stream) block that starts at `blk` (any of the four layouts).
+__device__ inline float latent_value(const DecodeParams& P, const uint16_t* blk, int tok, int c, bool value_stream) {
+  if (!P.q4) {
+    const int at = value_stream ? ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3)
+                                : ((c >> 3) * kPage + tok) * 8 + (c & 7);
+    return bf16lo(blk[at]);
+  }
+  const uint32_t* words = reinterpret_cast<const uint32_t*>(blk);
+  uint32_t code;
+  if (value_stream) {
+    const uint32_t w = words[2 * ((c >> 6) * 64 + (tok >> 2) * 16 + (c & 15)) + ((tok & 3) >> 1)];
+    code = (w >> (4 * ((c >> 4) & 3) + 16 * (tok & 1))) & 15u;
+  } else {
+    const uint32_t w = words[(c >> 3) * kPage + tok];
+    code = (w >> (4 * ((c & 7) >> 1) + 16 * (c & 1))) & 15u;
+  }
+  const uint16_t* sz = blk + 4 * P.R + (tok >> 2) * 8 + (tok & 3);      // four scales, then four zero points
+  return bf16lo(sz[0]) * (float)code + bf16lo(sz[4]);
+}
+
+__global__ __launch_bounds__(256) void k_rescue(DecodeParams P) {
+  const int gh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  if (P.rescue[(int64_t)b * P.Hq + gh] == 0) return;
+  const int G = P.G, Gp = P.Gp, R = P.R;
+  const int h = gh / G, g = gh % G;
+  const int L = seq_len_of(P, b);
+  const int n_ent = work_pages_of(P, b, L);                  // entries of the page list (>= 1: the row was flagged)
+  const int n_raw = P.raw_k ? clampi(P.raw_lens[b], 0, P.raw_cap) : 0;
+  const int n_ref = refs_below(L, P.stride);
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  __shared__ float ql[kHeadDim];        // W_uK q of this head (hi + lo), log2 units
+  __shared__ float pw[256];             // weights of the current tile
+  __shared__ int psl[256];              // reference slot of each token of the tile
+  __shared__ float red[256];
+  if (tid < R) {
+    const int64_t at = ((int64_t)b * P.Hq + gh) * R + tid;
+    ql[tid] = bf16lo(P.qlat[at]) + bf16lo(P.qlat[P.qlat_lo_offset + at]);
+  }
+  __syncthreads();
+  const float* sref = P.sref + bh * P.n_ref_max * Gp + g;
+  const int last_logical = ceil_div(L, kPage) - 1;
+  // token i of the row = (list entry i / 16, slot i % 16); returns whether it takes part, its logit and ordinal
+  auto token = [&](int i, float& x, int& ord, const uint16_t*& blk) {
+    const int e = i >> 4, tok = i & 15;
+    if (e >= n_ent) return false;
+    int logical = e;
+    uint32_t mask = 0xffffu;
+    if (P.sel_pages) {
+      logical = P.sel_pages[(int64_t)b * P.sel_stride + e];
+      mask = (uint32_t)P.sel_masks[(int64_t)b * P.sel_stride + e];
+      if ((uint32_t)logical > (uint32_t)last_logical) return false;
+    }
+    if (logical * kPage + tok >= L || !((mask >> tok) & 1u)) return false;
+    const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
+    ord = (int)min((uint32_t)P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok],
+                   (uint32_t)(n_ref - 1));
+    blk = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+    float acc = 0.f;
+    for (int c = 0; c < R; ++c) acc += ql[c] * latent_value(P, blk, tok, c, false);
+    x = sref[(int64_t)ord * Gp] + acc;
+    return true;
+  };
+  const int n_tok = n_ent * kPage;
+  // pass 1: the row's largest logit
+  float m = -INFINITY;
+  for (int i = tid; i < n_tok; i += 256) {
+    float x; int ord; const uint16_t* blk;
+    if (token(i, x, ord, blk)) m = fmaxf(m, x);
+  }
+  red[tid] = m;
+  __syncthreads();
+  for (int o2 = 128; o2 > 0; o2 >>= 1) {
+    if (tid < o2) red[tid] = fmaxf(red[tid], red[tid + o2]);
+    __syncthreads();
+  }
+  m = red[0];
+  __syncthreads();
+  // pass 2: tiles of 256 tokens; threads 0..127 own an output dim, threads 128..255 a latent column
+  float lsum = 0.f, o = 0.f, zs = 0.f;
+  const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;
+  const int64_t vstream = P.joint ? 0 : P.latent_stream_stride;
+  for (int i0 = 0; i0 < n_tok; i0 += 256) {
+    float x; int ord = 0; const uint16_t* blk = nullptr;
+    const bool on = token(i0 + tid, x, ord, blk);
+    pw[tid] = on ? __builtin_amdgcn_exp2f(x - m) : 0.f;
+    psl[tid] = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
+    __syncthreads();
+    const int n_here = min(256, n_tok - i0);
+    if (tid < 128) {
+      for (int t = 0; t < n_here; ++t) {
+        const float p = pw[t];
+        if (p != 0.f) o += p * bf16lo(vbase[(int64_t)psl[t] * kHeadDim + tid]);
+        lsum += p;
+      }
+    } else if (tid - 128 < R) {
+      for (int t = 0; t < n_here; ++t) {
+        const float p = pw[t];
+        if (p == 0.f) continue;                                // tokens that take no part may hold anything
+        const int i = i0 + t, e = i >> 4;
+        const int logical = P.sel_pages ? P.sel_pages[(int64_t)b * P.sel_stride + e] : e;
+        const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
+        const uint16_t* vb = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride + vstream;
+        zs += p * latent_value(P, vb, i & 15, tid - 128, !P.joint);
+      }
+    }
+    __syncthreads();
+  }
+  // up-projection of the weighted latent sum
+  red[tid] = zs;
+  __syncthreads();
+  if (tid < 128) {
+    for (int c = 0; c < R; ++c) o += red[128 + c] * bf16lo(P.w_up_v[(int64_t)c * kHeadDim + tid]);
+    finish_output(P, b, gh, h, g, tid, lsum, o, m, n_raw);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -624,7 +773,9 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
     case 128: hipLaunchKernelGGL(k_finalize<128>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
     default: return hipErrorInvalidValue;
   }
-  e = note_hip_error(hipGetLastError(), "launch of finalize");
+  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of finalize");
+  hipLaunchKernelGGL(k_rescue, dim3(P.Hq, batch), dim3(256), 0, st, P);
+  e = note_hip_error(hipGetLastError(), "launch of rescue");
   timing_mark(K_FINALIZE, st);
   return e;
 }

@@ -45,8 +45,8 @@ constexpr int kFixQ = 20;
 constexpr int kOvfCap = 256;
 // Entry (j, g) is kept in units of 2^-table_shift(S_ref[j][g], base(m_ref[g])): an integer within one of
 // kFixQ - s_j.  Both kernels evaluate exactly these two expressions, so they agree bit for bit.
-__device__ inline float table_shift_base(float mref) { return mref + (kExpBias + (float)kFixQ); }
-// (base - sref >= kExpBias + kFixQ; the conversion saturates and the scaling by a power of two takes any exponent, so
+__device__ inline float table_shift_base(float mref, float bias) { return mref + (bias + (float)kFixQ); }
+// (base - sref >= bias + kFixQ; the conversion saturates and the scaling by a power of two takes any exponent, so
 // no clamp is needed: an absurdly distant score just turns its weights into overflow-list records or zeros)
 __device__ inline int table_shift(float sref, float base) { return (int)(base - sref); }
 

@@ -368,6 +368,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   Pm.qk_scale_log2 = scale * kLog2e;
   char* wsb = static_cast<char*>(workspace);
   Pm.status = reinterpret_cast<int32_t*>(wsb + ws.status);
+  Pm.rescue = reinterpret_cast<int32_t*>(wsb + ws.rescue);
   Pm.qlat = reinterpret_cast<uint16_t*>(wsb + ws.qlat);
   Pm.qlat_lo_offset = (int64_t)batch * dims->n_q_heads * R;
   Pm.sref = reinterpret_cast<float*>(wsb + ws.sref);

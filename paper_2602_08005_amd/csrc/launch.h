@@ -46,6 +46,7 @@ struct DecodeParams {
   float qk_scale_log2;      // scale * log2(e)
   // workspace
   int32_t* status;
+  int32_t* rescue;          // int32 [B][Hq]: 1 = this output row is recomputed by the rescue kernel
   uint16_t* qlat;
   int64_t qlat_lo_offset;   // elements from the hi part to the lo part of qlat
   float* sref;

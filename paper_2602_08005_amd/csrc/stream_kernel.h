@@ -6,7 +6,8 @@
 namespace dkv {
 
 // ------------------------------------------------------------------------------------------------
-// stream: grid (S, Hkv, B), NW waves.  Dynamic LDS: [n_tab] w table, then small reduction buffers.
+// stream: 1-D grid over the (sequence, split) items that ref_scores lists, times kv-heads; NW waves.
+// Dynamic LDS: [n_tab] fixed-point w table, then small reduction buffers and the overflow list.
 // ------------------------------------------------------------------------------------------------
 template <int R, bool Q4>
 struct Tile {
@@ -163,8 +164,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
     }
   }
-  const float cinit = -(mref + kExpBias);
-  const float cshift = table_shift_base(mref);
+  const float cinit = -(mref + exp_bias(SUBSET));
+  const float cshift = table_shift_base(mref, exp_bias(SUBSET));
   if (tid < 16) { xbuf[tid] = cshift; xbuf[16 + tid] = 0.f; }
   float* zbuf = xbuf + 16;                                // [16] 4-bit latents: sum of weight x zero-point term per head
   // B operand of the score product: (W_uK q) for head g = ln, latent chunk 4*kk + lg
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        pend_fix[e] = f[e] < kLim ? (uint32_t)f[e] : 0u;
+        pend_fix[e] = f[e] < kLim ? (uint32_t)(f[e] + 0.5f) : 0u;      // to nearest: no one-sided loss per token
         pend_old[e] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off[e]), pend_fix[e]);
       }
       pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
@@ -570,7 +571,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       if (ovf_ent[i] >> 31) amount = __builtin_ldexpf(amount, -table_shift(sref_tab[ent], xbuf[ent & (Gp - 1)]));
       atomicAdd(&tab[ent], amount);
     }
-    if (tid == 0 && n_ovf > (uint32_t)kOvfCap) atomicOr(P.status, 2);   // list exhausted: weights were lost
+    if (n_ovf > (uint32_t)kOvfCap) {       // list exhausted, weights were lost: the pair's rows go to the rescue kernel
+      if (tid == 0) atomicOr(P.status, 2);
+      if (tid < G) P.rescue[(int64_t)b * P.Hq + (int64_t)h * G + tid] = 1;
+    }
     __syncthreads();
     for (int i = tid * 4; i < n_tab; i += NW * 64 * 4)
       *reinterpret_cast<float4*>(wp + i) = *reinterpret_cast<const float4*>(tab + i);

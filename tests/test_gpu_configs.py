@@ -180,19 +180,21 @@ def test_repeated_calls_agree():
         assert np.mean(a == b) > 0.99
 
 
-def test_status_flag_reports_logits_outside_the_exponent_range():
+def test_logits_outside_the_exponent_frame_are_recomputed_exactly():
     """A latent far outside anything a bounded residual produces pushes one logit hundreds of units above every
-    reference-token logit; the call still returns, and the workspace status word says the result cannot be trusted.
-    A normal call afterwards clears the word."""
+    reference-token logit, beyond what the streaming kernel's fixed exponent frame holds: the affected rows are
+    recomputed by the rescue kernel (the status word records that it ran) and match the oracle like any other row;
+    rows of the same call that stay inside the frame keep the streaming result.  A normal call afterwards clears
+    the word."""
     import torch
     from oracle import deltakv_oracle as O
-    from tests.helpers import Case, dev_bits
+    from tests.helpers import Case, dev_bits, out_f64, check_attention
     from tests.test_gpu_decode import _setup
     from synthetic import generator as G
     f = O.bf16_bits_to_f64
-    case = Case(8100, [600], Hkv=1, Hq=4, r=16, n_proto=8)
+    case = Case(8100, [600, 900], Hkv=1, Hq=4, r=16, n_proto=8)
     r0 = case.res[0]
-    q = G.f32_to_bf16_bits(np.full((1, 4, 128), 2.0, dtype=np.float32))
+    q = G.f32_to_bf16_bits(np.concatenate([np.full((1, 4, 128), 2.0), 0.1 * np.ones((1, 4, 128))]).astype(np.float32))
     qlat = f(case.W["w_up_k_bf16"]) @ f(q[0, 0])                  # direction in which a latent raises the logit
     zk_orig = r0["zb_k"]
     zk = zk_orig.copy()
@@ -202,9 +204,16 @@ def test_status_flag_reports_logits_outside_the_exponent_range():
     ref_logits = r0["ref_k"][:, 0] @ f(q[0, 0])
     assert (logits.max() - ref_logits.max()) * 1.4427 > 200     # far past the 2^124 range of the biased exponent
     cache = _setup(case)
-    cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(q), case.lens, 1.0)
+    lse = torch.zeros((2, 4), dtype=torch.float32, device="cuda")
+    out = cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(q), case.lens, 1.0,
+                            lse=lse)
     torch.cuda.synchronize()
     assert int(cache.decode_ws[:4].view(torch.int32)[0].item()) == 1
+    got = out_f64(out)
+    for b in range(2):
+        want, wl = case.oracle_decode(b, 1.0, f(q[b]))
+        check_attention(got[b], want, f"seq {b}", scale_with_magnitude=True)
+        assert np.max(np.abs(lse[b].cpu().numpy() - wl)) <= 2e-2 * max(1.0, float(np.max(np.abs(wl))) / 64)
     cache.put_sequence(0, r0["idx"], zk_orig, r0["zb_v"], None, None)
     cache.decode_attn(dev_bits(case.W["w_up_k_bf16"]), dev_bits(case.W["w_up_v_bf16"]), dev_bits(case.q), case.lens, 0.01)
     torch.cuda.synchronize()

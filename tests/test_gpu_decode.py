@@ -133,10 +133,19 @@ def test_needle_query_gives_order_one_outputs():
     q_bits = G.f32_to_bf16_bits(qn.astype(np.float32))[None]
     cache = _setup(case)
     scale = 1.0 / np.sqrt(128)
+    # (with up-projections independent of the down-projections the reconstructed keys sit far from their references:
+    # at this query scale the needle's logit lies beyond the fixed exponent frame, the rows are recomputed by the
+    # rescue kernel and the status word says so; the result is held to the same bar either way)
+    got, lse, status = _run(case, cache, scale, q_bits=q_bits)
+    want, _ = case.oracle_decode(0, scale, f64(q_bits[0]))
+    assert np.max(np.abs(want)) > 1.0
+    _compare(case, got, lse, scale, q_f64=f64(q_bits))
+    # a needle inside the frame: the same query direction at a quarter of the length, streaming path only
+    q_bits = G.f32_to_bf16_bits((0.25 * qn).astype(np.float32))[None]
     got, lse, status = _run(case, cache, scale, q_bits=q_bits)
     assert status == 0
     want, _ = case.oracle_decode(0, scale, f64(q_bits[0]))
-    assert np.max(np.abs(want)) > 1.0
+    assert np.max(np.abs(want)) > 0.5
     _compare(case, got, lse, scale, q_f64=f64(q_bits))
 
 
@@ -242,8 +251,9 @@ def test_weights_far_above_their_reference_take_the_overflow_list():
     assert np.max(np.abs(got[0, 0])) > 0.3
 
 
-def test_overflow_list_exhaustion_is_reported():
-    """More oversized weights in one block than the list holds: the status word says that weights were lost."""
+def test_overflow_list_exhaustion_falls_back_to_the_rescue_kernel():
+    """More oversized weights in one block than the list holds: the streaming result is incomplete, the pair's rows are
+    recomputed by the rescue kernel (the status word records it) and the output still matches the oracle."""
     from tests.helpers import Case
     case = Case(7300, [3000], Hkv=1, Hq=4, r=64, n_proto=16)
     scale = 1.0 / np.sqrt(128)
@@ -252,7 +262,9 @@ def test_overflow_list_exhaustion_is_reported():
     cache = _setup(case)
     B.tune("splits", 1)          # one block per (sequence, kv-head): all 750 oversized weights meet one list
     try:
-        _, _, status = _run(case, cache, scale)
+        got, lse, status = _run(case, cache, scale)
     finally:
         B.tune("splits", 0)
     assert status & 2
+    _compare(case, got, lse, scale)
+    assert np.max(np.abs(got[0, 0])) > 0.3

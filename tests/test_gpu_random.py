@@ -175,6 +175,7 @@ def test_random_compress_shapes_metrics_and_record_formats(seed):
             class Shim:
                 pass
             shim = Shim()
+            shim.s, shim.joint, shim.Hkv, shim.W, shim.K, shim.V = s, joint, Hkv, W, {b: K}, {b: V}
             shim.res = {b: O.compress(f64(K), f64(V), f64(W["w_down_k_bf16"]), f64(W["w_down_v_bf16"]), s=s,
                                       mode=O.JOINT if joint else O.SPLIT, metric=O.L2 if l2 else O.COSINE, latent_bits=4)}
             _compare_records(shim, cache, b, 0, L)

@@ -105,6 +105,38 @@ def test_reference_tokens_only_single_token_and_empty_selection():
     assert np.all(got[2] == 0) and np.all(np.isneginf(lse[2]))
 
 
+@pytest.mark.parametrize("joint", [False, True])
+def test_selected_tokens_far_below_a_sink_reference(joint):
+    """Reference 0 is made an attention sink: its key is aligned with the query so that its score lies more than 60
+    nats above the logit of every selected token (none of which is the sink).  The streaming kernel's exponent frame
+    hangs on the largest reference score, so all selected weights underflow there; the rows are recomputed by the
+    rescue kernel against their own largest logit and match the oracle.  A second sequence of the same call, with
+    an ordinary selection, keeps the streaming result."""
+    from tests.helpers import Case, f64
+    from tests.test_gpu_decode import _setup
+    from synthetic import generator as G
+    case = Case(9600 + joint, [1500, 800], Hkv=2, Hq=8, r=64, n_proto=16, joint=joint)
+    scale = 0.1
+    q = f64(case.q)
+    for h in range(2):                     # sink key of kv-head h: along the mean of its four queries, length 200
+        d = q[0, 4 * h:4 * h + 4].mean(0)
+        sink = G.f32_to_bf16_bits((200.0 * d / np.linalg.norm(d)).astype(np.float32))
+        case.K[0][0, h] = sink
+        case.res[0]["ref_k"][0, h] = f64(sink)
+    rng = np.random.default_rng(4)
+    cand = np.flatnonzero((case.res[0]["idx"] != 0).all(axis=1))          # tokens that do not lean on the sink
+    positions = [np.sort(rng.choice(cand, 300, replace=False)), np.sort(rng.choice(800, 200, replace=False))]
+    r = case.res[0]
+    kh = r["ref_k"][r["idx"], np.arange(2)[None, :]] + f64(r["zb_k"]) @ f64(case.W["w_up_k_bf16"])
+    for g in range(8):
+        sel = scale * kh[positions[0], g // 4] @ q[0, g]
+        assert scale * float(r["ref_k"][0, g // 4] @ q[0, g]) - sel.max() > 60.0
+    cache = _setup(case)
+    got, lse, status = _run_subset(case, cache, scale, positions)
+    assert status & 1
+    _compare(case, got, lse, scale, positions)
+
+
 def test_positions_past_the_sequence_are_ignored_and_bad_arguments_rejected():
     import torch
     from paper_2602_08005_amd import binding as B
