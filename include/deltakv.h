@@ -293,6 +293,27 @@ int deltakv_decode_attn_raw(const deltakv_dims* dims, const deltakv_layout* layo
                             int32_t batch, float scale, void* out, float* lse,
                             void* workspace, int64_t ws_bytes, void* stream);
 
+/* deltakv_decode_attn for callers that cannot allocate device memory and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments and result as
+ * deltakv_decode_attn without `workspace` / `ws_bytes`: the workspace is a DELTAKV_STATIC_WS_BYTES array inside the
+ * library's device image (each GPU the library runs on holds one copy until the process ends).  The call allocates
+ * nothing, on the device or through any library.  A call whose batch and sequence lengths need more workspace than
+ * that even with a single token-range split returns DELTAKV_E_WORKSPACE (deltakv_last_error_detail says so);
+ * deltakv_paged_layout(...).decode_ws_bytes <= DELTAKV_STATIC_WS_BYTES is a sufficient condition for acceptance
+ * (8 sequences of 131072 tokens with 8 kv-heads and 4 queries per kv-head fit).  Every call on one GPU uses the
+ * same array and overwrites what the last call left there (nothing needs clearing: the kernels write whatever they
+ * later read), so calls that overlap in time on one GPU -- from different streams or threads -- race; serialise them.
+ * The status word of the call is not readable by the caller.  Errors otherwise as deltakv_decode_attn, plus
+ * UNSUPPORTED for a device ordinal above 63. */
+#define DELTAKV_STATIC_WS_BYTES (64ll << 20)
+int deltakv_decode_attn_static(const deltakv_dims* dims, const deltakv_layout* layout,
+                               const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
+                               const int32_t* block_tables, int32_t bt_stride,
+                               const int32_t* ref_tables, int32_t rt_stride,
+                               const void* w_up_k, const void* w_up_v, const void* q,
+                               const int32_t* seq_lens, const int32_t* seq_lens_host,
+                               int32_t batch, float scale, void* out, float* lse, void* stream);
+
 const char* deltakv_strerror(int code);
 /* For DELTAKV_E_HIP: which runtime call failed and the runtime's message (calling thread's last failure;
  * empty string if none).  The pointer stays valid until the thread's next failing call. */

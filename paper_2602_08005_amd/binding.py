@@ -43,7 +43,9 @@ class Layout(C.Structure):
 class DeltaKVError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        detail = _lib.deltakv_last_error_detail().decode() if code == E_HIP else ""
+        detail = ""
+        if code == E_HIP or (code == E_WORKSPACE and where == "deltakv_decode_attn_static"):
+            detail = _lib.deltakv_last_error_detail().decode()
         super().__init__(f"{where}: {strerror(code)} ({code}) {detail}")
 
 
@@ -78,6 +80,9 @@ def _load() -> C.CDLL:
     lib.deltakv_decode_attn.restype = C.c_int
     lib.deltakv_decode_attn.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                         vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, i64, vp]
+    lib.deltakv_decode_attn_static.restype = C.c_int
+    lib.deltakv_decode_attn_static.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
+                                               vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp]
     lib.deltakv_decode_attn_subset.restype = C.c_int
     lib.deltakv_decode_attn_subset.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                                vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, C.c_float, vp, vp,
@@ -95,7 +100,8 @@ KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", 
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset",
-           "deltakv_decode_attn_raw")
+           "deltakv_decode_attn_raw", "deltakv_decode_attn_static")
+STATIC_WS_BYTES = 64 << 20
 
 
 def version() -> int:
@@ -199,6 +205,20 @@ def decode_attn(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if check and rc != OK:
         raise DeltaKVError(rc, "deltakv_decode_attn")
+    return rc
+
+
+def decode_attn_static(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref_tables, w_up_k, w_up_v, q,
+                       seq_lens, seq_lens_host, scale, out, lse, stream=None, check=True) -> int:
+    """deltakv_decode_attn on the library's own static workspace (the call allocates nothing)."""
+    sl_h = _host_i32(seq_lens_host)
+    rc = _lib.deltakv_decode_attn_static(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_up_k), _dp(w_up_v), _dp(q), _dp(seq_lens), sl_h.ctypes.data, len(sl_h), float(scale),
+        _dp(out), _dp(lse), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_decode_attn_static")
     return rc
 
 

@@ -469,6 +469,43 @@ int deltakv_decode_attn_raw(const deltakv_dims* dims, const deltakv_layout* lay,
                      ws_bytes, stream);
 }
 
+// ---- decode attention for callers that cannot allocate ------------------------------------------------------
+// The workspace of this entry point is an array in the library's own device image: every GPU the library runs on
+// holds one copy from the moment the image is loaded until the process ends.  Host code never uses the array's
+// name as an address (on the host it is only a handle for the runtime's symbol table): the device address is asked
+// for once per device, with that device current, and kept.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[DELTAKV_STATIC_WS_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+int deltakv_decode_attn_static(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                               const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                               int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                               const void* w_up_v, const void* q, const int32_t* seq_lens,
+                               const int32_t* seq_lens_host, int32_t batch, float scale, void* out, float* lse,
+                               void* stream) {
+  int dev = -1;
+  if (note_hip_error(hipGetDevice(&dev), "hipGetDevice") != hipSuccess) return DELTAKV_E_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return DELTAKV_E_UNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (note_hip_error(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(static workspace)") !=
+            hipSuccess || !ptr)
+      return DELTAKV_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  const int rc = decode_impl(dims, lay, latent_pool, idx_pool, ref_pool, block_tables, bt_stride, ref_tables, rt_stride,
+                             w_up_k, w_up_v, q, seq_lens, seq_lens_host, Selection{}, RawSegment{}, batch, scale, out,
+                             lse, g_scratch_ptr[dev], DELTAKV_STATIC_WS_BYTES, stream);
+  if (rc == DELTAKV_E_WORKSPACE)
+    snprintf(g_detail, sizeof(g_detail),
+             "this batch and these sequence lengths need more than the %lld bytes of the static workspace; use "
+             "deltakv_decode_attn with a caller-provided workspace", (long long)DELTAKV_STATIC_WS_BYTES);
+  return rc;
+}
+
 int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
                      void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
                      const int32_t* ref_tables, int32_t rt_stride, const void* w_down_k, const void* w_down_v,
