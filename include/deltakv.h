@@ -223,10 +223,11 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* layout,
  *                 Neither happens with residuals that are small next to the references
  *                 they refine; a set bit means the call took milliseconds instead of
  *                 microseconds for the rows concerned.
- * Errors: INVALID_ARG, UNSUPPORTED (a sequence needs more on-chip table space
- * than one compute unit has: roughly seq_len/ref_stride * g > 39000 in SPLIT and
- * > 34000 in JOINT mode, g = queries per kv-head rounded up to 4, 8 or 16),
- * WORKSPACE, HIP. */
+ * Sequences may be as long as the pools hold (up to 2^30 tokens and 2^29 / g reference ordinals, g = queries per
+ * kv-head rounded up to 4, 8 or 16).  Up to roughly seq_len / ref_stride * g = 39000 (34000 in JOINT mode) a
+ * sequence's per-reference weight table lives on chip; beyond, older ordinals are accumulated in global memory,
+ * which costs time, not accuracy.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP. */
 int deltakv_decode_attn(const deltakv_dims* dims, const deltakv_layout* layout,
                         const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
                         const int32_t* block_tables, int32_t bt_stride,
@@ -330,6 +331,9 @@ int deltakv_version(void);
  *   "sim_waves"     waves per block of the similarity kernel (4 or 8; 8 needs sim_tb <= 2)
  *   "sim_ns"        reference-range splits of the similarity search (1..64)
  *   "project_pages" consecutive pages per block of the projection kernel (1..16)
+ *   "table_rows"    cap on the reference ordinals a block of the streaming kernel keeps in its on-chip weight table
+ *                   (>= 16; the default is what the LDS holds); ordinals older than the window go to a table in
+ *                   global memory, as they do for sequences beyond about 160 000 tokens
  *   "ref_chunks"    reference chunks scored per block of the decode call's first kernel (1 or 4)
  *   "timing_period" timed regions record events for every value-th call only (0 or 1 = every call): an event costs
  *                   a few microseconds of stream time, which a benchmark may not want in front of every kernel

@@ -11,7 +11,7 @@ constexpr int kWave = 64;
 constexpr int kHeadDim = 128;
 constexpr int kPage = 16;          // tokens per page
 constexpr int kRefChunk = 256;     // reference ordinals handled by one block of the per-reference kernels
-constexpr int kMaxSplits = 16;     // upper bound on token-range splits of one (sequence, kv-head)
+constexpr int kMaxSplits = 32;     // upper bound on token-range splits of one (sequence, kv-head)
 constexpr int kWPad = 136;         // bf16 elements per staged W_down^T row (128 + 8: shifts LDS banks)
 constexpr int kRawChunk = 256;     // raw-segment tokens handled by one block
 constexpr int kRawMaxChunks = 16;  // a raw segment holds at most kRawChunk * kRawMaxChunks tokens per sequence
@@ -72,12 +72,16 @@ struct DecodeWs {
   int64_t items;    // int32 [1 + B*kMaxSplits]      number of non-empty (sequence, split) items, then the items
   int64_t accpart;  // fp32 [B][Hkv][S][Gp][R]
   int64_t opart;    // fp32 [B][Hkv][n_chunk_max][Gp][128]
-  int64_t wpart;    // fp32 [B][Hkv][S][n_ref_max][Gp]
+  int64_t wpart;    // fp32 [B][Hkv][S][tab_cap][Gp]     per-split weight tables (LDS windows)
+  int64_t spill;    // fp32 [B][Hkv][n_ref_max][Gp]      weights of ordinals older than the windows (long sequences)
   int64_t rawo;     // fp32 [B][Hkv][kRawMaxChunks][Gp][128]  raw-segment partial outputs
   int64_t rawml;    // fp32 [B][Hkv][kRawMaxChunks][Gp][2]    their (largest logit, weight sum)
   int64_t total;
 };
-inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_ref_max, int splits) {
+// Rows of the streaming kernel's LDS weight table on a compute unit with 160 KiB of LDS (the largest any call
+// uses; the host lowers it to what the device and the variant's other buffers leave).
+inline int64_t table_rows_max(int Gp) { return (160 * 1024) / (Gp * 4); }
+inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_ref_max, int splits, int64_t tab_cap) {
   const int64_t G = d.n_q_heads / d.n_kv_heads, Gp = padded_group((int)G), R = d.rank;
   const int64_t BH = batch * d.n_kv_heads, nch = ceil_div64(n_ref_max, kRefChunk);
   DecodeWs w;
@@ -93,7 +97,8 @@ inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_r
   w.items = take((1 + batch * kMaxSplits) * 4);
   w.accpart = take(BH * splits * Gp * R * 4);
   w.opart = take(BH * nch * Gp * kHeadDim * 4);
-  w.wpart = take(BH * splits * n_ref_max * Gp * 4);
+  w.wpart = take(BH * splits * tab_cap * Gp * 4);
+  w.spill = take(BH * n_ref_max * Gp * 4);
   w.rawo = take(BH * kRawMaxChunks * Gp * kHeadDim * 4);
   w.rawml = take(BH * kRawMaxChunks * Gp * 2 * 4);
   w.total = o;

@@ -135,8 +135,11 @@ __global__ __launch_bounds__(256) void k_ref_scores(DecodeParams P) {
       float4 o;
       o.x = acc[0] * P.qk_scale_log2; o.y = acc[1] * P.qk_scale_log2;
       o.z = acc[2] * P.qk_scale_log2; o.w = acc[3] * P.qk_scale_log2;
-      if (valid && 4 * lg < P.Gp)
+      if (valid && 4 * lg < P.Gp) {
         *reinterpret_cast<float4*>(P.sref + (bh * P.n_ref_max + j) * P.Gp + 4 * lg) = o;
+        // long sequences: the table that takes the weights of ordinals older than the blocks' LDS windows starts at 0
+        if (P.spill_on) *reinterpret_cast<float4*>(P.spill + (bh * P.n_ref_max + j) * P.Gp + 4 * lg) = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
       if (valid) {
         mx[0] = fmaxf(mx[0], o.x); mx[1] = fmaxf(mx[1], o.y);
         mx[2] = fmaxf(mx[2], o.z); mx[3] = fmaxf(mx[3], o.w);
@@ -215,31 +218,41 @@ __global__ __launch_bounds__(256) void k_ref_values(DecodeParams P) {
   // slot the caller did not admit: 0 * garbage could be NaN)
   const int slot = clampi(P.ref_tables[(int64_t)b * P.rt_stride + min(j, n_ref - 1)], 0, (int)P.n_ref_slots - 1);
   if (j < n_ref) {
-    uint32_t plain = 0;                        // splits whose table already holds plain weights (rare)
-    uint32_t wrote = 0;                        // splits whose table covers ordinal j
+    // splits in groups of four: within a group every load is issued before the first is used
+    for (int s0 = 0; s0 < sp.n_splits; s0 += 4) {
+      float4 t[4][GP / 4];
+      bool on[4], pl[4];
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s) {
-      const int p1 = min(n_pages, (s + 1) * sp.per);
-      if (s < sp.n_splits && s * sp.per < p1) {
-        if (P.wflag[bh * P.S + s] != 0) plain |= 1u << s;
-        if (j < refs_covered(P, b, L, p1)) wrote |= 1u << s;
+      for (int u = 0; u < 4; ++u) {
+        const int s = min(s0 + u, sp.n_splits - 1);            // (a repeated split is dropped below)
+        const int p1 = min(n_pages, (s + 1) * sp.per);
+        const int n_cov = s * sp.per < p1 ? refs_covered(P, b, L, p1) : 0;     // ordinals the split can touch
+        const int lo = n_cov - min(n_cov, P.tab_cap);          // first ordinal of its table window
+        on[u] = s0 + u < sp.n_splits && j >= lo && j < n_cov;
+        pl[u] = P.wflag[bh * P.S + s] != 0;                    // its table already holds plain weights (rare)
+        // row of ordinal j in the window (clamped: the load is unconditional, a row outside is dropped)
+        const float* wp = P.wpart + ((bh * P.S + s) * P.tab_cap + clampi(j - lo, 0, P.tab_cap - 1)) * GP;
+#pragma unroll
+        for (int g4 = 0; g4 < GP; g4 += 4) t[u][g4 / 4] = *reinterpret_cast<const float4*>(wp + g4);
       }
-    }
 #pragma unroll
-    for (int s = 0; s < kMaxSplits; ++s) {
-      if (s < sp.n_splits) {                   // uniform over the block
-        const float* wp = P.wpart + ((bh * P.S + s) * P.n_ref_max + j) * GP;
-        const bool on = (wrote >> s) & 1u, pl = (plain >> s) & 1u;
+      for (int u = 0; u < 4; ++u)
 #pragma unroll
         for (int g4 = 0; g4 < GP; g4 += 4) {
-          const float4 t = *reinterpret_cast<const float4*>(wp + g4);
-          const float tt[4] = {t.x, t.y, t.z, t.w};
+          const float tt[4] = {t[u][g4 / 4].x, t[u][g4 / 4].y, t[u][g4 / 4].z, t[u][g4 / 4].w};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            wfix[g4 + e] += on && !pl ? tt[e] : 0.f;
-            wplain[g4 + e] += on && pl ? tt[e] : 0.f;
+            wfix[g4 + e] += on[u] && !pl[u] ? tt[e] : 0.f;
+            wplain[g4 + e] += on[u] && pl[u] ? tt[e] : 0.f;
           }
         }
+    }
+    if (P.spill_on) {                          // plain weights from blocks whose window starts after ordinal j
+      const float* sp2 = P.spill + (bh * P.n_ref_max + j) * GP;
+#pragma unroll
+      for (int g4 = 0; g4 < GP; g4 += 4) {
+        const float4 t = *reinterpret_cast<const float4*>(sp2 + g4);
+        wplain[g4] += t.x; wplain[g4 + 1] += t.y; wplain[g4 + 2] += t.z; wplain[g4 + 3] += t.w;
       }
     }
     const float* sp_ = P.sref + (bh * P.n_ref_max + j) * GP;
@@ -498,6 +511,126 @@ __device__ inline void finish_output(const DecodeParams& P, int b, int gh, int h
 }
 
 // ------------------------------------------------------------------------------------------------
+// rescue (a branch of finalize: the block of one output row, 128 threads).  The streaming path keeps every softmax weight in one fixed frame per
+// (sequence, q-head), 2^(x - m_ref - bias) with m_ref the largest per-reference score; that holds logits up to 86
+// nats above m_ref (55 nats either way for a selection), which is where reconstructed keys of small residuals live.
+// A row whose weights left that range (finalize saw a sum at or beyond 2^60, or below 2^-100), or whose block ran out of room for oversized table
+// amounts, is recomputed here from the cache by the definition: pass 1 finds the exact largest logit of the row,
+// pass 2 accumulates weights against it (all <= 1), sum_t p_t V_ref[idx_t] and sum_t p_t z_V,t directly.  Slow
+// (every latent value is fetched on its own) and always right; logits use the same operands as the streaming
+// kernel (per-reference scores and W_uK q of ref_scores, in log2 units).
+// ------------------------------------------------------------------------------------------------
+// Latent value c of token `tok` in the (page, head, stream) block that starts at `blk` (any of the four layouts).
+__device__ inline float latent_value(const DecodeParams& P, const uint16_t* blk, int tok, int c, bool value_stream) {
+  if (!P.q4) {
+    const int at = value_stream ? ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3)
+                                : ((c >> 3) * kPage + tok) * 8 + (c & 7);
+    return bf16lo(blk[at]);
+  }
+  const uint32_t* words = reinterpret_cast<const uint32_t*>(blk);
+  uint32_t code;
+  if (value_stream) {
+    const uint32_t w = words[2 * ((c >> 6) * 64 + (tok >> 2) * 16 + (c & 15)) + ((tok & 3) >> 1)];
+    code = (w >> (4 * ((c >> 4) & 3) + 16 * (tok & 1))) & 15u;
+  } else {
+    const uint32_t w = words[(c >> 3) * kPage + tok];
+    code = (w >> (4 * ((c & 7) >> 1) + 16 * (c & 1))) & 15u;
+  }
+  const uint16_t* sz = blk + 4 * P.R + (tok >> 2) * 8 + (tok & 3);      // four scales, then four zero points
+  return bf16lo(sz[0]) * (float)code + bf16lo(sz[4]);
+}
+
+__device__ __forceinline__ void rescue_row(const DecodeParams& P, int b, int gh) {
+  constexpr int NT = 128;               // threads of the block = tokens per tile
+  const int tid = threadIdx.x;
+  const int G = P.G, Gp = P.Gp, R = P.R;
+  const int h = gh / G, g = gh % G;
+  const int L = seq_len_of(P, b);
+  const int n_ent = work_pages_of(P, b, L);                  // entries of the page list (>= 1: the row was flagged)
+  const int n_raw = P.raw_k ? clampi(P.raw_lens[b], 0, P.raw_cap) : 0;
+  const int n_ref = refs_below(L, P.stride);
+  const int64_t bh = (int64_t)b * P.Hkv + h;
+  __shared__ float ql[kHeadDim];        // W_uK q of this head (hi + lo), log2 units
+  __shared__ float pw[NT];              // weights of the current tile
+  __shared__ int psl[NT];               // reference slot of each token of the tile
+  __shared__ float red[NT];
+  if (tid < R) {
+    const int64_t at = ((int64_t)b * P.Hq + gh) * R + tid;
+    ql[tid] = bf16lo(P.qlat[at]) + bf16lo(P.qlat[P.qlat_lo_offset + at]);
+  }
+  __syncthreads();
+  const float* sref = P.sref + bh * P.n_ref_max * Gp + g;
+  const int last_logical = ceil_div(L, kPage) - 1;
+  // token i of the row = (list entry i / 16, slot i % 16); returns whether it takes part, its logit and ordinal
+  auto token = [&](int i, float& x, int& ord, const uint16_t*& blk) {
+    const int e = i >> 4, tok = i & 15;
+    if (e >= n_ent) return false;
+    int logical = e;
+    uint32_t mask = 0xffffu;
+    if (P.sel_pages) {
+      logical = P.sel_pages[(int64_t)b * P.sel_stride + e];
+      mask = (uint32_t)P.sel_masks[(int64_t)b * P.sel_stride + e];
+      if ((uint32_t)logical > (uint32_t)last_logical) return false;
+    }
+    if (logical * kPage + tok >= L || !((mask >> tok) & 1u)) return false;
+    const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
+    ord = (int)min((uint32_t)P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok],
+                   (uint32_t)(n_ref - 1));
+    blk = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+    float acc = 0.f;
+    for (int c = 0; c < R; ++c) acc += ql[c] * latent_value(P, blk, tok, c, false);
+    x = sref[(int64_t)ord * Gp] + acc;
+    return true;
+  };
+  const int n_tok = n_ent * kPage;
+  // pass 1: the row's largest logit
+  float m = -INFINITY;
+  for (int i = tid; i < n_tok; i += NT) {
+    float x; int ord; const uint16_t* blk;
+    if (token(i, x, ord, blk)) m = fmaxf(m, x);
+  }
+  red[tid] = m;
+  __syncthreads();
+  for (int o2 = NT / 2; o2 > 0; o2 >>= 1) {
+    if (tid < o2) red[tid] = fmaxf(red[tid], red[tid + o2]);
+    __syncthreads();
+  }
+  m = red[0];
+  __syncthreads();
+  // pass 2: tiles of 128 tokens; a thread owns an output dim and (the first R threads) a latent column
+  float lsum = 0.f, o = 0.f, zs = 0.f;
+  const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;
+  const int64_t vstream = P.joint ? 0 : P.latent_stream_stride;
+  for (int i0 = 0; i0 < n_tok; i0 += NT) {
+    float x; int ord = 0; const uint16_t* blk = nullptr;
+    const bool on = token(i0 + tid, x, ord, blk);
+    pw[tid] = on ? __builtin_amdgcn_exp2f(x - m) : 0.f;
+    psl[tid] = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
+    __syncthreads();
+    const int n_here = min(NT, n_tok - i0);
+    for (int t = 0; t < n_here; ++t) {
+      const float p = pw[t];
+      if (p == 0.f) continue;                                  // tokens that take no part may hold anything
+      o += p * bf16lo(vbase[(int64_t)psl[t] * kHeadDim + tid]);
+      lsum += p;
+      if (tid < R) {
+        const int i = i0 + t, e = i >> 4;
+        const int logical = P.sel_pages ? P.sel_pages[(int64_t)b * P.sel_stride + e] : e;
+        const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
+        const uint16_t* vb = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride + vstream;
+        zs += p * latent_value(P, vb, i & 15, tid, !P.joint);
+      }
+    }
+    __syncthreads();
+  }
+  // up-projection of the weighted latent sum
+  red[tid] = zs;
+  __syncthreads();
+  for (int c = 0; c < R; ++c) o += red[c] * bf16lo(P.w_up_v[(int64_t)c * kHeadDim + tid]);
+  finish_output(P, b, gh, h, g, tid, lsum, o, m, n_raw);
+}
+
+// ------------------------------------------------------------------------------------------------
 // finalize: grid (Hq, B), 128 threads (thread = output dim d); one block per query head.
 // ------------------------------------------------------------------------------------------------
 template <int R>
@@ -509,6 +642,7 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
   uint16_t wcol[R];
 #pragma unroll
   for (int cc = 0; cc < R; ++cc) wcol[cc] = P.w_up_v[(int64_t)cc * kHeadDim + d];
+  const int rescue_flag = P.rescue[(int64_t)b * P.Hq + gh];      // set by a streaming block that lost weights
   const int h = gh / G, g = gh % G;
   const int L = seq_len_of(P, b);
   const int64_t orow = ((int64_t)b * P.Hq + gh) * kHeadDim;
@@ -574,149 +708,25 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
     // makes the sum at least that large) risks overflow of the fp32 sums; a sum below 2^-100 means every attended
     // token lies so far under the largest reference score that weights of some weight may have been flushed to
     // zero (only a selection can do that: a reference token of the full cache weighs 2^-64 or more; with the sum
-    // at 2^-100 or more a flushed weight is below 2^-26 of it).  Such a row is recomputed by the rescue kernel
-    // with the row's exact maximum as its offset.
-    if (d == 0 && !(lsum >= kSumLo && lsum < kSumHi)) {
-      atomicOr(P.status, 1);
-      P.rescue[(int64_t)b * P.Hq + gh] = 1;
+    // at 2^-100 or more a flushed weight is below 2^-26 of it).  Such a row, and the rows of a (sequence, kv-head)
+    // whose streaming block ran out of room for oversized table amounts, are recomputed by the rescue branch
+    // with the row's exact maximum as its offset (uniform over the block: every thread holds the same sum).
+    if (!(lsum >= kSumLo && lsum < kSumHi) || rescue_flag != 0) {
+      if (d == 0 && !(lsum >= kSumLo && lsum < kSumHi)) atomicOr(P.status, 1);
+      __syncthreads();
+      rescue_row(P, b, gh);
+      return;
     }
   }
   finish_output(P, b, gh, h, g, d, lsum, o, frame, n_raw);
 }
 
 // ------------------------------------------------------------------------------------------------
-// rescue: grid (Hq, B), 256 threads.  The streaming path keeps every softmax weight in one fixed frame per
-// (sequence, q-head), 2^(x - m_ref - bias) with m_ref the largest per-reference score; that holds logits up to 86
-// nats above m_ref (55 nats either way for a selection), which is where reconstructed keys of small residuals live.
-// A row whose weights left that range (finalize saw a sum at or beyond 2^60, or below 2^-100), or whose block ran out of room for oversized table
-// amounts, is flagged, and this kernel -- launched with every call, a few microseconds when no row is flagged --
-// recomputes the flagged rows from the cache by the definition: pass 1 finds the exact largest logit of the row,
-// pass 2 accumulates weights against it (all <= 1), sum_t p_t V_ref[idx_t] and sum_t p_t z_V,t directly.  Slow
-// (every latent value is fetched on its own) and always right; logits use the same operands as the streaming
-// kernel (per-reference scores and W_uK q of ref_scores, in log2 units).
-// ------------------------------------------------------------------------------------------------
-// Latent value c of token `tok` in the (page, head, stream) block that starts at `blk` (any of the four layouts).
-__device__ inline float latent_value(const DecodeParams& P, const uint16_t* blk, int tok, int c, bool value_stream) {
-  if (!P.q4) {
-    const int at = value_stream ? ((c >> 4) * 64 + (tok >> 2) * 16 + (c & 15)) * 4 + (tok & 3)
-                                : ((c >> 3) * kPage + tok) * 8 + (c & 7);
-    return bf16lo(blk[at]);
-  }
-  const uint32_t* words = reinterpret_cast<const uint32_t*>(blk);
-  uint32_t code;
-  if (value_stream) {
-    const uint32_t w = words[2 * ((c >> 6) * 64 + (tok >> 2) * 16 + (c & 15)) + ((tok & 3) >> 1)];
-    code = (w >> (4 * ((c >> 4) & 3) + 16 * (tok & 1))) & 15u;
-  } else {
-    const uint32_t w = words[(c >> 3) * kPage + tok];
-    code = (w >> (4 * ((c & 7) >> 1) + 16 * (c & 1))) & 15u;
-  }
-  const uint16_t* sz = blk + 4 * P.R + (tok >> 2) * 8 + (tok & 3);      // four scales, then four zero points
-  return bf16lo(sz[0]) * (float)code + bf16lo(sz[4]);
-}
-
-__global__ __launch_bounds__(256) void k_rescue(DecodeParams P) {
-  const int gh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  if (P.rescue[(int64_t)b * P.Hq + gh] == 0) return;
-  const int G = P.G, Gp = P.Gp, R = P.R;
-  const int h = gh / G, g = gh % G;
-  const int L = seq_len_of(P, b);
-  const int n_ent = work_pages_of(P, b, L);                  // entries of the page list (>= 1: the row was flagged)
-  const int n_raw = P.raw_k ? clampi(P.raw_lens[b], 0, P.raw_cap) : 0;
-  const int n_ref = refs_below(L, P.stride);
-  const int64_t bh = (int64_t)b * P.Hkv + h;
-  __shared__ float ql[kHeadDim];        // W_uK q of this head (hi + lo), log2 units
-  __shared__ float pw[256];             // weights of the current tile
-  __shared__ int psl[256];              // reference slot of each token of the tile
-  __shared__ float red[256];
-  if (tid < R) {
-    const int64_t at = ((int64_t)b * P.Hq + gh) * R + tid;
-    ql[tid] = bf16lo(P.qlat[at]) + bf16lo(P.qlat[P.qlat_lo_offset + at]);
-  }
-  __syncthreads();
-  const float* sref = P.sref + bh * P.n_ref_max * Gp + g;
-  const int last_logical = ceil_div(L, kPage) - 1;
-  // token i of the row = (list entry i / 16, slot i % 16); returns whether it takes part, its logit and ordinal
-  auto token = [&](int i, float& x, int& ord, const uint16_t*& blk) {
-    const int e = i >> 4, tok = i & 15;
-    if (e >= n_ent) return false;
-    int logical = e;
-    uint32_t mask = 0xffffu;
-    if (P.sel_pages) {
-      logical = P.sel_pages[(int64_t)b * P.sel_stride + e];
-      mask = (uint32_t)P.sel_masks[(int64_t)b * P.sel_stride + e];
-      if ((uint32_t)logical > (uint32_t)last_logical) return false;
-    }
-    if (logical * kPage + tok >= L || !((mask >> tok) & 1u)) return false;
-    const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
-    ord = (int)min((uint32_t)P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok],
-                   (uint32_t)(n_ref - 1));
-    blk = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
-    float acc = 0.f;
-    for (int c = 0; c < R; ++c) acc += ql[c] * latent_value(P, blk, tok, c, false);
-    x = sref[(int64_t)ord * Gp] + acc;
-    return true;
-  };
-  const int n_tok = n_ent * kPage;
-  // pass 1: the row's largest logit
-  float m = -INFINITY;
-  for (int i = tid; i < n_tok; i += 256) {
-    float x; int ord; const uint16_t* blk;
-    if (token(i, x, ord, blk)) m = fmaxf(m, x);
-  }
-  red[tid] = m;
-  __syncthreads();
-  for (int o2 = 128; o2 > 0; o2 >>= 1) {
-    if (tid < o2) red[tid] = fmaxf(red[tid], red[tid + o2]);
-    __syncthreads();
-  }
-  m = red[0];
-  __syncthreads();
-  // pass 2: tiles of 256 tokens; threads 0..127 own an output dim, threads 128..255 a latent column
-  float lsum = 0.f, o = 0.f, zs = 0.f;
-  const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;
-  const int64_t vstream = P.joint ? 0 : P.latent_stream_stride;
-  for (int i0 = 0; i0 < n_tok; i0 += 256) {
-    float x; int ord = 0; const uint16_t* blk = nullptr;
-    const bool on = token(i0 + tid, x, ord, blk);
-    pw[tid] = on ? __builtin_amdgcn_exp2f(x - m) : 0.f;
-    psl[tid] = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
-    __syncthreads();
-    const int n_here = min(256, n_tok - i0);
-    if (tid < 128) {
-      for (int t = 0; t < n_here; ++t) {
-        const float p = pw[t];
-        if (p != 0.f) o += p * bf16lo(vbase[(int64_t)psl[t] * kHeadDim + tid]);
-        lsum += p;
-      }
-    } else if (tid - 128 < R) {
-      for (int t = 0; t < n_here; ++t) {
-        const float p = pw[t];
-        if (p == 0.f) continue;                                // tokens that take no part may hold anything
-        const int i = i0 + t, e = i >> 4;
-        const int logical = P.sel_pages ? P.sel_pages[(int64_t)b * P.sel_stride + e] : e;
-        const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
-        const uint16_t* vb = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride + vstream;
-        zs += p * latent_value(P, vb, i & 15, tid - 128, !P.joint);
-      }
-    }
-    __syncthreads();
-  }
-  // up-projection of the weighted latent sum
-  red[tid] = zs;
-  __syncthreads();
-  if (tid < 128) {
-    for (int c = 0; c < R; ++c) o += red[128 + c] * bf16lo(P.w_up_v[(int64_t)c * kHeadDim + tid]);
-    finish_output(P, b, gh, h, g, tid, lsum, o, m, n_raw);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
 
-size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint) {
-  size_t b = (size_t)(((n_ref_max * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
+size_t stream_lds_bytes(int n_rows, int Gp, int R, int nw, bool joint) {
+  size_t b = (size_t)(((n_rows * Gp + 3) & ~3) + Gp * R + 16 + nw * 16) * sizeof(float);
   if (joint) b += (size_t)nw * 16 * (R + 8) * 2;
   b += (size_t)(4 + 2 * kOvfCap) * 4;   // overflow list of the fixed-point table
   return b;
@@ -773,9 +783,7 @@ hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, 
     case 128: hipLaunchKernelGGL(k_finalize<128>, dim3(P.Hq, batch), dim3(128), 0, st, P); break;
     default: return hipErrorInvalidValue;
   }
-  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of finalize");
-  hipLaunchKernelGGL(k_rescue, dim3(P.Hq, batch), dim3(256), 0, st, P);
-  e = note_hip_error(hipGetLastError(), "launch of rescue");
+  e = note_hip_error(hipGetLastError(), "launch of finalize");
   timing_mark(K_FINALIZE, st);
   return e;
 }

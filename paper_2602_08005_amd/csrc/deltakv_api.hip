@@ -55,6 +55,7 @@ int g_tune_sim_ns = 0;
 int g_tune_sim_waves = 0;
 int g_tune_ref_chunks = 0;
 int g_tune_project_pages = 0;
+int g_tune_table_rows = 0;
 
 // per-kernel timing state (one timed region at a time, one stream)
 struct Mark { hipEvent_t ev; int id; };
@@ -126,6 +127,9 @@ int deltakv_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "project_pages")) {
     if (value > 16) return DELTAKV_E_INVALID_ARG;
     g_tune_project_pages = value;
+  } else if (!strcmp(name, "table_rows")) {
+    if (value != 0 && value < 16) return DELTAKV_E_INVALID_ARG;
+    g_tune_table_rows = value;
   } else if (!strcmp(name, "ref_chunks")) {
     if (value != 0 && value != 1 && value != 4) return DELTAKV_E_INVALID_ARG;
     g_tune_ref_chunks = value;
@@ -203,7 +207,10 @@ int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t ma
   out->ref_norm_head_stride = dims->n_ref_slots;
   out->ref_norm_pool_bytes = H * dims->n_ref_slots * 4;
   const int64_t n_ref_max = ceil_div64(max_seq_len, dims->ref_stride);
-  out->decode_ws_bytes = plan_decode_ws(*dims, max_batch, n_ref_max, kMaxSplits).total;
+  {
+    const int64_t rows = table_rows_max(padded_group(dims->n_q_heads / dims->n_kv_heads));
+    out->decode_ws_bytes = plan_decode_ws(*dims, max_batch, n_ref_max, kMaxSplits, n_ref_max < rows ? n_ref_max : rows).total;
+  }
   out->compress_ws_bytes = plan_compress_ws(*dims, max_batch, max_new_tokens, n_ref_max).total;
   return DELTAKV_OK;
 }
@@ -282,9 +289,21 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
 
   const int G = dims->n_q_heads / dims->n_kv_heads, Gp = padded_group(G), R = dims->rank;
   const int nw = g_tune_stream_waves ? g_tune_stream_waves : 8;
-  const size_t lds = stream_lds_bytes(n_ref_max, Gp, R, nw, dims->latent_mode == DELTAKV_JOINT);
+  // The streaming kernel keeps a (sequence, kv-head)'s per-reference weight table in LDS.  Longer sequences than
+  // one compute unit's LDS holds keep a window of the most recent ordinals there and send the rest to a table in
+  // global memory (the SPILL variants).
+  const bool joint = dims->latent_mode == DELTAKV_JOINT;
   const size_t kLdsLimit = device_lds_limit();
-  if (lds > kLdsLimit) return DELTAKV_E_UNSUPPORTED;
+  const size_t lds_other = stream_lds_bytes(0, Gp, R, nw, joint);
+  if (lds_other + 4096 > kLdsLimit) return DELTAKV_E_UNSUPPORTED;
+  int64_t tab_cap = (int64_t)((kLdsLimit - lds_other) / (Gp * 4)) & ~3ll;
+  if (tab_cap > table_rows_max(Gp)) tab_cap = table_rows_max(Gp);
+  if (tab_cap > 65535) tab_cap = 65535 & ~3;           // the kernel keeps table rows in 16 bits
+  if (g_tune_table_rows > 0 && g_tune_table_rows < tab_cap) tab_cap = g_tune_table_rows & ~3;
+  const bool spill_on = n_ref_max > tab_cap;
+  if (!spill_on) tab_cap = n_ref_max;
+  if ((int64_t)n_ref_max * Gp * 4 >= (1ll << 31)) return DELTAKV_E_UNSUPPORTED;   // 32-bit byte offsets into a pair's tables
+  const size_t lds = stream_lds_bytes((int)tab_cap, Gp, R, nw, joint);
   int per_cu = (int)(kLdsLimit / lds);
   const int wave_cap = 32 / nw;
   if (per_cu > wave_cap) per_cu = wave_cap;
@@ -316,10 +335,10 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   if (splits > kMaxSplits) splits = kMaxSplits;
   if (splits < 1) splits = 1;
   if (g_tune_splits) splits = g_tune_splits < split_cap ? g_tune_splits : split_cap;
-  DecodeWs ws = plan_decode_ws(*dims, batch, n_ref_max, splits);
+  DecodeWs ws = plan_decode_ws(*dims, batch, n_ref_max, splits, tab_cap);
   while (ws.total > ws_bytes && splits > 1) {
     --splits;
-    ws = plan_decode_ws(*dims, batch, n_ref_max, splits);
+    ws = plan_decode_ws(*dims, batch, n_ref_max, splits, tab_cap);
   }
   if (ws.total > ws_bytes) return DELTAKV_E_WORKSPACE;
 
@@ -379,6 +398,9 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   Pm.accpart = reinterpret_cast<float*>(wsb + ws.accpart);
   Pm.opart = reinterpret_cast<float*>(wsb + ws.opart);
   Pm.wpart = reinterpret_cast<float*>(wsb + ws.wpart);
+  Pm.spill = reinterpret_cast<float*>(wsb + ws.spill);
+  Pm.tab_cap = (int)tab_cap;
+  Pm.spill_on = spill_on;
   Pm.rawo = reinterpret_cast<float*>(wsb + ws.rawo);
   Pm.rawml = reinterpret_cast<float*>(wsb + ws.rawml);
   if (raw.cap > 0) {

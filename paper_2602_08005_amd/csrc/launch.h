@@ -43,6 +43,8 @@ struct DecodeParams {
   int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)
   int n_ref_max, n_chunk_max;
   int S, pages_per_split;   // split grid
+  int tab_cap;              // ordinals a block's LDS weight table holds (rows of a split's table in the workspace)
+  int spill_on;             // some sequence has more ordinals than that: older ordinals go to the spill table
   float qk_scale_log2;      // scale * log2(e)
   // workspace
   int32_t* status;
@@ -56,7 +58,8 @@ struct DecodeParams {
   int32_t* items;           // [0] = number of (sequence, split) items, then item = sequence * kMaxSplits + split
   float* accpart;
   float* opart;
-  float* wpart;
+  float* wpart;             // fp32 [B][Hkv][S][tab_cap][Gp]
+  float* spill;             // fp32 [B][Hkv][n_ref_max][Gp]: plain weights of ordinals older than a block's window
   float* rawo;              // fp32 [B][Hkv][kRawMaxChunks][Gp][128]: sum_t 2^(x_t - m) V_t of one raw chunk
   float* rawml;             // fp32 [B][Hkv][kRawMaxChunks][Gp][2]: the chunk's m (largest logit, log2 units) and sum of weights
 };
@@ -129,8 +132,8 @@ hipError_t launch_append(const CompressParams& P, hipStream_t st);
 enum KernelId { K_REF_SCORES = 0, K_STREAM, K_REF_VALUES, K_FINALIZE, K_ADMIT, K_SIM, K_RESOLVE, K_EXACT, K_PROJECT, K_RAW, K_COUNT };
 void timing_mark(int kernel_id, hipStream_t st);
 
-// LDS bytes of the streaming kernel for sequences with at most n_ref_max reference ordinals.
-size_t stream_lds_bytes(int n_ref_max, int Gp, int R, int nw, bool joint);
+// LDS bytes of the streaming kernel with a weight table of n_rows reference ordinals.
+size_t stream_lds_bytes(int n_rows, int Gp, int R, int nw, bool joint);
 // The streaming kernel, one function per family of template variants (stream_*.hip); each picks the rank.
 hipError_t stream_split_full(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
 hipError_t stream_split_subset(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);

@@ -96,7 +96,12 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // blocks are not free here: each needs a whole compute unit's LDS before it can start and exit.)  Blocks of the kv-heads
 // of one item run side by side and sweep the same pages; with eight kv-heads, block id % 8 = head, so all splits of a
 // (sequence, head) also share one XCD's L2 copy of that pair's per-reference score table.
-template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT>
+// SPILL: sequences whose per-reference weight table does not fit the LDS (beyond roughly 160 000 tokens at four query
+// heads per kv-head).  The LDS table then covers a window of the P.tab_cap most recent ordinals the block can touch
+// -- its own tokens' ordinals among them: every 16th token is a reference pointing at itself -- and weights of older
+// ordinals are added, as plain floats with hardware float atomics, to one table per (sequence, kv-head) in global
+// memory that all splits share (zeroed by ref_scores, read by ref_values).
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
@@ -117,7 +122,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const int n_cov = refs_covered(P, b, L, p1);          // ordinals this split can touch
   const int n_ref = refs_below(L, P.stride);
   const int Gp = P.Gp, G = P.G;
-  const int n_tab = n_cov * Gp;
+  const int n_win = SPILL ? min(n_cov, P.tab_cap) : n_cov;   // ordinals [win_lo, n_cov) live in the LDS table
+  const int win_lo = n_cov - n_win;
+  const int n_tab = n_win * Gp;
   float* tab = smem;
   float* accbuf = smem + ((n_tab + 3) & ~3);              // [Gp][R]
   float* lbuf = accbuf + Gp * R;                          // [16]
@@ -143,6 +150,20 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const bool cm_staged = n_cm <= kOvfCap;
   float cm_mine = -INFINITY;
   if (cm_staged && tid < n_cm) cm_mine = P.cmax[bh * P.n_chunk_max * Gp + tid];
+  if (!cm_staged) {
+    // long sequences (more chunk maxima than the list holds; the table then has thousands of entries): every thread
+    // reduces a strided share -- NW * 64 is a multiple of Gp, so a thread's entries all belong to one head -- and the
+    // partial maxima are staged in the table area, which is cleared afterwards
+    for (int i = tid; i < n_cm; i += NW * 64) cm_mine = fmaxf(cm_mine, P.cmax[bh * P.n_chunk_max * Gp + i]);
+    tab[tid] = cm_mine;
+    __syncthreads();
+  }
+  float mref = -INFINITY;                                  // exponent offset for q-head g = ln (see below)
+  if (!cm_staged) {
+    const int gcol = ln < (uint32_t)Gp ? ln : Gp - 1;
+    for (int k = gcol; k < NW * 64; k += Gp) mref = fmaxf(mref, tab[k]);
+    __syncthreads();
+  }
   for (int i = tid; i < n_tab; i += NW * 64) utab[i] = 0u;
   for (int i = tid; i < Gp * R + 16; i += NW * 64) accbuf[i] = 0.f;
   if (tid == 0) { ovf[0] = 0u; pgctr[0] = 0u; }
@@ -155,14 +176,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const bool ghead = ln < (uint32_t)G;
   // exponent offset for q-head g = ln: the largest chunk maximum (the staged copy is free again after the barrier
   // that ends the set-up)
-  float mref = -INFINITY;
-  {
+  if (cm_staged) {
     const int nch = ceil_div(n_ref, kRefChunk);
-    if (cm_staged) {
-      for (int c = 0; c < nch; ++c) mref = fmaxf(mref, ovf_val[c * Gp + gq]);
-    } else {
-      for (int c = 0; c < nch; ++c) mref = fmaxf(mref, P.cmax[(bh * P.n_chunk_max + c) * Gp + gq]);
-    }
+    for (int c = 0; c < nch; ++c) mref = fmaxf(mref, ovf_val[c * Gp + gq]);
   }
   const float cinit = -(mref + exp_bias(SUBSET));
   const float cshift = table_shift_base(mref, exp_bias(SUBSET));
@@ -214,6 +230,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const int gsh2 = group_shift(Gp) + 2;                   // ordinal -> byte offset of its table row
   const uint32_t gq4 = gq * 4u, ln4 = ln * 4u;
   const uint32_t id_hi = (uint32_t)(n_cov - 1);
+  float* spill_bh = SPILL ? P.spill + bh * P.n_ref_max * Gp : nullptr;
   __syncthreads();
 
   float4v acc[TileT::NB];
@@ -257,7 +274,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // wrapped is recorded in the overflow list (rare).  The check runs one page late, in the shadow of the next
   // page's score MFMAs, so the atomics' return latency is never waited for.
   uint32_t pend_old[4] = {0u, 0u, 0u, 0u}, pend_fix[4] = {0u, 0u, 0u, 0u};
-  uint32_t pend_ids[2] = {0u, 0u};      // the page's four ordinals (16 bits each: a table fits the LDS)
+  uint32_t pend_ids[2] = {0u, 0u};      // table rows of the page's four ordinals (16 bits each: a table fits the LDS)
   auto list_push = [&](uint32_t ent, float amount) {
     const uint32_t slot = atomicAdd(&ovf[0], 1u);
     if (slot < (uint32_t)kOvfCap) {
@@ -337,6 +354,18 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         f[e] = __builtin_ldexpf(p[e], table_shift(sr[e], cshift));
         off[e] = ((uint32_t)ids[e] << gsh2) + ln4;
       }
+      if constexpr (SPILL) {     // ordinals older than the window: plain weights into the pair's table in global memory
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (ids[e] < win_lo) {
+            if (p[e] != 0.f) unsafeAtomicAdd(reinterpret_cast<float*>(reinterpret_cast<char*>(spill_bh) + off[e]), p[e]);
+            f[e] = 0.f;
+            off[e] = ln4;          // a zero addend to the window's first row
+          } else {
+            off[e] -= (uint32_t)win_lo << gsh2;
+          }
+        }
+      }
       if (!(fmaxf(fmaxf(f[0], f[1]), fmaxf(f[2], f[3])) < kLim)) {   // an addend does not fit (rare): the whole
 #pragma unroll                                                      // weight goes to the list
         for (int e = 0; e < 4; ++e)
@@ -347,8 +376,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         pend_fix[e] = f[e] < kLim ? (uint32_t)(f[e] + 0.5f) : 0u;      // to nearest: no one-sided loss per token
         pend_old[e] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off[e]), pend_fix[e]);
       }
-      pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
-      pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
+      if constexpr (SPILL) {     // window-relative rows, recovered from the offsets
+        pend_ids[0] = (off[0] >> gsh2) | ((off[1] >> gsh2) << 16);
+        pend_ids[1] = (off[2] >> gsh2) | ((off[3] >> gsh2) << 16);
+      } else {
+        pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
+        pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
+      }
     }
     // 4-bit: the value product takes p * scale (rounded to bf16 for the matrix unit) against 16 + code; the scalar
     // that takes the offset back out must use the SAME rounded weights, or the two large terms would not cancel
@@ -548,7 +582,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   if (tid == 0) P.wflag[part] = ovf[0] != 0u;
   for (int i = tid; i < Gp * R; i += NW * 64) P.accpart[part * Gp * R + i] = accbuf[i] + (Q4 ? zbuf[i / R] : 0.f);
   // the table leaves the block as floats, normally still in the per-entry units of table_shift()
-  float* wp = P.wpart + part * P.n_ref_max * Gp;
+  float* wp = P.wpart + part * P.tab_cap * Gp;              // window entry i <-> table element win_lo * Gp + i
   const uint32_t n_ovf = ovf[0];
   if (n_ovf == 0) {
     for (int i = tid * 4; i < n_tab; i += NW * 64 * 4) {
@@ -560,7 +594,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   } else {
     // rare: turn the table into plain weights (entry i = (j, g) has the units of score-table element i)
-    const float* sref_tab = P.sref + bh * P.n_ref_max * Gp;
+    const float* sref_tab = P.sref + (bh * P.n_ref_max + win_lo) * Gp;
     for (int i = tid; i < n_tab; i += NW * 64)
       tab[i] = __builtin_ldexpf((float)utab[i], -table_shift(sref_tab[i], xbuf[i & (Gp - 1)]));
     __syncthreads();
@@ -584,8 +618,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false>
+template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  if constexpr (!SPILL) {        // (a spilling call is a long-sequence call: its bf16 latent loads are non-temporal)
+    if (P.spill_on) return launch_stream<R, NW, JOINT, SUBSET, Q4, !Q4, true>(P, grid, lds, st);
+  }
   if constexpr (!Q4 && !NT) {
     if (P.nt) return launch_stream<R, NW, JOINT, SUBSET, Q4, true>(P, grid, lds, st);
   }
@@ -606,12 +643,12 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 

@@ -26,6 +26,7 @@ def _setup(case, page_perm_seed=None, pool_slack=1.25):
     cache = dk.PagedCache(dims, B, 16, max_len, page_ids=page_ids, ref_slots=ref_slots)
     # poison the pools so that a read of an unwritten slot shows up (0x7fc0 = bf16 NaN)
     cache.latent_pool.fill_(0x7FC0)
+    cache.ref_pool.fill_(0x7FC0)
     cache.idx_pool.fill_(0x7FFFFFF0)
     for b, L in enumerate(case.lens):
         if L > 0:
@@ -172,6 +173,31 @@ def test_zero_query_gives_mean_of_reconstructed_values():
     for g in range(4):
         assert np.max(np.abs(got[0, g] - vh[:, g // 2].mean(0))) <= 1e-2
         assert abs(lse[0, g] - np.log(500)) < 1e-3
+
+
+def test_unadmitted_reference_slots_and_tail_records_hold_nan():
+    """Pool slots 0..2 are never admitted and hold NaN patterns, like every record past a sequence's end and every
+    reference slot past its last reference: rows that pad a kernel's last tile must not reach the results, not
+    even multiplied by a zero weight.  Lengths put the last reference chunk (256 references) and the last page at
+    ragged positions."""
+    import paper_2602_08005_amd as dk
+    from tests.helpers import Case
+    case = Case(7050, [16 * 300 + 7, 16 * 256, 16 * 257 + 1, 5], Hkv=2, Hq=8, r=32, n_proto=16)
+    nb, max_len = len(case.lens), max(case.lens)
+    pps = -(-max_len // 16)
+    dims = dk.make_dims(2, 8, 32, nb * pps + 3, nb * pps + 3)
+    cache = dk.PagedCache(dims, nb, 16, max_len, page_ids=[3 + b * pps + np.arange(pps) for b in range(nb)],
+                          ref_slots=[3 + b * pps + np.arange(pps) for b in range(nb)])
+    for pool in (cache.latent_pool, cache.ref_pool):
+        pool.fill_(0x7FC0)
+    cache.idx_pool.fill_(-1)
+    for b in range(nb):
+        r = case.res[b]
+        cache.put_sequence(b, r["idx"], r["zb_k"], r["zb_v"], case.K[b][::16], case.V[b][::16])
+    scale = 1.0 / np.sqrt(128)
+    got, lse, status = _run(case, cache, scale)
+    assert status == 0 and np.all(np.isfinite(got))
+    _compare(case, got, lse, scale)
 
 
 def test_unsupported_and_workspace_errors_on_device():
