@@ -26,14 +26,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain copy
-# of known size (the summaries under profiles/ give the commands and the raw counter values).
-MEASURED_STREAM_TRAFFIC_CFG3 = 2_271_000_000         # SPLIT: read 2.250 GB + written 0.021 GB
-MEASURED_STREAM_TRAFFIC_CFG3_JOINT = 1_189_000_000   # JOINT: read 1.168 GB + written 0.021 GB
-MEASURED_STREAM_TRAFFIC_RAGGED = 1_226_000_000       # irregular paged batch (SPLIT, rank 48): 1.196 + 0.030 GB
-MEASURED_SIM_TRAFFIC_PREFILL32K = 160_700_000        # similarity kernel, one 32768-token layer: 0.152 + 0.008 GB
-MEASURED_STREAM_TRAFFIC_CFG3_SELECT25 = 596_000_000  # SPLIT, a quarter of the pages selected: 0.575 + 0.021 GB
-MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4 = 476_000_000  # JOINT, 4-bit latents: 0.451 + 0.025 GB
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def measured_traffic(key):
+    """HBM bytes per launch of a workload's dominant kernel as counted by rocprofv3 (FETCH_SIZE / WRITE_SIZE runs
+    scaled by a plain copy of known size).  The figures live in a tracked summary, profiles/hbm_traffic.md, one table
+    row per workload key with the commit they were measured at; a shape that has no row reports null."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 3 and cells[0] == key:
+                    return int(cells[2].replace("_", "").replace(",", ""))
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def timing_begin_sampled(B, calls):
@@ -111,6 +119,7 @@ def prefill_workload(args, torch, dk, B, G):
     idx, zk, zv = cache.get_sequence(0, 0, L)
     t0 = time.perf_counter()
     nsamp = min(L, 32768 if not l2 else 8192)    # the L2 oracle evaluates the definition token by token (slower)
+    nsamp = min(nsamp, getattr(args, "parity_tokens", None) or nsamp)
     ref = O.compress(f(Kh), f(Vh), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s,
                      mode=O.JOINT if joint else O.SPLIT, start=L - nsamp, metric=O.L2 if l2 else O.COSINE)
     t_or = time.perf_counter() - t0
@@ -125,7 +134,7 @@ def prefill_workload(args, torch, dk, B, G):
                                f"{'squared-L2' if l2 else 'cosine'} top-1"},
         "roofline": {"bound": "mfma", "kernel": "k_sim_top2", "achieved": round(tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_SIM_TRAFFIC_PREFILL32K if (L, Hkv, r) == (32768, 8, 64) else None,
+                     "traffic": measured_traffic("prefill32k_sim_top2") if (L, Hkv, r, NL) == (32768, 8, 64, 32) and not joint and not l2 else None,
                      "flops_per_launch": flops, "avg_launch_ms": round(ms_sim, 4)},
         "cpu_baseline": {"value": round(nsamp / t_or / NL, 1), "unit": "tokens/s", "cores":
                          int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
@@ -135,7 +144,7 @@ def prefill_workload(args, torch, dk, B, G):
         "kernel_timing": timing_note,
         "parity": {"what": f"ordinals of the last {nsamp} tokens of the last layer vs CPU oracle", "mismatches": mism},
     }
-    print(json.dumps(result))
+    return result
 
 
 def _oracle_decode_seq(cache, b, L, K, V, W, q_bits_row, s, scale):
@@ -224,7 +233,7 @@ def ragged_workload(args, torch, dk, B, G):
         "roofline": {"bound": "hbm", "kernel": "k_stream", "achieved": round(stream_bytes / (ms_stream * 1e-3) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(stream_bytes / (ms_stream * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_STREAM_TRAFFIC_RAGGED if args.mode == "split" and not args.contiguous else None,
+                     "traffic": measured_traffic("ragged_split") if args.mode == "split" and not args.contiguous else None,
                      "algorithmic_bytes_per_launch": stream_bytes, "avg_launch_ms": round(ms_stream, 5)},
         "cpu_baseline": {"value": round(nseq / (t_or * int(lens.sum()) / samp_tokens), 3), "unit": "tokens/s",
                          "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
@@ -235,7 +244,7 @@ def ragged_workload(args, torch, dk, B, G):
         "kernel_timing": timing_note,
         "parity": {"what": "shortest, median, longest sequence vs CPU oracle", "max_abs_err": worst},
     }
-    print(json.dumps(result))
+    return result
 
 
 def append_workload(args, torch, dk, B, G):
@@ -324,7 +333,7 @@ def append_workload(args, torch, dk, B, G):
         ms_stream = kern["stream"][0] / kern["stream"][1]
         ach = result["roofline"]["algorithmic_bytes_per_launch"] / (ms_stream * 1e-3) / 1e9
         result["roofline"]["achieved"], result["roofline"]["frac"] = round(ach, 1), round(ach / HBM_PEAK_GBS, 4)
-    print(json.dumps(result))
+    return result
 
 
 def main():
@@ -362,6 +371,8 @@ def main():
     ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
                     help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
+    ap.add_argument("--no-extras", dest="extras", action="store_false",
+                    help="decode128k: do not append the short runs of the other configurations ('workloads')")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not record per-kernel events (roofline.achieved is then null)")
     args = ap.parse_args()
@@ -390,11 +401,51 @@ def main():
         B.tune(name, int(val))
     torch.cuda.set_device(0)
     if args.workload == "prefill32k":
-        return prefill_workload(args, torch, dk, B, G)
-    if args.workload == "ragged":
-        return ragged_workload(args, torch, dk, B, G)
-    if args.workload == "append32k":
-        return append_workload(args, torch, dk, B, G)
+        result = prefill_workload(args, torch, dk, B, G)
+    elif args.workload == "ragged":
+        result = ragged_workload(args, torch, dk, B, G)
+    elif args.workload == "append32k":
+        result = append_workload(args, torch, dk, B, G)
+    else:
+        result = decode_workload(args, torch, dk, B, G)
+        plain = (args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, args.mode, args.latent_bits,
+                 args.select, args.raw) == (8, 131072, 32, 8, 32, 64, "split", 16, 0.0, 0)
+        if args.extras and plain:             # the headline run also carries short runs of the other configurations
+            result["workloads"] = extra_workloads(args, torch, dk, B, G)
+    print(json.dumps(result))
+
+
+def extra_workloads(args, torch, dk, B, G):
+    """Short runs of the other configurations, reported inside the headline's JSON line: the long-context decode with
+    JOINT latents, the irregular paged batch, the 32768-token prefill compression and the single-sequence append
+    loop.  Each entry carries its throughput, the roofline of its dominant kernel and its parity figure against the
+    CPU oracle (on a smaller sample than the workload's own command line takes)."""
+    import copy
+    import gc
+    out = {}
+    runs = [("decode128k_joint", decode_workload, dict(mode="joint", steps=5, warmup=1, parity_seqs=2)),
+            ("ragged", ragged_workload, dict(workload="ragged", steps=20, warmup=2)),
+            ("prefill32k", prefill_workload, dict(workload="prefill32k", steps=3, warmup=1, parity_tokens=4096)),
+            ("append32k", append_workload, dict(workload="append32k", warmup=1))]
+    for name, fn, over in runs:
+        gc.collect()
+        torch.cuda.empty_cache()
+        a = copy.copy(args)
+        for k, v in over.items():
+            setattr(a, k, v)
+        t0 = time.time()
+        r = fn(a, torch, dk, B, G)
+        keep = ("value", "unit", "steps", "ms_per_step", "config", "roofline", "path_hbm_frac", "kernel_ms", "kernel_us",
+                "kernel_timing", "parity", "status_flag", "cpu_baseline", "metric")
+        out[name] = {k: r[k] for k in keep if k in r}
+        out[name]["command"] = "python bench.py " + {"decode128k_joint": "--mode joint", "ragged": "--workload ragged",
+                                                     "prefill32k": "--workload prefill32k",
+                                                     "append32k": "--workload append32k"}[name]
+        log(f"[bench] extra workload {name}: {r['value']} {r['unit']} ({time.time() - t0:.1f} s wall)")
+    return out
+
+
+def decode_workload(args, torch, dk, B, G):
     Bt, L, NL, Hkv, Hq, r, D, s = args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, 128, 16
     scale = 1.0 / np.sqrt(D)
     pages_per_seq, refs_per_seq = -(-L // 16), -(-L // s)
@@ -516,13 +567,11 @@ def main():
         path_bytes += Bt * args.raw * Hkv * 2 * D * 2             # raw K and V rows, read once
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
-    if q4:
-        if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None and joint:
-            roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT_Q4
-    elif (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and selections is None:   # a raw segment does not touch k_stream
-        roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_JOINT if joint else MEASURED_STREAM_TRAFFIC_CFG3
-    elif (Bt, L, Hkv, Hq, r, joint) == (8, 131072, 8, 32, 64, False) and args.select == 0.25 and not args.select_tokens:
-        roof["traffic"] = MEASURED_STREAM_TRAFFIC_CFG3_SELECT25
+    if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and raw is None:        # the rows of profiles/hbm_traffic.md
+        key = "decode128k_" + args.mode + ("_q4" if q4 else "")
+        if selections is not None:
+            key += f"_select{args.select:g}" + ("_tokens" if args.select_tokens else "")
+        roof["traffic"] = measured_traffic(key)
     kernel_ms = {}
     if timing:
         for k, (ms, n) in kern.items():
@@ -541,7 +590,8 @@ def main():
         from oracle import deltakv_oracle as O
         f = O.bf16_bits_to_f64
         t_layer, worst_abs, worst_rel = 0.0, 0.0, 0.0
-        for b in range(Bt):
+        n_par = min(Bt, getattr(args, "parity_seqs", None) or Bt)
+        for b in range(n_par):
             if q4:      # the values the GPU's own 4-bit records read back as (scale * code + zero)
                 i0, c0, s0, z0 = cache.get_sequence_q4(b, 0, L)
                 zkf = zvf = f(s0)[..., None] * c0 + f(z0)[..., None]
@@ -568,12 +618,12 @@ def main():
             worst_abs = max(worst_abs, float(np.max(np.abs(got - want))))
             worst_rel = max(worst_rel, float(np.linalg.norm(got - want) / np.linalg.norm(want)))
             del i0, zkf, zvf
-        parity = {"what": f"layer 0, all {Bt} sequences, all query heads vs CPU oracle (worst sequence)",
+        parity = {"what": f"layer 0, {n_par} of {Bt} sequences, all query heads vs CPU oracle (worst sequence)",
                   "max_abs_err": worst_abs, "rel_l2_err": worst_rel}
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        cpu = {"value": round(Bt / (t_layer * NL), 5), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-               "sample": f"decode attention of layer 0 for all {Bt} sequences = 1 of {NL} layers of one step "
-                         f"({t_layer:.2f} s), extrapolated linearly to the step"}
+        cpu = {"value": round(n_par / (t_layer * NL), 5), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"decode attention of layer 0 for {n_par} of the {Bt} sequences = {n_par}/{Bt} of 1 of {NL} "
+                         f"layers of one step ({t_layer:.2f} s), extrapolated linearly to the step"}
 
     result = {
         "metric": "decode-attn tokens/s over compressed cache + % HBM roofline; compress tokens/s",
@@ -604,7 +654,7 @@ def main():
         "parity": parity, "status_flag": status,
         "context": "paper: 29% KV memory and up to 2x vLLM decode throughput, whole model on 1x RTX PRO 6000 (not comparable)",
     }
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":
