@@ -11,7 +11,8 @@ What it follows (paper: "DeltaKV: Residual-Based KV Cache Compression via
 Long-Range Similarity"):
 
 * strided reference set T = {kv_t : t mod s = 0, t < i}        -- section 4.1
-* retrieval of the nearest reference (top-k with k = 1)          -- section 4.1
+* retrieval of the nearest references (arg top-k; k = 1 by
+  default) and the mean of the retrieved set as the reference    -- section 4.1
 * residual against the retrieved reference, then the
   down-projection encoder                                        -- section 4.1 (compressor), appendix B.2 (lifecycle steps 1-3)
 * reconstruction KV_hat = f_d(z) + KV_ref with the bias-free
@@ -26,7 +27,8 @@ in the repository's design notes; the ones that shape this file:
     for head_dim 128); a zero-norm vector scores 0 against everything; the
     paper's own metric, squared L2 distance over the same vector, is the
     alternative (metric = L2);
-  - k = 1, ties go to the lowest reference ordinal;
+  - k = 1 unless top_k says otherwise; ties go to the lowest reference ordinal; a token with fewer
+    candidates than k takes all of them (the paper does not say);
   - positions are 0-indexed, token 0 is a reference, candidates are strictly
     earlier (ordinal j is token j*s < i);
   - a reference token is stored raw and attends as itself: idx = own ordinal,
@@ -196,9 +198,22 @@ def quantize_tokenwise_4bit(z: np.ndarray):
     return codes, scale_b, zero_b, back
 
 
+def reference_mean(X: np.ndarray, idx: np.ndarray, s: int) -> np.ndarray:
+    """Mean of the raw rows of the references each (token, head) retrieved (section 4.1, the reference
+    representation: the mean of the retrieved set).  X [L, H, D] raw states; idx [n, H, k] reference
+    ordinals (ordinal j is token j*s), -1 in unused slots; every (token, head) has at least one.
+    Returns [n, H, D]."""
+    idx = np.asarray(idx)
+    valid = idx >= 0                                         # [n, H, k]
+    tok = np.where(valid, idx, 0).astype(np.int64) * s
+    hh = np.arange(X.shape[1])[None, :, None]
+    rows = X[tok, hh] * valid[..., None]                     # [n, H, k, D]
+    return rows.sum(axis=2) / valid.sum(axis=2)[..., None]
+
+
 def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.ndarray,
              s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048, metric: int = COSINE,
-             latent_bits: int = 16):
+             latent_bits: int = 16, top_k: int = 1):
     """Compress tokens start..L-1 of one sequence.
 
     K, V: float64 [L, H, D] -- the raw states of the WHOLE sequence so far (the
@@ -206,7 +221,12 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
 
     Returns a dict of per-token results for tokens start..L-1 (index 0 of each
     array is token `start`):
-      idx      int32   [n, H]      reference ordinal (own ordinal for reference tokens)
+      idx      int32   [n, H]      reference ordinal (own ordinal for reference tokens); with top_k > 1
+                                   [n, H, top_k]: the top_k nearest references in order of rank (section 4.1,
+                                   arg top-k; equal scores go to the lower ordinal first), -1 in the slots of a
+                                   token that has fewer candidates than top_k; a reference token holds its own
+                                   ordinal in slot 0 and -1 elsewhere.  The residual is taken against the MEAN of
+                                   the retrieved references' raw rows (section 4.1, reference representation).
       cos      float64 [n, H]      the winning score: cosine (1.0 stored for reference tokens), or with
                                    metric = L2 minus the squared distance to the chosen reference
       z_k, z_v float64 [n, H, r]   unrounded latents (JOINT: z_v is z_k)
@@ -226,6 +246,7 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
     refs = kv[0::s]                                        # ordinal j <-> token j*s
     ref_norm = np.sqrt(np.einsum("jhn,jhn->jh", refs, refs))
     idx = np.zeros((n, H), dtype=np.int32)
+    idx_k = np.full((n, H, top_k), -1, dtype=np.int32)
     cos = np.zeros((n, H), dtype=np.float64)
     pos = np.arange(start, L)
     is_ref = (pos % s) == 0
@@ -249,13 +270,25 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
             j = np.argmax(c, axis=1)                       # lowest ordinal among equal maxima
             idx[b0:b1, h] = j
             cos[b0:b1, h] = c[np.arange(b1 - b0), j]
+            if top_k > 1:
+                # descending score, equal scores in ascending ordinal (a stable sort of the negated scores keeps
+                # the ascending order of the columns among equals); slots beyond the candidates stay -1
+                rank = np.argsort(-c, axis=1, kind="stable")[:, :top_k]
+                ok = np.arange(rank.shape[1])[None, :] < ncand[:, None]
+                idx_k[b0:b1, h, :rank.shape[1]] = np.where(ok, rank, -1)
     # reference tokens point at themselves and carry a zero latent
     idx[is_ref] = (pos[is_ref] // s)[:, None]
     cos[is_ref] = 0.0 if metric == L2 else 1.0
-    tok_ref = idx.astype(np.int64) * s                     # token position of the chosen reference
     hh = np.arange(H)[None, :]
-    r_k = K[pos[:, None], hh] - K[tok_ref, hh]             # [n, H, D]
-    r_v = V[pos[:, None], hh] - V[tok_ref, hh]
+    if top_k > 1:
+        idx_k[:, :, 0] = np.where(is_ref[:, None], idx, idx_k[:, :, 0])
+        idx_k[is_ref, :, 1:] = -1
+        r_k = K[pos[:, None], hh] - reference_mean(K, idx_k, s)
+        r_v = V[pos[:, None], hh] - reference_mean(V, idx_k, s)
+    else:
+        tok_ref = idx.astype(np.int64) * s                 # token position of the chosen reference
+        r_k = K[pos[:, None], hh] - K[tok_ref, hh]         # [n, H, D]
+        r_v = V[pos[:, None], hh] - V[tok_ref, hh]
     if mode == SPLIT:
         z_k = r_k @ w_down_k
         z_v = r_v @ w_down_v
@@ -266,7 +299,7 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
     if mode == SPLIT:
         z_v[is_ref] = 0.0
     out = {
-        "idx": idx, "cos": cos, "z_k": z_k, "z_v": z_v,
+        "idx": idx_k if top_k > 1 else idx, "cos": cos, "z_k": z_k, "z_v": z_v,
         "zb_k": f64_to_bf16_bits(z_k), "ref_k": K[0::s].copy(), "ref_v": V[0::s].copy(),
         "mode": mode, "s": s, "start": start,
     }
@@ -291,12 +324,17 @@ def cosine_of(K: np.ndarray, V: np.ndarray, i: int, h: int, j: int, s: int) -> f
 # Reconstruction and decode attention
 # ----------------------------------------------------------------------------
 def reconstruct(idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v):
-    """KV_hat = reference + z W_up for every (token, head).  Shapes: idx [L,H],
-    z_* [L,H,r], ref_* [n_ref,H,D], w_up_* [r,D]; all float64."""
-    L, H = idx.shape
-    hh = np.arange(H)[None, :]
-    k_hat = ref_k[idx, hh] + z_k @ w_up_k
-    v_hat = ref_v[idx, hh] + z_v @ w_up_v
+    """KV_hat = reference + z W_up for every (token, head).  Shapes: idx [L,H] (one reference) or
+    [L,H,k] (the mean of the references in the slots that are not -1: section 4.1, the decoded
+    residual is added back to the mean reference), z_* [L,H,r], ref_* [n_ref,H,D], w_up_* [r,D];
+    all float64."""
+    if idx.ndim == 3:
+        base_k, base_v = reference_mean(ref_k, idx, 1), reference_mean(ref_v, idx, 1)
+    else:
+        hh = np.arange(idx.shape[1])[None, :]
+        base_k, base_v = ref_k[idx, hh], ref_v[idx, hh]
+    k_hat = base_k + z_k @ w_up_k
+    v_hat = base_v + z_v @ w_up_v
     return k_hat, v_hat
 
 

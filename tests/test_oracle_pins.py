@@ -648,3 +648,89 @@ def test_4bit_record_validity_criterion_accepts_fp32_decisions_and_rejects_plant
     with pytest.raises(AssertionError):
         check_q4_records(const, np.full(const.shape, 1e-12), np.ones((1, 8), np.uint8), np.zeros(1, np.uint16),
                          O.f64_to_bf16_bits(np.array([0.375])))
+
+
+# ---------------------------------------------------------------- top-k retrieval with the mean of the references
+@pytest.mark.parametrize("metric", [O.COSINE, O.L2])
+@pytest.mark.parametrize("top_k", [2, 4])
+def test_topk_retrieval_is_brute_force_ranking_and_the_residual_is_against_the_mean(metric, top_k):
+    """Section 4.1 (arg top-k, then the mean of the retrieved references), by hand in pure Python on a tiny case
+    with duplicated references (equal scores: lower ordinal first), an exact copy of a reference, and tokens that
+    have fewer candidates than k (they take all of them)."""
+    import math
+    K, V, cls, P = _small_case(seed=83, L=61, H=2, D=8, r=4, s=4, n_proto=3)
+    K[8], V[8] = K[0], V[0]                       # reference 2 duplicates reference 0
+    K[20], V[20] = K[4], V[4]                     # reference 5 duplicates reference 1
+    K[27], V[27] = K[12], V[12]                   # token 27 is an exact copy of reference 3
+    wk, wv = _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"])
+    res = O.compress(K, V, wk, wv, s=4, mode=O.SPLIT, metric=metric, top_k=top_k)
+    L, H, D = K.shape
+    assert res["idx"].shape == (L, H, top_k)
+    for i in range(L):
+        for h in range(H):
+            got = [int(x) for x in res["idx"][i, h]]
+            if i % 4 == 0:
+                assert got == [i // 4] + [-1] * (top_k - 1)
+                assert np.all(res["z_k"][i, h] == 0) and np.all(res["z_v"][i, h] == 0)
+                continue
+            a = [float(x) for x in K[i, h]] + [float(x) for x in V[i, h]]
+            scored = []
+            for j in range((i + 3) // 4):
+                bvec = [float(x) for x in K[4 * j, h]] + [float(x) for x in V[4 * j, h]]
+                if metric == O.L2:
+                    sc = -math.fsum((x - y) ** 2 for x, y in zip(a, bvec))
+                else:
+                    den = math.sqrt(math.fsum(x * x for x in a)) * math.sqrt(math.fsum(y * y for y in bvec))
+                    sc = math.fsum(x * y for x, y in zip(a, bvec)) / den if den > 0 else 0.0
+                scored.append((sc, j))
+            # exact duplicates must tie exactly whatever the summation order: compare on rounded scores
+            ranked = sorted(scored, key=lambda t: (-round(t[0], 12), t[1]))[:top_k]
+            want = [j for _, j in ranked] + [-1] * (top_k - len(ranked))
+            assert got == want, (i, h, got, want)
+            m = len(ranked)
+            mean_k = sum(K[4 * j, h] for _, j in ranked) / m
+            mean_v = sum(V[4 * j, h] for _, j in ranked) / m
+            assert np.max(np.abs(res["z_k"][i, h] - (K[i, h] - mean_k) @ wk)) < 1e-12
+            assert np.max(np.abs(res["z_v"][i, h] - (V[i, h] - mean_v) @ wv)) < 1e-12
+    assert list(res["idx"][27, 0][:1]) == [3]                    # the exact copy is its own nearest reference
+    if top_k == 4:                                               # token 1..3 see one candidate, 5..7 two, 9..11 three
+        assert [int((res["idx"][t, 0] >= 0).sum()) for t in (1, 5, 9, 13)] == [1, 2, 3, 4]
+
+
+def test_topk_first_slot_is_the_top1_choice_and_k_identical_references_give_a_zero_latent():
+    K, V, cls, P = _small_case(seed=85, L=70, H=2, D=8, r=4, s=4, n_proto=4)
+    wk, wv = _f64(P["w_down_k_bf16"]), _f64(P["w_down_v_bf16"])
+    one = O.compress(K, V, wk, wv, s=4, mode=O.JOINT)
+    four = O.compress(K, V, wk, wv, s=4, mode=O.JOINT, top_k=4)
+    assert np.array_equal(four["idx"][:, :, 0], one["idx"])
+    # every reference identical and the token a copy of them: the mean is that vector, the latent is zero
+    K2, V2 = K.copy(), V.copy()
+    K2[::4], V2[::4] = K[0], V[0]
+    K2[33], V2[33] = K[0], V[0]
+    res = O.compress(K2, V2, wk, wv, s=4, mode=O.JOINT, top_k=4)
+    assert res["idx"][33, 0].tolist() == [0, 1, 2, 3] and np.all(res["z_k"][33] == 0)
+
+
+@pytest.mark.parametrize("joint", [False, True])
+def test_topk_full_rank_reconstruction_and_decode_against_dense_attention(joint):
+    """With full-rank orthonormal projections the decoded residual added back to the mean reference is the raw
+    token whatever k is, so decode over the k = 4 cache equals dense attention over the raw K, V (library routine)."""
+    D = 16
+    r = 2 * D if joint else D
+    K, V, cls, _ = _small_case(seed=87, L=90, H=2, D=D, r=8, s=4)
+    P = G.make_projections(98, D, r, joint=joint, recipe="paired")
+    mode = O.JOINT if joint else O.SPLIT
+    res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4, mode=mode, top_k=4, metric=O.L2)
+    kh, vh = O.reconstruct(res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
+                           P["w_up_k_f64"], P["w_up_v_f64"])
+    assert np.max(np.abs(kh - K)) < 1e-12 and np.max(np.abs(vh - V)) < 1e-12
+    q = _f64(G.make_queries(87, 1, 4, D))[0]
+    out, _ = O.decode_attn_direct(q, res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"],
+                                  P["w_up_k_f64"], P["w_up_v_f64"], 0.25)
+    assert np.max(np.abs(out - _torch_sdpa(q, K, V, 0.25))) < 1e-11
+    # and with zero latents the reconstruction is the mean of the retrieved references, by hand for one token
+    t, h = 57, 1
+    js = [int(j) for j in res["idx"][t, h] if j >= 0]
+    kz, _ = O.reconstruct(res["idx"], 0 * res["z_k"], 0 * res["z_v"], res["ref_k"], res["ref_v"],
+                          P["w_up_k_f64"], P["w_up_v_f64"])
+    assert len(js) == 4 and np.max(np.abs(kz[t, h] - sum(K[4 * j, h] for j in js) / 4)) < 1e-14
