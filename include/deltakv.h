@@ -91,7 +91,7 @@ typedef struct {
   int64_t n_pages;      /* capacity of the latent / index pools, in pages          */
   int64_t n_ref_slots;  /* capacity of the reference pool, in reference tokens     */
   int32_t latent_bits;  /* 16 (or 0): bf16 latents; 4: 4-bit token-wise latents    */
-  int32_t reserved;     /* must be 0                                               */
+  int32_t top_k;        /* 1 (or 0), 2 or 4: references retrieved per (token, kv-head) */
 } deltakv_dims;
 
 /* Filled by deltakv_paged_layout; the only source of sizes and strides.
@@ -118,7 +118,12 @@ typedef struct {
  *                    tok%4 = 0, 1 in the first dword and 2, 3 in the second; the
  *                    code of value c in bits [s, s+3], s = 4*((c/16)%4) + 16*(tok%2)
  *                Strides stay in 2-byte elements.
- *   index pool   int32  [n_pages][n_kv_heads][P]   reference ordinal per token
+ *   index pool   int32  [n_pages][n_kv_heads][top_k][P]   reference ordinals per token: slot i holds the token's
+ *                i-th nearest reference (section 4.1, arg top-k), -1 where a token has fewer candidates than
+ *                top_k; a reference token holds its own ordinal in slot 0 and -1 elsewhere.  The token's reference
+ *                is the MEAN of the raw rows of the slots in use (section 4.1), in compress and in decode alike.
+ *                top_k > 1 needs bf16 latents, and decode then needs every sequence's weight table on chip
+ *                (roughly seq_len / ref_stride * g <= 39000): otherwise DELTAKV_E_UNSUPPORTED.
  *   reference pool bf16 [n_kv_heads][2][n_ref_slots][head_dim]   (0 = K, 1 = V)
  *   reference inverse norms fp32 [n_kv_heads][n_ref_slots]: 1/||K||V|| of the
  *                slot's raw vector (0 for a zero vector), written at admission;
@@ -127,7 +132,7 @@ typedef struct {
 typedef struct {
   int64_t latent_pool_bytes, idx_pool_bytes, ref_pool_bytes, ref_norm_pool_bytes;
   int64_t latent_page_stride, latent_head_stride, latent_stream_stride;
-  int64_t idx_page_stride, idx_head_stride;
+  int64_t idx_page_stride, idx_head_stride, idx_slot_stride;
   int64_t ref_head_stride, ref_kv_stride, ref_slot_stride;
   int64_t ref_norm_head_stride;
   int64_t compress_ws_bytes; /* workspace for deltakv_compress at the sizes asked  */

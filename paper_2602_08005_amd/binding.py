@@ -28,14 +28,14 @@ class Dims(C.Structure):
                 ("rank", C.c_int32), ("latent_mode", C.c_int32), ("ref_stride", C.c_int32),
                 ("page_tokens", C.c_int32), ("metric", C.c_int32),
                 ("n_pages", C.c_int64), ("n_ref_slots", C.c_int64),
-                ("latent_bits", C.c_int32), ("reserved", C.c_int32)]
+                ("latent_bits", C.c_int32), ("top_k", C.c_int32)]
 
 
 class Layout(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "latent_pool_bytes", "idx_pool_bytes", "ref_pool_bytes", "ref_norm_pool_bytes",
         "latent_page_stride", "latent_head_stride", "latent_stream_stride",
-        "idx_page_stride", "idx_head_stride",
+        "idx_page_stride", "idx_head_stride", "idx_slot_stride",
         "ref_head_stride", "ref_kv_stride", "ref_slot_stride", "ref_norm_head_stride",
         "compress_ws_bytes", "decode_ws_bytes")] + [("n_streams", C.c_int32), ("alignment", C.c_int32)]
 
@@ -135,9 +135,9 @@ def timing_end() -> dict:
 
 
 def make_dims(n_kv_heads, n_q_heads, rank, n_pages, n_ref_slots, latent_mode=SPLIT, ref_stride=16,
-              head_dim=128, page_tokens=16, metric=METRIC_COSINE, latent_bits=16) -> Dims:
+              head_dim=128, page_tokens=16, metric=METRIC_COSINE, latent_bits=16, top_k=1) -> Dims:
     return Dims(n_kv_heads, n_q_heads, head_dim, rank, latent_mode, ref_stride, page_tokens, metric,
-                n_pages, n_ref_slots, latent_bits, 0)
+                n_pages, n_ref_slots, latent_bits, top_k)
 
 
 def paged_layout(dims: Dims, max_batch: int, max_new_tokens: int, max_seq_len: int) -> Layout:

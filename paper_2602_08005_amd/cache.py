@@ -66,8 +66,10 @@ class PagedCache:
         d, L = self.dims, self.layout
         t = np.arange(t0, t1)
         page = self.block_tables_host[b, t // d.page_tokens].astype(np.int64)
-        return page[:, None] * L.idx_page_stride + np.arange(d.n_kv_heads)[None, :] * L.idx_head_stride \
-            + (t % d.page_tokens)[:, None]
+        ks = max(int(d.top_k), 1)
+        ii = page[:, None, None] * L.idx_page_stride + np.arange(d.n_kv_heads)[None, :, None] * L.idx_head_stride \
+            + np.arange(ks)[None, None, :] * L.idx_slot_stride + (t % d.page_tokens)[:, None, None]
+        return ii if ks > 1 else ii[:, :, 0]                 # [n, H] or, with top_k > 1 ordinal slots, [n, H, top_k]
 
     def _ref_index(self, b: int, j0: int, j1: int, kv: int) -> np.ndarray:
         d, L = self.dims, self.layout
@@ -109,7 +111,7 @@ class PagedCache:
         torch = self.torch
         out = []
         ii = torch.from_numpy(self._idx_index(b, t0, t1).ravel()).to(self.device)
-        idx = self.idx_pool[ii].cpu().numpy().reshape(t1 - t0, self.dims.n_kv_heads)
+        idx = self.idx_pool[ii].cpu().numpy().reshape(self._idx_index(b, t0, t1).shape)
         for stream in range(self.layout.n_streams):
             ii = torch.from_numpy(self._latent_index(b, t0, t1, stream).ravel()).to(self.device)
             out.append(self.latent_pool[ii].cpu().numpy().view(np.uint16)

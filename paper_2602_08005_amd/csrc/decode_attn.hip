@@ -552,7 +552,7 @@ __device__ __forceinline__ void rescue_row(const DecodeParams& P, int b, int gh)
   const int64_t bh = (int64_t)b * P.Hkv + h;
   __shared__ float ql[kHeadDim];        // W_uK q of this head (hi + lo), log2 units
   __shared__ float pw[NT];              // weights of the current tile
-  __shared__ int psl[NT];               // reference slot of each token of the tile
+  __shared__ int psl[4][NT];            // reference pool slots of each token of the tile (-1: ordinal slot unused)
   __shared__ float red[NT];
   if (tid < R) {
     const int64_t at = ((int64_t)b * P.Hq + gh) * R + tid;
@@ -562,7 +562,8 @@ __device__ __forceinline__ void rescue_row(const DecodeParams& P, int b, int gh)
   const float* sref = P.sref + bh * P.n_ref_max * Gp + g;
   const int last_logical = ceil_div(L, kPage) - 1;
   // token i of the row = (list entry i / 16, slot i % 16); returns whether it takes part, its logit and ordinal
-  auto token = [&](int i, float& x, int& ord, const uint16_t*& blk) {
+  // (ords: the token's reference ordinals, -1 in unused slots; the reference part of the logit is the mean score)
+  auto token = [&](int i, float& x, int (&ords)[4], const uint16_t*& blk) {
     const int e = i >> 4, tok = i & 15;
     if (e >= n_ent) return false;
     int logical = e;
@@ -574,20 +575,28 @@ __device__ __forceinline__ void rescue_row(const DecodeParams& P, int b, int gh)
     }
     if (logical * kPage + tok >= L || !((mask >> tok) & 1u)) return false;
     const int page = clampi(P.block_tables[(int64_t)b * P.bt_stride + logical], 0, (int)P.n_pages_pool - 1);
-    ord = (int)min((uint32_t)P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok],
-                   (uint32_t)(n_ref - 1));
+    const int32_t* ip = P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + tok;
+    float sacc = 0.f;
+    int cnt = 0;
+    for (int i2 = 0; i2 < 4; ++i2) {
+      const int raw = i2 < P.top_k ? ip[i2 * kPage] : -1;
+      // one slot per token: the stored value is clamped, never trusted; several: a negative one marks an unused slot
+      const bool used = i2 < P.top_k && (P.top_k == 1 || raw >= 0);
+      ords[i2] = used ? (int)min((uint32_t)raw, (uint32_t)(n_ref - 1)) : -1;
+      if (used) { sacc += sref[(int64_t)ords[i2] * Gp]; ++cnt; }
+    }
     blk = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
     float acc = 0.f;
     for (int c = 0; c < R; ++c) acc += ql[c] * latent_value(P, blk, tok, c, false);
-    x = sref[(int64_t)ord * Gp] + acc;
+    x = sacc / (float)max(cnt, 1) + acc;
     return true;
   };
   const int n_tok = n_ent * kPage;
   // pass 1: the row's largest logit
   float m = -INFINITY;
   for (int i = tid; i < n_tok; i += NT) {
-    float x; int ord; const uint16_t* blk;
-    if (token(i, x, ord, blk)) m = fmaxf(m, x);
+    float x; int ords[4]; const uint16_t* blk;
+    if (token(i, x, ords, blk)) m = fmaxf(m, x);
   }
   red[tid] = m;
   __syncthreads();
@@ -602,16 +611,21 @@ __device__ __forceinline__ void rescue_row(const DecodeParams& P, int b, int gh)
   const uint16_t* vbase = P.ref + (int64_t)h * P.ref_head_stride + P.ref_kv_stride;
   const int64_t vstream = P.joint ? 0 : P.latent_stream_stride;
   for (int i0 = 0; i0 < n_tok; i0 += NT) {
-    float x; int ord = 0; const uint16_t* blk = nullptr;
-    const bool on = token(i0 + tid, x, ord, blk);
+    float x; int ords[4] = {-1, -1, -1, -1}; const uint16_t* blk = nullptr;
+    const bool on = token(i0 + tid, x, ords, blk);
     pw[tid] = on ? __builtin_amdgcn_exp2f(x - m) : 0.f;
-    psl[tid] = clampi(P.ref_tables[(int64_t)b * P.rt_stride + ord], 0, (int)P.n_ref_slots - 1);
+    for (int i2 = 0; i2 < 4; ++i2)
+      psl[i2][tid] = on && ords[i2] >= 0 ? clampi(P.ref_tables[(int64_t)b * P.rt_stride + ords[i2]], 0, (int)P.n_ref_slots - 1) : -1;
     __syncthreads();
     const int n_here = min(NT, n_tok - i0);
     for (int t = 0; t < n_here; ++t) {
       const float p = pw[t];
       if (p == 0.f) continue;                                  // tokens that take no part may hold anything
-      o += p * bf16lo(vbase[(int64_t)psl[t] * kHeadDim + tid]);
+      float vsum = 0.f;                                        // mean of the token's reference value rows
+      int cnt = 0;
+      for (int i2 = 0; i2 < 4; ++i2)
+        if (psl[i2][t] >= 0) { vsum += bf16lo(vbase[(int64_t)psl[i2][t] * kHeadDim + tid]); ++cnt; }
+      o += p * vsum / (float)max(cnt, 1);
       lsum += p;
       if (tid < R) {
         const int i = i0 + t, e = i >> 4;

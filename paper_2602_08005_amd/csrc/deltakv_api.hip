@@ -24,9 +24,10 @@ int check_dims(const deltakv_dims* d) {
   if (d->rank % 16 != 0 || d->rank < 16 || d->rank > 128) return DELTAKV_E_UNSUPPORTED;
   if (d->metric != DELTAKV_METRIC_COSINE && d->metric != DELTAKV_METRIC_L2) return DELTAKV_E_INVALID_ARG;
   if (d->n_pages > (1ll << 31) - 1 || d->n_ref_slots > (1ll << 31) - 1) return DELTAKV_E_UNSUPPORTED;
-  if (d->reserved != 0) return DELTAKV_E_INVALID_ARG;
+  if (d->top_k != 0 && d->top_k != 1 && d->top_k != 2 && d->top_k != 4) return DELTAKV_E_INVALID_ARG;
   if (d->latent_bits != 0 && d->latent_bits != 16 && d->latent_bits != 4) return DELTAKV_E_INVALID_ARG;
   if (d->latent_bits == 4 && d->latent_mode != DELTAKV_JOINT && d->rank % 64 != 0) return DELTAKV_E_UNSUPPORTED;
+  if (d->top_k > 1 && d->latent_bits == 4) return DELTAKV_E_UNSUPPORTED;
   return DELTAKV_OK;
 }
 
@@ -197,8 +198,10 @@ int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t ma
   out->latent_head_stride = out->n_streams * out->latent_stream_stride;
   out->latent_page_stride = H * out->latent_head_stride;
   out->latent_pool_bytes = dims->n_pages * out->latent_page_stride * 2;
-  out->idx_head_stride = P;
-  out->idx_page_stride = H * P;
+  const int64_t KS = dims->top_k > 1 ? dims->top_k : 1;
+  out->idx_slot_stride = P;
+  out->idx_head_stride = KS * P;
+  out->idx_page_stride = H * KS * P;
   out->idx_pool_bytes = dims->n_pages * out->idx_page_stride * 4;
   out->ref_slot_stride = D;
   out->ref_kv_stride = dims->n_ref_slots * D;
@@ -233,7 +236,8 @@ double deltakv_keep_ratio(const deltakv_dims* dims) {
   if (check_dims(dims) != DELTAKV_OK) return -1.0;
   const double streams = dims->latent_mode == DELTAKV_JOINT ? 1.0 : 2.0;
   const double raw = 2.0 * dims->head_dim * 2.0;
-  const double rec = streams * (dims->latent_bits == 4 ? dims->rank / 2.0 + 4.0 : dims->rank * 2.0) + 4.0;
+  const double rec = streams * (dims->latent_bits == 4 ? dims->rank / 2.0 + 4.0 : dims->rank * 2.0) +
+                     4.0 * (dims->top_k > 1 ? dims->top_k : 1);
   return (rec + (raw + 4.0) / dims->ref_stride) / raw;
 }
 
@@ -301,6 +305,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   if (tab_cap > 65535) tab_cap = 65535 & ~3;           // the kernel keeps table rows in 16 bits
   if (g_tune_table_rows > 0 && g_tune_table_rows < tab_cap) tab_cap = g_tune_table_rows & ~3;
   const bool spill_on = n_ref_max > tab_cap;
+  if (spill_on && dims->top_k > 1) return DELTAKV_E_UNSUPPORTED;
   if (!spill_on) tab_cap = n_ref_max;
   if ((int64_t)n_ref_max * Gp * 4 >= (1ll << 31)) return DELTAKV_E_UNSUPPORTED;   // 32-bit byte offsets into a pair's tables
   const size_t lds = stream_lds_bytes((int)tab_cap, Gp, R, nw, joint);
@@ -375,6 +380,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   Pm.stride = S;
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
   Pm.q4 = dims->latent_bits == 4;
+  Pm.top_k = dims->top_k > 1 ? dims->top_k : 1;
   Pm.max_seq_len = max_len;
   Pm.n_ref_max = n_ref_max;
   Pm.n_chunk_max = ceil_div(n_ref_max, kRefChunk);

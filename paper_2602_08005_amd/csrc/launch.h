@@ -38,6 +38,7 @@ struct DecodeParams {
   // shape
   int batch, Hkv, Hq, G, Gp, R, stride, joint;
   int q4;                   // 4-bit token-wise latents
+  int top_k;                // ordinal slots per token in the index pool (1, 2 or 4)
   int nt;                   // the call streams more than the last-level cache holds: non-temporal latent loads
   int ref_cpb;              // reference chunks scored per block of ref_scores (1 or 4)
   int max_seq_len;          // host's bound on seq_lens (device values are clamped to it)

@@ -86,6 +86,15 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
 __device__ inline int load_ordinal(const char* idx_h, uint32_t page_bytes, int page, uint32_t l) {
   return *reinterpret_cast<const int*>(idx_h + (uint64_t)(uint32_t)page * page_bytes + (((l >> 4) * 4u + (l & 3u)) * 4u));
 }
+// Top-k retrieval (section 4.1: the reference of a token is the mean of its k nearest references): the index pool
+// holds KS ordinal slots per token, [slot][token] inside a (page, head) block, -1 in the slots a token does not use.
+// The kernel variant for k > 1 always works on four slots; with k = 2 slots 2 and 3 re-read slot 1 and are ignored.
+template <int KS>
+__device__ inline void load_ordinals(const char* idx_h, uint32_t page_bytes, int page, uint32_t l, int top_k, int (&out)[KS]) {
+  const char* base = idx_h + (uint64_t)(uint32_t)page * page_bytes + (((l >> 4) * 4u + (l & 3u)) * 4u);
+#pragma unroll
+  for (int i = 0; i < KS; ++i) out[i] = *reinterpret_cast<const int*>(base + (uint32_t)min(i, top_k - 1) * (kPage * 4u));
+}
 template <int E>
 __device__ inline int quad_bcast(int v) {   // value held by lane E of the caller's quad
   return __builtin_amdgcn_update_dpp(0, v, E * 0x55, 0xf, 0xf, true);
@@ -101,8 +110,9 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // -- its own tokens' ordinals among them: every 16th token is a reference pointing at itself -- and weights of older
 // ordinals are added, as plain floats with hardware float atomics, to one table per (sequence, kv-head) in global
 // memory that all splits share (zeroed by ref_scores, read by ref_values).
-template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL>
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL, int KS>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
+  static_assert(KS == 1 || (KS == 4 && !SPILL && !Q4), "four ordinal slots: bf16 latents, on-chip table only");
   static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
   extern __shared__ float smem[];
@@ -248,11 +258,17 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const uint32_t quad4 = (ln >> 2) * 4u;
   const bool quad_live = quad4 < (uint32_t)G;
   const uint32_t quad_off = (quad4 < (uint32_t)Gp ? quad4 : 0u) * 4u;
-  auto gather = [&](int& id, float4& sr) {
-    // stored ordinals are clamped (unsigned min: negatives become the last ordinal), never trusted
-    id = (int)min((uint32_t)id, id_hi);
-    sr = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (quad_live) sr = *reinterpret_cast<const float4*>(sref_bh + (((uint32_t)id << gsh2) + quad_off));
+  const int top_k = KS == 1 ? 1 : P.top_k;
+  auto gather = [&](int (&id)[KS], float4 (&sr)[KS]) {
+    // stored ordinals are clamped (unsigned min: negatives become the last ordinal), never trusted; with several
+    // slots the raw values stay as they are (a negative one marks an unused slot) and only the address is clamped
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+      const uint32_t idc = min((uint32_t)id[i], id_hi);
+      if (KS == 1) id[i] = (int)idc;
+      sr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (quad_live) sr[i] = *reinterpret_cast<const float4*>(sref_bh + ((idc << gsh2) + quad_off));
+    }
   };
   auto quad_xchg = [](float v, int ctrl_is_pair) {   // value of the lane at position ^1 (pair) or ^2 of the quad
     const int i = __builtin_bit_cast(int, v);
@@ -273,8 +289,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // Table updates of the previous page whose returned old values have not been looked at yet: an entry that
   // wrapped is recorded in the overflow list (rare).  The check runs one page late, in the shadow of the next
   // page's score MFMAs, so the atomics' return latency is never waited for.
-  uint32_t pend_old[4] = {0u, 0u, 0u, 0u}, pend_fix[4] = {0u, 0u, 0u, 0u};
-  uint32_t pend_ids[2] = {0u, 0u};      // table rows of the page's four ordinals (16 bits each: a table fits the LDS)
+  constexpr int NU = 4 * KS;            // table updates per lane and page: four tokens x ordinal slots
+  uint32_t pend_old[NU], pend_fix[NU];
+  uint32_t pend_ids[NU / 2];            // table rows of the page's updates (16 bits each: a table fits the LDS)
+#pragma unroll
+  for (int n = 0; n < NU; ++n) { pend_old[n] = 0u; pend_fix[n] = 0u; }
+#pragma unroll
+  for (int n = 0; n < NU / 2; ++n) pend_ids[n] = 0u;
   auto list_push = [&](uint32_t ent, float amount) {
     const uint32_t slot = atomicAdd(&ovf[0], 1u);
     if (slot < (uint32_t)kOvfCap) {
@@ -283,11 +304,12 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
   };
   auto check_pending = [&]() {
-    const bool any = (pend_old[0] + pend_fix[0] < pend_fix[0]) | (pend_old[1] + pend_fix[1] < pend_fix[1]) |
-                     (pend_old[2] + pend_fix[2] < pend_fix[2]) | (pend_old[3] + pend_fix[3] < pend_fix[3]);
+    bool any = false;
+#pragma unroll
+    for (int n = 0; n < NU; ++n) any |= pend_old[n] + pend_fix[n] < pend_fix[n];
     if (any) {      // one branch per page; lanes without a query head keep all-zero state
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int e = 0; e < NU; ++e) {
         const uint32_t j = (e & 1) ? pend_ids[e >> 1] >> 16 : pend_ids[e >> 1] & 0xffffu;
         // 2^32 table units: marked (top bit) for conversion to a plain weight when the block flushes.  No
         // memory load may sit on this path: a conditional load in the loop would cost every wait its exact count.
@@ -297,10 +319,41 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   };
   // FULL: all 16 tokens of the page take part (no masking code at all); otherwise bit t of `mask` says whether
   // token t does (a valid token of the sequence and, in subset attention, a selected one).
-  auto compute = [&](auto full_tag, TileT& t, const int id, const float4& srv, const uint32_t mask) {
+  auto compute = [&](auto full_tag, TileT& t, const int (&idv)[KS], const float4 (&srvv)[KS], const uint32_t mask) {
     constexpr bool FULL = decltype(full_tag)::value;
-    float sr[4];
-    quad_transpose(srv, sr);
+    const int id = idv[0];
+    float sr[4];                       // per-reference score part of the quad's four tokens, this lane's head
+    // several ordinal slots: score of every slot (the table units of an entry hang on ITS reference's score), table
+    // row and validity of every (token, slot), 1 / (references the token uses); sr = mean over the used slots
+    float sri[KS][4];
+    uint32_t rown[4][KS];
+    bool usedn[4][KS];
+    float inv_m[4] = {1.f, 1.f, 1.f, 1.f};
+    if constexpr (KS == 1) {
+      quad_transpose(srvv[0], sr);
+    } else {
+#pragma unroll
+      for (int i = 0; i < KS; ++i) quad_transpose(srvv[i], sri[i]);
+      float cnt[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sr[e] = 0.f;
+#pragma unroll
+      for (int i = 0; i < KS; ++i) {
+        const int raw[4] = {quad_bcast<0>(idv[i]), quad_bcast<1>(idv[i]), quad_bcast<2>(idv[i]), quad_bcast<3>(idv[i])};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          usedn[e][i] = i < top_k && raw[e] >= 0;
+          rown[e][i] = min((uint32_t)raw[e], id_hi);
+          cnt[e] += usedn[e][i] ? 1.f : 0.f;
+          sr[e] += usedn[e][i] ? sri[i][e] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        inv_m[e] = __builtin_amdgcn_rcpf(fmaxf(cnt[e], 1.f));
+        sr[e] *= inv_m[e];
+      }
+    }
     uint4 zk[TileT::NKK];                      // the scores operand as bf16
     float sc[4] = {1.f, 1.f, 1.f, 1.f}, zf[4] = {0.f, 0.f, 0.f, 0.f};   // 4-bit: scale, zero - 16 * scale per token
     if constexpr (Q4) {
@@ -343,6 +396,35 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       p[e] = __builtin_amdgcn_exp2f(x);
       lsum += p[e];
     }
+    if constexpr (KS > 1) {
+      if (ghead) {     // one table update per (token, used slot): weight p / m in the units of the slot's reference
+        constexpr float kLim = 4294967040.f;     // largest float below 2^32
+        float f[NU];
+        uint32_t off[NU];
+        float fmax_all = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int i = 0; i < KS; ++i) {
+            const int n = e * KS + i;
+            f[n] = usedn[e][i] ? __builtin_ldexpf(p[e] * inv_m[e], table_shift(sri[i][e], cshift)) : 0.f;
+            off[n] = (rown[e][i] << gsh2) + ln4;
+            fmax_all = fmaxf(fmax_all, f[n]);
+          }
+        if (!(fmax_all < kLim)) {                  // an addend does not fit (rare): the whole weight goes to the list
+#pragma unroll
+          for (int n = 0; n < NU; ++n)
+            if (!(f[n] < kLim)) list_push(off[n] >> 2, p[n / KS] * inv_m[n / KS]);
+        }
+#pragma unroll
+        for (int n = 0; n < NU; ++n) {
+          pend_fix[n] = f[n] < kLim ? (uint32_t)(f[n] + 0.5f) : 0u;
+          pend_old[n] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off[n]), pend_fix[n]);
+        }
+#pragma unroll
+        for (int n = 0; n < NU / 2; ++n) pend_ids[n] = (off[2 * n] >> gsh2) | ((off[2 * n + 1] >> gsh2) << 16);
+      }
+    } else {
     // (cross-lane moves read 0 from lanes that are switched off, so they stay outside the per-head branch)
     const int ids[4] = {quad_bcast<0>(id), quad_bcast<1>(id), quad_bcast<2>(id), quad_bcast<3>(id)};
     if (ghead) {       // fixed-point table update (weights of masked tokens are 0; their clamped ordinal is valid)
@@ -383,6 +465,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         pend_ids[0] = (uint32_t)ids[0] | ((uint32_t)ids[1] << 16);
         pend_ids[1] = (uint32_t)ids[2] | ((uint32_t)ids[3] << 16);
       }
+    }
     }
     // 4-bit: the value product takes p * scale (rounded to bf16 for the matrix unit) against 16 + code; the scalar
     // that takes the offset back out must use the SAME rounded weights, or the two large terms would not cancel
@@ -521,8 +604,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       return (int)__builtin_amdgcn_readfirstlane(v);
     };
     TileT t[ST];
-    int id[ST];
-    float4 sr[ST];
+    int id[ST][KS];
+    float4 sr[ST][KS];
     int pg[ST];          // pg[k % ST] = pool page of the wave's k-th page, kept LI+1 pages ahead
     int cb = draw(), cb1 = draw(), cb2 = draw();              // positions of this, the next and the next-but-one draw
     {
@@ -533,7 +616,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     int pgit_next = page_vec(cb1);
     int mk_next = mask_vec(cb);                               // masks of the draw about to be computed
 #pragma unroll
-    for (int u = 0; u < LI; ++u) id[u] = load_ordinal(idx_h, idx_page_bytes, pg[u], l);
+    for (int u = 0; u < LI; ++u) load_ordinals<KS>(idx_h, idx_page_bytes, pg[u], l, top_k, id[u]);
 #pragma unroll
     for (int u = 0; u < LZ; ++u) load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
 #pragma unroll
@@ -546,7 +629,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       const int cb3 = draw();
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
-        id[(u + LI) % ST] = load_ordinal(idx_h, idx_page_bytes, pg[(u + LI) % ST], l);
+        load_ordinals<KS>(idx_h, idx_page_bytes, pg[(u + LI) % ST], l, top_k, id[(u + LI) % ST]);
         load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
         pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
@@ -618,12 +701,19 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false>
+template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false, int KS = 1>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
-  if constexpr (!SPILL) {        // (a spilling call is a long-sequence call: its bf16 latent loads are non-temporal)
+  if constexpr (KS == 1 && !Q4 && !SPILL) {      // several ordinal slots per token: bf16 latents, on-chip table
+    if (P.top_k > 1) {
+      if (P.spill_on) return hipErrorInvalidValue;
+      return P.nt ? launch_stream<R, NW, JOINT, SUBSET, Q4, true, false, 4>(P, grid, lds, st)
+                  : launch_stream<R, NW, JOINT, SUBSET, Q4, false, false, 4>(P, grid, lds, st);
+    }
+  }
+  if constexpr (!SPILL && KS == 1) {        // (a spilling call is a long-sequence call: its bf16 latent loads are non-temporal)
     if (P.spill_on) return launch_stream<R, NW, JOINT, SUBSET, Q4, !Q4, true>(P, grid, lds, st);
   }
-  if constexpr (!Q4 && !NT) {
+  if constexpr (!Q4 && !NT && KS == 1) {
     if (P.nt) return launch_stream<R, NW, JOINT, SUBSET, Q4, true>(P, grid, lds, st);
   }
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
@@ -634,21 +724,22 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int tile_regs = Q4 ? NKK + 4 + (JOINT ? 0 : 2 * NQ + 4) : 4 * NKK + (JOINT ? 0 : 2 * NB);
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
   // operands built per page in extra registers (the constants are fitted to what the compiler keeps without spilling)
-  constexpr int transient = (JOINT || Q4 ? 2 * NB : 0) + (Q4 ? 4 * NKK + (JOINT ? 40 : 16) : 0);
-  constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6);
+  // (four ordinal slots: 2 x 16 pending table updates, 16 slot scores, 16 table rows per page being computed)
+  constexpr int transient = (JOINT || Q4 ? 2 * NB : 0) + (Q4 ? 4 * NKK + (JOINT ? 40 : 16) : 0) + (KS > 1 ? 64 : 0);
+  constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6 * KS);
   // loads outstanding at once: (2LG+1) ordinals + (LG+1) pages of latents + LG pages of 4 score gathers (+ the page
   // vector); the hardware counter has 6 bits
-  constexpr int by_counter = (56 - 1 - lat_loads) / (6 + lat_loads);
+  constexpr int by_counter = (56 - KS - lat_loads) / (6 * KS + lat_loads);
   constexpr int lg0 = by_counter < by_regs ? by_counter : by_regs;
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 

@@ -20,8 +20,9 @@ def out_f64(t):
 class Case:
     """One sequence per entry of `lens`; raw K/V, oracle-compressed cache, projections."""
 
-    def __init__(self, seed, lens, Hkv=8, Hq=32, r=64, s=16, n_proto=64, joint=False, D=128):
+    def __init__(self, seed, lens, Hkv=8, Hq=32, r=64, s=16, n_proto=64, joint=False, D=128, top_k=1, metric=O.COSINE):
         self.lens, self.Hkv, self.Hq, self.r, self.s, self.D, self.joint = list(lens), Hkv, Hq, r, s, D, joint
+        self.top_k, self.metric = top_k, metric
         self.W = G.make_projections(seed, D, r, joint=joint)
         self.K, self.V, self.res = [], [], []
         mode = O.JOINT if joint else O.SPLIT
@@ -32,7 +33,7 @@ class Case:
             self.V.append(V)
             if L > 0:
                 self.res.append(O.compress(f64(K), f64(V), f64(self.W["w_down_k_bf16"]), f64(self.W["w_down_v_bf16"]),
-                                           s=s, mode=mode))
+                                           s=s, mode=mode, top_k=top_k, metric=metric))
             else:
                 self.res.append(None)
         self.q = G.make_queries(seed, len(self.lens), Hq, D)

@@ -22,7 +22,7 @@ def _setup(case, page_perm_seed=None, pool_slack=1.25):
         page_ids = [pp[b * per_seq_pages:(b + 1) * per_seq_pages] for b in range(B)]
         ref_slots = [rp[b * per_seq_refs:(b + 1) * per_seq_refs] for b in range(B)]
     dims = dk.make_dims(case.Hkv, case.Hq, case.r, n_pages, n_slots, ref_stride=case.s,
-                        latent_mode=dk.JOINT if case.joint else dk.SPLIT)
+                        latent_mode=dk.JOINT if case.joint else dk.SPLIT, top_k=getattr(case, "top_k", 1))
     cache = dk.PagedCache(dims, B, 16, max_len, page_ids=page_ids, ref_slots=ref_slots)
     # poison the pools so that a read of an unwritten slot shows up (0x7fc0 = bf16 NaN)
     cache.latent_pool.fill_(0x7FC0)
