@@ -56,6 +56,21 @@ __device__ inline bool gap_is_safe(float best, float second, float na2, int metr
 }
 
 constexpr int kKeyIdxMask = 0xFFFFFF;   // low 24 bits of an exact-pass key hold (2^24 - 1 - ordinal)
+// Values of the per-round `ord` array besides an ordinal: -1 = queued for the exact pass (the ordinal is in the
+// round's exact_key), kOrdNone = the token has no reference of this rank (fewer candidates than top_k; every slot
+// but the first of a reference token).
+constexpr int kOrdNone = -2;
+
+// Top-k retrieval (section 4.1, arg top-k) runs as top_k rounds of the top-1 search: round r finds the best
+// candidate that rounds 0..r-1 did not take, so the r-th slot holds the token's (r+1)-th nearest reference with
+// equal scores in ascending ordinal.  The final ordinal round rr assigned to (token n, head h), or -1 for none.
+__device__ inline int round_ordinal(const CompressParams& P, int rr, int64_t n, int h) {
+  const int64_t at = (int64_t)rr * P.round_stride + n * P.Hkv + h;
+  const int o = P.ord_all[at];
+  if (o >= 0) return o;
+  if (o == kOrdNone) return -1;
+  return kKeyIdxMask - (int)(P.exact_key_all[at] & kKeyIdxMask);
+}
 
 // 4-bit token-wise latents (section 5.3): scale = bf16((max - min) / 15), zero = bf16(min), code =
 // clamp(round_half_even((z - zero) / scale), 0, 15), all in fp32 (the decision precision of the format).
@@ -99,8 +114,8 @@ __device__ inline int find_seq(const int32_t* cu, int batch, int n) {   // large
 // admit_refs: one wave per (new reference token, kv-head); grid (ceil(max new refs * Hkv / 4), B), 256 threads.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
-  if (blockIdx.x == 0 && blockIdx.y == 0)   // queue counters of the exact pass (cleared here, not by a memset node)
-    for (int i = threadIdx.x; i < P.batch * P.Hkv; i += 256) P.flag_count[i] = 0;
+  if (blockIdx.x == 0 && blockIdx.y == 0)   // queue counters of the exact pass, every round's (cleared here, not by a memset node)
+    for (int i = threadIdx.x; i < P.top_k * P.batch * P.Hkv; i += 256) P.flag_count_all[i] = 0;
   // W_down^T of both streams with padded rows, the form the projection kernel stages into LDS with wide copies:
   // element (stream, c, d) <- w_down[d][c]; the pad columns are zeroed
   if (blockIdx.y == 0)
@@ -162,7 +177,8 @@ __device__ inline void top2_merge(Top2& a, float ob, float os, int oi) {
 // accumulator sets), software-pipelined by hand: while the 8*TB MFMAs of step q run, the LDS reads of step
 // q+1's operands are in flight and the VALU epilogue of step q-1 (scale, mask, top-2) is issued in the MFMA
 // shadow; reference tiles are staged through three LDS buffers so that one barrier per tile suffices.
-template <int TB, bool L2M, int NW>
+// EXC (rounds after the first of a top-k search): candidates that an earlier round took are left out.
+template <int TB, bool L2M, int NW, bool EXC>
 __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
   constexpr int WM = 16 * TB, MT = NW * WM;
   constexpr int LPW = 32 / NW;                                // direct loads of reference rows per wave and tile
@@ -221,6 +237,21 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
   Top2 st[TB];
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) st[tb] = Top2{-INFINITY, -INFINITY, -1};
+  // ordinals taken by earlier rounds, as the codes this lane's epilogue sees them (a lane group sees the ordinals
+  // with (j % 16) / 4 = lg; code = (j / 16) * 4 + j % 4); -1 (no code is negative) where there is none
+  int exc[TB][3];
+  if constexpr (EXC) {
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      const int r = row0 + tb * 16 + ln;
+      const int64_t n = P.cu_new[b] + (r < n_new ? r : 0);
+#pragma unroll
+      for (int e = 0; e < 3; ++e) {
+        const int x = e < P.round ? round_ordinal(P, e, n, h) : -1;
+        exc[tb][e] = (x >= 0 && ((x >> 2) & 3) == lg) ? (((x >> 4) << 2) | (x & 3)) : -1;
+      }
+    }
+  }
 
   const uint16_t* refk = P.ref + (int64_t)h * P.ref_head_stride;
   const uint16_t* refv = refk + P.ref_kv_stride;
@@ -303,11 +334,13 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
         for (int tb = 0; tb < TB; ++tb) c[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kk], tok[tb][kk], c[tb], 0, 0, 0);
     };
     // lane holds references s.jb + i (i = 0..3) of token ln in every block
+    auto taken = [&](int tb, int code) { return EXC && (code == exc[tb][0] || code == exc[tb][1] || code == exc[tb][2]); };
     auto epilogue_full = [&](const float4v (&c)[TB], const Step& s) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int tb = 0; tb < TB; ++tb) top2_push(st[tb], L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i], s.code0 + i);
+        for (int tb = 0; tb < TB; ++tb)
+          top2_push(st[tb], taken(tb, s.code0 + i) ? -INFINITY : (L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i]), s.code0 + i);
     };
     auto epilogue_masked = [&](const float4v (&c)[TB], const Step& s) {
 #pragma unroll
@@ -315,7 +348,8 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
         const int left = ncand_tok[tb] - s.jb;               // this lane's references i < left are candidates
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          top2_push(st[tb], i < left ? (L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i]) : -INFINITY, s.code0 + i);
+          top2_push(st[tb], i < left && !taken(tb, s.code0 + i) ? (L2M ? c[tb][i] - s.inv[i] : c[tb][i] * s.inv[i]) : -INFINITY,
+                    s.code0 + i);
       }
     };
     // a step needs no mask if even its last reference is a candidate of the wave's first (lowest) token
@@ -387,8 +421,11 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
       const int64_t n = P.cu_new[b] + r;
       if (P.NS == 1) {        // the whole reference range was this block's: decide here, no resolve kernel
         const int pos = lb + r;
-        P.ord[n * P.Hkv + h] = pos % P.stride == 0 ? pos / P.stride
-                                                   : decide_ordinal(P, n, b, h, t.best, t.second, t.idx, na2[tb]);
+        int o;
+        if (pos % P.stride == 0) o = P.round == 0 ? pos / P.stride : kOrdNone;   // a reference token: itself, once
+        else if (P.round >= min(refs_below(pos, P.stride), P.rt_stride)) o = kOrdNone;   // fewer candidates than rounds
+        else o = decide_ordinal(P, n, b, h, t.best, t.second, t.idx, na2[tb]);
+        P.ord[n * P.Hkv + h] = o;
       } else {
         float4 o;
         o.x = t.best; o.y = t.second; o.z = __int_as_float(t.idx); o.w = na2[tb];
@@ -409,7 +446,9 @@ __global__ __launch_bounds__(256) void k_resolve(CompressParams P) {
   const int pos = P.len_before[b] + (n - P.cu_new[b]);
   int ord;
   if (pos % P.stride == 0) {
-    ord = pos / P.stride;
+    ord = P.round == 0 ? pos / P.stride : kOrdNone;
+  } else if (P.round >= min(refs_below(pos, P.stride), P.rt_stride)) {
+    ord = kOrdNone;
   } else {
     // merge the reference-range splits (ascending ranges: strict '>' keeps the lowest ordinal)
     float bb = -INFINITY, b2 = -INFINITY, na2 = 0.f;
@@ -498,6 +537,11 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
     double na2_row[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) na2_row[i] = __shfl(na2, 4 * i + lg);
+    int exc_row[4][3];                     // ordinals earlier rounds of a top-k search took (-1: none)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int e = 0; e < 3; ++e) exc_row[i][e] = e < P.round ? round_ordinal(P, e, n_row[i], h) : -1;
     double cbest[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     int jbest[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
     for (int rt = lane_tile0; rt * 16 < ncand; rt += tile_step) {
@@ -526,7 +570,8 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
       for (int i = 0; i < 4; ++i) {
         const double den = na_row[i] * nb;
         const double c = P.metric ? -fmax(na2_row[i] - 2.0 * acc[i] + nb2, 0.0) : (den > 0.0 ? acc[i] / den : 0.0);
-        const bool ok = j < ncand && (int64_t)j * P.stride < pos_row[i];
+        const bool ok = j < ncand && (int64_t)j * P.stride < pos_row[i] && j != exc_row[i][0] && j != exc_row[i][1] &&
+                        j != exc_row[i][2];
         if (ok && c > cbest[i]) { cbest[i] = c; jbest[i] = j; }   // ascending j per lane: strict '>'
       }
     }
@@ -556,7 +601,9 @@ __global__ __launch_bounds__(256) void k_exact(CompressParams P) {
 // A wave owns one page of one sequence: lane (ln, lg) <-> token slot ln of the page, 8-wide chunk.
 // ------------------------------------------------------------------------------------------------
 
-template <int R>
+// KS = 4 (top-k retrieval, section 4.1): the residual is taken against the MEAN of the raw rows of the references
+// the rounds assigned to the token (one to four), and every ordinal slot of the token is written.
+template <int R, int KS>
 __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   constexpr int NB = R / 16;
   extern __shared__ uint16_t wlds[];   // [2][R][kWPad]: W_dK^T, W_dV^T
@@ -587,8 +634,8 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
   // chain ordinal -> table entry -> reference row of the next head runs under the current head's arithmetic
   auto fetch_ord = [&](int h) {
     const int hh = min(h, P.Hkv - 1);
-    const int o = P.ord[n * P.Hkv + hh];
-    const int oe = kKeyIdxMask - (int)(P.exact_key[n * P.Hkv + hh] & kKeyIdxMask);
+    const int o = P.ord_all[n * P.Hkv + hh];                      // (round 0)
+    const int oe = kKeyIdxMask - (int)(P.exact_key_all[n * P.Hkv + hh] & kKeyIdxMask);
     return clampi(o < 0 ? oe : o, 0, P.rt_stride - 1);
   };
   int ord_next = fetch_ord(w);
@@ -604,6 +651,24 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
     const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
     const uint16_t* rv = rk + P.ref_kv_stride;
     const bool zero = !tok_ok || is_ref;
+    // several references: slot 0 is `ord` above; the others, where the token has them
+    int ords[KS];
+    const uint16_t* rks[KS];
+    float inv_m = 1.f;
+    if constexpr (KS > 1) {
+      int cnt = 1;
+      ords[0] = ord;
+      rks[0] = rk;
+#pragma unroll
+      for (int i = 1; i < KS; ++i) {
+        const int o = i < P.top_k ? round_ordinal(P, i, n, h) : -1;
+        ords[i] = o < 0 ? -1 : min(o, P.rt_stride - 1);
+        const int sl = clampi(rtab[max(ords[i], 0)], 0, (int)P.n_ref_slots - 1);
+        rks[i] = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)sl * kHeadDim;
+        cnt += ords[i] >= 0 ? 1 : 0;
+      }
+      inv_m = 1.0f / (float)cnt;
+    }
     bf16x8 res[2][4][2];   // [stream][kk][hi/lo]
 #pragma unroll
     for (int st = 0; st < 2; ++st)
@@ -612,10 +677,25 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
         const uint4 x = *reinterpret_cast<const uint4*>((st ? vr : kr) + (4 * kk + lg) * 8);
         const uint4 y = *reinterpret_cast<const uint4*>((st ? rv : rk) + (4 * kk + lg) * 8);
         const uint32_t xu[4] = {x.x, x.y, x.z, x.w}, yu[4] = {y.x, y.y, y.z, y.w};
+        float m0[4], m1[4];                  // the reference the residual is taken against, fp32
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { m0[e] = bf16lo(yu[e]); m1[e] = bf16hi(yu[e]); }
+        if constexpr (KS > 1) {              // mean of the rows in use (sum in fp32, one rounding per addition)
+#pragma unroll
+          for (int i = 1; i < KS; ++i) {
+            const uint4 yi = *reinterpret_cast<const uint4*>(rks[i] + (st ? P.ref_kv_stride : 0) + (4 * kk + lg) * 8);
+            const uint32_t yiu[4] = {yi.x, yi.y, yi.z, yi.w};
+            const bool on = ords[i] >= 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { m0[e] += on ? bf16lo(yiu[e]) : 0.f; m1[e] += on ? bf16hi(yiu[e]) : 0.f; }
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { m0[e] *= inv_m; m1[e] *= inv_m; }
+        }
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float r0 = bf16lo(xu[e]) - bf16lo(yu[e]), r1 = bf16hi(xu[e]) - bf16hi(yu[e]);
+          float r0 = bf16lo(xu[e]) - m0[e], r1 = bf16hi(xu[e]) - m1[e];
           if (zero) { r0 = 0.f; r1 = 0.f; }
           hi[e] = pack_bf16(r0, r1);
           lo[e] = pack_bf16(r0 - bf16lo(hi[e]), r1 - bf16hi(hi[e]));
@@ -753,8 +833,15 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
         }
       }
     }
-    if (tok_ok && lg == 0)
-      P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + ln] = ord;
+    if (tok_ok && lg == 0) {
+      int32_t* ip = P.idx + (int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + ln;
+      ip[0] = ord;
+      if constexpr (KS > 1) {
+#pragma unroll
+        for (int i = 1; i < KS; ++i)
+          if (i < P.top_k) ip[i * P.idx_slot_stride] = ords[i];
+      }
+    }
   }
   }
 }
@@ -1064,17 +1151,20 @@ __global__ __launch_bounds__(256) void k_append_finish(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int TB, bool L2M, int NW>
+template <int TB, bool L2M, int NW, bool EXC = false>
 static hipError_t launch_sim_m(const CompressParams& P, dim3 grid, hipStream_t st) {
+  if constexpr (!EXC) {
+    if (P.round > 0) return launch_sim_m<TB, L2M, NW, true>(P, grid, st);
+  }
   const size_t lds = 3 * kNT * 256 * 2 + 3 * kNT * 4;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB, L2M, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_sim_top2<TB, L2M, NW, EXC>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(similarity kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_sim_top2<TB, L2M, NW>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_sim_top2<TB, L2M, NW, EXC>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of sim_top2");
 }
 template <int TB>
@@ -1085,25 +1175,29 @@ static hipError_t launch_sim(const CompressParams& P, int nw, dim3 grid, hipStre
   return P.metric ? launch_sim_m<TB, true, 4>(P, grid, st) : launch_sim_m<TB, false, 4>(P, grid, st);
 }
 
-template <int R>
+template <int R, int KS = 1>
 static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t st) {
+  if constexpr (KS == 1) {
+    if (P.top_k > 1) return launch_project<R, 4>(P, grid, st);
+  }
   const size_t lds = 2 * R * kWPad * 2;
   static bool attr_set = false;
   if (!attr_set && lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project<R>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project<R, KS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(projection kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_project<R>), grid, dim3(256), lds, st, P);
+  hipLaunchKernelGGL((k_project<R, KS>), grid, dim3(256), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of project");
 }
 
 int sim_tile_rows(int rb, int nw) { return (nw == 8 && rb <= 2 ? 8 : 4) * 16 * rb; }
 
-hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_max, int page_tiles_max, int max_new_refs,
-                           hipStream_t st) {
+hipError_t launch_compress(const CompressParams& P0, const CompressWs& cw, char* ws, int rb, int nw, int tiles_max,
+                           int page_tiles_max, int max_new_refs, hipStream_t st) {
   hipError_t e;
+  CompressParams P = P0;
   const int items = P.n_new_total * P.Hkv;
   timing_mark(-1, st);
   hipLaunchKernelGGL(k_admit_refs, dim3(ceil_div(max_new_refs * P.Hkv, 4) > 0 ? ceil_div(max_new_refs * P.Hkv, 4) : 1, P.batch),
@@ -1111,23 +1205,32 @@ hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_ma
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of admit_refs");
   timing_mark(K_ADMIT, st);
   dim3 gs(P.batch * P.Hkv, P.NS, tiles_max);
-  switch (rb) {
-    case 1: e = launch_sim<1>(P, nw, gs, st); break;
-    case 2: e = launch_sim<2>(P, nw, gs, st); break;
-    case 3: e = launch_sim<3>(P, nw, gs, st); break;
-    case 4: e = launch_sim<4>(P, nw, gs, st); break;
-    default: return hipErrorInvalidValue;
+  // one retrieval round per reference rank (a single round unless top_k > 1): similarity search that leaves out
+  // what earlier rounds took, merge of the reference-range splits, exact pass for the near-ties of the round
+  for (int round = 0; round < P.top_k; ++round) {
+    P.round = round;
+    P.ord = reinterpret_cast<int32_t*>(ws + cw.ord + round * cw.ord_round);
+    P.flag_count = reinterpret_cast<int32_t*>(ws + cw.flag_count + round * cw.flag_count_round);
+    P.flag_list = reinterpret_cast<int32_t*>(ws + cw.flag_list + round * cw.flag_list_round);
+    P.exact_key = reinterpret_cast<uint64_t*>(ws + cw.exact_key + round * cw.exact_key_round);
+    switch (rb) {
+      case 1: e = launch_sim<1>(P, nw, gs, st); break;
+      case 2: e = launch_sim<2>(P, nw, gs, st); break;
+      case 3: e = launch_sim<3>(P, nw, gs, st); break;
+      case 4: e = launch_sim<4>(P, nw, gs, st); break;
+      default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+    timing_mark(K_SIM, st);
+    if (P.NS > 1) {           // with one reference-range split the similarity kernel has decided already
+      hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
+      if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
+      timing_mark(K_RESOLVE, st);
+    }
+    hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
+    if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
+    timing_mark(K_EXACT, st);
   }
-  if (e != hipSuccess) return e;
-  timing_mark(K_SIM, st);
-  if (P.NS > 1) {           // with one reference-range split the similarity kernel has decided already
-    hipLaunchKernelGGL(k_resolve, dim3(ceil_div(items, 256)), dim3(256), 0, st, P);
-    if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of resolve");
-    timing_mark(K_RESOLVE, st);
-  }
-  hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
-  if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
-  timing_mark(K_EXACT, st);
   dim3 gp(ceil_div(page_tiles_max, P.proj_ppb), P.batch);
   e = hipErrorInvalidValue;
   switch (P.R) {

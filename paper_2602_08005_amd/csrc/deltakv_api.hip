@@ -634,6 +634,8 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.joint = dims->latent_mode == DELTAKV_JOINT;
   Pm.q4 = dims->latent_bits == 4;
   Pm.metric = dims->metric;
+  Pm.top_k = dims->top_k > 1 ? dims->top_k : 1;
+  Pm.idx_slot_stride = lay->idx_slot_stride;
   Pm.NS = (int)ns;
   char* wsb = static_cast<char*>(workspace);
   Pm.ord = reinterpret_cast<int32_t*>(wsb + cw.ord);
@@ -642,8 +644,12 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.exact_key = reinterpret_cast<uint64_t*>(wsb + cw.exact_key);
   Pm.part = reinterpret_cast<float*>(wsb + cw.part);
   Pm.wt = reinterpret_cast<uint16_t*>(wsb + cw.wt);
+  Pm.ord_all = Pm.ord;
+  Pm.exact_key_all = Pm.exact_key;
+  Pm.flag_count_all = Pm.flag_count;
+  Pm.round_stride = (int64_t)n_new_total * dims->n_kv_heads;
   // decode append (one new token for every sequence): two small kernels instead of five
-  bool one_each = n_new_total == batch;
+  bool one_each = n_new_total == batch && Pm.top_k == 1;   // (top-k retrieval runs the general path)
   for (int b = 0; b < batch && one_each; ++b) one_each = cu_new_host[b + 1] - cu_new_host[b] == 1;
   hipError_t e;
   if (one_each) {
@@ -661,7 +667,7 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
       Pm.proj_ppb = q >= 4 ? 4 : (q >= 2 ? 2 : 1);
     }
     if (g_tune_project_pages) Pm.proj_ppb = g_tune_project_pages;
-    e = launch_compress(Pm, rb, sim_nw, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
+    e = launch_compress(Pm, cw, wsb, rb, sim_nw, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }

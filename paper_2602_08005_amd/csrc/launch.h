@@ -87,6 +87,13 @@ struct CompressParams {
   int Hkv, R, stride, joint;
   int q4;                           // 4-bit token-wise latents (single stream)
   int metric;                       // 0: cosine, 1: squared L2 distance (section 4.1)
+  int top_k;                        // references retrieved per (token, kv-head): 1, 2 or 4 (section 4.1, arg top-k)
+  int round;                        // retrieval round of this launch: finds each token's (round+1)-th nearest reference
+  int64_t idx_slot_stride;          // elements between the ordinal slots of a token in the index pool
+  int64_t round_stride;             // elements between the rounds' copies of ord / exact_key
+  const int32_t* ord_all;           // [top_k][n_new_total][Hkv]: ord of every round (round r at r * round_stride)
+  const uint64_t* exact_key_all;    // [top_k][n_new_total][Hkv]
+  int32_t* flag_count_all;          // [top_k][batch][Hkv] (cleared by admit_refs)
   int proj_ppb;                     // consecutive pages a block of the projection kernel takes
   int NS;            // reference-range splits of the similarity search
   float* part;       // fp32x4 [n_new_total][Hkv][NS]: best, second best, arg best (int bits), |token|^2
@@ -99,6 +106,7 @@ struct CompressParams {
 
 struct CompressWs {
   int64_t ord, flag_count, flag_list, exact_key, wt, part;   // byte offsets; `part` takes everything from its offset on
+  int64_t ord_round, flag_count_round, flag_list_round, exact_key_round;   // bytes between the rounds of a top-k call
   int64_t total;
 };
 // Offsets for a call with n_new tokens in total; `total` leaves room for 8 reference-range splits of a large
@@ -107,11 +115,16 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
   CompressWs w;
   int64_t o = 0;
   auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
-  w.ord = take(n_new * d.n_kv_heads * 4);
-  w.flag_count = take(batch * d.n_kv_heads * 4);
+  const int64_t K = d.top_k > 1 ? d.top_k : 1;              // one set of retrieval state per round
+  w.ord_round = n_new * d.n_kv_heads * 4;
+  w.flag_count_round = batch * d.n_kv_heads * 4;
+  w.flag_list_round = n_new * d.n_kv_heads * 4;
+  w.exact_key_round = n_new * d.n_kv_heads * 8;
+  w.ord = take(K * w.ord_round);
+  w.flag_count = take(K * w.flag_count_round);
   w.wt = take(2 * (int64_t)d.rank * kWPad * 2);
-  w.flag_list = take(n_new * d.n_kv_heads * 4);
-  w.exact_key = take(n_new * d.n_kv_heads * 8);
+  w.flag_list = take(K * w.flag_list_round);
+  w.exact_key = take(K * w.exact_key_round);
   w.part = o;
   const int64_t slots = 8 * n_new > n_new + 64 * batch ? 8 * n_new : n_new + 64 * batch;
   w.total = o + align_up(slots * d.n_kv_heads * 16, 256);
@@ -121,8 +134,8 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
 // Token rows per block of the similarity kernel for row-block factor rb (1, 2 or 4).
 int sim_tile_rows(int rb, int nw);
 // Enqueues the three compress kernels on `st`.
-hipError_t launch_compress(const CompressParams& P, int rb, int nw, int tiles_max, int page_tiles_max, int max_new_refs,
-                           hipStream_t st);
+hipError_t launch_compress(const CompressParams& P, const CompressWs& cw, char* ws, int rb, int nw, int tiles_max,
+                           int page_tiles_max, int max_new_refs, hipStream_t st);
 
 // Enqueues the two kernels of the decode-append path (every sequence brings exactly one new token; P.NS = blocks
 // per (sequence, kv-head) of the candidate scan).

@@ -51,7 +51,7 @@ def _check_against_oracle(K, V, W, s, joint, idx, zk, zv, t0=0, l2=False):
 
 
 def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, n_proto=16, perm=None, Hq=None,
-                   capacity=0, l2=False, edit=None):
+                   capacity=0, l2=False, edit=None, top_k=1):
     """Build sequences of lens_before+lens_new tokens; prefill `before` and then append `new` on the GPU."""
     import torch
     import paper_2602_08005_amd as dk
@@ -68,7 +68,7 @@ def _compress_case(seed, lens_before, lens_new, Hkv=2, r=64, s=16, joint=False, 
         page_ids = [pp[b * pps:(b + 1) * pps] for b in range(B)]
         ref_slots = [rp[b * rps:(b + 1) * rps] for b in range(B)]
     dims = dk.make_dims(Hkv, Hq or 4 * Hkv, r, n_pages, n_slots, ref_stride=s, latent_mode=dk.JOINT if joint else dk.SPLIT,
-                        metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
+                        metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE, top_k=top_k)
     cache = dk.PagedCache(dims, B, max(sum(lens_new), sum(lens_before), 1), max_len, page_ids=page_ids, ref_slots=ref_slots)
     cache.latent_pool.fill_(0x7FC0)
     cache.idx_pool.fill_(-7)
