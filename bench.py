@@ -368,6 +368,8 @@ def main():
                     help="with --select: draw single tokens instead of whole pages (same number of tokens)")
     ap.add_argument("--latent-bits", type=int, choices=[16, 4], default=16,
                     help="decode128k: 4 = 4-bit token-wise latents")
+    ap.add_argument("--top-k", type=int, choices=[1, 2, 4], default=1,
+                    help="decode128k: references retrieved per token (the reference is their mean; section 4.1)")
     ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
                     help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
@@ -409,7 +411,7 @@ def main():
     else:
         result = decode_workload(args, torch, dk, B, G)
         plain = (args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, args.mode, args.latent_bits,
-                 args.select, args.raw) == (8, 131072, 32, 8, 32, 64, "split", 16, 0.0, 0)
+                 args.select, args.raw, args.top_k) == (8, 131072, 32, 8, 32, 64, "split", 16, 0.0, 0, 1)
         if args.extras and plain:             # the headline run also carries short runs of the other configurations
             result["workloads"] = extra_workloads(args, torch, dk, B, G)
     print(json.dumps(result))
@@ -453,9 +455,10 @@ def decode_workload(args, torch, dk, B, G):
     n_streams = 1 if joint else 2
     q4 = args.latent_bits == 4
     dims = dk.make_dims(Hkv, Hq, r, n_pages=Bt * pages_per_seq, n_ref_slots=Bt * refs_per_seq,
-                        latent_mode=dk.JOINT if joint else dk.SPLIT, latent_bits=args.latent_bits)
-    # latent record(s) (codes + bf16 scale and zero point, or bf16 latents) + int32 ordinal, per (token, kv-head)
-    rec_bytes = n_streams * (r // 2 + 4 if q4 else r * 2) + 4
+                        latent_mode=dk.JOINT if joint else dk.SPLIT, latent_bits=args.latent_bits, top_k=args.top_k,
+                        metric=dk.METRIC_L2 if args.metric == "l2" else dk.METRIC_COSINE)
+    # latent record(s) (codes + bf16 scale and zero point, or bf16 latents) + int32 ordinal(s), per (token, kv-head)
+    rec_bytes = n_streams * (r // 2 + 4 if q4 else r * 2) + 4 * args.top_k
     t_setup = time.time()
     cache = dk.PagedCache(dims, Bt, L, L)
     W = G.make_projections(G.seed_for(3), D, r, joint=joint, recipe="baseline")
@@ -568,7 +571,7 @@ def decode_workload(args, torch, dk, B, G):
     roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
     if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and raw is None:        # the rows of profiles/hbm_traffic.md
-        key = "decode128k_" + args.mode + ("_q4" if q4 else "")
+        key = "decode128k_" + args.mode + ("_q4" if q4 else "") + (f"_top{args.top_k}" if args.top_k > 1 else "")
         if selections is not None:
             key += f"_select{args.select:g}" + ("_tokens" if args.select_tokens else "")
         roof["traffic"] = measured_traffic(key)
@@ -632,7 +635,8 @@ def decode_workload(args, torch, dk, B, G):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"long-context decode: batch {Bt} x {L} tokens, {NL} layers sequential, "
                                f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents"
-                               f"{' (4-bit token-wise)' if q4 else ''}, stride {s}, 16-token pages",
+                               f"{' (4-bit token-wise)' if q4 else ''}, stride {s}, 16-token pages"
+                               + (f", top-{args.top_k} references per token ({args.metric}), mean" if args.top_k > 1 else ""),
                    "latent_mode": args.mode.upper(), "latent_bits": args.latent_bits,
                    "keep_ratio": round(dk.keep_ratio(dims), 4),
                    "layers_are_copies_of_layer0": True,
