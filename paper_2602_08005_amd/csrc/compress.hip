@@ -315,13 +315,17 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
     const int swz = ln & 7;
     // operands and inverse norms of step (ti, cb): every LDS read of a tile happens before the barrier that
     // lets other waves overwrite its buffer
-    auto prefetch = [&](int ti, int cb, bf16x8 (&dst)[8], Step& s) {
+    // (The per-reference floats of a step come from `invt`, read once per tile: the compiler puts a wait for EVERY
+    // outstanding global load in front of an LDS read of memory that direct-to-LDS loads write.  In front of each
+    // step that wait exposed the whole latency of the loads issued a moment earlier, several hundred cycles per
+    // tile and wave; at the top of a tile, before the tile's own loads are issued, only loads a tile old are in
+    // flight.)
+    auto prefetch = [&](int ti, int cb, bf16x8 (&dst)[8], Step& s, const float4* invt) {
       const int buf = ti % 3;
       const uint16_t* base = lds_raw + buf * kTile + (cb * 16 + ln) * 256;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) dst[kk] = *reinterpret_cast<const bf16x8*>(base + (((4 * kk + lg) ^ swz) * 8));
-      const float4 inv = *reinterpret_cast<const float4*>(nrm + buf * kNT + cb * 16 + 4 * lg);
-      s.inv[0] = inv.x; s.inv[1] = inv.y; s.inv[2] = inv.z; s.inv[3] = inv.w;
+      if (invt) { s.inv[0] = invt[cb].x; s.inv[1] = invt[cb].y; s.inv[2] = invt[cb].z; s.inv[3] = invt[cb].w; }
       s.jb = (t_begin + ti) * kNT + cb * 16 + 4 * lg;
       s.code0 = ((t_begin + ti) * 4 + cb) * 4;               // wave-uniform; the ordinal is rebuilt from it at the end
     };
@@ -359,7 +363,7 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
     };
 
     // pipeline prologue: operands of step (0, 0); a dummy "previous step" whose scores are all masked
-    prefetch(0, 0, aop[0], icur);
+    prefetch(0, 0, aop[0], icur, nullptr);
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) acc[1][tb] = float4v{0.f, 0.f, 0.f, 0.f};
     iprev.inv[0] = iprev.inv[1] = iprev.inv[2] = iprev.inv[3] = 0.f;
@@ -369,14 +373,21 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
 
     // one tile: S(ti+3) into `fill`, D(ti+2) from `use`, four steps with the barrier before the last one
     auto tile_body = [&](int ti, const int (&use)[LPW + 1], int (&fill)[LPW + 1]) {
+      // per-reference floats of the tile's four steps (the barrier that let step (ti, 0) be prefetched made them visible)
+      float4 invt[4];
+      __builtin_amdgcn_sched_barrier(0);       // not earlier than here: the loads of a whole tile ago must have had their time ...
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) invt[cb] = *reinterpret_cast<const float4*>(nrm + (ti % 3) * kNT + cb * 16 + 4 * lg);
+      __builtin_amdgcn_sched_barrier(0);       // ... and only then the tile's own loads
+      icur.inv[0] = invt[0].x; icur.inv[1] = invt[0].y; icur.inv[2] = invt[0].z; icur.inv[3] = invt[0].w;
       // loads are unconditional (past the end they re-load the last tile into a buffer nobody reads), so that
       // the number of loads in flight -- and with it the wait count below -- is the same in every iteration
       load_slots(t_begin + min(ti + 3, n_t - 1), fill);
       issue_tile((ti + 2) % 3, use);
       auto step = [&](auto CB) {
         constexpr int cb = decltype(CB)::value, cur = cb & 1, nxt = cur ^ 1;
-        if (cb < 3) prefetch(ti, cb + 1, aop[nxt], inext);
-        else if (ti + 1 < n_t) prefetch(ti + 1, 0, aop[nxt], inext);
+        if (cb < 3) prefetch(ti, cb + 1, aop[nxt], inext, invt);
+        else if (ti + 1 < n_t) prefetch(ti + 1, 0, aop[nxt], inext, nullptr);
         // one basic block per variant: the MFMAs of this step and the epilogue of the previous one interleave
         if (prev_full) {
           mfmas(aop[cur], acc[cur]);
@@ -1169,7 +1180,7 @@ static hipError_t launch_sim_m(const CompressParams& P, dim3 grid, hipStream_t s
 }
 template <int TB>
 static hipError_t launch_sim(const CompressParams& P, int nw, dim3 grid, hipStream_t st) {
-  if constexpr (TB <= 2) {
+  if constexpr (TB <= 3) {
     if (nw == 8) return P.metric ? launch_sim_m<TB, true, 8>(P, grid, st) : launch_sim_m<TB, false, 8>(P, grid, st);
   }
   return P.metric ? launch_sim_m<TB, true, 4>(P, grid, st) : launch_sim_m<TB, false, 4>(P, grid, st);
@@ -1192,7 +1203,7 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
   return note_hip_error(hipGetLastError(), "launch of project");
 }
 
-int sim_tile_rows(int rb, int nw) { return (nw == 8 && rb <= 2 ? 8 : 4) * 16 * rb; }
+int sim_tile_rows(int rb, int nw) { return (nw == 8 && rb <= 3 ? 8 : 4) * 16 * rb; }
 
 hipError_t launch_compress(const CompressParams& P0, const CompressWs& cw, char* ws, int rb, int nw, int tiles_max,
                            int page_tiles_max, int max_new_refs, hipStream_t st) {
