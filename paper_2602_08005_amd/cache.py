@@ -193,6 +193,14 @@ class PagedCache:
         self.torch.cuda.synchronize()
         return int(self.decode_ws[:4].view(self.torch.int32)[0].item())
 
+    def _keep(self, stream, *tensors):
+        """Per-call device tensors (lengths, selections) are temporaries of the caller's current stream; when the
+        call runs on another stream the allocator must not hand their memory out again before that stream is done."""
+        if stream is not None:
+            for t in tensors:
+                if t is not None and hasattr(t, "record_stream"):
+                    t.record_stream(stream)
+
     # -- calls ------------------------------------------------------------------------------------
     def compress(self, w_down_k, w_down_v, k_new, v_new, cu_new_host, len_before_host, stream=None,
                  first_seq: int = 0):
@@ -201,6 +209,7 @@ class PagedCache:
         cu = torch.tensor(np.asarray(cu_new_host, dtype=np.int32), device=self.device)
         lb = torch.tensor(np.asarray(len_before_host, dtype=np.int32), device=self.device)
         n = len(len_before_host)
+        self._keep(stream, cu, lb)
         return B.compress(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
                           self.ref_inv_norm, self.block_tables[first_seq:first_seq + n],
                           self.ref_tables[first_seq:first_seq + n], w_down_k, w_down_v, k_new,
@@ -213,6 +222,7 @@ class PagedCache:
             seq_lens = torch.tensor(np.asarray(seq_lens_host, dtype=np.int32), device=self.device)
         if out is None:
             out = torch.empty_like(q)
+        self._keep(stream, seq_lens, out)
         B.decode_attn(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
                       self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host, scale,
                       out, lse, self.decode_ws, stream)
@@ -245,6 +255,7 @@ class PagedCache:
         sp, sm, n_dev, n_host = self.selection(positions_per_seq)
         if out is None:
             out = torch.empty_like(q)
+        self._keep(stream, seq_lens, sp, sm, n_dev, out)
         B.decode_attn_subset(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
                              self.block_tables, self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host,
                              sp, sm, n_dev, n_host, scale, out, lse, self.decode_ws, stream)
@@ -260,6 +271,7 @@ class PagedCache:
         sel = self.selection(positions_per_seq) if positions_per_seq is not None else None
         if out is None:
             out = torch.empty_like(q)
+        self._keep(stream, seq_lens, raw_lens, out, *(sel[:3] if sel is not None else ()))
         B.decode_attn_raw(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool, self.block_tables,
                           self.ref_tables, w_up_k, w_up_v, q, seq_lens, seq_lens_host, raw_k, raw_v, raw_lens, scale,
                           out, lse, self.decode_ws, selection=sel, stream=stream)

@@ -78,13 +78,9 @@ void timing_mark(int kernel_id, hipStream_t st) {
   if (!g_timing) return;
   if (kernel_id < 0) g_timing_this_call = g_timing_calls++ % g_timing_period == 0;   // the mark that opens a call
   if (!g_timing_this_call) return;
-  hipEvent_t ev;
-  if (!g_event_pool.empty()) {
-    ev = g_event_pool.back();
-    g_event_pool.pop_back();
-  } else if (hipEventCreate(&ev) != hipSuccess) {
-    return;
-  }
+  if (g_event_pool.empty()) return;      // pool exhausted: the rest of the region goes unmarked
+  hipEvent_t ev = g_event_pool.back();
+  g_event_pool.pop_back();
   if (hipEventRecord(ev, st) != hipSuccess) {
     g_event_pool.push_back(ev);
     return;
@@ -148,6 +144,13 @@ int deltakv_tune(const char* name, int32_t value) {
 int deltakv_timing_begin(void) {
   for (auto& m : g_marks) g_event_pool.push_back(m.ev);
   g_marks.clear();
+  // events are created here, not inside a compress / decode call (which never allocates and may be under capture);
+  // a region that needs more than this many marks records the first ones only
+  while (g_event_pool.size() < 4096) {
+    hipEvent_t ev;
+    if (hipEventCreate(&ev) != hipSuccess) break;
+    g_event_pool.push_back(ev);
+  }
   g_timing_calls = 0;
   g_timing_this_call = true;
   g_timing = true;
@@ -432,6 +435,7 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   int64_t n_items = 0;
   for (int b = 0; b < batch; ++b) n_items += used_splits(work_pages(b), Pm.S, Pm.pages_per_split);
   hipError_t e = launch_decode(Pm, batch, (int)n_items, nw, lds, static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue && g_detail[0] == 0) return DELTAKV_E_UNSUPPORTED;   // no kernel variant for this shape
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 
