@@ -365,6 +365,32 @@ def decode_attn_direct(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale):
     return dense_attention(q, k_hat, v_hat, scale)
 
 
+def rope_rotate(x, positions, base: float = 10000.0):
+    """Rotary position embedding of x [..., D] at integer positions [...] (broadcast against x's leading axes):
+    dimension pair (i, i + D/2) is rotated by the angle position * base**(-2i/D), i = 0 .. D/2 - 1 (the
+    "rotate-half" pairing of the Llama / Qwen families the paper evaluates).  float64."""
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[-1]
+    half = D // 2
+    inv_freq = base ** (-np.arange(half, dtype=np.float64) * 2.0 / D)
+    ang = np.asarray(positions, dtype=np.float64)[..., None] * inv_freq              # [..., D/2]
+    c, s_ = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s_, x2 * c + x1 * s_], axis=-1)
+
+
+def decode_attn_rope(q_rot, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale, base: float = 10000.0, positions=None):
+    """Decode attention when the model applies rotary position embedding to keys: the cache holds PRE-RoPE
+    states (section 4.1: every operation of the method works on pre-RoPE key-value states, to keep the
+    representations position-invariant), so a key is reconstructed, K_hat = reference + z W_uK, and THEN rotated
+    at its token's position before it meets the query (appendix B.5 names the fused de-/re-rotation as future
+    work).  q_rot [Hq, D] is the query already rotated at its own position; cached token t has position t unless
+    `positions` [L] says otherwise; values carry no rotation.  The definition: reconstruct, rotate, attend."""
+    k_hat, v_hat = reconstruct(idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v)
+    pos = np.arange(k_hat.shape[0]) if positions is None else np.asarray(positions)
+    return dense_attention(q_rot, rope_rotate(k_hat, pos[:, None], base), v_hat, scale)
+
+
 def decode_attn_subset(q, idx, z_k, z_v, ref_k, ref_v, w_up_k, w_up_v, scale, positions):
     """Attention over the selected cached tokens only: section 4.2 ("Inference with Sparse
     Attention": selective decompression reconstructs just the KV pairs the sparse attention mask

@@ -734,3 +734,43 @@ def test_topk_full_rank_reconstruction_and_decode_against_dense_attention(joint)
     kz, _ = O.reconstruct(res["idx"], 0 * res["z_k"], 0 * res["z_v"], res["ref_k"], res["ref_v"],
                           P["w_up_k_f64"], P["w_up_v_f64"])
     assert len(js) == 4 and np.max(np.abs(kz[t, h] - sum(K[4 * j, h] for j in js) / 4)) < 1e-14
+
+
+# ---------------------------------------------------------------- rotary position embedding on reconstructed keys
+def test_rope_rotation_properties_and_complex_multiplication():
+    """A rotation: norms kept, position 0 the identity; the score of a rotated query and key depends on the
+    position DIFFERENCE only; dimension pair (i, i + D/2) is the complex number x_i + j x_{i+D/2} multiplied by
+    exp(j pos theta_i) (numpy's complex arithmetic as the library routine); D = 2 by hand."""
+    rng = np.random.default_rng(91)
+    x, y = rng.standard_normal((5, 3, 16)), rng.standard_normal((5, 3, 16))
+    pos = np.array([0, 1, 7, 1000, 131071])
+    r = O.rope_rotate(x, pos[:, None], 10000.0)
+    assert np.allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    assert np.array_equal(r[0], x[0])
+    a = np.sum(O.rope_rotate(x[1], 1234, 500.0) * O.rope_rotate(y[1], 1200, 500.0), axis=-1)
+    b = np.sum(O.rope_rotate(x[1], 34, 500.0) * O.rope_rotate(y[1], 0, 500.0), axis=-1)
+    assert np.max(np.abs(a - b)) < 1e-9
+    theta = 10000.0 ** (-np.arange(8) * 2.0 / 16)
+    z = (x[..., :8] + 1j * x[..., 8:]) * np.exp(1j * pos[:, None, None] * theta)
+    assert np.max(np.abs(r - np.concatenate([z.real, z.imag], axis=-1))) < 1e-9
+    two = O.rope_rotate(np.array([1.0, 0.0]), 3, 10000.0)                 # D = 2: one pair, theta = 1
+    assert np.max(np.abs(two - np.array([np.cos(3.0), np.sin(3.0)]))) < 1e-15
+
+
+def test_rope_decode_reduces_to_library_attention_over_rotated_raw_keys():
+    """Full-rank orthonormal projections reconstruct the raw pre-RoPE keys exactly, so decode with rotation equals
+    dense attention (library routine) over explicitly rotated raw K; with every position 0 it gives back the
+    un-rotated decode."""
+    D = 16
+    K, V, cls, _ = _small_case(seed=93, L=75, H=2, D=D, r=8, s=4)
+    P = G.make_projections(94, D, D, recipe="paired")
+    res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4)
+    q = _f64(G.make_queries(93, 1, 4, D))[0]
+    args = (res["idx"], res["z_k"], res["z_v"], res["ref_k"], res["ref_v"], P["w_up_k_f64"], P["w_up_v_f64"], 0.25)
+    out, lse = O.decode_attn_rope(q, *args, base=100.0)
+    want = _torch_sdpa(q, O.rope_rotate(K, np.arange(75)[:, None], 100.0), V, 0.25)
+    assert np.max(np.abs(out - want)) < 1e-11
+    flat, _ = O.decode_attn_rope(q, *args, base=100.0, positions=np.zeros(75, dtype=np.int64))
+    plain, _ = O.decode_attn_direct(q, *args)
+    assert np.max(np.abs(flat - plain)) < 1e-13
+    assert np.max(np.abs(out - plain)) > 1e-3                      # the rotation matters
