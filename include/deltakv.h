@@ -299,6 +299,28 @@ int deltakv_decode_attn_raw(const deltakv_dims* dims, const deltakv_layout* layo
                             int32_t batch, float scale, void* out, float* lse,
                             void* workspace, int64_t ws_bytes, void* stream);
 
+/* Decode attention for models that apply rotary position embedding to keys.  Section 4.1: the method works on
+ * pre-RoPE key-value states, so the cache holds un-rotated keys; a key is reconstructed, K_hat = K_ref[idx] + z_K W_uK,
+ * and then rotated at its token's position (cached token t has position t) before it meets the query -- the fused
+ * re-rotation that appendix B.5 names as future work.  Values carry no rotation.
+ *   q_rot      device bf16 [batch][n_q_heads][head_dim]: the query ALREADY rotated at its own position
+ *   rope_base  > 1: dimension pair (i, i + head_dim/2) turns by position * rope_base^(-2i/head_dim) (the pairing of
+ *              the Llama / Qwen families); no frequency scaling
+ * out / lse as deltakv_decode_attn: the softmax attention over K_rot, V_hat of every cached token below seq_lens[b].
+ * The per-reference factorisation of the plain call does not exist under a per-token rotation: every token's key is
+ * rebuilt (matrix unit) and the raw K and V rows of its reference are gathered, so this call moves about three times
+ * the bytes of deltakv_decode_attn.  Softmax is online (running maximum): no exponent frame, no status word.
+ * Supported: bf16 latents (both latent modes), top_k = 1, at most 8 queries per kv-head; otherwise
+ * DELTAKV_E_UNSUPPORTED.  workspace >= layout->decode_ws_bytes.  Errors as deltakv_decode_attn. */
+int deltakv_decode_attn_rope(const deltakv_dims* dims, const deltakv_layout* layout,
+                             const void* latent_pool, const int32_t* idx_pool, const void* ref_pool,
+                             const int32_t* block_tables, int32_t bt_stride,
+                             const int32_t* ref_tables, int32_t rt_stride,
+                             const void* w_up_k, const void* w_up_v, const void* q_rot,
+                             const int32_t* seq_lens, const int32_t* seq_lens_host,
+                             int32_t batch, float scale, float rope_base, void* out, float* lse,
+                             void* workspace, int64_t ws_bytes, void* stream);
+
 /* deltakv_decode_attn for callers that cannot allocate device memory and have no workspace to hand over: code
  * under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments and result as
  * deltakv_decode_attn without `workspace` / `ws_bytes`: the workspace is a DELTAKV_STATIC_WS_BYTES array inside the

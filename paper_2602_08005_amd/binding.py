@@ -80,6 +80,9 @@ def _load() -> C.CDLL:
     lib.deltakv_decode_attn.restype = C.c_int
     lib.deltakv_decode_attn.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                         vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, i64, vp]
+    lib.deltakv_decode_attn_rope.restype = C.c_int
+    lib.deltakv_decode_attn_rope.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
+                                             vp, vp, vp, vp, vp, i32, C.c_float, C.c_float, vp, vp, vp, i64, vp]
     lib.deltakv_decode_attn_static.restype = C.c_int
     lib.deltakv_decode_attn_static.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                                vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp]
@@ -100,7 +103,7 @@ KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", 
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset",
-           "deltakv_decode_attn_raw", "deltakv_decode_attn_static")
+           "deltakv_decode_attn_raw", "deltakv_decode_attn_static", "deltakv_decode_attn_rope")
 STATIC_WS_BYTES = 64 << 20
 
 
@@ -205,6 +208,21 @@ def decode_attn(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if check and rc != OK:
         raise DeltaKVError(rc, "deltakv_decode_attn")
+    return rc
+
+
+def decode_attn_rope(dims, layout, latent_pool, idx_pool, ref_pool, block_tables, ref_tables, w_up_k, w_up_v, q_rot,
+                     seq_lens, seq_lens_host, scale, rope_base, out, lse, workspace, stream=None, check=True) -> int:
+    """Decode attention with rotary position embedding on the reconstructed keys (q_rot: already rotated)."""
+    sl_h = _host_i32(seq_lens_host)
+    rc = _lib.deltakv_decode_attn_rope(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        _dp(w_up_k), _dp(w_up_v), _dp(q_rot), _dp(seq_lens), sl_h.ctypes.data, len(sl_h), float(scale), float(rope_base),
+        _dp(out), _dp(lse), _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_decode_attn_rope")
     return rc
 
 

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdeltakv.so")
 SOURCES = ["deltakv_api.hip", "decode_attn.hip", "compress.hip",
            "stream_split_full.hip", "stream_split_subset.hip", "stream_joint_full.hip", "stream_joint_subset.hip",
-           "stream_q4_joint.hip", "stream_q4_split.hip"]
+           "stream_q4_joint.hip", "stream_q4_split.hip", "rope_attn.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

@@ -228,6 +228,17 @@ class PagedCache:
                       out, lse, self.decode_ws, stream)
         return out
 
+    def decode_attn_rope(self, w_up_k, w_up_v, q_rot, seq_lens_host, scale, rope_base, out=None, lse=None, stream=None):
+        torch = self.torch
+        seq_lens = torch.tensor(np.asarray(seq_lens_host, dtype=np.int32), device=self.device)
+        if out is None:
+            out = torch.empty_like(q_rot)
+        self._keep(stream, seq_lens, out)
+        B.decode_attn_rope(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool, self.block_tables,
+                           self.ref_tables, w_up_k, w_up_v, q_rot, seq_lens, seq_lens_host, scale, rope_base, out, lse,
+                           self.decode_ws, stream)
+        return out
+
     def selection(self, positions_per_seq):
         """Page lists + token masks (device int32 tensors) for per-sequence arrays of selected token positions."""
         torch = self.torch

@@ -105,6 +105,25 @@ inline DecodeWs plan_decode_ws(const deltakv_dims& d, int64_t batch, int64_t n_r
   return w;
 }
 
+// ---- workspace of the rotary-embedding decode call
+struct RopeWs {
+  int64_t tab;      // float2 [n_pages_max][64]   (cos, sin) of each page's first position
+  int64_t ml;       // fp32 [B][Hkv][S][Gp][2]    running maximum (log2 units) and weight sum of a split
+  int64_t acc;      // fp32 [B][Hkv][S][Gp][128 + R]  sum p V_ref, sum p z_V of a split
+  int64_t total;
+};
+inline RopeWs plan_rope_ws(const deltakv_dims& d, int64_t batch, int64_t n_pages_max, int splits) {
+  const int64_t Gp = padded_group(d.n_q_heads / d.n_kv_heads), BH = batch * d.n_kv_heads;
+  RopeWs w;
+  int64_t o = 0;
+  auto take = [&](int64_t bytes) { int64_t at = o; o = align_up(o + bytes, 256); return at; };
+  w.tab = take(n_pages_max * 64 * 8);
+  w.ml = take(BH * splits * Gp * 2 * 4);
+  w.acc = take(BH * splits * Gp * (kHeadDim + d.rank) * 4);
+  w.total = o;
+  return w;
+}
+
 // Records which HIP call failed (shown by deltakv_last_error_detail) and passes the code through.
 hipError_t note_hip_error(hipError_t e, const char* what);
 // Largest dynamic LDS a block may ask for on the current device, bytes.

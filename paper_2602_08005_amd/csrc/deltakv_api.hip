@@ -216,6 +216,8 @@ int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t ma
   {
     const int64_t rows = table_rows_max(padded_group(dims->n_q_heads / dims->n_kv_heads));
     out->decode_ws_bytes = plan_decode_ws(*dims, max_batch, n_ref_max, kMaxSplits, n_ref_max < rows ? n_ref_max : rows).total;
+    const int64_t rope = plan_rope_ws(*dims, max_batch, ceil_div64(max_seq_len, P), kMaxSplits).total;
+    if (rope > out->decode_ws_bytes) out->decode_ws_bytes = rope;
   }
   out->compress_ws_bytes = plan_compress_ws(*dims, max_batch, max_new_tokens, n_ref_max).total;
   return DELTAKV_OK;
@@ -536,6 +538,94 @@ int deltakv_decode_attn_static(const deltakv_dims* dims, const deltakv_layout* l
              "this batch and these sequence lengths need more than the %lld bytes of the static workspace; use "
              "deltakv_decode_attn with a caller-provided workspace", (long long)DELTAKV_STATIC_WS_BYTES);
   return rc;
+}
+
+int deltakv_decode_attn_rope(const deltakv_dims* dims, const deltakv_layout* lay, const void* latent_pool,
+                             const int32_t* idx_pool, const void* ref_pool, const int32_t* block_tables,
+                             int32_t bt_stride, const int32_t* ref_tables, int32_t rt_stride, const void* w_up_k,
+                             const void* w_up_v, const void* q_rot, const int32_t* seq_lens,
+                             const int32_t* seq_lens_host, int32_t batch, float scale, float rope_base, void* out,
+                             float* lse, void* workspace, int64_t ws_bytes, void* stream) {
+  int rc = check_dims(dims);
+  if (rc != DELTAKV_OK) return rc;
+  if (!lay || !latent_pool || !idx_pool || !ref_pool || !block_tables || !ref_tables || !w_up_k || !w_up_v ||
+      !q_rot || !seq_lens || !seq_lens_host || !out || batch < 0 || bt_stride <= 0 || rt_stride <= 0 ||
+      !(scale == scale) || !(rope_base > 1.0f))
+    return DELTAKV_E_INVALID_ARG;
+  const int G = dims->n_q_heads / dims->n_kv_heads, Gp = padded_group(G);
+  if (dims->latent_bits == 4 || dims->top_k > 1 || Gp > 8) return DELTAKV_E_UNSUPPORTED;
+  if (batch == 0) return DELTAKV_OK;
+  if (batch > 65535) return DELTAKV_E_UNSUPPORTED;
+  if (!workspace || !aligned(workspace, 256) || ws_bytes <= 0) return DELTAKV_E_WORKSPACE;
+  if (!aligned(latent_pool, 16) || !aligned(idx_pool, 16) || !aligned(ref_pool, 16) || !aligned(q_rot, 16) ||
+      !aligned(w_up_k, 16) || !aligned(w_up_v, 16))
+    return DELTAKV_E_INVALID_ARG;
+  int max_len = 0;
+  int64_t total_pages = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_lens_host[b] < 0) return DELTAKV_E_INVALID_ARG;
+    if (seq_lens_host[b] > max_len) max_len = seq_lens_host[b];
+    total_pages += ceil_div(seq_lens_host[b], dims->page_tokens);
+  }
+  const int max_pages = ceil_div(max_len > 0 ? max_len : 1, dims->page_tokens);
+  const int n_ref_max = ceil_div(max_len > 0 ? max_len : 1, dims->ref_stride);
+  if (max_pages > bt_stride || n_ref_max > rt_stride) return DELTAKV_E_INVALID_ARG;
+  if ((int64_t)max_pages > dims->n_pages || (int64_t)n_ref_max > dims->n_ref_slots) return DELTAKV_E_INVALID_ARG;
+  if (rope_lds_bytes(dims->rank, Gp) > device_lds_limit()) return DELTAKV_E_UNSUPPORTED;
+  // token-range splits: about three blocks' worth of work per compute unit over the whole batch, at least 32 pages each
+  int64_t want = ceil_div64(3ll * device_cu_count(), (int64_t)batch * dims->n_kv_heads);
+  int splits = (int)(want < 1 ? 1 : (want > kMaxSplits ? kMaxSplits : want));
+  const int split_cap = max_pages / 32 > 1 ? max_pages / 32 : 1;
+  if (splits > split_cap) splits = split_cap;
+  if (g_tune_splits) splits = g_tune_splits < split_cap ? g_tune_splits : split_cap;
+  RopeWs ws = plan_rope_ws(*dims, batch, max_pages, splits);
+  while (ws.total > ws_bytes && splits > 1) ws = plan_rope_ws(*dims, batch, max_pages, --splits);
+  if (ws.total > ws_bytes) return DELTAKV_E_WORKSPACE;
+  DecodeParams Pm;
+  memset(&Pm, 0, sizeof(Pm));
+  Pm.latent = static_cast<const uint16_t*>(latent_pool);
+  Pm.idx = idx_pool;
+  Pm.ref = static_cast<const uint16_t*>(ref_pool);
+  Pm.block_tables = block_tables;
+  Pm.ref_tables = ref_tables;
+  Pm.seq_lens = seq_lens;
+  Pm.bt_stride = bt_stride;
+  Pm.rt_stride = rt_stride;
+  Pm.latent_page_stride = lay->latent_page_stride;
+  Pm.latent_head_stride = lay->latent_head_stride;
+  Pm.latent_stream_stride = lay->latent_stream_stride;
+  Pm.idx_page_stride = lay->idx_page_stride;
+  Pm.idx_head_stride = lay->idx_head_stride;
+  Pm.ref_head_stride = lay->ref_head_stride;
+  Pm.ref_kv_stride = lay->ref_kv_stride;
+  Pm.n_pages_pool = dims->n_pages;
+  Pm.n_ref_slots = dims->n_ref_slots;
+  Pm.w_up_k = static_cast<const uint16_t*>(w_up_k);
+  Pm.w_up_v = static_cast<const uint16_t*>(w_up_v);
+  Pm.q = static_cast<const uint16_t*>(q_rot);
+  Pm.out = static_cast<uint16_t*>(out);
+  Pm.lse = lse;
+  Pm.batch = batch;
+  Pm.Hkv = dims->n_kv_heads;
+  Pm.Hq = dims->n_q_heads;
+  Pm.G = G;
+  Pm.Gp = Gp;
+  Pm.R = dims->rank;
+  Pm.stride = dims->ref_stride;
+  Pm.joint = dims->latent_mode == DELTAKV_JOINT;
+  Pm.top_k = 1;
+  Pm.max_seq_len = max_len;
+  Pm.n_ref_max = n_ref_max;
+  Pm.S = splits;
+  Pm.pages_per_split = ceil_div(max_pages, splits);
+  Pm.qk_scale_log2 = scale * kLog2e;
+  char* wsb = static_cast<char*>(workspace);
+  Pm.lpart = reinterpret_cast<float*>(wsb + ws.ml);
+  Pm.accpart = reinterpret_cast<float*>(wsb + ws.acc);
+  hipError_t e = launch_rope(Pm, reinterpret_cast<float2*>(wsb + ws.tab), max_pages, rope_base, batch,
+                             static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue && g_detail[0] == 0) return DELTAKV_E_UNSUPPORTED;
+  return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 
 int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,

@@ -155,6 +155,10 @@ hipError_t stream_joint_full(const DecodeParams& P, dim3 grid, size_t lds, hipSt
 hipError_t stream_joint_subset(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
 hipError_t stream_q4_joint(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
 hipError_t stream_q4_split(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st);
+// Decode attention with rotary position embedding on the reconstructed keys (rope_attn.hip): table of the pages'
+// rotations, attention over every token's rebuilt and rotated key, merge of the splits.
+size_t rope_lds_bytes(int R, int Gp);
+hipError_t launch_rope(const DecodeParams& P, float2* tab, int n_pages_max, float base, int batch, hipStream_t st);
 // Enqueues the four decode kernels on `st`.
 hipError_t launch_decode(const DecodeParams& P, int batch, int n_items, int nw, size_t lds, hipStream_t st);
 
