@@ -370,6 +370,9 @@ def main():
                     help="decode128k: 4 = 4-bit token-wise latents")
     ap.add_argument("--top-k", type=int, choices=[1, 2, 4], default=1,
                     help="decode128k: references retrieved per token (the reference is their mean; section 4.1)")
+    ap.add_argument("--rope", type=float, default=0.0, metavar="BASE",
+                    help="decode128k: deltakv_decode_attn_rope with this base (keys rotated at their position after "
+                         "reconstruction; the queries are taken as already rotated)")
     ap.add_argument("--raw", type=int, default=0, metavar="TOKENS",
                     help="decode128k: also attend this many uncompressed (sink / recent) tokens per sequence")
     ap.add_argument("--tune", action="append", default=[], help="name=value launch-shape override (repeatable)")
@@ -411,7 +414,7 @@ def main():
     else:
         result = decode_workload(args, torch, dk, B, G)
         plain = (args.batch, args.seq_len, args.layers, args.kv_heads, args.q_heads, args.rank, args.mode, args.latent_bits,
-                 args.select, args.raw, args.top_k) == (8, 131072, 32, 8, 32, 64, "split", 16, 0.0, 0, 1)
+                 args.select, args.raw, args.top_k, args.rope) == (8, 131072, 32, 8, 32, 64, "split", 16, 0.0, 0, 1, 0.0)
         if args.extras and plain:             # the headline run also carries short runs of the other configurations
             result["workloads"] = extra_workloads(args, torch, dk, B, G)
     print(json.dumps(result))
@@ -526,7 +529,11 @@ def decode_workload(args, torch, dk, B, G):
 
     def step():
         for layer in range(NL):
-            if raw is not None:
+            if args.rope > 0:
+                B.decode_attn_rope(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
+                                   cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, scale, args.rope,
+                                   outs[layer], None, cache.decode_ws)
+            elif raw is not None:
                 sel = None if selections is None else selections[layer][:4]
                 B.decode_attn_raw(dims, cache.layout, lat[layer], idx[layer], ref[layer], cache.block_tables,
                                   cache.ref_tables, wuk, wuv, qs[layer], seq_lens, seq_lens_host, raw[0], raw[1],
@@ -568,10 +575,11 @@ def decode_workload(args, torch, dk, B, G):
         path_bytes = stream_bytes + units * (2 * D * 2 / s)
     if raw is not None:
         path_bytes += Bt * args.raw * Hkv * 2 * D * 2             # raw K and V rows, read once
-    roof = {"bound": "hbm", "kernel": "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    roof = {"bound": "hbm", "kernel": "k_rope_attn" if args.rope > 0 else "k_stream", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None, "traffic": None, "algorithmic_bytes_per_launch": stream_bytes}
     if (Bt, L, Hkv, Hq, r) == (8, 131072, 8, 32, 64) and raw is None:        # the rows of profiles/hbm_traffic.md
-        key = "decode128k_" + args.mode + ("_q4" if q4 else "") + (f"_top{args.top_k}" if args.top_k > 1 else "")
+        key = "decode128k_" + args.mode + ("_q4" if q4 else "") + (f"_top{args.top_k}" if args.top_k > 1 else "") \
+            + ("_rope" if args.rope > 0 else "")
         if selections is not None:
             key += f"_select{args.select:g}" + ("_tokens" if args.select_tokens else "")
         roof["traffic"] = measured_traffic(key)
@@ -609,7 +617,9 @@ def decode_workload(args, torch, dk, B, G):
             wuk_f, wuv_f = f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"])
             sel_b = None if selections is None else selections[0][4][b]
             t0 = time.perf_counter()
-            if raw is not None:
+            if args.rope > 0:
+                want, _ = O.decode_attn_rope(qh, i0, zkf, zvf, rk, rv, wuk_f, wuv_f, scale, base=args.rope)
+            elif raw is not None:
                 want, _ = O.decode_attn_with_raw(qh, i0, zkf, zvf, rk, rv, wuk_f, wuv_f, scale, f(raw[3][b]), f(raw[4][b]),
                                                  positions=sel_b)
             elif selections is None:
@@ -636,7 +646,9 @@ def decode_workload(args, torch, dk, B, G):
         "config": {"workload": f"long-context decode: batch {Bt} x {L} tokens, {NL} layers sequential, "
                                f"{Hkv} kv-heads x {D}, {Hq} q-heads, rank {r}, {args.mode.upper()} latents"
                                f"{' (4-bit token-wise)' if q4 else ''}, stride {s}, 16-token pages"
-                               + (f", top-{args.top_k} references per token ({args.metric}), mean" if args.top_k > 1 else ""),
+                               + (f", top-{args.top_k} references per token ({args.metric}), mean" if args.top_k > 1 else "")
+                               + (f", keys rotated after reconstruction (RoPE base {args.rope:g}; every token's key "
+                                  f"rebuilt, its reference's raw K and V rows gathered)" if args.rope > 0 else ""),
                    "latent_mode": args.mode.upper(), "latent_bits": args.latent_bits,
                    "keep_ratio": round(dk.keep_ratio(dims), 4),
                    "layers_are_copies_of_layer0": True,
