@@ -198,6 +198,29 @@ def quantize_tokenwise_4bit(z: np.ndarray):
     return codes, scale_b, zero_b, back
 
 
+GELU = 0
+SWIGLU = 1
+
+
+def mlp_compressor(x: np.ndarray, mlp: dict) -> np.ndarray:
+    """The non-linear compressor f_c of section 4.1 applied to vectors x [..., n_in] (n_in = 2 * head_dim: the
+    per-head K||V vector).  mlp = {"kind", "w1" [n_in, d_h], "b1" [d_h], "w2" [d_h, r]} and, for SwiGLU, "wg"
+    [n_in, d_h]:
+        GELU   (the section's own form)          f_c(x) = GeLU(x W1 + b1) W2          (GeLU with the exact erf)
+        SWIGLU (section 5.3, the heavy variant)  f_c(x) = (SiLU(x Wg) * (x W1 + b1)) W2
+    The output bias of the section's formula is left out: the latent is a difference of two f_c values, in which it
+    cancels.  float64."""
+    from scipy.special import erf
+    x = np.asarray(x, dtype=np.float64)
+    u = x @ mlp["w1"] + mlp["b1"]
+    if mlp["kind"] == GELU:
+        h = 0.5 * u * (1.0 + erf(u / np.sqrt(2.0)))
+    else:
+        g = x @ mlp["wg"]
+        h = g / (1.0 + np.exp(-g)) * u
+    return h @ mlp["w2"]
+
+
 def reference_mean(X: np.ndarray, idx: np.ndarray, s: int) -> np.ndarray:
     """Mean of the raw rows of the references each (token, head) retrieved (section 4.1, the reference
     representation: the mean of the retrieved set).  X [L, H, D] raw states; idx [n, H, k] reference
@@ -213,7 +236,7 @@ def reference_mean(X: np.ndarray, idx: np.ndarray, s: int) -> np.ndarray:
 
 def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.ndarray,
              s: int = 16, mode: int = SPLIT, start: int = 0, token_block: int = 2048, metric: int = COSINE,
-             latent_bits: int = 16, top_k: int = 1):
+             latent_bits: int = 16, top_k: int = 1, mlp: dict = None):
     """Compress tokens start..L-1 of one sequence.
 
     K, V: float64 [L, H, D] -- the raw states of the WHOLE sequence so far (the
@@ -236,11 +259,13 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
       zq_k, zq_v float64 [n, H, r] the latents as read back from the 4-bit record (what decode uses)
     and the reference pool of the whole sequence:
       ref_k, ref_v float64 [ceil(L/s), H, D]
+    With `mlp` (see mlp_compressor; JOINT mode) the latent is f_c(token) - f_c(reference) instead of the projected
+    residual; w_down_* are then ignored.
     """
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     L, H, D = K.shape
-    r = w_down_k.shape[1]
+    r = mlp["w2"].shape[1] if mlp is not None else w_down_k.shape[1]
     n = L - start
     kv = np.concatenate([K, V], axis=2)                    # [L, H, 2D]
     refs = kv[0::s]                                        # ordinal j <-> token j*s
@@ -289,7 +314,15 @@ def compress(K: np.ndarray, V: np.ndarray, w_down_k: np.ndarray, w_down_v: np.nd
         tok_ref = idx.astype(np.int64) * s                 # token position of the chosen reference
         r_k = K[pos[:, None], hh] - K[tok_ref, hh]         # [n, H, D]
         r_v = V[pos[:, None], hh] - V[tok_ref, hh]
-    if mode == SPLIT:
+    if mlp is not None:
+        # non-linear compressor (section 4.1): the token's K||V and its reference's are compressed SEPARATELY and the
+        # latent is the difference, z = f_c(kv) - f_c(kv_ref); one latent per (token, head), i.e. JOINT mode
+        assert mode == JOINT, "the non-linear compressor produces the single latent over K||V"
+        x_tok = np.concatenate([K[pos[:, None], hh], V[pos[:, None], hh]], axis=-1)
+        x_ref = x_tok - np.concatenate([r_k, r_v], axis=-1)
+        z_k = mlp_compressor(x_tok, mlp) - mlp_compressor(x_ref, mlp)
+        z_v = z_k
+    elif mode == SPLIT:
         z_k = r_k @ w_down_k
         z_v = r_v @ w_down_v
     else:

@@ -145,6 +145,23 @@ def make_projections(seed: int, head_dim: int, rank: int, joint: bool = False, r
     return out
 
 
+def make_mlp_compressor(seed: int, head_dim: int, rank: int, hidden: int, swiglu: bool = False):
+    """Random weights of a non-linear compressor over the per-head K||V vector (2 * head_dim inputs): W1 (and, for
+    SwiGLU, Wg) ~ N(0, 1 / n_in), b1 ~ N(0, 0.01), W2 ~ N(0, 1 / hidden).  Returns fp64 ("*_f64": the values of the
+    bf16-rounded weights) and bf16-bit ("*_bf16") arrays; b1 stays fp32 ("b1_f32")."""
+    g = _rng(seed, 7_000_005)
+    n_in = 2 * head_dim
+    out = {}
+    names = ["w1", "w2"] + (["wg"] if swiglu else [])
+    shapes = {"w1": (n_in, hidden), "wg": (n_in, hidden), "w2": (hidden, rank)}
+    for k in names:
+        w = g.standard_normal(shapes[k]).astype(np.float32) / np.float32(np.sqrt(shapes[k][0]))
+        out[k + "_bf16"] = f32_to_bf16_bits(w)
+        out[k + "_f64"] = bf16_bits_to_f32(out[k + "_bf16"]).astype(np.float64)
+    out["b1_f32"] = (0.1 * g.standard_normal(hidden)).astype(np.float32)
+    return out
+
+
 def loguniform_lengths(seed: int, n_seqs: int, lo: int, hi: int) -> np.ndarray:
     """Sequence lengths floor(exp(U(ln lo, ln hi))), int32."""
     g = _rng(seed, 7_000_003)

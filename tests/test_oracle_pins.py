@@ -774,3 +774,46 @@ def test_rope_decode_reduces_to_library_attention_over_rotated_raw_keys():
     plain, _ = O.decode_attn_direct(q, *args)
     assert np.max(np.abs(flat - plain)) < 1e-13
     assert np.max(np.abs(out - plain)) > 1e-3                      # the rotation matters
+
+
+# ---------------------------------------------------------------- non-linear compressor
+def _mlp(kind, n_in=32, hidden=24, r=8, seed=5):
+    rng = np.random.default_rng(seed)
+    m = {"kind": kind, "w1": rng.standard_normal((n_in, hidden)) / np.sqrt(n_in), "b1": 0.1 * rng.standard_normal(hidden),
+         "w2": rng.standard_normal((hidden, r)) / np.sqrt(hidden)}
+    if kind == O.SWIGLU:
+        m["wg"] = rng.standard_normal((n_in, hidden)) / np.sqrt(n_in)
+    return m
+
+
+@pytest.mark.parametrize("kind", [O.GELU, O.SWIGLU])
+def test_mlp_compressor_against_library_activations_and_difference_structure(kind):
+    """f_c evaluated with torch's gelu / silu (library routines) on the same weights; the latent is the difference
+    f_c(token) - f_c(reference): a token that equals its reference gets exactly zero, reference tokens get zero, and
+    for a residual shrunk by 10^-6 the latent approaches the directional derivative (it is linear in small residuals)."""
+    import torch
+    m = _mlp(kind)
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((11, 32))
+    tx = torch.from_numpy(x)
+    u = tx @ torch.from_numpy(m["w1"]) + torch.from_numpy(m["b1"])
+    if kind == O.GELU:
+        h = torch.nn.functional.gelu(u)
+    else:
+        h = torch.nn.functional.silu(tx @ torch.from_numpy(m["wg"])) * u
+    want = (h @ torch.from_numpy(m["w2"])).numpy()
+    assert np.max(np.abs(O.mlp_compressor(x, m) - want)) < 1e-12
+    K, V, cls, P = _small_case(seed=97, L=60, H=2, D=16, r=8, s=4, joint=True)
+    K[13], V[13] = K[8], V[8]                      # token 13 is an exact copy of reference 2
+    res = O.compress(K, V, None, None, s=4, mode=O.JOINT, mlp=m)
+    assert res["idx"][13, 0] == 2 and np.all(res["z_k"][13] == 0) and np.all(res["z_k"][::4] == 0)
+    # by hand for one token: f_c(x) - f_c(ref)
+    t, h_ = 27, 1
+    j = int(res["idx"][t, h_])
+    xt = np.concatenate([K[t, h_], V[t, h_]])
+    xr = np.concatenate([K[4 * j, h_], V[4 * j, h_]])
+    assert np.max(np.abs(res["z_k"][t, h_] - (O.mlp_compressor(xt, m) - O.mlp_compressor(xr, m)))) < 1e-13
+    eps = 1e-6
+    small = (O.mlp_compressor(xr + eps * (xt - xr), m) - O.mlp_compressor(xr, m)) / eps
+    smaller = (O.mlp_compressor(xr + 0.5 * eps * (xt - xr), m) - O.mlp_compressor(xr, m)) / (0.5 * eps)
+    assert np.max(np.abs(small - smaller)) < 1e-5 * max(1.0, np.max(np.abs(small)))
