@@ -193,6 +193,43 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* layout,
                      const int32_t* len_before, const int32_t* len_before_host,
                      int32_t batch, void* workspace, int64_t ws_bytes, void* stream);
 
+/* The non-linear compressor f_c of section 4.1 over the per-head vector
+ * x = K||V (2 * head_dim values):
+ *   DELTAKV_MLP_GELU    f_c(x) = GeLU(x W1 + b1) W2      (GeLU with the exact erf)
+ *   DELTAKV_MLP_SWIGLU  f_c(x) = (SiLU(x Wg) * (x W1 + b1)) W2   (section 5.3, the
+ *                       gated variant)
+ * The output bias of the section's formula is not taken: the latent is a
+ * difference of two f_c values, in which it cancels.  All pointers are device
+ * memory owned by the caller; row-major. */
+#define DELTAKV_MLP_GELU 0
+#define DELTAKV_MLP_SWIGLU 1
+typedef struct deltakv_mlp {
+  int32_t kind;      /* DELTAKV_MLP_*                                          */
+  int32_t hidden;    /* hidden width d_h, 1 .. 1024                            */
+  const void* w1;    /* bf16 [2 * head_dim][hidden]                            */
+  const void* wg;    /* bf16 [2 * head_dim][hidden] (SWIGLU), else NULL        */
+  const float* b1;   /* fp32 [hidden]                                          */
+  const void* w2;    /* bf16 [hidden][rank]                                    */
+} deltakv_mlp;
+
+/* deltakv_compress with the non-linear compressor (section 4.1): references,
+ * retrieval, indices and layout as there, but the latent of a non-reference token
+ * is  f_c(K||V of the token) - f_c(K||V of its reference)  rounded to bf16 (the
+ * compressor is applied to both sides separately; the decoder stays the linear
+ * W_up of deltakv_decode_attn).  Needs latent_mode JOINT (one latent over K||V),
+ * 16-bit latents and top_k <= 1: anything else is UNSUPPORTED.  The weights are
+ * re-packed into the workspace by every call (a few microseconds).
+ * Other arguments and errors: as deltakv_compress. */
+int deltakv_compress_mlp(const deltakv_dims* dims, const deltakv_layout* layout,
+                         void* latent_pool, int32_t* idx_pool, void* ref_pool, float* ref_inv_norm,
+                         const int32_t* block_tables, int32_t bt_stride,
+                         const int32_t* ref_tables, int32_t rt_stride,
+                         const deltakv_mlp* mlp,
+                         const void* k_new, const void* v_new,
+                         const int32_t* cu_new, const int32_t* cu_new_host,
+                         const int32_t* len_before, const int32_t* len_before_host,
+                         int32_t batch, void* workspace, int64_t ws_bytes, void* stream);
+
 /* Grouped-query softmax attention of one query token per sequence over the
  * compressed cache: for q-head g (kv-head h = g / (n_q_heads/n_kv_heads)) and
  * every cached token t < seq_lens[b],

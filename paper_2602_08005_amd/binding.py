@@ -31,6 +31,15 @@ class Dims(C.Structure):
                 ("latent_bits", C.c_int32), ("top_k", C.c_int32)]
 
 
+class Mlp(C.Structure):
+    """deltakv_mlp: the non-linear compressor's weights (device pointers)."""
+    _fields_ = [("kind", C.c_int32), ("hidden", C.c_int32), ("w1", C.c_void_p), ("wg", C.c_void_p),
+                ("b1", C.c_void_p), ("w2", C.c_void_p)]
+
+
+MLP_GELU, MLP_SWIGLU = 0, 1
+
+
 class Layout(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "latent_pool_bytes", "idx_pool_bytes", "ref_pool_bytes", "ref_norm_pool_bytes",
@@ -77,6 +86,9 @@ def _load() -> C.CDLL:
     lib.deltakv_compress.restype = C.c_int
     lib.deltakv_compress.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, vp, i32, vp, i32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i64, vp]
+    lib.deltakv_compress_mlp.restype = C.c_int
+    lib.deltakv_compress_mlp.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, vp, i32, vp, i32,
+                                         C.POINTER(Mlp), vp, vp, vp, vp, vp, vp, i32, vp, i64, vp]
     lib.deltakv_decode_attn.restype = C.c_int
     lib.deltakv_decode_attn.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, i32, vp, i32,
                                         vp, vp, vp, vp, vp, i32, C.c_float, vp, vp, vp, i64, vp]
@@ -103,7 +115,7 @@ KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", 
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset",
-           "deltakv_decode_attn_raw", "deltakv_decode_attn_static", "deltakv_decode_attn_rope")
+           "deltakv_decode_attn_raw", "deltakv_decode_attn_static", "deltakv_decode_attn_rope", "deltakv_compress_mlp")
 STATIC_WS_BYTES = 64 << 20
 
 
@@ -194,6 +206,24 @@ def compress(dims, layout, latent_pool, idx_pool, ref_pool, ref_inv_norm, block_
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if check and rc != OK:
         raise DeltaKVError(rc, "deltakv_compress")
+    return rc
+
+
+def compress_mlp(dims, layout, latent_pool, idx_pool, ref_pool, ref_inv_norm, block_tables, ref_tables,
+                 kind, w1, wg, b1, w2, k_new, v_new, cu_new, cu_new_host, len_before, len_before_host,
+                 workspace, stream=None, check=True) -> int:
+    """deltakv_compress with the non-linear compressor: w1 / wg bf16 [2 * head_dim][hidden], b1 fp32 [hidden],
+    w2 bf16 [hidden][rank] (device tensors; wg None unless kind is MLP_SWIGLU)."""
+    cu_h, lb_h = _host_i32(cu_new_host), _host_i32(len_before_host)
+    mlp = Mlp(int(kind), int(w1.shape[1]), _dp(w1), _dp(wg), _dp(b1), _dp(w2))
+    rc = _lib.deltakv_compress_mlp(
+        C.byref(dims), C.byref(layout), _dp(latent_pool), _dp(idx_pool), _dp(ref_pool), _dp(ref_inv_norm),
+        _dp(block_tables), block_tables.shape[1], _dp(ref_tables), ref_tables.shape[1],
+        C.byref(mlp), _dp(k_new), _dp(v_new), _dp(cu_new), cu_h.ctypes.data,
+        _dp(len_before), lb_h.ctypes.data, len(lb_h), _dp(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if check and rc != OK:
+        raise DeltaKVError(rc, "deltakv_compress_mlp")
     return rc
 
 

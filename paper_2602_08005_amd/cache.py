@@ -215,6 +215,19 @@ class PagedCache:
                           self.ref_tables[first_seq:first_seq + n], w_down_k, w_down_v, k_new,
                           v_new, cu, cu_new_host, lb, len_before_host, self.compress_ws, stream)
 
+    def compress_mlp(self, kind, w1, wg, b1, w2, k_new, v_new, cu_new_host, len_before_host, stream=None,
+                     first_seq: int = 0):
+        """compress() with the non-linear compressor (JOINT caches with 16-bit latents)."""
+        torch = self.torch
+        cu = torch.tensor(np.asarray(cu_new_host, dtype=np.int32), device=self.device)
+        lb = torch.tensor(np.asarray(len_before_host, dtype=np.int32), device=self.device)
+        n = len(len_before_host)
+        self._keep(stream, cu, lb)
+        return B.compress_mlp(self.dims, self.layout, self.latent_pool, self.idx_pool, self.ref_pool,
+                              self.ref_inv_norm, self.block_tables[first_seq:first_seq + n],
+                              self.ref_tables[first_seq:first_seq + n], kind, w1, wg, b1, w2, k_new,
+                              v_new, cu, cu_new_host, lb, len_before_host, self.compress_ws, stream)
+
     def decode_attn(self, w_up_k, w_up_v, q, seq_lens_host, scale, out=None, lse=None, seq_lens=None,
                     stream=None):
         torch = self.torch

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void k_admit_refs(CompressParams P) {
     for (int i = threadIdx.x; i < P.top_k * P.batch * P.Hkv; i += 256) P.flag_count_all[i] = 0;
   // W_down^T of both streams with padded rows, the form the projection kernel stages into LDS with wide copies:
   // element (stream, c, d) <- w_down[d][c]; the pad columns are zeroed
-  if (blockIdx.y == 0)
+  if (blockIdx.y == 0 && P.mlp_kind < 0)   // (the non-linear compressor brings no W_down: its weights are packed by mlp_prep)
     for (int i = blockIdx.x * 256 + threadIdx.x; i < 2 * P.R * kWPad; i += gridDim.x * 256) {
       const int st = i / (P.R * kWPad), rem = i % (P.R * kWPad), c = rem / kWPad, d = rem % kWPad;
       P.wt[i] = d < kHeadDim ? (st ? P.w_down_v : P.w_down_k)[d * P.R + c] : (uint16_t)0;
@@ -858,6 +858,153 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Non-linear compressor (section 4.1: z = f_c(kv) - f_c(kv_ref) with a two-layer f_c; section 5.3: the gated
+// variant).  One latent over K||V per (token, kv-head): JOINT layout, stream 0.
+//   mlp_prep     transposes and zero-pads the weights into the workspace: W1^T (and Wg^T) [hidden_pad][kMlpXPad],
+//                W2^T by chunks of kMlpChunk hidden columns, b1 padded.  Padded hidden columns have zero weights
+//                and bias on both sides, so they contribute act(0) * 0 = 0.
+//   project_mlp  grid (pages, B), 512 threads; wave w takes kv-head w (+8, ...) of the block's page.  Both GEMMs run
+//                transposed so that the first one's result is already the second one's operand:
+//                  H^T[j][tok]  = sum_f W1^T[j][f] x[tok][f]      A = W1^T rows from LDS, B = the token's raw row
+//                  z^T[c][tok] += sum_j W2^T[c][j] d[j][tok]      B = d = act(H_token) - act(H_reference), in the
+//                                                                  lane that computed it, split into bf16 hi + lo
+//                (the second GEMM is linear, so the difference is formed BEFORE it: one GEMM instead of two, and
+//                the cancellation happens in fp32 rather than after a rounding to bf16).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mlp_prep(CompressParams P) {
+  const int hp = P.mlp_hidden_pad, hd = P.mlp_hidden;
+  const int64_t n1 = (int64_t)hp * kMlpXPad, n2 = (int64_t)(hp / kMlpChunk) * P.R * kMlpW2Pad;
+  const int64_t total = n1 + n2 + hp;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    if (i < n1) {
+      const int j = (int)(i / kMlpXPad), f = (int)(i % kMlpXPad);
+      const bool in = j < hd && f < 2 * kHeadDim;
+      P.mlp_w1t[i] = in ? P.mlp_w1[(int64_t)f * hd + j] : (uint16_t)0;
+      if (P.mlp_kind == 1) P.mlp_wgt[i] = in ? P.mlp_wg[(int64_t)f * hd + j] : (uint16_t)0;
+    } else if (i < n1 + n2) {
+      const int64_t k = i - n1;
+      const int jj = (int)(k % kMlpW2Pad), rc = (int)((k / kMlpW2Pad) % P.R), c = (int)(k / ((int64_t)kMlpW2Pad * P.R));
+      const int j = c * kMlpChunk + jj;
+      P.mlp_w2t[k] = (jj < kMlpChunk && j < hd) ? P.mlp_w2[(int64_t)j * P.R + rc] : (uint16_t)0;
+    } else {
+      const int j = (int)(i - n1 - n2);
+      P.mlp_b1p[j] = j < hd ? P.mlp_b1[j] : 0.f;
+    }
+  }
+}
+
+__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+__device__ inline float silu(float g) { return g / (1.0f + __expf(-g)); }
+
+template <int R, bool GATED>
+__global__ __launch_bounds__(512) void k_project_mlp(CompressParams P) {
+  constexpr int NB = R / 16;
+  extern __shared__ uint16_t mlds[];
+  uint16_t* w1s = mlds;                                        // [kMlpChunk][kMlpXPad]
+  uint16_t* wgs = w1s + kMlpChunk * kMlpXPad;                  // (GATED)
+  uint16_t* w2s = wgs + (GATED ? kMlpChunk * kMlpXPad : 0);    // [R][kMlpW2Pad]
+  const int b = blockIdx.y;
+  const int lb = P.len_before[b];
+  const int n_new = P.cu_new[b + 1] - P.cu_new[b];
+  const int la = lb + n_new;
+  const int lp = lb / kPage + blockIdx.x;
+  if (n_new <= 0 || lp * kPage >= la) return;
+  const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, ln = l & 15, lg = l >> 4;
+  const int pos = lp * kPage + ln;
+  const bool tok_ok = pos >= lb && pos < la;
+  const int64_t n = P.cu_new[b] + (tok_ok ? pos - lb : 0);
+  const bool is_ref = (pos % P.stride) == 0;
+  int page = P.block_tables[(int64_t)b * P.bt_stride + min(lp, P.bt_stride - 1)];
+  page = clampi(page, 0, (int)P.n_pages_pool - 1);
+  const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
+  const int n_chunks = P.mlp_hidden_pad / kMlpChunk;
+  for (int h0 = 0; h0 < P.Hkv; h0 += 8) {
+    const bool head_ok = h0 + w < P.Hkv;
+    const int h = min(h0 + w, P.Hkv - 1);
+    const int o = P.ord_all[n * P.Hkv + h];
+    const int oe = kKeyIdxMask - (int)(P.exact_key_all[n * P.Hkv + h] & kKeyIdxMask);
+    const int ord = clampi(o < 0 ? oe : o, 0, P.rt_stride - 1);
+    const int slot = clampi(rtab[ord], 0, (int)P.n_ref_slots - 1);
+    const uint16_t* kr = P.k_new + (n * P.Hkv + h) * kHeadDim;
+    const uint16_t* vr = P.v_new + (n * P.Hkv + h) * kHeadDim;
+    const uint16_t* rk = P.ref + (int64_t)h * P.ref_head_stride + (int64_t)slot * kHeadDim;
+    const uint16_t* rv = rk + P.ref_kv_stride;
+    // operand rows: contraction step kk covers features 32 kk .. 32 kk + 31 of K||V, the lane its 8-wide chunk lg
+    bf16x8 xt[8], xr[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const int off = (4 * (kk & 3) + lg) * 8;
+      xt[kk] = *reinterpret_cast<const bf16x8*>((kk < 4 ? kr : vr) + off);
+      xr[kk] = *reinterpret_cast<const bf16x8*>((kk < 4 ? rk : rv) + off);
+    }
+    float4v zacc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) zacc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < n_chunks; ++c) {
+      __syncthreads();                       // the previous chunk has been consumed
+      {
+        const uint4* s1 = reinterpret_cast<const uint4*>(P.mlp_w1t + (int64_t)c * kMlpChunk * kMlpXPad);
+        for (int i = tid; i < kMlpChunk * kMlpXPad / 8; i += 512) reinterpret_cast<uint4*>(w1s)[i] = s1[i];
+        if constexpr (GATED) {
+          const uint4* sg = reinterpret_cast<const uint4*>(P.mlp_wgt + (int64_t)c * kMlpChunk * kMlpXPad);
+          for (int i = tid; i < kMlpChunk * kMlpXPad / 8; i += 512) reinterpret_cast<uint4*>(wgs)[i] = sg[i];
+        }
+        const uint2* s2 = reinterpret_cast<const uint2*>(P.mlp_w2t + (int64_t)c * R * kMlpW2Pad);
+        for (int i = tid; i < R * kMlpW2Pad / 4; i += 512) reinterpret_cast<uint2*>(w2s)[i] = s2[i];
+      }
+      __syncthreads();
+#pragma unroll 1
+      for (int jb = 0; jb < kMlpChunk / 16; ++jb) {
+        float4v ht = {0.f, 0.f, 0.f, 0.f}, hr = ht, gt = ht, gr = ht;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(w1s + (jb * 16 + ln) * kMlpXPad + (4 * kk + lg) * 8);
+          ht = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, xt[kk], ht, 0, 0, 0);
+          hr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, xr[kk], hr, 0, 0, 0);
+          if constexpr (GATED) {
+            const bf16x8 ag = *reinterpret_cast<const bf16x8*>(wgs + (jb * 16 + ln) * kMlpXPad + (4 * kk + lg) * 8);
+            gt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, xt[kk], gt, 0, 0, 0);
+            gr = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ag, xr[kk], gr, 0, 0, 0);
+          }
+        }
+        // the lane holds hidden columns 16 jb + 4 lg + i (i = 0..3) of token ln: bias, activation, difference
+        const float4 bias = *reinterpret_cast<const float4*>(P.mlp_b1p + c * kMlpChunk + jb * 16 + 4 * lg);
+        const float bi[4] = {bias.x, bias.y, bias.z, bias.w};
+        float d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float ut = ht[i] + bi[i], ur = hr[i] + bi[i];
+          d[i] = GATED ? silu(gt[i]) * ut - silu(gr[i]) * ur : gelu_erf(ut) - gelu_erf(ur);
+        }
+        const uint32_t hi0 = pack_bf16(d[0], d[1]), hi1 = pack_bf16(d[2], d[3]);
+        const uint32_t lo0 = pack_bf16(d[0] - bf16lo(hi0), d[1] - bf16hi(hi0));
+        const uint32_t lo1 = pack_bf16(d[2] - bf16lo(hi1), d[3] - bf16hi(hi1));
+        const short4v dhi = __builtin_bit_cast(short4v, make_uint2(hi0, hi1));
+        const short4v dlo = __builtin_bit_cast(short4v, make_uint2(lo0, lo1));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const short4v a2 = *reinterpret_cast<const short4v*>(w2s + (nb * 16 + ln) * kMlpW2Pad + jb * 16 + 4 * lg);
+          zacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a2, dhi, zacc[nb], 0, 0, 0);
+          zacc[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a2, dlo, zacc[nb], 0, 0, 0);
+        }
+      }
+    }
+    if (head_ok && tok_ok) {
+      uint16_t* lat = P.latent + (int64_t)page * P.latent_page_stride + (int64_t)h * P.latent_head_stride;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int cc = nb * 16 + 4 * lg;
+        uint2 ov;
+        ov.x = is_ref ? 0u : pack_bf16(zacc[nb][0], zacc[nb][1]);
+        ov.y = is_ref ? 0u : pack_bf16(zacc[nb][2], zacc[nb][3]);
+        *reinterpret_cast<uint2*>(lat + ((cc >> 3) * kPage + ln) * 8 + (cc & 7)) = ov;
+      }
+      if (lg == 0) P.idx[(int64_t)page * P.idx_page_stride + (int64_t)h * P.idx_head_stride + ln] = ord;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Decode append: every sequence of the call brings exactly one new token.  Two kernels instead of five (the
 // step is bound by launch latency: a few microseconds of work per kernel).
 //   append_scan   grid (NS, Hkv, B), 256 threads: block (s, h, b) scores its share of the token's candidate
@@ -1203,6 +1350,24 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
   return note_hip_error(hipGetLastError(), "launch of project");
 }
 
+template <int R, bool GATED>
+static hipError_t launch_project_mlp_g(const CompressParams& P, dim3 grid, hipStream_t st) {
+  const size_t lds = ((GATED ? 2 : 1) * kMlpChunk * kMlpXPad + R * kMlpW2Pad) * 2;
+  static bool attr_set = false;
+  if (!attr_set && lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_mlp<R, GATED>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(non-linear projection kernel LDS)");
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_project_mlp<R, GATED>), grid, dim3(512), lds, st, P);
+  return note_hip_error(hipGetLastError(), "launch of project_mlp");
+}
+template <int R>
+static hipError_t launch_project_mlp(const CompressParams& P, dim3 grid, hipStream_t st) {
+  return P.mlp_kind == 1 ? launch_project_mlp_g<R, true>(P, grid, st) : launch_project_mlp_g<R, false>(P, grid, st);
+}
+
 int sim_tile_rows(int rb, int nw) { return (nw == 8 && rb <= 3 ? 8 : 4) * 16 * rb; }
 
 hipError_t launch_compress(const CompressParams& P0, const CompressWs& cw, char* ws, int rb, int nw, int tiles_max,
@@ -1241,6 +1406,24 @@ hipError_t launch_compress(const CompressParams& P0, const CompressWs& cw, char*
     hipLaunchKernelGGL(k_exact, dim3(kExactX, kExactSplits, P.batch * P.Hkv), dim3(256), 0, st, P);
     if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of exact");
     timing_mark(K_EXACT, st);
+  }
+  if (P.mlp_kind >= 0) {
+    hipLaunchKernelGGL(k_mlp_prep, dim3(256), dim3(256), 0, st, P);
+    if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of mlp_prep");
+    dim3 gm(page_tiles_max, P.batch);
+    e = hipErrorInvalidValue;
+    switch (P.R) {
+      case 16: e = launch_project_mlp<16>(P, gm, st); break;
+      case 32: e = launch_project_mlp<32>(P, gm, st); break;
+      case 48: e = launch_project_mlp<48>(P, gm, st); break;
+      case 64: e = launch_project_mlp<64>(P, gm, st); break;
+      case 80: e = launch_project_mlp<80>(P, gm, st); break;
+      case 96: e = launch_project_mlp<96>(P, gm, st); break;
+      case 112: e = launch_project_mlp<112>(P, gm, st); break;
+      case 128: e = launch_project_mlp<128>(P, gm, st); break;
+    }
+    timing_mark(K_PROJECT, st);
+    return e;
   }
   dim3 gp(ceil_div(page_tiles_max, P.proj_ppb), P.batch);
   e = hipErrorInvalidValue;

@@ -628,23 +628,36 @@ int deltakv_decode_attn_rope(const deltakv_dims* dims, const deltakv_layout* lay
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
 }
 
-int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
-                     void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
-                     const int32_t* ref_tables, int32_t rt_stride, const void* w_down_k, const void* w_down_v,
-                     const void* k_new, const void* v_new, const int32_t* cu_new, const int32_t* cu_new_host,
-                     const int32_t* len_before, const int32_t* len_before_host, int32_t batch, void* workspace,
-                     int64_t ws_bytes, void* stream) {
+static int compress_impl(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
+                         void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
+                         const int32_t* ref_tables, int32_t rt_stride, const void* w_down_k, const void* w_down_v,
+                         const deltakv_mlp* mlp,
+                         const void* k_new, const void* v_new, const int32_t* cu_new, const int32_t* cu_new_host,
+                         const int32_t* len_before, const int32_t* len_before_host, int32_t batch, void* workspace,
+                         int64_t ws_bytes, void* stream) {
   int rc = check_dims(dims);
   if (rc != DELTAKV_OK) return rc;
   if (!lay || !latent_pool || !idx_pool || !ref_pool || !ref_inv_norm || !block_tables || !ref_tables ||
-      !w_down_k || !w_down_v || !k_new || !v_new || !cu_new || !cu_new_host || !len_before ||
+      !k_new || !v_new || !cu_new || !cu_new_host || !len_before ||
       !len_before_host || batch < 0 || bt_stride <= 0 || rt_stride <= 0)
     return DELTAKV_E_INVALID_ARG;
+  if (mlp) {
+    if (mlp->kind != DELTAKV_MLP_GELU && mlp->kind != DELTAKV_MLP_SWIGLU) return DELTAKV_E_INVALID_ARG;
+    if (!mlp->w1 || !mlp->b1 || !mlp->w2 || (mlp->kind == DELTAKV_MLP_SWIGLU && !mlp->wg)) return DELTAKV_E_INVALID_ARG;
+    if (mlp->hidden < 1) return DELTAKV_E_INVALID_ARG;
+    if (!aligned(mlp->w1, 2) || !aligned(mlp->w2, 2) || !aligned(mlp->b1, 4) || (mlp->wg && !aligned(mlp->wg, 2)))
+      return DELTAKV_E_INVALID_ARG;
+    // one latent over K||V, stored as bf16, against one reference
+    if (mlp->hidden > kMlpHiddenMax || dims->latent_mode != DELTAKV_JOINT || dims->latent_bits == 4 || dims->top_k > 1)
+      return DELTAKV_E_UNSUPPORTED;
+  } else if (!w_down_k || !w_down_v || !aligned(w_down_k, 2) || !aligned(w_down_v, 2)) {
+    return DELTAKV_E_INVALID_ARG;
+  }
   if (batch == 0) return DELTAKV_OK;
   if (batch > 65535 / dims->n_kv_heads) return DELTAKV_E_UNSUPPORTED;
   if (rt_stride > (1 << 24)) return DELTAKV_E_UNSUPPORTED;   // exact-pass keys carry 24-bit ordinals
   if (!aligned(latent_pool, 16) || !aligned(idx_pool, 16) || !aligned(ref_pool, 16) || !aligned(k_new, 16) ||
-      !aligned(v_new, 16) || !aligned(w_down_k, 2) || !aligned(w_down_v, 2))
+      !aligned(v_new, 16))
     return DELTAKV_E_INVALID_ARG;
   if (cu_new_host[0] != 0) return DELTAKV_E_INVALID_ARG;
   const int P = dims->page_tokens, S = dims->ref_stride;
@@ -742,8 +755,25 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
   Pm.exact_key_all = Pm.exact_key;
   Pm.flag_count_all = Pm.flag_count;
   Pm.round_stride = (int64_t)n_new_total * dims->n_kv_heads;
+  Pm.mlp_kind = -1;
+  if (mlp) {
+    Pm.mlp_kind = mlp->kind;
+    Pm.mlp_hidden = mlp->hidden;
+    Pm.mlp_hidden_pad = (int)align_up(mlp->hidden, kMlpChunk);
+    Pm.mlp_w1 = static_cast<const uint16_t*>(mlp->w1);
+    Pm.mlp_wg = static_cast<const uint16_t*>(mlp->wg);
+    Pm.mlp_w2 = static_cast<const uint16_t*>(mlp->w2);
+    Pm.mlp_b1 = mlp->b1;
+    char* mb = wsb + cw.mlp;
+    const int64_t w1_bytes = align_up((int64_t)Pm.mlp_hidden_pad * kMlpXPad * 2, 256);
+    Pm.mlp_w1t = reinterpret_cast<uint16_t*>(mb);
+    Pm.mlp_wgt = reinterpret_cast<uint16_t*>(mb + w1_bytes);
+    Pm.mlp_w2t = reinterpret_cast<uint16_t*>(mb + 2 * w1_bytes);
+    Pm.mlp_b1p = reinterpret_cast<float*>(mb + 2 * w1_bytes +
+                                          align_up((int64_t)(Pm.mlp_hidden_pad / kMlpChunk) * dims->rank * kMlpW2Pad * 2, 256));
+  }
   // decode append (one new token for every sequence): two small kernels instead of five
-  bool one_each = n_new_total == batch && Pm.top_k == 1;   // (top-k retrieval runs the general path)
+  bool one_each = n_new_total == batch && Pm.top_k == 1 && !mlp;   // (top-k and the non-linear compressor: general path)
   for (int b = 0; b < batch && one_each; ++b) one_each = cu_new_host[b + 1] - cu_new_host[b] == 1;
   hipError_t e;
   if (one_each) {
@@ -764,6 +794,29 @@ int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* 
     e = launch_compress(Pm, cw, wsb, rb, sim_nw, tiles_max, page_tiles_max, max_new_refs, static_cast<hipStream_t>(stream));
   }
   return e == hipSuccess ? DELTAKV_OK : DELTAKV_E_HIP;
+}
+
+int deltakv_compress(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
+                     void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
+                     const int32_t* ref_tables, int32_t rt_stride, const void* w_down_k, const void* w_down_v,
+                     const void* k_new, const void* v_new, const int32_t* cu_new, const int32_t* cu_new_host,
+                     const int32_t* len_before, const int32_t* len_before_host, int32_t batch, void* workspace,
+                     int64_t ws_bytes, void* stream) {
+  return compress_impl(dims, lay, latent_pool, idx_pool, ref_pool, ref_inv_norm, block_tables, bt_stride, ref_tables,
+                       rt_stride, w_down_k, w_down_v, nullptr, k_new, v_new, cu_new, cu_new_host, len_before,
+                       len_before_host, batch, workspace, ws_bytes, stream);
+}
+
+int deltakv_compress_mlp(const deltakv_dims* dims, const deltakv_layout* lay, void* latent_pool, int32_t* idx_pool,
+                         void* ref_pool, float* ref_inv_norm, const int32_t* block_tables, int32_t bt_stride,
+                         const int32_t* ref_tables, int32_t rt_stride, const deltakv_mlp* mlp,
+                         const void* k_new, const void* v_new, const int32_t* cu_new, const int32_t* cu_new_host,
+                         const int32_t* len_before, const int32_t* len_before_host, int32_t batch, void* workspace,
+                         int64_t ws_bytes, void* stream) {
+  if (!mlp) return DELTAKV_E_INVALID_ARG;
+  return compress_impl(dims, lay, latent_pool, idx_pool, ref_pool, ref_inv_norm, block_tables, bt_stride, ref_tables,
+                       rt_stride, nullptr, nullptr, mlp, k_new, v_new, cu_new, cu_new_host, len_before,
+                       len_before_host, batch, workspace, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -102,10 +102,27 @@ struct CompressParams {
   int32_t* flag_list;  // [Hkv][n_new_total] queued token indices, sequence b's segment starts at cu_new[b]
   uint64_t* exact_key; // [n_new_total][Hkv] result keys of the exact pass (valid for queued tokens)
   uint16_t* wt;        // bf16 [2][R][kWPad]: W_dK^T and W_dV^T, rows padded, written by admit_refs for project
+  // non-linear compressor (section 4.1): mlp_kind < 0 means the linear projection above is used
+  int mlp_kind;                     // 0: GeLU(x W1 + b1) W2; 1: (SiLU(x Wg) * (x W1 + b1)) W2
+  int mlp_hidden, mlp_hidden_pad;   // hidden width, and the same rounded up to a multiple of kMlpChunk
+  const uint16_t* mlp_w1;           // bf16 [2 * head_dim][hidden]
+  const uint16_t* mlp_wg;           // bf16 [2 * head_dim][hidden] (kind 1)
+  const uint16_t* mlp_w2;           // bf16 [hidden][R]
+  const float* mlp_b1;              // fp32 [hidden]
+  uint16_t* mlp_w1t;                // bf16 [hidden_pad][kMlpXPad]: W1^T, zero padded (written by mlp_prep)
+  uint16_t* mlp_wgt;                // the same for Wg
+  uint16_t* mlp_w2t;                // bf16 [hidden_pad / kMlpChunk][R][kMlpW2Pad]: W2^T by chunks of hidden columns
+  float* mlp_b1p;                   // fp32 [hidden_pad]
 };
+constexpr int kMlpChunk = 64;       // hidden columns staged in LDS per step of the non-linear projection kernel
+constexpr int kMlpXPad = 2 * kHeadDim + 8;   // bf16 elements per staged W1^T row
+constexpr int kMlpW2Pad = kMlpChunk + 4;     // bf16 elements per staged W2^T row
+constexpr int kMlpHiddenMax = 1024;
+constexpr int64_t kMlpWsBytes = 2ll * kMlpHiddenMax * kMlpXPad * 2 + (int64_t)kMlpHiddenMax / kMlpChunk * 128 * kMlpW2Pad * 2 +
+                                kMlpHiddenMax * 4 + 4 * 256;
 
 struct CompressWs {
-  int64_t ord, flag_count, flag_list, exact_key, wt, part;   // byte offsets; `part` takes everything from its offset on
+  int64_t ord, flag_count, flag_list, exact_key, wt, mlp, part;   // byte offsets; `part` takes everything from its offset on
   int64_t ord_round, flag_count_round, flag_list_round, exact_key_round;   // bytes between the rounds of a top-k call
   int64_t total;
 };
@@ -123,6 +140,7 @@ inline CompressWs plan_compress_ws(const deltakv_dims& d, int64_t batch, int64_t
   w.ord = take(K * w.ord_round);
   w.flag_count = take(K * w.flag_count_round);
   w.wt = take(2 * (int64_t)d.rank * kWPad * 2);
+  w.mlp = take(kMlpWsBytes);                                // transposed weights of the non-linear compressor
   w.flag_list = take(K * w.flag_list_round);
   w.exact_key = take(K * w.exact_key_round);
   w.part = o;
