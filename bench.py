@@ -74,7 +74,11 @@ def prefill_workload(args, torch, dk, B, G):
     earlier token, residual, W_down projection)."""
     L, NL, Hkv, Hq, r, D, s = 32768 if args.seq_len == 131072 else args.seq_len, args.layers, args.kv_heads, \
         args.q_heads, args.rank, 128, 16
-    joint = args.mode == "joint"
+    mlp = None
+    if getattr(args, "mlp", None):                               # non-linear compressor: "gelu:256", "swiglu:256"
+        kind_name, hidden = args.mlp.split(":")
+        mlp = (1 if kind_name == "swiglu" else 0, int(hidden))
+    joint = args.mode == "joint" or mlp is not None
     l2 = args.metric == "l2"
     dims = dk.make_dims(Hkv, Hq, r, n_pages=-(-L // 16), n_ref_slots=-(-L // s),
                         latent_mode=dk.JOINT if joint else dk.SPLIT, metric=dk.METRIC_L2 if l2 else dk.METRIC_COSINE)
@@ -82,6 +86,10 @@ def prefill_workload(args, torch, dk, B, G):
     W = G.make_projections(G.seed_for(4), D, r, joint=joint, recipe="baseline")
     dev = lambda bits: torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
     wdk, wdv = dev(W["w_down_k_bf16"]), dev(W["w_down_v_bf16"])
+    if mlp:
+        M = G.make_mlp_compressor(G.seed_for(4), D, r, mlp[1], swiglu=mlp[0] == 1)
+        mw1, mw2, mb1 = dev(M["w1_bf16"]), dev(M["w2_bf16"]), torch.from_numpy(M["b1_f32"]).cuda()
+        mwg = dev(M["wg_bf16"]) if mlp[0] == 1 else None
     n_in = 4                                                     # distinct input sets, used round-robin
     kv = []
     for i in range(n_in):
@@ -93,6 +101,11 @@ def prefill_workload(args, torch, dk, B, G):
     def step():
         for layer in range(NL):
             kd, vd = kv[layer % n_in]
+            if mlp:
+                B.compress_mlp(dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool,
+                               cache.ref_inv_norm, cache.block_tables, cache.ref_tables, mlp[0], mw1, mwg, mb1, mw2,
+                               kd, vd, cu, [0, L], lb, [0], cache.compress_ws)
+                continue
             B.compress(dims, cache.layout, cache.latent_pool, cache.idx_pool, cache.ref_pool, cache.ref_inv_norm,
                        cache.block_tables, cache.ref_tables, wdk, wdv, kd, vd, cu, [0, L], lb, [0], cache.compress_ws)
 
@@ -120,17 +133,26 @@ def prefill_workload(args, torch, dk, B, G):
     t0 = time.perf_counter()
     nsamp = min(L, 32768 if not l2 else 8192)    # the L2 oracle evaluates the definition token by token (slower)
     nsamp = min(nsamp, getattr(args, "parity_tokens", None) or nsamp)
+    om = None
+    if mlp:
+        om = {"kind": O.SWIGLU if mlp[0] == 1 else O.GELU, "w1": M["w1_f64"], "b1": M["b1_f32"].astype(np.float64),
+              "w2": M["w2_f64"]}
+        if mlp[0] == 1:
+            om["wg"] = M["wg_f64"]
     ref = O.compress(f(Kh), f(Vh), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s,
-                     mode=O.JOINT if joint else O.SPLIT, start=L - nsamp, metric=O.L2 if l2 else O.COSINE)
+                     mode=O.JOINT if joint else O.SPLIT, start=L - nsamp, metric=O.L2 if l2 else O.COSINE, mlp=om)
     t_or = time.perf_counter() - t0
     mism = int(np.sum(ref["idx"] != idx[L - nsamp:]))
+    same = ref["idx"] == idx[L - nsamp:]
+    lat_off = int(np.sum((f(zk[L - nsamp:]) != O.f64_round_to_bf16(ref["z_k"]))[same]))
     result = {
         "metric": "compress tokens/s (prefill compression of one 32768-token prompt, all layers)",
         "value": round(L / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"prefill compression: 1 x {L} tokens, {NL} layers, {Hkv} kv-heads x {D}, rank {r}, "
-                               f"{args.mode.upper()} latents, references every {s}th earlier token, "
+                               f"{'JOINT' if joint else 'SPLIT'} latents"
+                               f"{' from the ' + args.mlp + ' non-linear compressor' if mlp else ''}, references every {s}th earlier token, "
                                f"{'squared-L2' if l2 else 'cosine'} top-1"},
         "roofline": {"bound": "mfma", "kernel": "k_sim_top2", "achieved": round(tflops, 1),
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -142,7 +164,8 @@ def prefill_workload(args, torch, dk, B, G):
                                    f"token count and to {NL} layers"},
         "kernel_ms": {k: round(ms / n, 4) for k, (ms, n) in kern.items() if n},
         "kernel_timing": timing_note,
-        "parity": {"what": f"ordinals of the last {nsamp} tokens of the last layer vs CPU oracle", "mismatches": mism},
+        "parity": {"what": f"ordinals of the last {nsamp} tokens of the last layer vs CPU oracle", "mismatches": mism,
+                   "latents_not_the_correctly_rounded_value": lat_off, "latents_compared": int(same.sum()) * r},
     }
     return result
 
@@ -354,6 +377,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run 5 plain device copies of this many MiB (to scale rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--mlp", default=None, help="prefill32k with the non-linear compressor: gelu:HIDDEN or swiglu:HIDDEN "
+                    "(JOINT latents)")
     ap.add_argument("--workload", choices=["decode128k", "prefill32k", "ragged", "append32k"], default="decode128k",
                     help="decode128k: the headline long-context decode (default); prefill32k: compression of one "
                          "32768-token prompt over the layers (reports compress tokens/s and the similarity GEMM's "

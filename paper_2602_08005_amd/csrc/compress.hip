@@ -861,9 +861,10 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 // Non-linear compressor (section 4.1: z = f_c(kv) - f_c(kv_ref) with a two-layer f_c; section 5.3: the gated
 // variant).  One latent over K||V per (token, kv-head): JOINT layout, stream 0.
 //   mlp_prep     transposes and zero-pads the weights into the workspace: W1^T (and Wg^T) [hidden_pad][kMlpXPad],
-//                W2^T by chunks of kMlpChunk hidden columns, b1 padded.  Padded hidden columns have zero weights
+//                W2^T by chunks of kMlpChunk hidden columns (each chunk padded to whole KB), b1 padded.  Padded hidden columns have zero weights
 //                and bias on both sides, so they contribute act(0) * 0 = 0.
-//   project_mlp  grid (pages, B), 512 threads; wave w takes kv-head w (+8, ...) of the block's page.  Both GEMMs run
+//   project_mlp  grid (pages, B, ceil(Hkv / 4)), 256 threads; wave w takes kv-head 4 z + w of the block's page (the
+//                four waves share the staged weights).  Both GEMMs run
 //                transposed so that the first one's result is already the second one's operand:
 //                  H^T[j][tok]  = sum_f W1^T[j][f] x[tok][f]      A = W1^T rows from LDS, B = the token's raw row
 //                  z^T[c][tok] += sum_j W2^T[c][j] d[j][tok]      B = d = act(H_token) - act(H_reference), in the
@@ -873,7 +874,7 @@ __global__ __launch_bounds__(256) void k_project(CompressParams P) {
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_mlp_prep(CompressParams P) {
   const int hp = P.mlp_hidden_pad, hd = P.mlp_hidden;
-  const int64_t n1 = (int64_t)hp * kMlpXPad, n2 = (int64_t)(hp / kMlpChunk) * P.R * kMlpW2Pad;
+  const int64_t n1 = (int64_t)hp * kMlpXPad, n2 = (int64_t)(hp / kMlpChunk) * mlp_w2_chunk_elems(P.R);
   const int64_t total = n1 + n2 + hp;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
     if (i < n1) {
@@ -883,9 +884,10 @@ __global__ __launch_bounds__(256) void k_mlp_prep(CompressParams P) {
       if (P.mlp_kind == 1) P.mlp_wgt[i] = in ? P.mlp_wg[(int64_t)f * hd + j] : (uint16_t)0;
     } else if (i < n1 + n2) {
       const int64_t k = i - n1;
-      const int jj = (int)(k % kMlpW2Pad), rc = (int)((k / kMlpW2Pad) % P.R), c = (int)(k / ((int64_t)kMlpW2Pad * P.R));
+      const int ce = mlp_w2_chunk_elems(P.R);                 // (a chunk's rows, then padding up to whole KB)
+      const int c = (int)(k / ce), rem = (int)(k % ce), rc = rem / kMlpW2Pad, jj = rem % kMlpW2Pad;
       const int j = c * kMlpChunk + jj;
-      P.mlp_w2t[k] = (jj < kMlpChunk && j < hd) ? P.mlp_w2[(int64_t)j * P.R + rc] : (uint16_t)0;
+      P.mlp_w2t[k] = (rc < P.R && jj < kMlpChunk && j < hd) ? P.mlp_w2[(int64_t)j * P.R + rc] : (uint16_t)0;
     } else {
       const int j = (int)(i - n1 - n2);
       P.mlp_b1p[j] = j < hd ? P.mlp_b1[j] : 0.f;
@@ -893,11 +895,29 @@ __global__ __launch_bounds__(256) void k_mlp_prep(CompressParams P) {
   }
 }
 
-__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
-__device__ inline float silu(float g) { return g / (1.0f + __expf(-g)); }
+// erf with one code path: sign(x) (1 - 2^(t P(t))), t = min(|x|, 4), where t P(t) approximates log2(erfc(t)) on
+// [0, 4] (beyond, erfc < 2e-8).  Absolute error <= 1e-7 (dominated by the rounding of 1 - 2^q), which is all the GeLU
+// below needs: the factor 1 + erf is of order one wherever its error matters.  The coefficients come from the
+// weighted least-squares fit in fit_erf_coefficients.py beside this file.  About a third of the instructions of the
+// two-branch library routine, and no divergence.
+__device__ inline float erf_1b(float x) {
+  const float t = fminf(fabsf(x), 4.0f);
+  float p = 1.160530155e-05f;
+  p = fmaf(p, t, -1.529687725e-04f);
+  p = fmaf(p, t, 8.482503472e-04f);
+  p = fmaf(p, t, -2.274815692e-03f);
+  p = fmaf(p, t, 8.483727288e-05f);
+  p = fmaf(p, t, 2.772445790e-02f);
+  p = fmaf(p, t, -1.483079046e-01f);
+  p = fmaf(p, t, -9.184429049e-01f);
+  p = fmaf(p, t, -1.627907276e+00f);
+  return copysignf(1.0f - __builtin_amdgcn_exp2f(p * t), x);
+}
+__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erf_1b(u * 0.70710678118654752f)); }
+__device__ inline float silu(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * g)); }
 
 template <int R, bool GATED>
-__global__ __launch_bounds__(512) void k_project_mlp(CompressParams P) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(R <= 64 ? 4 : 3))) void k_project_mlp(CompressParams P) {
   constexpr int NB = R / 16;
   extern __shared__ uint16_t mlds[];
   uint16_t* w1s = mlds;                                        // [kMlpChunk][kMlpXPad]
@@ -918,7 +938,8 @@ __global__ __launch_bounds__(512) void k_project_mlp(CompressParams P) {
   page = clampi(page, 0, (int)P.n_pages_pool - 1);
   const int32_t* rtab = P.ref_tables + (int64_t)b * P.rt_stride;
   const int n_chunks = P.mlp_hidden_pad / kMlpChunk;
-  for (int h0 = 0; h0 < P.Hkv; h0 += 8) {
+  {
+    const int h0 = blockIdx.z * 4;
     const bool head_ok = h0 + w < P.Hkv;
     const int h = min(h0 + w, P.Hkv - 1);
     const int o = P.ord_all[n * P.Hkv + h];
@@ -942,15 +963,34 @@ __global__ __launch_bounds__(512) void k_project_mlp(CompressParams P) {
     for (int nb = 0; nb < NB; ++nb) zacc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
     for (int c = 0; c < n_chunks; ++c) {
       __syncthreads();                       // the previous chunk has been consumed
+      // The chunk's weights are contiguous in the packed buffers, in the LDS layout: direct-to-LDS copies of 1 KB per
+      // wave instruction (lane l brings 16 bytes to base + 16 l), all issued before any is waited for.
       {
-        const uint4* s1 = reinterpret_cast<const uint4*>(P.mlp_w1t + (int64_t)c * kMlpChunk * kMlpXPad);
-        for (int i = tid; i < kMlpChunk * kMlpXPad / 8; i += 512) reinterpret_cast<uint4*>(w1s)[i] = s1[i];
-        if constexpr (GATED) {
-          const uint4* sg = reinterpret_cast<const uint4*>(P.mlp_wgt + (int64_t)c * kMlpChunk * kMlpXPad);
-          for (int i = tid; i < kMlpChunk * kMlpXPad / 8; i += 512) reinterpret_cast<uint4*>(wgs)[i] = sg[i];
+        constexpr int kW1Kb = kMlpChunk * kMlpXPad * 2 / 1024, kW2Kb = mlp_w2_chunk_elems(R) * 2 / 1024;
+        static_assert(kMlpChunk * kMlpXPad * 2 % 1024 == 0, "whole wave copies");
+        const uint16_t* s1 = P.mlp_w1t + (int64_t)c * kMlpChunk * kMlpXPad;
+        const uint16_t* sg = P.mlp_wgt + (int64_t)c * kMlpChunk * kMlpXPad;
+        const uint16_t* s2 = P.mlp_w2t + (int64_t)c * mlp_w2_chunk_elems(R);
+        const int wu = __builtin_amdgcn_readfirstlane(w);
+#pragma unroll
+        for (int k = 0; k < (kW1Kb + 3) / 4; ++k) {
+          const int kb = 4 * k + wu;
+          if (kb < kW1Kb) {
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(s1 + kb * 512 + l * 8),
+                                             (void __attribute__((address_space(3)))*)(w1s + kb * 512), 16, 0, 0);
+            if constexpr (GATED)
+              __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(sg + kb * 512 + l * 8),
+                                               (void __attribute__((address_space(3)))*)(wgs + kb * 512), 16, 0, 0);
+          }
         }
-        const uint2* s2 = reinterpret_cast<const uint2*>(P.mlp_w2t + (int64_t)c * R * kMlpW2Pad);
-        for (int i = tid; i < R * kMlpW2Pad / 4; i += 512) reinterpret_cast<uint2*>(w2s)[i] = s2[i];
+#pragma unroll
+        for (int k = 0; k < (kW2Kb + 3) / 4; ++k) {
+          const int kb = 4 * k + wu;
+          if (kb < kW2Kb)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(s2 + kb * 512 + l * 8),
+                                             (void __attribute__((address_space(3)))*)(w2s + kb * 512), 16, 0, 0);
+        }
+        __builtin_amdgcn_s_waitcnt(0);       // this wave's copies have landed before it signals the barrier
       }
       __syncthreads();
 #pragma unroll 1
@@ -1352,7 +1392,7 @@ static hipError_t launch_project(const CompressParams& P, dim3 grid, hipStream_t
 
 template <int R, bool GATED>
 static hipError_t launch_project_mlp_g(const CompressParams& P, dim3 grid, hipStream_t st) {
-  const size_t lds = ((GATED ? 2 : 1) * kMlpChunk * kMlpXPad + R * kMlpW2Pad) * 2;
+  const size_t lds = ((GATED ? 2 : 1) * kMlpChunk * kMlpXPad + mlp_w2_chunk_elems(R)) * 2;
   static bool attr_set = false;
   if (!attr_set && lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_project_mlp<R, GATED>),
@@ -1360,7 +1400,7 @@ static hipError_t launch_project_mlp_g(const CompressParams& P, dim3 grid, hipSt
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(non-linear projection kernel LDS)");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_project_mlp<R, GATED>), grid, dim3(512), lds, st, P);
+  hipLaunchKernelGGL((k_project_mlp<R, GATED>), grid, dim3(256), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of project_mlp");
 }
 template <int R>
@@ -1410,7 +1450,7 @@ hipError_t launch_compress(const CompressParams& P0, const CompressWs& cw, char*
   if (P.mlp_kind >= 0) {
     hipLaunchKernelGGL(k_mlp_prep, dim3(256), dim3(256), 0, st, P);
     if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of mlp_prep");
-    dim3 gm(page_tiles_max, P.batch);
+    dim3 gm(page_tiles_max, P.batch, ceil_div(P.Hkv, 4));
     e = hipErrorInvalidValue;
     switch (P.R) {
       case 16: e = launch_project_mlp<16>(P, gm, st); break;

@@ -770,7 +770,7 @@ static int compress_impl(const deltakv_dims* dims, const deltakv_layout* lay, vo
     Pm.mlp_wgt = reinterpret_cast<uint16_t*>(mb + w1_bytes);
     Pm.mlp_w2t = reinterpret_cast<uint16_t*>(mb + 2 * w1_bytes);
     Pm.mlp_b1p = reinterpret_cast<float*>(mb + 2 * w1_bytes +
-                                          align_up((int64_t)(Pm.mlp_hidden_pad / kMlpChunk) * dims->rank * kMlpW2Pad * 2, 256));
+                                          align_up((int64_t)(Pm.mlp_hidden_pad / kMlpChunk) * mlp_w2_chunk_elems(dims->rank) * 2, 256));
   }
   // decode append (one new token for every sequence): two small kernels instead of five
   bool one_each = n_new_total == batch && Pm.top_k == 1 && !mlp;   // (top-k and the non-linear compressor: general path)

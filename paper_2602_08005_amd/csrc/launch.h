@@ -111,13 +111,17 @@ struct CompressParams {
   const float* mlp_b1;              // fp32 [hidden]
   uint16_t* mlp_w1t;                // bf16 [hidden_pad][kMlpXPad]: W1^T, zero padded (written by mlp_prep)
   uint16_t* mlp_wgt;                // the same for Wg
-  uint16_t* mlp_w2t;                // bf16 [hidden_pad / kMlpChunk][R][kMlpW2Pad]: W2^T by chunks of hidden columns
+  uint16_t* mlp_w2t;                // bf16 [hidden_pad / kMlpChunk][mlp_w2_chunk_elems(R)]: W2^T by chunks of hidden
+                                    // columns, each chunk [R][kMlpW2Pad] and padding
   float* mlp_b1p;                   // fp32 [hidden_pad]
 };
 constexpr int kMlpChunk = 64;       // hidden columns staged in LDS per step of the non-linear projection kernel
 constexpr int kMlpXPad = 2 * kHeadDim + 8;   // bf16 elements per staged W1^T row
 constexpr int kMlpW2Pad = kMlpChunk + 4;     // bf16 elements per staged W2^T row
 constexpr int kMlpHiddenMax = 1024;
+// bf16 elements of one chunk of the packed W2^T: [R][kMlpW2Pad], rounded up to whole KB (the unit of a wave's
+// direct-to-LDS copy)
+__host__ __device__ constexpr int mlp_w2_chunk_elems(int R) { return (R * kMlpW2Pad * 2 + 1023) / 1024 * 512; }
 constexpr int64_t kMlpWsBytes = 2ll * kMlpHiddenMax * kMlpXPad * 2 + (int64_t)kMlpHiddenMax / kMlpChunk * 128 * kMlpW2Pad * 2 +
                                 kMlpHiddenMax * 4 + 4 * 256;
 
