@@ -692,7 +692,7 @@ def decode_workload(args, torch, dk, B, G):
         "compress": {"tokens_per_s": round(compress_tok_s, 1), "tokens": Bt * L,
                      "kernel_ms_total": {k: round(v, 3) for k, v in comp_kern.items()},
                      "what": f"prefill compression of {Bt} x {L} tokens for one layer, batch-1 calls"},
-        "parity": parity, "status_flag": status,
+        "parity": parity, "status_flag": None if args.rope > 0 else status,   # (the rope path keeps no status word)
         "context": "paper: 29% KV memory and up to 2x vLLM decode throughput, whole model on 1x RTX PRO 6000 (not comparable)",
     }
     return result
