@@ -448,7 +448,7 @@ def main():
 def extra_workloads(args, torch, dk, B, G):
     """Short runs of the other configurations, reported inside the headline's JSON line: the long-context decode with
     JOINT latents, the irregular paged batch, the 32768-token prefill compression and the single-sequence append
-    loop.  Each entry carries its throughput, the roofline of its dominant kernel and its parity figure against the
+    loop, the decode path with rotary position embedding and the prefill with the non-linear compressor.  Each entry carries its throughput, the roofline of its dominant kernel and its parity figure against the
     CPU oracle (on a smaller sample than the workload's own command line takes)."""
     import copy
     import gc
@@ -456,7 +456,10 @@ def extra_workloads(args, torch, dk, B, G):
     runs = [("decode128k_joint", decode_workload, dict(mode="joint", steps=5, warmup=1, parity_seqs=2)),
             ("ragged", ragged_workload, dict(workload="ragged", steps=20, warmup=2)),
             ("prefill32k", prefill_workload, dict(workload="prefill32k", steps=3, warmup=1, parity_tokens=4096)),
-            ("append32k", append_workload, dict(workload="append32k", warmup=1))]
+            ("append32k", append_workload, dict(workload="append32k", warmup=1)),
+            ("decode128k_rope", decode_workload, dict(rope=500000.0, steps=3, warmup=1, parity_seqs=1)),
+            ("prefill32k_mlp_gelu", prefill_workload, dict(workload="prefill32k", mlp="gelu:256", steps=3, warmup=1,
+                                                           parity_tokens=2048))]
     for name, fn, over in runs:
         gc.collect()
         torch.cuda.empty_cache()
@@ -470,7 +473,9 @@ def extra_workloads(args, torch, dk, B, G):
         out[name] = {k: r[k] for k in keep if k in r}
         out[name]["command"] = "python bench.py " + {"decode128k_joint": "--mode joint", "ragged": "--workload ragged",
                                                      "prefill32k": "--workload prefill32k",
-                                                     "append32k": "--workload append32k"}[name]
+                                                     "append32k": "--workload append32k",
+                                                     "decode128k_rope": "--rope 500000",
+                                                     "prefill32k_mlp_gelu": "--workload prefill32k --mlp gelu:256"}[name]
         log(f"[bench] extra workload {name}: {r['value']} {r['unit']} ({time.time() - t0:.1f} s wall)")
     return out
 

@@ -153,6 +153,15 @@ int deltakv_paged_layout(const deltakv_dims* dims, int32_t max_batch, int64_t ma
  * (tok, c) inside one (page, head, stream) block; `out` holds P*rank int32. */
 int deltakv_latent_block_offsets(const deltakv_dims* dims, int32_t stream, int32_t* out);
 
+/* Host-only, pure; latent_bits = 4 only (UNSUPPORTED otherwise).  Where the 4-bit
+ * record of token slot `tok` lives inside one (page, head, stream) block, in
+ * 2-byte elements from the block's start:
+ *   code of column c : bits code_shift[tok*rank+c] .. +3 of element code_elem[tok*rank+c]
+ *   scale, zero point: elements scale_elem[tok], zero_elem[tok] (bf16 bits)
+ * code_elem and code_shift hold P*rank int32, scale_elem and zero_elem P int32. */
+int deltakv_q4_block_offsets(const deltakv_dims* dims, int32_t stream, int32_t* code_elem,
+                             int32_t* code_shift, int32_t* scale_elem, int32_t* zero_elem);
+
 /* Host-only, pure.  Bytes this layout keeps per cached token (latent record +
  * index + the amortised raw reference and its norm) over the bytes of the dense
  * bf16 K and V it replaces: the per-layer bracket of the paper's keep-ratio

@@ -83,6 +83,8 @@ def _load() -> C.CDLL:
     lib.deltakv_latent_block_offsets.argtypes = [C.POINTER(Dims), i32, vp]
     lib.deltakv_keep_ratio.restype = C.c_double
     lib.deltakv_keep_ratio.argtypes = [C.POINTER(Dims)]
+    lib.deltakv_q4_block_offsets.restype = C.c_int
+    lib.deltakv_q4_block_offsets.argtypes = [C.POINTER(Dims), i32, vp, vp, vp, vp]
     lib.deltakv_compress.restype = C.c_int
     lib.deltakv_compress.argtypes = [C.POINTER(Dims), C.POINTER(Layout), vp, vp, vp, vp, vp, i32, vp, i32,
                                      vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, i64, vp]
@@ -115,7 +117,7 @@ KERNEL_NAMES = ("ref_scores", "stream", "ref_values", "finalize", "admit_refs", 
 EXPORTS = ("deltakv_version", "deltakv_strerror", "deltakv_last_error_detail", "deltakv_timing_begin",
            "deltakv_timing_end", "deltakv_tune", "deltakv_paged_layout", "deltakv_latent_block_offsets",
            "deltakv_keep_ratio", "deltakv_compress", "deltakv_decode_attn", "deltakv_decode_attn_subset",
-           "deltakv_decode_attn_raw", "deltakv_decode_attn_static", "deltakv_decode_attn_rope", "deltakv_compress_mlp")
+           "deltakv_decode_attn_raw", "deltakv_decode_attn_static", "deltakv_decode_attn_rope", "deltakv_compress_mlp", "deltakv_q4_block_offsets")
 STATIC_WS_BYTES = 64 << 20
 
 
@@ -169,6 +171,17 @@ def latent_block_offsets(dims: Dims, stream: int) -> np.ndarray:
     if rc != OK:
         raise DeltaKVError(rc, "deltakv_latent_block_offsets")
     return out
+
+
+def q4_block_offsets(dims: Dims, stream: int):
+    """(code_elem [P, r], code_shift [P, r], scale_elem [P], zero_elem [P]) of the 4-bit record layout."""
+    P, r = dims.page_tokens, dims.rank
+    ce, cs = np.zeros((P, r), dtype=np.int32), np.zeros((P, r), dtype=np.int32)
+    se, ze = np.zeros(P, dtype=np.int32), np.zeros(P, dtype=np.int32)
+    rc = _lib.deltakv_q4_block_offsets(C.byref(dims), stream, ce.ctypes.data, cs.ctypes.data, se.ctypes.data, ze.ctypes.data)
+    if rc != OK:
+        raise DeltaKVError(rc, "deltakv_q4_block_offsets")
+    return ce, cs, se, ze
 
 
 def keep_ratio(dims: Dims) -> float:

@@ -50,6 +50,8 @@ class PagedCache:
         self.ref_tables = torch.from_numpy(rt).to(device)
         self.q4 = dims.latent_bits == 4
         self.off = [] if self.q4 else [B.latent_block_offsets(dims, s).astype(np.int64) for s in range(L.n_streams)]
+        self.q4_off = [tuple(a.astype(np.int64) for a in B.q4_block_offsets(dims, s)) for s in range(L.n_streams)] \
+            if self.q4 else []
         self.compress_ws = torch.empty(max(L.compress_ws_bytes, 256), dtype=torch.uint8, device=device)
         self.decode_ws = torch.empty(max(L.decode_ws_bytes, 256), dtype=torch.uint8, device=device)
 
@@ -129,17 +131,10 @@ class PagedCache:
         page = self.block_tables_host[b, t // d.page_tokens].astype(np.int64)
         base = page[:, None] * L.latent_page_stride + np.arange(d.n_kv_heads)[None, :] * L.latent_head_stride \
             + stream * L.latent_stream_stride
-        tok = (t % d.page_tokens)[:, None, None]
-        c = np.arange(d.rank)[None, None, :]
-        if stream == 0:
-            code_el = base[:, :, None] + 2 * ((c >> 3) * d.page_tokens + tok) + (c & 1)
-            shift = 4 * ((np.arange(d.rank) & 7) >> 1)
-        else:
-            code_el = base[:, :, None] + 4 * ((c >> 6) * 64 + (tok >> 2) * 16 + (c & 15)) + 2 * ((tok & 3) >> 1) + (tok & 1)
-            shift = 4 * ((np.arange(d.rank) >> 4) & 3)
-        tk = (t % d.page_tokens)[:, None]
-        sc_el = base + 4 * d.rank + (tk >> 2) * 8 + (tk & 3)
-        return code_el, shift, sc_el, sc_el + 4
+        code_off, shift_off, sc_off, zp_off = self.q4_off[stream]           # the library's statement of the record layout
+        tok = t % d.page_tokens
+        code_el = base[:, :, None] + code_off[tok][:, None, :]
+        return code_el, shift_off[0], base + sc_off[tok][:, None], base + zp_off[tok][:, None]
 
     def get_sequence_q4(self, b: int, t0: int, t1: int, stream: int = 0):
         """Token-major copies of the 4-bit records of tokens t0..t1-1 in one latent stream: idx [n, H], codes uint8

@@ -260,7 +260,7 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
 
   // Reference tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
   // a wave-uniform base + 16*l; placement checked on the hardware), no staging registers.  A tile is 64 rows of
-  // 32 sixteen-byte chunks (K half then V half), unpadded; chunk c of row r is stored at position c ^ (r & 7),
+  // 32 sixteen-byte chunks (K half then V half), unpadded; chunk c of row r is stored at position c ^ (r & 15),
   // which the loads realise by permuting their SOURCE chunk, so that the 16 rows read by one operand fetch hit
   // distinct banks.  Wave w issues loads i = 0..7 of a tile; load (w, i) fills rows 2*(8w+i) and 2*(8w+i)+1.
   // Every wave also copies the 64 inverse norms (same values to the same place: keeps all waves' load counts equal).
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
       const int r = 2 * (LPW * w + i) + my_row;
-      const int c = my_pos ^ (r & 7);
+      const int c = my_pos ^ (r & 15);
       // unsigned clamp (a negative table entry lands on the last slot): one instruction, zero-extended address
       const uint16_t* src = (c < 16 ? refk : refv) + (uint64_t)min((uint32_t)slot[i], (uint32_t)P.n_ref_slots - 1u) * kHeadDim + (c & 15) * 8;
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
@@ -312,7 +312,7 @@ __global__ __launch_bounds__(NW * 64) void k_sim_top2(CompressParams P) {
     bf16x8 aop[2][8];
     float4v acc[2][TB];
     Step inext, icur, iprev;                                  // of the step being prefetched / computed / finished
-    const int swz = ln & 7;
+    const int swz = ln;
     // operands and inverse norms of step (ti, cb): every LDS read of a tile happens before the barrier that
     // lets other waves overwrite its buffer
     // (The per-reference floats of a step come from `invt`, read once per tile: the compiler puts a wait for EVERY

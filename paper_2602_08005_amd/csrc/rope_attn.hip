@@ -47,7 +47,7 @@ __device__ inline float row16_sum(float v) {           // sum over the 16 lanes 
   return v;
 }
 
-// Grid (S, Hkv, B), 256 threads.  GP: query heads per kv-head padded to 4 or 8 (the lane keeps its row's share of
+// Grid (pairs padded to a multiple of 8) x S blocks, 256 or 512 threads.  GP: query heads per kv-head padded to 4 or 8 (the lane keeps its row's share of
 // every head's query in registers).
 // Eight waves per block share the staged W_uK^T when the rank is at most 64 (150 KB of LDS), four beyond.
 template <int R, bool JOINT, int GP>
@@ -58,7 +58,13 @@ __global__ __launch_bounds__((R <= 64 ? 8 : 4) * 64) void k_rope_attn(DecodePara
   uint16_t* wt = lds;                                               // [128][WP]   W_uK^T
   uint16_t* tiles = wt + kHeadDim * WP;                             // [waves][2 buffers][K tile, V tile]
   float* red = reinterpret_cast<float*>(tiles + kRopeWaves * 4 * kRopeTileElems);   // cross-wave merge area
-  const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  // Blocks are handed to the eight XCDs round-robin by linear index, and every XCD has an L2 of its own.  All splits
+  // of one (sequence, kv-head) pair go to ONE XCD, pair after pair: the pair's raw reference rows, which every token
+  // of the pair gathers, then stay in that L2 instead of being fetched by all eight.
+  const int xcd = blockIdx.x & 7, k_in = blockIdx.x >> 3;
+  const int pair = xcd + 8 * (k_in / P.S), s = k_in % P.S;
+  if (pair >= P.batch * P.Hkv) return;                              // (the pair count is padded to a multiple of 8)
+  const int h = pair % P.Hkv, b = pair / P.Hkv;
   const int tid = threadIdx.x, l = tid & 63, ln = l & 15, lg = l >> 4;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int L = seq_len_of(P, b);
@@ -137,10 +143,12 @@ __global__ __launch_bounds__((R <= 64 ? 8 : 4) * 64) void k_rope_attn(DecodePara
     const char* base = lat_h + (uint64_t)(uint32_t)pool_page(i) * lat_page_bytes;
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk)
-      t.zk[kk] = 4 * kk + lg < R / 8 ? *reinterpret_cast<const uint4*>(base + (l * 16u + kk * 1024u)) : make_uint4(0, 0, 0, 0);
+      t.zk[kk] = 4 * kk + lg < R / 8 ? __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(base + (l * 16u + kk * 1024u))))
+                                     : make_uint4(0, 0, 0, 0);          // (streamed once: kept out of the L2's way)
     if (!JOINT) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) t.zv[nb] = *reinterpret_cast<const uint2*>(base + lat_stream_bytes + (l * 8u + nb * 512u));
+      for (int nb = 0; nb < NB; ++nb)
+        t.zv[nb] = __builtin_bit_cast(uint2, __builtin_nontemporal_load(reinterpret_cast<const uint2v*>(base + lat_stream_bytes + (l * 8u + nb * 512u))));
     }
   };
 
@@ -404,7 +412,7 @@ hipError_t launch_rope(const DecodeParams& P, float2* tab, int n_pages_max, floa
   hipLaunchKernelGGL(k_rope_table, dim3(ceil_div(n_pages_max * 64, 256)), dim3(256), 0, st, tab, n_pages_max, base);
   if ((e = hipGetLastError()) != hipSuccess) return note_hip_error(e, "launch of rope table");
   timing_mark(K_REF_SCORES, st);
-  dim3 grid(P.S, P.Hkv, batch);
+  dim3 grid((batch * P.Hkv + 7) / 8 * 8 * P.S);              // (pair, split) slots, pairs padded to whole XCD rounds
   switch (P.R) {
     case 16: e = launch_rope_r<16>(P, tab, base, grid, st); break;
     case 32: e = launch_rope_r<32>(P, tab, base, grid, st); break;

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "deltakv.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(deltakv_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(deltakv_[a-z0-9_]+)\s*\(", hdr))
     assert {"deltakv_compress", "deltakv_decode_attn", "deltakv_paged_layout"} <= declared
     lib = C.CDLL(B.LIB_PATH)
     for name in declared:
@@ -55,6 +55,24 @@ def test_block_offsets_are_permutations_with_the_documented_formula(rank):
             assert off[tok, c] == want
     with pytest.raises(dk.DeltaKVError):
         dk.latent_block_offsets(dk.make_dims(4, 28, rank, 8, 8, latent_mode=dk.JOINT), 1)
+
+
+@pytest.mark.parametrize("rank,mode", [(16, "joint"), (64, "joint"), (64, "split"), (128, "split"), (48, "joint")])
+def test_4bit_record_offsets_tile_the_block_without_overlap(rank, mode):
+    """Every (token, column) owns its own nibble, scales and zero points their own half-words behind the codes, and
+    the whole record block (rank / 2 + 4 bytes per token) is covered exactly once."""
+    from paper_2602_08005_amd import binding as B
+    d = dk.make_dims(4, 28, rank, 8, 8, latent_mode=dk.JOINT if mode == "joint" else dk.SPLIT, latent_bits=4)
+    for stream in range(1 if mode == "joint" else 2):
+        ce, cs, se, ze = B.q4_block_offsets(d, stream)
+        assert ce.shape == (16, rank) and se.shape == (16,)
+        nibbles = (ce.astype(np.int64) * 4 + cs // 4).ravel()              # nibble index inside the block
+        assert len(set(nibbles.tolist())) == 16 * rank and set(cs.ravel().tolist()) == {0, 4, 8, 12}
+        assert nibbles.min() == 0 and nibbles.max() == 16 * rank - 1       # the codes fill the first 8 * rank bytes
+        tail = sorted(se.tolist() + ze.tolist())
+        assert tail == list(range(4 * rank, 4 * rank + 32))                 # 16 scales + 16 zero points behind them
+    with pytest.raises(dk.DeltaKVError):
+        B.q4_block_offsets(dk.make_dims(4, 28, rank, 8, 8), 0)             # bf16 latents: not this layout
 
 
 def test_keep_ratio_matches_record_accounting():
