@@ -164,6 +164,72 @@ def test_prefill_32k_ordinals_and_latents_on_a_sample():
     _check_against_oracle(K, V, W, s, False, idx, zk, zv, t0=t0)
 
 
+def test_prefill_32k_two_full_layers_every_ordinal_and_latent():
+    """Config 4 at full size: two layers (different inputs) of one 32768-token prompt, every token's ordinal and latent
+    against the oracle."""
+    import torch
+    import paper_2602_08005_amd as dk
+    from synthetic import generator as G
+    from tests.test_gpu_compress import _check_against_oracle
+    L, Hkv, r, s = 32768, 8, 64, 16
+    dims = dk.make_dims(Hkv, 32, r, n_pages=L // 16, n_ref_slots=L // s)
+    cache = dk.PagedCache(dims, 1, L, L)
+    W = G.make_projections(G.seed_for(4), 128, r)
+    n_diff = 0
+    for layer in (0, 1):
+        K, V, _ = G.make_kv(G.seed_for(4, layer), L, Hkv, 128, n_proto=1024, threads=8)
+        print("layer", layer, "compress", flush=True)
+        cache.compress(_dev(W["w_down_k_bf16"]), _dev(W["w_down_v_bf16"]), _dev(K), _dev(V), [0, L], [0])
+        torch.cuda.synchronize()
+        idx, zk, zv = cache.get_sequence(0, 0, L)
+        print("layer", layer, "oracle", flush=True)
+        n_diff += _check_against_oracle(K, V, W, s, False, idx, zk, zv)
+    assert n_diff <= 4          # (ordinals that differ are accepted only on ties of the oracle's own scores within 1e-6)
+
+
+def test_decode_loop_full_size_32k_prompt_256_appended_tokens():
+    """Config 2 at full size: a 32768-token prompt, then 256 steps that each append one compressed token and attend
+    over the whole cache; every ordinal of prompt and appended tokens, and the outputs of steps 0, 127 and 255."""
+    import torch
+    import paper_2602_08005_amd as dk
+    from oracle import deltakv_oracle as O
+    from synthetic import generator as G
+    from tests.helpers import check_attention
+    L0, n, Hkv, Hq, r, s = 32768, 256, 8, 32, 64, 16
+    dims = dk.make_dims(Hkv, Hq, r, n_pages=(L0 + n) // 16 + 1, n_ref_slots=(L0 + n) // s + 1)
+    cache = dk.PagedCache(dims, 1, L0, L0 + n)
+    W = G.make_projections(G.seed_for(2), 128, r)
+    K, V, _ = G.make_kv(G.seed_for(2), L0 + n, Hkv, 128, n_proto=1024, threads=8)
+    q_bits = G.make_queries(G.seed_for(2), n, Hq, 128)
+    wdk, wdv, wuk, wuv = (_dev(W[k]) for k in ("w_down_k_bf16", "w_down_v_bf16", "w_up_k_bf16", "w_up_v_bf16"))
+    Kd, Vd, qd = _dev(K), _dev(V), _dev(q_bits)
+    cache.compress(wdk, wdv, Kd[:L0], Vd[:L0], [0, L0], [0])
+    keep = {}
+    for i in range(n):
+        t = L0 + i
+        cache.compress(wdk, wdv, Kd[t:t + 1], Vd[t:t + 1], [0, 1], [t])
+        out = cache.decode_attn(wuk, wuv, qd[i:i + 1], [t + 1], 1 / np.sqrt(128))
+        if i in (0, n // 2 - 1, n - 1):
+            keep[i] = out.clone()
+    torch.cuda.synchronize()
+    assert cache.status() == 0
+    f = O.bf16_bits_to_f64
+    print("oracle", flush=True)
+    ref = O.compress(f(K), f(V), f(W["w_down_k_bf16"]), f(W["w_down_v_bf16"]), s=s)
+    idx, zk, zv = cache.get_sequence(0, 0, L0 + n)
+    diff = np.argwhere(idx != ref["idx"])
+    assert len(diff) <= 2, diff[:5]
+    for (i, h) in diff:
+        assert O.cosine_of(f(K), f(V), i, h, int(idx[i, h]), s) >= ref["cos"][i, h] - 1e-6
+    for i, out in keep.items():
+        Lc = L0 + i + 1
+        # the oracle attends over the cache as the kernels wrote it (its own ordinals and latents but for near-ties)
+        want, _ = O.decode_attn_direct(f(q_bits[i]), idx[:Lc], f(zk[:Lc]), f(zv[:Lc]),
+                                       ref["ref_k"][:-(-Lc // s)], ref["ref_v"][:-(-Lc // s)],
+                                       f(W["w_up_k_bf16"]), f(W["w_up_v_bf16"]), 1 / np.sqrt(128))
+        check_attention(f(out.cpu().numpy().view(np.uint16))[0], want, f"step {i}")
+
+
 def test_repeated_calls_agree():
     """Two runs over the same cache agree to within one bf16 ulp (float atomics make the summation order free, so
     bit-identity is not guaranteed; a race would show up as a large difference)."""

@@ -817,3 +817,25 @@ def test_mlp_compressor_against_library_activations_and_difference_structure(kin
     small = (O.mlp_compressor(xr + eps * (xt - xr), m) - O.mlp_compressor(xr, m)) / eps
     smaller = (O.mlp_compressor(xr + 0.5 * eps * (xt - xr), m) - O.mlp_compressor(xr, m)) / (0.5 * eps)
     assert np.max(np.abs(small - smaller)) < 1e-5 * max(1.0, np.max(np.abs(small)))
+
+
+def test_retrieve_one_agrees_with_the_batched_retrieval_and_brute_force():
+    """`retrieve_one` (used by GPU tests to re-score single tokens) against `compress`' ordinals on every token of a
+    small case, and against a brute-force loop over the candidates written out here for a few tokens."""
+    K, V, cls, P = _small_case(seed=123, L=90, H=3, D=16, r=8, s=4)
+    res = O.compress(K, V, P["w_down_k_f64"], P["w_down_v_f64"], s=4)
+    kv = np.concatenate([K, V], axis=2)
+    for i in range(90):
+        for h in range(3):
+            if i % 4 == 0:
+                continue
+            j, c = O.retrieve_one(kv, i, h, 4)
+            assert j == res["idx"][i, h] and abs(c - res["cos"][i, h]) < 1e-12
+    for i, h in ((1, 0), (37, 2), (89, 1)):
+        best, arg = -np.inf, -1
+        for j in range((i + 3) // 4):
+            a, b = kv[i, h], kv[4 * j, h]
+            c = float(a @ b) / (np.sqrt(float(a @ a)) * np.sqrt(float(b @ b)))
+            if c > best:
+                best, arg = c, j
+        assert O.retrieve_one(kv, i, h, 4)[0] == arg
