@@ -53,7 +53,12 @@ __device__ inline float row16_sum(float v) {           // sum over the 16 lanes 
 template <int R, bool JOINT, int GP>
 __global__ __launch_bounds__((R <= 64 ? 8 : 4) * 64) void k_rope_attn(DecodeParams P, const float2* hi_tab, float rope_base) {
   constexpr int kRopeWaves = R <= 64 ? 8 : 4;
-  constexpr int NKK = (R + 31) / 32, NB = R / 16, WP = R + 8;      // WP: padded row of W_uK^T in LDS
+  // W_uK^T rows in LDS: for ranks with a power-of-two number of 16-byte chunks the chunks of row d are XOR-swizzled
+  // by d (operand fetches of 16 rows then hit distinct banks: 2.4 times the LDS rate of rows padded by 16 bytes,
+  // measured); other ranks keep padded rows
+  constexpr bool kSwz = (R & (R - 1)) == 0;
+  constexpr int kSwzMask = kSwz ? R / 8 - 1 : 0;
+  constexpr int NKK = (R + 31) / 32, NB = R / 16, WP = kSwz ? R : R + 8;
   extern __shared__ uint16_t lds[];
   uint16_t* wt = lds;                                               // [128][WP]   W_uK^T
   uint16_t* tiles = wt + kHeadDim * WP;                             // [waves][2 buffers][K tile, V tile]
@@ -82,7 +87,7 @@ __global__ __launch_bounds__((R <= 64 ? 8 : 4) * 64) void k_rope_attn(DecodePara
   // W_uK^T into LDS: element (d, c) <- w_up_k[c][d]
   for (int i = tid; i < kHeadDim * R; i += kRopeWaves * 64) {
     const int c = i / kHeadDim, d = i % kHeadDim;
-    wt[d * WP + c] = P.w_up_k[i];
+    wt[d * WP + ((((c >> 3) ^ (d & kSwzMask)) << 3) | (c & 7))] = P.w_up_k[i];
   }
   // the lane's share of the queries: q[g][16 nb + ln] for nb = 0..7, times scale * log2(e)
   float qv[GP][8];
@@ -194,7 +199,7 @@ __global__ __launch_bounds__((R <= 64 ? 8 : 4) * 64) void k_rope_attn(DecodePara
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) {
           const bf16x8 wb = 4 * kk + lg < R / 8
-              ? *reinterpret_cast<const bf16x8*>(wt + (16 * nb + ln) * WP + (4 * kk + lg) * 8)
+              ? *reinterpret_cast<const bf16x8*>(wt + (16 * nb + ln) * WP + ((4 * kk + lg) ^ ((int)ln & kSwzMask)) * 8)
               : __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
           kh[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, lat_cur.zk[kk]), wb, kh[nb], 0, 0, 0);
         }
@@ -383,7 +388,7 @@ __global__ __launch_bounds__(128) void k_rope_merge(DecodeParams P) {
 
 size_t rope_lds_bytes(int R, int Gp) {
   const int kRopeWaves = R <= 64 ? 8 : 4;
-  return (size_t)(kHeadDim * (R + 8) + kRopeWaves * 4 * kRopeTileElems) * 2 + (size_t)(2 * kRopeWaves * 16 + Gp * (kHeadDim + R)) * 4;
+  return (size_t)(kHeadDim * (R + 8) + kRopeWaves * 4 * kRopeTileElems) * 2 + (size_t)(2 * kRopeWaves * 16 + Gp * (kHeadDim + R)) * 4;   // (an upper bound for the swizzled ranks, whose rows carry no padding)
 }
 
 template <int R, bool JOINT, int GP>
