@@ -336,13 +336,13 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
   if (!spill_on) tab_cap = n_ref_max;
   if ((int64_t)n_ref_max * Gp * 4 >= (1ll << 31)) return DELTAKV_E_UNSUPPORTED;   // 32-bit byte offsets into a pair's tables
   const size_t lds = stream_lds_bytes((int)tab_cap, Gp, R, nw, joint);
-  int per_cu = (int)(kLdsLimit / lds);
-  const int wave_cap = 32 / nw;
-  if (per_cu > wave_cap) per_cu = wave_cap;
-  const int64_t slots = (int64_t)device_cu_count() * per_cu;
-  // Blocks of at most pages_per_split pages: about one per block slot when all sequences have the same length,
-  // about two when the lengths differ (blocks are handed out as slots free up, so smaller blocks even out a
-  // ragged batch; each block costs several microseconds of set-up and flush, which nothing overlaps).
+  // Blocks of at most pages_per_split pages: about one per COMPUTE UNIT when all sequences have the same length
+  // (blocks are handed out longest first as slots free up; each block costs several microseconds of set-up and
+  // flush, which nothing overlaps).  Short
+  // sequences would let several blocks share a compute unit, but more blocks than compute units only add set-up
+  // time: at 8 sequences x 8 kv-heads, 256 blocks beat 512 and 1024 at every length from 2048 to 131072 tokens
+  // (2048 tokens: 18 us against 28 and 48; 32768: 95 against 99 and 108).
+  const int64_t slots = (int64_t)device_cu_count();
   // pages a sequence's blocks iterate over: all of its pages, or the selected ones
   auto work_pages = [&](int b) {
     const int n_pages = ceil_div(seq_lens_host[b], P);
@@ -360,7 +360,9 @@ static int decode_impl(const deltakv_dims* dims, const deltakv_layout* lay, cons
     uniform = uniform && wp == work_pages(0);
   }
   total_pages *= dims->n_kv_heads;
-  const int64_t pages_target = ceil_div64(total_pages, (uniform ? 1 : 2) * slots);
+  // mixed lengths: half as many blocks again, so that the long sequences' blocks even out (the ragged batch of 64
+  // sequences: 199, 210, 201, 195 k tokens/s with 3, 4, 6, 8 splits of the longest sequence; this rule picks 4)
+  const int64_t pages_target = ceil_div64(2 * total_pages, (uniform ? 2 : 3) * slots);
   int splits = (int)ceil_div64(max_work, pages_target > 0 ? pages_target : 1);
   const int split_cap = max_work / 8 > 1 ? max_work / 8 : 1;    // at least 8 pages per split
   if (splits > split_cap) splits = split_cap;

@@ -89,9 +89,10 @@ __device__ inline int load_ordinal(const char* idx_h, uint32_t page_bytes, int p
 // Top-k retrieval (section 4.1: the reference of a token is the mean of its k nearest references): the index pool
 // holds KS ordinal slots per token, [slot][token] inside a (page, head) block, -1 in the slots a token does not use.
 // The kernel variant for k > 1 always works on four slots; with k = 2 slots 2 and 3 re-read slot 1 and are ignored.
-template <int KS>
+// DENSE (see k_stream): the lane holds the ordinal of token 4*(l/16) + (l%16)/4 instead.
+template <int KS, bool DENSE = false>
 __device__ inline void load_ordinals(const char* idx_h, uint32_t page_bytes, int page, uint32_t l, int top_k, int (&out)[KS]) {
-  const char* base = idx_h + (uint64_t)(uint32_t)page * page_bytes + (((l >> 4) * 4u + (l & 3u)) * 4u);
+  const char* base = idx_h + (uint64_t)(uint32_t)page * page_bytes + (((l >> 4) * 4u + (DENSE ? (l & 15u) >> 2 : l & 3u)) * 4u);
 #pragma unroll
   for (int i = 0; i < KS; ++i) out[i] = *reinterpret_cast<const int*>(base + (uint32_t)min(i, top_k - 1) * (kPage * 4u));
 }
@@ -110,9 +111,18 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 // -- its own tokens' ordinals among them: every 16th token is a reference pointing at itself -- and weights of older
 // ordinals are added, as plain floats with hardware float atomics, to one table per (sequence, kv-head) in global
 // memory that all splits share (zeroed by ref_scores, read by ref_values).
-template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL, int KS>
+// DENSE (at most four query heads per kv-head, one ordinal slot): the score product leaves a lane with four tokens of
+// ONE head, and only the 16 lanes of heads 0..3 hold anything; everything that is done once per (token, head) --
+// exponential, table units, rounding, the LDS atomic and the check of its return value, about two thirds of the
+// kernel's vector instructions -- then runs four times per lane on a quarter of the lanes.  The dense variant first
+// spreads the 64 (token, head) pairs of a page over the 64 lanes (three DPP row shifts: lane (lg, 4e + g) takes token
+// 4 lg + e of head g from lane (lg, g)), does that work once per lane, and shifts the weights back into the operand
+// layout of the value product (three row shifts the other way).  Ordinals and per-reference scores are loaded
+// directly in the dense mapping.
+template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL, int KS, bool DENSE = false>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   static_assert(KS == 1 || (KS == 4 && !SPILL && !Q4), "four ordinal slots: bf16 latents, on-chip table only");
+  static_assert(!DENSE || KS == 1, "the dense mapping handles one ordinal slot");
   static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
   extern __shared__ float smem[];
@@ -141,6 +151,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   float* xbuf = lbuf + 16;                                // [NW][16]; the first 16 hold each head's table-unit base
   const int tid = threadIdx.x;
   const uint32_t l = tid & 63, ln = l & 15, lg = l >> 4;
+  const uint32_t hd = DENSE ? (ln & 3u) : ln;             // the query head of the lane's per-(token, head) arithmetic
+  const uint32_t te = ln >> 2;                            // DENSE: the lane's token is 4 lg + te
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   // JOINT: per-wave [16 tokens][R + 8] bf16 scratch used to turn the single latent stream (stored in
   // scores-operand order) into the value-operand order of the P.z product
@@ -168,9 +180,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     tab[tid] = cm_mine;
     __syncthreads();
   }
-  float mref = -INFINITY;                                  // exponent offset for q-head g = ln (see below)
+  float mref = -INFINITY;                                  // exponent offset for q-head g = hd (see below)
   if (!cm_staged) {
-    const int gcol = ln < (uint32_t)Gp ? ln : Gp - 1;
+    const int gcol = hd < (uint32_t)Gp ? hd : Gp - 1;
     for (int k = gcol; k < NW * 64; k += Gp) mref = fmaxf(mref, tab[k]);
     __syncthreads();
   }
@@ -182,9 +194,10 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     __syncthreads();
   }
 
-  const uint32_t gq = ln < (uint32_t)Gp ? ln : Gp - 1;    // column of the score table this lane reads
-  const bool ghead = ln < (uint32_t)G;
-  // exponent offset for q-head g = ln: the largest chunk maximum (the staged copy is free again after the barrier
+  const uint32_t gq = hd < (uint32_t)Gp ? hd : Gp - 1;    // column of the score table this lane reads
+  const bool ghead = hd < (uint32_t)G;                    // the lane does per-(token, head) work
+  const bool ghead_op = ln < (uint32_t)G;                 // the lane's column of the matrix operands is a query head
+  // exponent offset for q-head g = hd: the largest chunk maximum (the staged copy is free again after the barrier
   // that ends the set-up)
   if (cm_staged) {
     const int nch = ceil_div(n_ref, kRefChunk);
@@ -198,11 +211,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // (stored as bf16 hi + lo parts, so that the latent part of the logit keeps fp32-like accuracy)
   bf16x8 qb[TileT::NKK], qbl[TileT::NKK];
   {
-    const uint16_t* qrow = P.qlat + ((int64_t)b * P.Hq + (int64_t)h * G + (ghead ? ln : 0)) * R;
+    const uint16_t* qrow = P.qlat + ((int64_t)b * P.Hq + (int64_t)h * G + (ghead_op ? ln : 0)) * R;
 #pragma unroll
     for (int kk = 0; kk < TileT::NKK; ++kk) {
       uint4 v = make_uint4(0, 0, 0, 0), vl = v;
-      if (ghead && 4 * kk + lg < R / 8) {
+      if (ghead_op && 4 * kk + lg < R / 8) {
         v = *reinterpret_cast<const uint4*>(qrow + (4 * kk + lg) * 8);
         vl = *reinterpret_cast<const uint4*>(qrow + P.qlat_lo_offset + (4 * kk + lg) * 8);
       }
@@ -225,6 +238,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
     qsum += __shfl_xor(qsum, 16);
     qsum += __shfl_xor(qsum, 32);
+    if (DENSE) qsum = __shfl(qsum, (int)hd);              // of the lane's own head (lanes 0..3 hold heads 0..3)
   }
   float zacc = 0.f;
   // bf16 pair (16.0, 16.0); kept in a vector register (opaque to the compiler) so that (x & mask) | c16 is a single
@@ -238,7 +252,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   const uint32_t lat_page_bytes = (uint32_t)P.latent_page_stride * 2u, lat_stream_bytes = (uint32_t)P.latent_stream_stride * 2u;
   const uint32_t idx_page_bytes = (uint32_t)P.idx_page_stride * 4u;
   const int gsh2 = group_shift(Gp) + 2;                   // ordinal -> byte offset of its table row
-  const uint32_t gq4 = gq * 4u, ln4 = ln * 4u;
+  const uint32_t gq4 = gq * 4u, ln4 = hd * 4u;            // (byte offset of the lane's head inside a table row)
   const uint32_t id_hi = (uint32_t)(n_cov - 1);
   float* spill_bh = SPILL ? P.spill + bh * P.n_ref_max * Gp : nullptr;
   __syncthreads();
@@ -248,7 +262,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   for (int nb = 0; nb < TileT::NB; ++nb) acc[nb] = float4v{0.f, 0.f, 0.f, 0.f};
   float lsum = 0.f;
   // lanes that hold no query head start their accumulator at -inf, so their weights are exactly 0
-  const float cstart = ghead ? cinit : -INFINITY;
+  // (the accumulator belongs to the operand column ln; for ln < 4 that is the lane's own head in either mapping)
+  const float cstart = (Q4 ? ghead : ghead_op) ? cinit : -INFINITY;
 
   // Per-reference scores of a page: the lane fetches, with ONE 16-byte load, four heads of the row of the token
   // whose ordinal it holds (token 4*lg + l%4; heads 4*(ln/4)..+3), and compute() turns the quad's 4x4 block
@@ -267,7 +282,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       const uint32_t idc = min((uint32_t)id[i], id_hi);
       if (KS == 1) id[i] = (int)idc;
       sr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (quad_live) sr[i] = *reinterpret_cast<const float4*>(sref_bh + ((idc << gsh2) + quad_off));
+      if constexpr (DENSE) {          // the lane's own (token, head): one float
+        sr[i].x = *reinterpret_cast<const float*>(sref_bh + ((idc << gsh2) + gq4));
+      } else {
+        if (quad_live) sr[i] = *reinterpret_cast<const float4*>(sref_bh + ((idc << gsh2) + quad_off));
+      }
     }
   };
   auto quad_xchg = [](float v, int ctrl_is_pair) {   // value of the lane at position ^1 (pair) or ^2 of the quad
@@ -289,13 +308,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // Table updates of the previous page whose returned old values have not been looked at yet: an entry that
   // wrapped is recorded in the overflow list (rare).  The check runs one page late, in the shadow of the next
   // page's score MFMAs, so the atomics' return latency is never waited for.
-  constexpr int NU = 4 * KS;            // table updates per lane and page: four tokens x ordinal slots
+  constexpr int NU = DENSE ? 1 : 4 * KS;   // table updates per lane and page: four tokens x ordinal slots (DENSE: one)
   uint32_t pend_old[NU], pend_fix[NU];
-  uint32_t pend_ids[NU / 2];            // table rows of the page's updates (16 bits each: a table fits the LDS)
+  uint32_t pend_ids[(NU + 1) / 2];      // table rows of the page's updates (16 bits each: a table fits the LDS)
 #pragma unroll
   for (int n = 0; n < NU; ++n) { pend_old[n] = 0u; pend_fix[n] = 0u; }
 #pragma unroll
-  for (int n = 0; n < NU / 2; ++n) pend_ids[n] = 0u;
+  for (int n = 0; n < (NU + 1) / 2; ++n) pend_ids[n] = 0u;
   auto list_push = [&](uint32_t ent, float amount) {
     const uint32_t slot = atomicAdd(&ovf[0], 1u);
     if (slot < (uint32_t)kOvfCap) {
@@ -317,6 +336,16 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
     }
   };
+  // DENSE: row shifts with a bank mask (a bank = four lanes of a row): only the lanes of one quad take the shifted value
+  auto shr_into = [](float keep, float src, auto N) {       // lanes of quad N take src of the lane 4 N places down
+    constexpr int n = decltype(N)::value;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, src),
+                                                                 0x110 + 4 * n, 0xf, 1 << n, false));
+  };
+  auto shl_to_quad0 = [](float src, auto N) {               // lanes of quad 0 take src of the lane 4 N places up; others 0
+    constexpr int n = decltype(N)::value;
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, src), 0x100 + 4 * n, 0xf, 0x1, false));
+  };
   // FULL: all 16 tokens of the page take part (no masking code at all); otherwise bit t of `mask` says whether
   // token t does (a valid token of the sequence and, in subset attention, a selected one).
   auto compute = [&](auto full_tag, TileT& t, const int (&idv)[KS], const float4 (&srvv)[KS], const uint32_t mask) {
@@ -329,7 +358,9 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     uint32_t rown[4][KS];
     bool usedn[4][KS];
     float inv_m[4] = {1.f, 1.f, 1.f, 1.f};
-    if constexpr (KS == 1) {
+    if constexpr (DENSE) {
+      sr[0] = srvv[0].x;                 // of the lane's own (token, head)
+    } else if constexpr (KS == 1) {
       quad_transpose(srvv[0], sr);
     } else {
 #pragma unroll
@@ -365,6 +396,16 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         zk[kk].z = ((wd >> 5) & 0x00780078u) | c16;
         zk[kk].w = ((wd >> 9) & 0x00780078u) | c16;
       }
+      if constexpr (DENSE) {                     // scale and zero point of the lane's own token 4 lg + te, in slot 0
+        const uint32_t ws = te < 2u ? t.sz.x : t.sz.y, wz = te < 2u ? t.sz.z : t.sz.w;
+        sc[0] = (te & 1u) ? bf16hi(ws) : bf16lo(ws);
+        zf[0] = ((te & 1u) ? bf16hi(wz) : bf16lo(wz)) - 16.f * sc[0];
+        if (!FULL) {
+          const bool on = (mask >> (4 * lg + te)) & 1u;
+          sc[0] = on ? sc[0] : 0.f;
+          zf[0] = on ? zf[0] : 0.f;
+        }
+      } else {
       sc[0] = bf16lo(t.sz.x); sc[1] = bf16hi(t.sz.x); sc[2] = bf16lo(t.sz.y); sc[3] = bf16hi(t.sz.y);
       zf[0] = bf16lo(t.sz.z) - 16.f * sc[0]; zf[1] = bf16hi(t.sz.z) - 16.f * sc[1];
       zf[2] = bf16lo(t.sz.w) - 16.f * sc[2]; zf[3] = bf16hi(t.sz.w) - 16.f * sc[3];
@@ -375,6 +416,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
           sc[e] = on ? sc[e] : 0.f;
           zf[e] = on ? zf[e] : 0.f;
         }
+      }
       }
     } else {
 #pragma unroll
@@ -389,12 +431,24 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     }
     check_pending();
     float p[4];
+    if constexpr (DENSE) {
+      // the lane's own score: token 4 lg + te of head hd, from lane (lg, hd)
+      float dd = d[0];
+      dd = shr_into(dd, d[1], std::integral_constant<int, 1>{});
+      dd = shr_into(dd, d[2], std::integral_constant<int, 2>{});
+      dd = shr_into(dd, d[3], std::integral_constant<int, 3>{});
+      float x = Q4 ? cstart + (sr[0] + (sc[0] * dd + zf[0] * qsum)) : dd + sr[0];
+      if (!FULL) x = ((mask >> (4 * lg + te)) & 1u) ? x : -INFINITY;
+      p[0] = __builtin_amdgcn_exp2f(x);
+      lsum += p[0];
+    } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float x = Q4 ? cstart + (sr[e] + (sc[e] * d[e] + zf[e] * qsum)) : d[e] + sr[e];
       if (!FULL) x = ((mask >> (4 * lg + e)) & 1u) ? x : -INFINITY;   // select, not arithmetic: garbage may be NaN
       p[e] = __builtin_amdgcn_exp2f(x);
       lsum += p[e];
+    }
     }
     if constexpr (KS > 1) {
       if (ghead) {     // one table update per (token, used slot): weight p / m in the units of the slot's reference
@@ -423,6 +477,27 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         }
 #pragma unroll
         for (int n = 0; n < NU / 2; ++n) pend_ids[n] = (off[2 * n] >> gsh2) | ((off[2 * n + 1] >> gsh2) << 16);
+      }
+    } else if constexpr (DENSE) {
+      // (merging the pages of a draw into one basic block -- update unconditional, returned values checked once per draw
+      // -- was measured: no faster for bf16 latents, 12 % slower for 4-bit ones)
+      if (ghead) {     // one fixed-point table update per lane
+        constexpr float kLim = 4294967040.f;     // largest float below 2^32
+        float f = __builtin_ldexpf(p[0], table_shift(sr[0], cshift));
+        uint32_t off = ((uint32_t)id << gsh2) + ln4;
+        if constexpr (SPILL) {     // ordinals older than the window: plain weights into the pair's table in global memory
+          if (id < win_lo) {
+            if (p[0] != 0.f) unsafeAtomicAdd(reinterpret_cast<float*>(reinterpret_cast<char*>(spill_bh) + off), p[0]);
+            f = 0.f;
+            off = ln4;             // a zero addend to the window's first row
+          } else {
+            off -= (uint32_t)win_lo << gsh2;
+          }
+        }
+        if (!(f < kLim)) list_push(off >> 2, p[0]);     // the addend does not fit (rare): the whole weight goes to the list
+        pend_fix[0] = f < kLim ? (uint32_t)(f + 0.5f) : 0u;
+        pend_old[0] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off), pend_fix[0]);
+        pend_ids[0] = off >> gsh2;               // (window-relative row)
       }
     } else {
     // (cross-lane moves read 0 from lanes that are switched off, so they stay outside the per-head branch)
@@ -473,7 +548,28 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     // taken out is 23.5, the centre of 16 + code, so that what the rounding of a weight multiplies is the centred
     // code (-7.5 .. 7.5), as it multiplies a centred latent in the bf16 layouts; the 7.5 scale goes with the zero point.
     float pzero = 0.f;                           // sum_e p[e] * (zero[e] + 7.5 scale[e])
-    if constexpr (Q4 && JOINT) {
+    if constexpr (DENSE) {
+      // the same per lane for its own token; then the weights go back to the operand layout of the value product:
+      // lane (lg, g) of quad 0 collects tokens 4 lg + 0..3 of head g from lanes (lg, 4 e + g), every other lane holds 0
+      if constexpr (Q4 && JOINT) {
+        pzero = p[0] * (zf[0] + 23.5f * sc[0]);
+        p[0] *= sc[0];
+      }
+      if constexpr (Q4 && !JOINT) {
+        const uint32_t ws = te < 2u ? t.szv.x : t.szv.y, wz = te < 2u ? t.szv.z : t.szv.w;
+        const float sv = (te & 1u) ? bf16hi(ws) : bf16lo(ws), zv0 = (te & 1u) ? bf16hi(wz) : bf16lo(wz);
+        const bool on = FULL || ((mask >> (4 * lg + te)) & 1u);
+        pzero = p[0] * (on ? zv0 + 7.5f * sv : 0.f);
+        p[0] *= on ? sv : 0.f;
+      }
+      if constexpr (Q4) zacc += pzero - 23.5f * bf16lo(pack_bf16(p[0], 0.f));     // (the weight as the matrix unit sees it)
+      const float pd = p[0];
+      p[0] = ln < 4u ? pd : 0.f;
+      p[1] = shl_to_quad0(pd, std::integral_constant<int, 1>{});
+      p[2] = shl_to_quad0(pd, std::integral_constant<int, 2>{});
+      p[3] = shl_to_quad0(pd, std::integral_constant<int, 3>{});
+    }
+    if constexpr (Q4 && JOINT && !DENSE) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         pzero += p[e] * (zf[e] + 23.5f * sc[e]); // zf = zero - 16 scale
@@ -481,6 +577,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       }
     }
     if constexpr (Q4 && !JOINT) {  // the same with the value stream's own scales and zero points
+      if constexpr (!DENSE) {
       float sv[4] = {bf16lo(t.szv.x), bf16hi(t.szv.x), bf16lo(t.szv.y), bf16hi(t.szv.y)};
       float zv0[4] = {bf16lo(t.szv.z), bf16hi(t.szv.z), bf16lo(t.szv.w), bf16hi(t.szv.w)};
 #pragma unroll
@@ -488,6 +585,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         const bool on = FULL || ((mask >> (4 * lg + e)) & 1u);
         pzero += p[e] * (on ? zv0[e] + 7.5f * sv[e] : 0.f);
         p[e] *= on ? sv[e] : 0.f;
+      }
       }
 #pragma unroll
       for (int nb = 0; nb < TileT::NB; ++nb) {
@@ -500,7 +598,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     uint2 pk;
     pk.x = pack_bf16(p[0], p[1]);
     pk.y = pack_bf16(p[2], p[3]);
-    if constexpr (Q4) zacc += pzero - 23.5f * ((bf16lo(pk.x) + bf16hi(pk.x)) + (bf16lo(pk.y) + bf16hi(pk.y)));
+    if constexpr (Q4 && !DENSE) zacc += pzero - 23.5f * ((bf16lo(pk.x) + bf16hi(pk.x)) + (bf16lo(pk.y) + bf16hi(pk.y)));
     const short4v pa = __builtin_bit_cast(short4v, pk);
     if (JOINT) {
 #pragma unroll
@@ -616,7 +714,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     int pgit_next = page_vec(cb1);
     int mk_next = mask_vec(cb);                               // masks of the draw about to be computed
 #pragma unroll
-    for (int u = 0; u < LI; ++u) load_ordinals<KS>(idx_h, idx_page_bytes, pg[u], l, top_k, id[u]);
+    for (int u = 0; u < LI; ++u) load_ordinals<KS, DENSE>(idx_h, idx_page_bytes, pg[u], l, top_k, id[u]);
 #pragma unroll
     for (int u = 0; u < LZ; ++u) load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
 #pragma unroll
@@ -629,7 +727,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       const int cb3 = draw();
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
-        load_ordinals<KS>(idx_h, idx_page_bytes, pg[(u + LI) % ST], l, top_k, id[(u + LI) % ST]);
+        load_ordinals<KS, DENSE>(idx_h, idx_page_bytes, pg[(u + LI) % ST], l, top_k, id[(u + LI) % ST]);
         load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
         pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
@@ -644,13 +742,21 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   }
 
   // ---- block reduction of the per-wave partials -------------------------------------------------
+  if (DENSE) {                     // the four tokens of a lane group's head sit in four quads
+    lsum += __shfl_xor(lsum, 4);
+    lsum += __shfl_xor(lsum, 8);
+  }
   lsum += __shfl_xor(lsum, 16);
   lsum += __shfl_xor(lsum, 32);
-  if (l < 16) atomicAdd(&lbuf[l], lsum);
+  if (l < (DENSE ? 4u : 16u)) atomicAdd(&lbuf[l], lsum);
   if (Q4) {
+    if (DENSE) {
+      zacc += __shfl_xor(zacc, 4);
+      zacc += __shfl_xor(zacc, 8);
+    }
     zacc += __shfl_xor(zacc, 16);
     zacc += __shfl_xor(zacc, 32);
-    if (l < 16) atomicAdd(&zbuf[l], zacc);
+    if (l < (DENSE ? 4u : 16u)) atomicAdd(&zbuf[l], zacc);
   }
 #pragma unroll
   for (int nb = 0; nb < TileT::NB; ++nb)
@@ -701,8 +807,11 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 // host launcher
 // ------------------------------------------------------------------------------------------------
-template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false, int KS = 1>
+template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false, int KS = 1, bool DENSE = false>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
+  if constexpr (KS == 1 && !DENSE) {       // at most four query heads per kv-head: one (token, head) pair per lane
+    if (P.Gp == 4 && P.top_k <= 1) return launch_stream<R, NW, JOINT, SUBSET, Q4, NT, SPILL, 1, true>(P, grid, lds, st);
+  }
   if constexpr (KS == 1 && !Q4 && !SPILL) {      // several ordinal slots per token: bf16 latents, on-chip table
     if (P.top_k > 1) {
       if (P.spill_on) return hipErrorInvalidValue;
@@ -711,10 +820,10 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
     }
   }
   if constexpr (!SPILL && KS == 1) {        // (a spilling call is a long-sequence call: its bf16 latent loads are non-temporal)
-    if (P.spill_on) return launch_stream<R, NW, JOINT, SUBSET, Q4, !Q4, true>(P, grid, lds, st);
+    if (P.spill_on) return launch_stream<R, NW, JOINT, SUBSET, Q4, !Q4, true, 1, DENSE>(P, grid, lds, st);
   }
   if constexpr (!Q4 && !NT && KS == 1) {
-    if (P.nt) return launch_stream<R, NW, JOINT, SUBSET, Q4, true>(P, grid, lds, st);
+    if (P.nt) return launch_stream<R, NW, JOINT, SUBSET, Q4, true, false, 1, DENSE>(P, grid, lds, st);
   }
   // Gather lead of the software pipeline (pages of loads kept in flight per wave), bounded by the 6-bit
   // load counter (loads per page) and by the register file (registers per page in flight).
@@ -734,12 +843,12 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   constexpr int ST = lg0 < 1 ? 1 : (lg0 > 8 ? 8 : lg0);
   static size_t attr_bytes = 48 * 1024;
   if (lds > attr_bytes) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS, DENSE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_lds_limit());
     if (e != hipSuccess) return note_hip_error(e, "hipFuncSetAttribute(stream kernel LDS)");
     attr_bytes = device_lds_limit();
   }
-  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS>), grid, dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_stream<R, NW, ST, JOINT, SUBSET, Q4, NT, SPILL, KS, DENSE>), grid, dim3(NW * 64), lds, st, P);
   return note_hip_error(hipGetLastError(), "launch of the stream kernel");
 }
 
