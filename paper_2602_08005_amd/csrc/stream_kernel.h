@@ -39,11 +39,13 @@ struct Tile<R, true> {
 // kernel's time).  The same hint on the ordinals, or on the small 4-bit records, changed nothing; and a cache that
 // fits the chip's last-level cache and is read again by the next call (a single sequence's decode loop) is better
 // off with ordinary loads, so the host picks the variant (NT) by the size of what the call streams.
-template <int R, bool JOINT, bool NT>
+// DENSE (see k_stream): the lane needs the scale and zero point of ONE token, 4*(l/16) + (l%16)/4: two 2-byte loads
+// into sz.x / sz.z (szv likewise) instead of the group's sixteen bytes and the selects that pick a token out of them.
+template <int R, bool JOINT, bool NT, bool DENSE = false>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
                                     uint32_t l, Tile<R, true>& t) {
   const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
-  const uint32_t lg = l >> 4;
+  const uint32_t lg = l >> 4, te2 = ((l & 15u) >> 2) * 2u;
 #pragma unroll
   for (int kk = 0; kk < Tile<R, true>::NKK; ++kk) {
     if (4 * kk + lg < R / 8)
@@ -51,15 +53,25 @@ __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint
     else
       t.zc[kk] = 0u;
   }
-  t.sz = *reinterpret_cast<const uint4*>(base + (8u * R + lg * 16u));
+  if constexpr (DENSE) {
+    t.sz.x = *reinterpret_cast<const uint16_t*>(base + (8u * R + lg * 16u + te2));
+    t.sz.z = *reinterpret_cast<const uint16_t*>(base + (8u * R + lg * 16u + 8u + te2));
+  } else {
+    t.sz = *reinterpret_cast<const uint4*>(base + (8u * R + lg * 16u));
+  }
   if (!JOINT) {
     const char* vb = base + stream_bytes;
 #pragma unroll
     for (int q = 0; q < Tile<R, true>::NQ; ++q) t.zvc[q] = *reinterpret_cast<const uint2*>(vb + (l * 8u + q * 512u));
-    t.szv = *reinterpret_cast<const uint4*>(vb + (8u * R + lg * 16u));
+    if constexpr (DENSE) {
+      t.szv.x = *reinterpret_cast<const uint16_t*>(vb + (8u * R + lg * 16u + te2));
+      t.szv.z = *reinterpret_cast<const uint16_t*>(vb + (8u * R + lg * 16u + 8u + te2));
+    } else {
+      t.szv = *reinterpret_cast<const uint4*>(vb + (8u * R + lg * 16u));
+    }
   }
 }
-template <int R, bool JOINT, bool NT>
+template <int R, bool JOINT, bool NT, bool DENSE = false>
 __device__ inline void load_latents(const char* lat_h, uint32_t page_bytes, uint32_t stream_bytes, int page,
                                     uint32_t l, Tile<R, false>& t) {
   const char* base = lat_h + (uint64_t)(uint32_t)page * page_bytes;
@@ -342,9 +354,13 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, keep), __builtin_bit_cast(int, src),
                                                                  0x110 + 4 * n, 0xf, 1 << n, false));
   };
-  auto shl_to_quad0 = [](float src, auto N) {               // lanes of quad 0 take src of the lane 4 N places up; others 0
+  // every lane takes src of the lane 4 N places up in its row (0 past the row's end).  Only quad 0 needs the result:
+  // the other lanes hold rows 4..15 of the weights operand, whose products land in accumulator rows of query heads
+  // that do not exist and are never read.
+  auto shl_quads = [](float src, auto N) {
     constexpr int n = decltype(N)::value;
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, src), 0x100 + 4 * n, 0xf, 0x1, false));
+    const int v = __builtin_bit_cast(int, src);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x100 + 4 * n, 0xf, 0xf, true));
   };
   // FULL: all 16 tokens of the page take part (no masking code at all); otherwise bit t of `mask` says whether
   // token t does (a valid token of the sequence and, in subset attention, a selected one).
@@ -397,9 +413,8 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
         zk[kk].w = ((wd >> 9) & 0x00780078u) | c16;
       }
       if constexpr (DENSE) {                     // scale and zero point of the lane's own token 4 lg + te, in slot 0
-        const uint32_t ws = te < 2u ? t.sz.x : t.sz.y, wz = te < 2u ? t.sz.z : t.sz.w;
-        sc[0] = (te & 1u) ? bf16hi(ws) : bf16lo(ws);
-        zf[0] = ((te & 1u) ? bf16hi(wz) : bf16lo(wz)) - 16.f * sc[0];
+        sc[0] = bf16lo(t.sz.x);              // (loaded for this token alone: bf16 bits in the low half)
+        zf[0] = bf16lo(t.sz.z) - 16.f * sc[0];
         if (!FULL) {
           const bool on = (mask >> (4 * lg + te)) & 1u;
           sc[0] = on ? sc[0] : 0.f;
@@ -550,24 +565,22 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     float pzero = 0.f;                           // sum_e p[e] * (zero[e] + 7.5 scale[e])
     if constexpr (DENSE) {
       // the same per lane for its own token; then the weights go back to the operand layout of the value product:
-      // lane (lg, g) of quad 0 collects tokens 4 lg + 0..3 of head g from lanes (lg, 4 e + g), every other lane holds 0
+      // lane (lg, g) of quad 0 collects tokens 4 lg + 0..3 of head g from lanes (lg, 4 e + g); the other lanes do not matter
       if constexpr (Q4 && JOINT) {
         pzero = p[0] * (zf[0] + 23.5f * sc[0]);
         p[0] *= sc[0];
       }
       if constexpr (Q4 && !JOINT) {
-        const uint32_t ws = te < 2u ? t.szv.x : t.szv.y, wz = te < 2u ? t.szv.z : t.szv.w;
-        const float sv = (te & 1u) ? bf16hi(ws) : bf16lo(ws), zv0 = (te & 1u) ? bf16hi(wz) : bf16lo(wz);
+        const float sv = bf16lo(t.szv.x), zv0 = bf16lo(t.szv.z);
         const bool on = FULL || ((mask >> (4 * lg + te)) & 1u);
         pzero = p[0] * (on ? zv0 + 7.5f * sv : 0.f);
         p[0] *= on ? sv : 0.f;
       }
       if constexpr (Q4) zacc += pzero - 23.5f * bf16lo(pack_bf16(p[0], 0.f));     // (the weight as the matrix unit sees it)
       const float pd = p[0];
-      p[0] = ln < 4u ? pd : 0.f;
-      p[1] = shl_to_quad0(pd, std::integral_constant<int, 1>{});
-      p[2] = shl_to_quad0(pd, std::integral_constant<int, 2>{});
-      p[3] = shl_to_quad0(pd, std::integral_constant<int, 3>{});
+      p[1] = shl_quads(pd, std::integral_constant<int, 1>{});
+      p[2] = shl_quads(pd, std::integral_constant<int, 2>{});
+      p[3] = shl_quads(pd, std::integral_constant<int, 3>{});
     }
     if constexpr (Q4 && JOINT && !DENSE) {
 #pragma unroll
@@ -716,7 +729,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
     for (int u = 0; u < LI; ++u) load_ordinals<KS, DENSE>(idx_h, idx_page_bytes, pg[u], l, top_k, id[u]);
 #pragma unroll
-    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
+    for (int u = 0; u < LZ; ++u) load_latents<R, JOINT, NT, DENSE>(lat_h, lat_page_bytes, lat_stream_bytes, pg[u], l, t[u]);
 #pragma unroll
     for (int u = 0; u < LG; ++u) gather(id[u], sr[u]);
     auto body = [&](auto full_tag) {
@@ -728,7 +741,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 #pragma unroll
       for (int u = 0; u < ST; ++u) {
         load_ordinals<KS, DENSE>(idx_h, idx_page_bytes, pg[(u + LI) % ST], l, top_k, id[(u + LI) % ST]);
-        load_latents<R, JOINT, NT>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
+        load_latents<R, JOINT, NT, DENSE>(lat_h, lat_page_bytes, lat_stream_bytes, pg[(u + LZ) % ST], l, t[(u + LZ) % ST]);
         pg[u] = __builtin_amdgcn_readlane(pgit, u);
         gather(id[(u + LG) % ST], sr[(u + LG) % ST]);
         compute(full_tag, t[u], id[u], sr[u],
@@ -829,7 +842,8 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   // load counter (loads per page) and by the register file (registers per page in flight).
   constexpr int NKK = (R + 31) / 32, NB = R / 16;
   constexpr int NQ = (NB + 3) / 4;
-  constexpr int lat_loads = Q4 ? NKK + 1 + (JOINT ? 0 : NQ + 1) : NKK + (JOINT ? 0 : NB);       // latent loads per page
+  constexpr int lat_loads = Q4 ? NKK + (DENSE ? 2 : 1) + (JOINT ? 0 : NQ + (DENSE ? 2 : 1))
+                               : NKK + (JOINT ? 0 : NB);                                        // latent loads per page
   constexpr int tile_regs = Q4 ? NKK + 4 + (JOINT ? 0 : 2 * NQ + 4) : 4 * NKK + (JOINT ? 0 : 2 * NB);
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
   // operands built per page in extra registers (the constants are fitted to what the compiler keeps without spilling)
