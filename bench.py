@@ -448,7 +448,8 @@ def main():
 def extra_workloads(args, torch, dk, B, G):
     """Short runs of the other configurations, reported inside the headline's JSON line: the long-context decode with
     JOINT latents, the irregular paged batch, the 32768-token prefill compression and the single-sequence append
-    loop, the decode path with rotary position embedding and the prefill with the non-linear compressor.  Each entry carries its throughput, the roofline of its dominant kernel and its parity figure against the
+    loop, the decode over 4-bit latents, the decode path with rotary position embedding and the prefill with the
+    non-linear compressor.  Each entry carries its throughput, the roofline of its dominant kernel and its parity figure against the
     CPU oracle (on a smaller sample than the workload's own command line takes)."""
     import copy
     import gc
@@ -457,6 +458,7 @@ def extra_workloads(args, torch, dk, B, G):
             ("ragged", ragged_workload, dict(workload="ragged", steps=20, warmup=2)),
             ("prefill32k", prefill_workload, dict(workload="prefill32k", steps=3, warmup=1, parity_tokens=4096)),
             ("append32k", append_workload, dict(workload="append32k", warmup=1)),
+            ("decode128k_joint_q4", decode_workload, dict(mode="joint", latent_bits=4, steps=5, warmup=1, parity_seqs=1)),
             ("decode128k_rope", decode_workload, dict(rope=500000.0, steps=3, warmup=1, parity_seqs=1)),
             ("prefill32k_mlp_gelu", prefill_workload, dict(workload="prefill32k", mlp="gelu:256", steps=3, warmup=1,
                                                            parity_tokens=2048))]
@@ -474,6 +476,7 @@ def extra_workloads(args, torch, dk, B, G):
         out[name]["command"] = "python bench.py " + {"decode128k_joint": "--mode joint", "ragged": "--workload ragged",
                                                      "prefill32k": "--workload prefill32k",
                                                      "append32k": "--workload append32k",
+                                                     "decode128k_joint_q4": "--mode joint --latent-bits 4",
                                                      "decode128k_rope": "--rope 500000",
                                                      "prefill32k_mlp_gelu": "--workload prefill32k --mlp gelu:256"}[name]
         log(f"[bench] extra workload {name}: {r['value']} {r['unit']} ({time.time() - t0:.1f} s wall)")
