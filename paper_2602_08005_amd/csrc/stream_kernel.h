@@ -134,7 +134,7 @@ __device__ inline int quad_bcast(int v) {   // value held by lane E of the calle
 template <int R, int NW, int PIPE_LG, bool JOINT, bool SUBSET, bool Q4, bool NT, bool SPILL, int KS, bool DENSE = false>
 __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   static_assert(KS == 1 || (KS == 4 && !SPILL && !Q4), "four ordinal slots: bf16 latents, on-chip table only");
-  static_assert(!DENSE || KS == 1, "the dense mapping handles one ordinal slot");
+
   static_assert(!Q4 || JOINT || R % 64 == 0, "two-stream 4-bit latents: four 16-column blocks share a dword");
   typedef Tile<R, Q4> TileT;
   extern __shared__ float smem[];
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
   // Table updates of the previous page whose returned old values have not been looked at yet: an entry that
   // wrapped is recorded in the overflow list (rare).  The check runs one page late, in the shadow of the next
   // page's score MFMAs, so the atomics' return latency is never waited for.
-  constexpr int NU = DENSE ? 1 : 4 * KS;   // table updates per lane and page: four tokens x ordinal slots (DENSE: one)
+  constexpr int NU = DENSE ? KS : 4 * KS;  // table updates per lane and page: four tokens x ordinal slots (DENSE: one token)
   uint32_t pend_old[NU], pend_fix[NU];
   uint32_t pend_ids[(NU + 1) / 2];      // table rows of the page's updates (16 bits each: a table fits the LDS)
 #pragma unroll
@@ -374,8 +374,21 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
     uint32_t rown[4][KS];
     bool usedn[4][KS];
     float inv_m[4] = {1.f, 1.f, 1.f, 1.f};
-    if constexpr (DENSE) {
+    if constexpr (DENSE && KS == 1) {
       sr[0] = srvv[0].x;                 // of the lane's own (token, head)
+    } else if constexpr (DENSE) {        // several slots: mean of the scores of the slots the lane's token uses
+      float cnt = 0.f;
+      sr[0] = 0.f;
+#pragma unroll
+      for (int i = 0; i < KS; ++i) {
+        sri[i][0] = srvv[i].x;
+        usedn[0][i] = i < top_k && idv[i] >= 0;
+        rown[0][i] = min((uint32_t)idv[i], id_hi);
+        cnt += usedn[0][i] ? 1.f : 0.f;
+        sr[0] += usedn[0][i] ? sri[i][0] : 0.f;
+      }
+      inv_m[0] = __builtin_amdgcn_rcpf(fmaxf(cnt, 1.f));
+      sr[0] *= inv_m[0];
     } else if constexpr (KS == 1) {
       quad_transpose(srvv[0], sr);
     } else {
@@ -465,7 +478,32 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
       lsum += p[e];
     }
     }
-    if constexpr (KS > 1) {
+    if constexpr (KS > 1 && DENSE) {
+      if (ghead) {     // one table update per used slot of the lane's token: weight p / m in the units of the slot's reference
+        constexpr float kLim = 4294967040.f;     // largest float below 2^32
+        float f[NU];
+        uint32_t off[NU];
+        float fmax_all = 0.f;
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+          f[i] = usedn[0][i] ? __builtin_ldexpf(p[0] * inv_m[0], table_shift(sri[i][0], cshift)) : 0.f;
+          off[i] = (rown[0][i] << gsh2) + ln4;
+          fmax_all = fmaxf(fmax_all, f[i]);
+        }
+        if (!(fmax_all < kLim)) {                  // an addend does not fit (rare): the whole weight goes to the list
+#pragma unroll
+          for (int n = 0; n < NU; ++n)
+            if (!(f[n] < kLim)) list_push(off[n] >> 2, p[0] * inv_m[0]);
+        }
+#pragma unroll
+        for (int n = 0; n < NU; ++n) {
+          pend_fix[n] = f[n] < kLim ? (uint32_t)(f[n] + 0.5f) : 0u;
+          pend_old[n] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(utab) + off[n]), pend_fix[n]);
+        }
+#pragma unroll
+        for (int n = 0; n < NU / 2; ++n) pend_ids[n] = (off[2 * n] >> gsh2) | ((off[2 * n + 1] >> gsh2) << 16);
+      }
+    } else if constexpr (KS > 1) {
       if (ghead) {     // one table update per (token, used slot): weight p / m in the units of the slot's reference
         constexpr float kLim = 4294967040.f;     // largest float below 2^32
         float f[NU];
@@ -822,14 +860,14 @@ __global__ __launch_bounds__(NW * 64) void k_stream(DecodeParams P) {
 // ------------------------------------------------------------------------------------------------
 template <int R, int NW, bool JOINT, bool SUBSET, bool Q4, bool NT = false, bool SPILL = false, int KS = 1, bool DENSE = false>
 static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hipStream_t st) {
-  if constexpr (KS == 1 && !DENSE) {       // at most four query heads per kv-head: one (token, head) pair per lane
-    if (P.Gp == 4 && P.top_k <= 1) return launch_stream<R, NW, JOINT, SUBSET, Q4, NT, SPILL, 1, true>(P, grid, lds, st);
+  if constexpr (!DENSE) {                  // at most four query heads per kv-head: one (token, head) pair per lane
+    if (P.Gp == 4 && (KS > 1 || P.top_k <= 1)) return launch_stream<R, NW, JOINT, SUBSET, Q4, NT, SPILL, KS, true>(P, grid, lds, st);
   }
   if constexpr (KS == 1 && !Q4 && !SPILL) {      // several ordinal slots per token: bf16 latents, on-chip table
     if (P.top_k > 1) {
       if (P.spill_on) return hipErrorInvalidValue;
-      return P.nt ? launch_stream<R, NW, JOINT, SUBSET, Q4, true, false, 4>(P, grid, lds, st)
-                  : launch_stream<R, NW, JOINT, SUBSET, Q4, false, false, 4>(P, grid, lds, st);
+      return P.nt ? launch_stream<R, NW, JOINT, SUBSET, Q4, true, false, 4, DENSE>(P, grid, lds, st)
+                  : launch_stream<R, NW, JOINT, SUBSET, Q4, false, false, 4, DENSE>(P, grid, lds, st);
     }
   }
   if constexpr (!SPILL && KS == 1) {        // (a spilling call is a long-sequence call: its bf16 latent loads are non-temporal)
@@ -848,6 +886,8 @@ static hipError_t launch_stream(const DecodeParams& P, dim3 grid, size_t lds, hi
   // live registers ~ (LG+2) latent tiles + (2LG+2) ordinals + (LG+1) score quads + ~100 for the rest
   // operands built per page in extra registers (the constants are fitted to what the compiler keeps without spilling)
   // (four ordinal slots: 2 x 16 pending table updates, 16 slot scores, 16 table rows per page being computed)
+  // (the dense four-slot variant would have registers for a gather lead of two pages at rank 64; measured: 470 us
+  // against 459 with one)
   constexpr int transient = (JOINT || Q4 ? 2 * NB : 0) + (Q4 ? 4 * NKK + (JOINT ? 40 : 16) : 0) + (KS > 1 ? 64 : 0);
   constexpr int by_regs = ((NW >= 16 ? 110 : 216) - transient - 112 - 2 * tile_regs) / (tile_regs + 6 * KS);
   // loads outstanding at once: (2LG+1) ordinals + (LG+1) pages of latents + LG pages of 4 score gathers (+ the page
