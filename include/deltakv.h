@@ -20,10 +20,21 @@
  *   deltakv_paged_layout appendix B.1 (separate pools for raw reference tokens
  *                        and for latents, addressed through per-sequence maps).
  *
+ * Variants of the two operations (each documented at its declaration):
+ *   deltakv_decode_attn_subset / _raw   section 4.2 (attention over the selected
+ *                        tokens only) and appendix B.2 (raw sink / recent segment);
+ *   deltakv_decode_attn_rope            section 4.1 (pre-RoPE cache): keys rotated
+ *                        at their positions after reconstruction;
+ *   deltakv_decode_attn_static          the same as deltakv_decode_attn for
+ *                        callers that may not allocate or pass a workspace;
+ *   deltakv_compress_mlp                section 4.1's non-linear compressor
+ *                        (GeLU MLP; the gated variant of section 5.3).
+ *
  * Readings fixed by this build (the paper is silent or differs):
- *   - one reference per (token, kv-head), chosen by cosine similarity over the
- *     256-value vector K||V of that head, lowest ordinal wins ties (the paper's
- *     retrieval is top-k by squared L2 over all heads, k = 4);
+ *   - by default one reference per (token, kv-head), chosen by cosine similarity
+ *     over the 256-value vector K||V of that head, lowest ordinal wins ties; the
+ *     paper's retrieval (top-k by squared L2, k = 4, mean of the references) is
+ *     selected with the dims' `metric` and `top_k` fields;
  *   - positions are 0-indexed; token t is a reference iff t % ref_stride == 0,
  *     its ordinal is t / ref_stride; candidates of token i are ordinals j with
  *     j * ref_stride < i;
