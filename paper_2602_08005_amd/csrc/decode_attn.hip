@@ -703,19 +703,30 @@ __global__ __launch_bounds__(128) void k_finalize(DecodeParams P) {
       for (int s = 0; s < kMaxSplits; ++s) a += s < n_used ? ap[s] : 0.f;
       if (d < R) zsum[d] = a;
     }
+    // the chunk partials do not depend on anything above either: their loads go out before the barrier, sixteen at a
+    // time (a 131072-token sequence has 32 chunks: two round trips instead of the four behind the barrier)
+    {
+      const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
+      const int64_t cstride = (int64_t)Gp * kHeadDim;
+      int c = 0;
+      for (; c + 16 <= nch; c += 16) {
+        float t[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) t[u] = op[(c + u) * cstride];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) o += t[u];
+      }
+      for (; c + 4 <= nch; c += 4) {
+        float t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = op[(c + u) * cstride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o += t[u];
+      }
+      for (; c < nch; ++c) o += op[c * cstride];
+    }
     __syncthreads();
     frame = fmaxf(redm[0], redm[1]) + exp_bias(P.sel_pages != nullptr);
-    const float* op = P.opart + (bh * P.n_chunk_max * Gp + g) * kHeadDim + d;
-    const int64_t cstride = (int64_t)Gp * kHeadDim;
-    int c = 0;
-    for (; c + 8 <= nch; c += 8) {
-      float t[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) t[u] = op[(c + u) * cstride];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) o += t[u];
-    }
-    for (; c < nch; ++c) o += op[c * cstride];
 #pragma unroll
     for (int cc = 0; cc < R; ++cc) o += zsum[cc] * bf16lo(wcol[cc]);
     // The fixed exponent frame holds weights between 2^-126 and 2^127.  A weight of 2^60 or more (any such weight
